@@ -1,0 +1,192 @@
+/*
+ * moe_janus.h - C ABI of the MI355X (gfx950) MoE-instance layer step.
+ *
+ * One MoE instance of a disaggregated MoE deployment runs, per layer and per decode
+ * batch (Janus, arXiv 2512.13525, Sec. 3.4, "Scheduling workflow"):
+ *
+ *   moe_route        gating selection on the MoE side          (Sec. 3.3 "Gating on the MoE side")
+ *   moe_schedule     Activated-Expert-Balanced Scheduling       (Sec. 3.4, Alg. 1, Steps 1-3)
+ *   moe_permute      this instance's share of the dispatch      (Sec. 3.4, Step 4)
+ *   moe_grouped_ffn  expert FFN over the activated experts only (Sec. 2.2, roofline paragraph)
+ *   moe_combine      weighted top-k combine, instance-partial   (Sec. 3.3, reverse path)
+ *
+ * Conventions
+ *   - Pointers named *_dev are device pointers owned by the caller; *_host are host
+ *     pointers.  The library never frees or reallocates caller memory.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Every
+ *     compute call only enqueues work on `stream`: it does not synchronise, does not
+ *     allocate and does not read results back to the host, so a whole layer step can be
+ *     queued without CPU-GPU synchronisation (Sec. 3.4, "Synchronization-free scheduling").
+ *   - All matrices are row-major and densely packed unless stated otherwise.
+ *   - Every function returns MOE_OK (0) or a negative error code.  Arguments are checked
+ *     on the host before anything is launched; device-resident values (expert ids, replica
+ *     ids) are trusted.  moe_strerror() describes a code; moe_last_error() adds the HIP
+ *     error text of the calling thread's most recent MOE_EHIP.
+ *   - Calls that share output or workspace buffers must be ordered by the caller (same
+ *     stream or events).  A placement object is immutable and may be shared.
+ *
+ * Symbols (paper notation): T tokens, k experts per token, E logical experts, n_inst MoE
+ * instances (n_e), C replica slots per instance, d_h hidden size, d_e expert intermediate
+ * size.  A request is the pair p = i*k + j (token i, choice j).  The physical replica id
+ * (RID) of slot s on instance g is g*C + s.
+ */
+#ifndef MOE_JANUS_H
+#define MOE_JANUS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define MOE_OK           0
+#define MOE_EINVAL     (-1)   /* null or misaligned pointer, non-positive or inconsistent size */
+#define MOE_ESHAPE     (-2)   /* a size the kernels do not support (see each call) */
+#define MOE_EPLACEMENT (-3)   /* invalid replica layout */
+#define MOE_EHIP       (-4)   /* a HIP runtime call or kernel launch failed */
+#define MOE_ENOMEM     (-5)   /* host or device allocation failed (placement create only) */
+#define MOE_EWORKSPACE (-6)   /* workspace_bytes smaller than moe_workspace_bytes() */
+
+#define MOE_DTYPE_BF16 0
+#define MOE_DTYPE_F32  1
+
+#define MOE_ROUTE_SOFTMAX        0
+#define MOE_ROUTE_SIGMOID_GROUP  1
+
+#define MOE_MAX_EXPERTS    1024   /* E */
+#define MOE_MAX_INSTANCES    64   /* n_inst */
+#define MOE_MAX_SLOTS       256   /* C */
+#define MOE_MAX_TOPK         32   /* k */
+
+const char *moe_strerror(int code);
+const char *moe_last_error(void);
+
+/* ------------------------------------------------------------------ replica layout
+ * The layout is what the MoE controller distributes at reconfiguration time (Sec. 3.4:
+ * "replica layout" metadata, updated on the order of hours; Appendix B).  It fixes
+ * R(e), G(e) and P(e,g) of Alg. 1's input list.
+ *
+ * slot_to_expert_host[g*C + s] = logical expert held by slot s of instance g, or -1 for
+ * an empty slot.  Rejected with MOE_EPLACEMENT: an expert without any replica, an expert
+ * with two replicas on one instance, an id outside [-1, E).  Limits (MOE_ESHAPE):
+ * E <= MOE_MAX_EXPERTS, n_inst <= MOE_MAX_INSTANCES, C <= MOE_MAX_SLOTS.
+ *
+ * The object owns small host and device tables on the device that is current at create
+ * time; create and destroy synchronise with the device (they are not on the hot path).
+ */
+typedef struct moe_placement moe_placement_t;
+
+int  moe_placement_create(moe_placement_t **out, int E, int n_inst, int C,
+                          const int32_t *slot_to_expert_host);
+void moe_placement_destroy(moe_placement_t *pl);
+/* Host-side queries (no device access): replica count R(e), and layout sizes. */
+int  moe_placement_replicas(const moe_placement_t *pl, int e);
+int  moe_placement_dims(const moe_placement_t *pl, int *E, int *n_inst, int *C);
+
+/* ------------------------------------------------------------------ a0: gating selection
+ * Sec. 3.4 workflow: "gating first produces the top-k logical expert ids".  The score
+ * function is a property of the model, not of the paper:
+ *   MOE_ROUTE_SOFTMAX        ids = the k largest logits (largest first; equal logits:
+ *                            lower id first); w = softmax over all E logits gathered at
+ *                            ids, rescaled to sum to 1 when renormalize != 0.
+ *   MOE_ROUTE_SIGMOID_GROUP  s = sigmoid(logit); E/n_group contiguous experts per group;
+ *                            group score = sum of its two largest s; the topk_group best
+ *                            groups survive (lower group id on ties); ids = the k largest
+ *                            logits among surviving experts; w = s / sum(selected s) * scale.
+ * logits_dev [T,E] float32 -> topk_ids_dev [T,k] int32, topk_w_dev [T,k] float32.
+ * Limits: 1 <= k <= min(E, MOE_MAX_TOPK); E <= MOE_MAX_EXPERTS; group mode needs
+ * E % n_group == 0, E/n_group >= 2, k <= topk_group*E/n_group, n_group <= 64.  T == 0 is a no-op.
+ */
+typedef struct moe_route_cfg {
+    int   mode;          /* MOE_ROUTE_* */
+    int   renormalize;   /* softmax mode only */
+    int   n_group;       /* group mode only */
+    int   topk_group;    /* group mode only */
+    float scale;         /* group mode only */
+} moe_route_cfg;
+
+int moe_route(const float *logits_dev, int T, int E, int k, const moe_route_cfg *cfg,
+              int32_t *topk_ids_dev, float *topk_w_dev, void *stream);
+
+/* ------------------------------------------------------------------ a1-a3: Alg. 1
+ * Step 1 collects the set of activated experts, Step 2 seats every activated
+ * single-replica expert on its only host and then every activated multi-replica expert,
+ * in ascending expert id, on its least-loaded host (load = activated experts seated on the
+ * instance so far in this layer; ties: lowest instance), Step 3 rewrites each request.
+ *
+ * topk_ids_dev [T,k] int32 (values in [0,E)) ->
+ *   rid_dev     [T,k] int32  O(i,j): replica id chosen for request (i,j)
+ *   act_rep_dev [E]   int32  actRep[e], -1 for experts not activated
+ *   load_dev    [n_inst] int32  activated experts per instance; max = a_max
+ * The result depends only on the layout and the set of activated experts, so every
+ * instance that runs this call on the same inputs obtains the same schedule.
+ * T == 0 yields act_rep = -1, load = 0.  k <= MOE_MAX_TOPK.
+ */
+int moe_schedule(const moe_placement_t *pl, const int32_t *topk_ids_dev, int T, int k,
+                 int32_t *rid_dev, int32_t *act_rep_dev, int32_t *load_dev, void *stream);
+
+/* ------------------------------------------------------------------ a4: dispatch (Step 4)
+ * Keeps the requests whose replica lives on instance g_self and groups them by local slot
+ * s = rid - g_self*C, ascending request id inside a slot (a stable grouping: the output is
+ * unique).
+ *   slot_count_dev [C]    int32  requests per local slot
+ *   slot_off_dev   [C+1]  int32  exclusive scan of slot_count; slot_off[C] = n_local
+ *   perm_dev       [T*k]  int32  capacity T*k; the first n_local entries are request ids
+ *   pos_dev        [T*k]  int32  pos[p] = row of request p in perm, or -1 if p is not local
+ * n_local stays on the device (slot_off_dev[C]); nothing is read back.
+ */
+int moe_permute(const moe_placement_t *pl, int g_self, const int32_t *rid_dev, int T, int k,
+                int32_t *slot_count_dev, int32_t *slot_off_dev, int32_t *perm_dev,
+                int32_t *pos_dev, void *stream);
+
+/* ------------------------------------------------------------------ expert weights
+ * Canonical layout of one instance's physical experts (what a checkpoint holds):
+ *   W13 [C, 2*d_e, d_h]  rows 0..d_e-1 = gate projection, rows d_e..2*d_e-1 = up projection
+ *   W2  [C, d_h, d_e]    down projection
+ * MOE_DTYPE_F32 consumes the canonical layout directly.  MOE_DTYPE_BF16 consumes a
+ * tile-packed copy made once when the replica is pinned (weights are static for hours,
+ * Sec. 3.4): every 16-row x 32-column tile is stored as the 1 KiB register image of one
+ * wavefront, so that the FFN kernel streams each expert with fully coalesced 128-bit
+ * loads.  moe_pack_weights_bf16 converts canonical -> packed on the device
+ * (dst and src must not overlap; sizes in elements are equal).
+ * Needs d_h % 32 == 0 and d_e % 32 == 0 (MOE_ESHAPE otherwise).
+ */
+int moe_pack_weights_bf16(const void *W13_dev, const void *W2_dev, int C, int d_h, int d_e,
+                          void *W13_packed_dev, void *W2_packed_dev, void *stream);
+
+/* ------------------------------------------------------------------ a5: grouped expert FFN
+ * For every local slot s with slot_count[s] > 0 and every request row r in
+ * [slot_off[s], slot_off[s+1]), token i = perm[r] / k:
+ *     h = Wgate_s x_i, u = Wup_s x_i, a = h/(1+exp(-h)) * u, Yp[r,:] = Wdown_s a.
+ * Slots without requests are skipped and their weights are never read, so HBM traffic
+ * scales with the number of activated experts (Sec. 2.2, R2).
+ *
+ *   X_dev  [T, d_h]  bf16 or f32 (dtype)
+ *   W13_dev, W2_dev  packed (bf16) or canonical (f32), see above
+ *   Yp_dev [T*k, d_h] float32, capacity T*k rows, rows >= n_local are left untouched
+ *   workspace_dev    at least moe_workspace_bytes() bytes, 256-byte aligned; holds the
+ *                    intermediate a (bf16 or f32) between the two GEMM stages
+ * bf16 inputs are multiplied on the matrix cores with fp32 accumulation; `a` is rounded
+ * to bf16 once.  Limits: d_h % 32 == 0, d_e % 32 == 0 (bf16); d_h % 4 == 0, d_e % 4 == 0 (f32).
+ */
+size_t moe_workspace_bytes(int T, int k, int C, int d_h, int d_e, int dtype);
+
+int moe_grouped_ffn(const void *X_dev, const void *W13_dev, const void *W2_dev,
+                    int T, int k, int C, int d_h, int d_e, int dtype,
+                    const int32_t *slot_off_dev, const int32_t *perm_dev,
+                    float *Yp_dev, void *workspace_dev, size_t workspace_bytes, void *stream);
+
+/* ------------------------------------------------------------------ a6: combine
+ * Y[i,:] = sum over j with pos[i*k+j] >= 0, in ascending j, of topk_w[i,j] * Yp[pos[i*k+j],:]
+ * accumulated in fp32; tokens without a local request get zeros.  This is the instance's
+ * partial result that enters the reverse-path reduction across instances (Sec. 3.3).
+ *   Y_dev [T, d_h] bf16 or f32 (dtype).  d_h % 4 == 0.
+ */
+int moe_combine(const float *Yp_dev, const int32_t *pos_dev, const float *topk_w_dev,
+                int T, int k, int d_h, int dtype, void *Y_dev, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOE_JANUS_H */

@@ -1,0 +1,175 @@
+"""Thin ctypes binding over libmoe_janus.so: same names as the C ABI (include/moe_janus.h),
+argument marshalling only.  Tensors are torch CUDA tensors used purely as device memory;
+every step of the path runs in the library's HIP kernels.  There is no fallback: if the
+library is missing or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import numpy as np
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libmoe_janus.so")
+
+MOE_OK = 0
+MOE_EINVAL, MOE_ESHAPE, MOE_EPLACEMENT, MOE_EHIP, MOE_ENOMEM, MOE_EWORKSPACE = -1, -2, -3, -4, -5, -6
+MOE_DTYPE_BF16, MOE_DTYPE_F32 = 0, 1
+MOE_ROUTE_SOFTMAX, MOE_ROUTE_SIGMOID_GROUP = 0, 1
+
+EXPORTS = [
+    "moe_strerror", "moe_last_error",
+    "moe_placement_create", "moe_placement_destroy", "moe_placement_replicas", "moe_placement_dims",
+    "moe_route", "moe_schedule", "moe_permute", "moe_pack_weights_bf16",
+    "moe_workspace_bytes", "moe_grouped_ffn", "moe_combine",
+]
+
+
+class MoeError(RuntimeError):
+    def __init__(self, code: int, what: str):
+        self.code = code
+        super().__init__(what)
+
+
+class moe_route_cfg(ctypes.Structure):
+    _fields_ = [("mode", ctypes.c_int), ("renormalize", ctypes.c_int), ("n_group", ctypes.c_int),
+                ("topk_group", ctypes.c_int), ("scale", ctypes.c_float)]
+
+
+_lib: Optional[ctypes.CDLL] = None
+
+
+def lib() -> ctypes.CDLL:
+    """Load the library (once).  Raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise MoeError(MOE_EINVAL, f"{LIB_PATH} is missing: build it with "
+                                   f"`python -m paper_2512_13525_amd.build` (no CPU fallback exists)")
+    L = ctypes.CDLL(LIB_PATH)
+    vp, ci, cs = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
+    L.moe_strerror.restype = ctypes.c_char_p
+    L.moe_strerror.argtypes = [ci]
+    L.moe_last_error.restype = ctypes.c_char_p
+    L.moe_last_error.argtypes = []
+    L.moe_placement_create.restype = ci
+    L.moe_placement_create.argtypes = [ctypes.POINTER(vp), ci, ci, ci, vp]
+    L.moe_placement_destroy.restype = None
+    L.moe_placement_destroy.argtypes = [vp]
+    L.moe_placement_replicas.restype = ci
+    L.moe_placement_replicas.argtypes = [vp, ci]
+    L.moe_placement_dims.restype = ci
+    L.moe_placement_dims.argtypes = [vp, ctypes.POINTER(ci), ctypes.POINTER(ci), ctypes.POINTER(ci)]
+    L.moe_route.restype = ci
+    L.moe_route.argtypes = [vp, ci, ci, ci, ctypes.POINTER(moe_route_cfg), vp, vp, vp]
+    L.moe_schedule.restype = ci
+    L.moe_schedule.argtypes = [vp, vp, ci, ci, vp, vp, vp, vp]
+    L.moe_permute.restype = ci
+    L.moe_permute.argtypes = [vp, ci, vp, ci, ci, vp, vp, vp, vp, vp]
+    L.moe_pack_weights_bf16.restype = ci
+    L.moe_pack_weights_bf16.argtypes = [vp, vp, ci, ci, ci, vp, vp, vp]
+    L.moe_workspace_bytes.restype = cs
+    L.moe_workspace_bytes.argtypes = [ci, ci, ci, ci, ci, ci]
+    L.moe_grouped_ffn.restype = ci
+    L.moe_grouped_ffn.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, ci, vp, vp, vp, vp, cs, vp]
+    L.moe_combine.restype = ci
+    L.moe_combine.argtypes = [vp, vp, vp, ci, ci, ci, ci, vp, vp]
+    _lib = L
+    return L
+
+
+def _check(code: int, what: str) -> None:
+    if code != MOE_OK:
+        L = lib()
+        msg = L.moe_strerror(code).decode()
+        if code == MOE_EHIP:
+            msg += ": " + L.moe_last_error().decode()
+        raise MoeError(code, f"{what}: {msg}")
+
+
+def _ptr(t) -> Optional[int]:
+    if t is None:
+        return None
+    return t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    """hipStream_t of a torch stream (None = torch's current stream)."""
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return s.cuda_stream or None
+
+
+class Placement:
+    """Owner of a moe_placement_t."""
+
+    def __init__(self, slot_to_expert, E: int, n_inst: int, C: int):
+        arr = np.ascontiguousarray(np.asarray(slot_to_expert), dtype=np.int32)
+        if arr.shape != (n_inst * C,):
+            raise MoeError(MOE_EINVAL, "slot_to_expert must have n_inst*C entries")
+        self._h = ctypes.c_void_p()
+        self.E, self.n_inst, self.C = E, n_inst, C
+        _check(lib().moe_placement_create(ctypes.byref(self._h), E, n_inst, C, arr.ctypes.data),
+               "moe_placement_create")
+
+    @property
+    def handle(self):
+        return self._h
+
+    def replicas(self, e: int) -> int:
+        return lib().moe_placement_replicas(self._h, e)
+
+    def close(self):
+        if getattr(self, "_h", None) is not None and self._h:
+            lib().moe_placement_destroy(self._h)
+            self._h = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def moe_route(logits, k: int, topk_ids, topk_w, mode: int = MOE_ROUTE_SOFTMAX, renormalize: bool = True,
+              n_group: int = 1, topk_group: int = 1, scale: float = 1.0, stream=None) -> None:
+    T, E = logits.shape
+    cfg = moe_route_cfg(mode, int(renormalize), n_group, topk_group, scale)
+    _check(lib().moe_route(_ptr(logits), T, E, k, ctypes.byref(cfg), _ptr(topk_ids), _ptr(topk_w),
+                           _stream(stream)), "moe_route")
+
+
+def moe_schedule(pl: Placement, topk_ids, T: int, k: int, rid, act_rep, load, stream=None) -> None:
+    _check(lib().moe_schedule(pl.handle, _ptr(topk_ids), T, k, _ptr(rid), _ptr(act_rep), _ptr(load),
+                              _stream(stream)), "moe_schedule")
+
+
+def moe_permute(pl: Placement, g_self: int, rid, T: int, k: int, slot_count, slot_off, perm, pos,
+                stream=None) -> None:
+    _check(lib().moe_permute(pl.handle, g_self, _ptr(rid), T, k, _ptr(slot_count), _ptr(slot_off),
+                             _ptr(perm), _ptr(pos), _stream(stream)), "moe_permute")
+
+
+def moe_pack_weights_bf16(W13, W2, C: int, d_h: int, d_e: int, W13_packed, W2_packed, stream=None) -> None:
+    _check(lib().moe_pack_weights_bf16(_ptr(W13), _ptr(W2), C, d_h, d_e, _ptr(W13_packed), _ptr(W2_packed),
+                                       _stream(stream)), "moe_pack_weights_bf16")
+
+
+def moe_workspace_bytes(T: int, k: int, C: int, d_h: int, d_e: int, dtype: int) -> int:
+    return int(lib().moe_workspace_bytes(T, k, C, d_h, d_e, dtype))
+
+
+def moe_grouped_ffn(X, W13, W2, T: int, k: int, C: int, d_h: int, d_e: int, dtype: int, slot_off, perm,
+                    Yp, workspace, stream=None) -> None:
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().moe_grouped_ffn(_ptr(X), _ptr(W13), _ptr(W2), T, k, C, d_h, d_e, dtype, _ptr(slot_off),
+                                 _ptr(perm), _ptr(Yp), _ptr(workspace), ws_bytes, _stream(stream)),
+           "moe_grouped_ffn")
+
+
+def moe_combine(Yp, pos, topk_w, T: int, k: int, d_h: int, dtype: int, Y, stream=None) -> None:
+    _check(lib().moe_combine(_ptr(Yp), _ptr(pos), _ptr(topk_w), T, k, d_h, dtype, _ptr(Y), _stream(stream)),
+           "moe_combine")

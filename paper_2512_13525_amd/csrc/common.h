@@ -1,0 +1,61 @@
+// Internal helpers shared by the translation units of libmoe_janus (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdio.h>
+
+#include "moe_janus.h"
+
+#define MOE_WAVE 64
+
+struct moe_placement {
+    int E, n_inst, C;
+    int n_words;                 // ceil(E/64): 64-bit words of an expert bitset
+    // host tables
+    int32_t *slot_to_expert_h;   // [n_inst*C]
+    int32_t *R_h;                // [E]
+    // device tables (one allocation, 256-byte aligned sub-arrays)
+    void     *dev_block;
+    uint64_t *host_mask_d;       // [E]  bit g set <=> instance g hosts a replica of e
+    int16_t  *slot_of_d;         // [E*n_inst] local slot of e on g, -1 if not hosted
+    int32_t  *single_rid_d;      // [E]  RID when R(e) == 1, else -1
+    uint64_t *multi_mask_d;      // [n_words] bit e set <=> R(e) > 1
+    uint64_t *single_mask_d;     // [n_inst*n_words] single-replica experts hosted on g
+    int device;
+};
+
+namespace moe {
+
+void set_hip_error(hipError_t e, const char *where);
+
+inline int check_launch(const char *where) {
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        set_hip_error(e, where);
+        return MOE_EHIP;
+    }
+    return MOE_OK;
+}
+
+inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+__device__ __forceinline__ int lane_id() { return threadIdx.x & (MOE_WAVE - 1); }
+
+__device__ __forceinline__ uint64_t lanemask_lt() {
+    return (1ull << lane_id()) - 1ull;
+}
+
+__device__ __forceinline__ float bf16_to_f32(uint16_t b) {
+    return __uint_as_float(static_cast<uint32_t>(b) << 16);
+}
+
+// round-to-nearest-even; NaN stays NaN
+__device__ __forceinline__ uint16_t f32_to_bf16(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return static_cast<uint16_t>((u >> 16) | 0x40u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return static_cast<uint16_t>(u >> 16);
+}
+
+}  // namespace moe

@@ -1,0 +1,48 @@
+"""Shared plumbing of the GPU parity tests: run the oracle and the HIP path on the same
+seeded inputs.  Holds no arithmetic of its own."""
+from __future__ import annotations
+
+import numpy as np
+
+from oracle import dispatch, ffn, routing, scheduling
+from paper_2512_13525_amd import workloads as W
+
+
+def oracle_route(cfg, logits):
+    if cfg.route == "softmax":
+        ids, w = routing.route_softmax(logits, cfg.k)
+        return ids, w, None
+    ids, w, info = routing.route_sigmoid_group(logits, cfg.k, cfg.n_group, cfg.topk_group)
+    return ids, w, info
+
+
+class OracleRun:
+    """Everything the oracle computes for (cfg, g_self) on the seeded inputs."""
+
+    def __init__(self, cfg, g_self=None, with_ffn=True, weights=None):
+        self.cfg = cfg
+        self.lay = W.build_placement(cfg)
+        self.pl = scheduling.make_placement(self.lay, cfg.E, cfg.n_inst, cfg.C)
+        self.logits = W.router_logits(cfg)
+        self.X = W.activations(cfg)
+        self.ids, self.w, self.route_info = oracle_route(cfg, self.logits)
+        self.O, self.act_rep, self.load = scheduling.aebs(self.ids, self.pl)
+        if g_self is None:
+            g_self = int(np.argmax(self.load))          # the straggler instance sets layer latency
+        self.g_self = g_self
+        self.slot_count, self.slot_off, self.perm = dispatch.permute(self.O, g_self, cfg.C)
+        self.pos = np.full(cfg.T * cfg.k, -1, dtype=np.int32)
+        self.pos[self.perm] = np.arange(len(self.perm), dtype=np.int32)
+        if with_ffn:
+            if weights is None:
+                weights = W.instance_weights(cfg, self.lay, g_self)
+            self.W13, self.W2 = weights
+            self.Yp = ffn.grouped_ffn(self.X, self.W13, self.W2, self.slot_off, self.perm, cfg.k)
+            self.Y = dispatch.combine(self.Yp, self.perm, self.w, cfg.T, cfg.k)
+
+
+def rel_fro(a, b):
+    a = np.asarray(a, dtype=np.float64)
+    b = np.asarray(b, dtype=np.float64)
+    den = np.linalg.norm(b)
+    return float(np.linalg.norm(a - b) / den) if den > 0 else float(np.linalg.norm(a - b))
