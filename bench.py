@@ -1,0 +1,227 @@
+#!/usr/bin/env python3
+"""Benchmark of the MoE-instance layer step on one MI355X.
+
+One step = route -> AEBS schedule -> permute -> grouped expert FFN -> combine for the
+straggler instance of a seeded synthetic batch, queued on one stream with no host
+synchronisation.  Consecutive steps use different weight copies and different batches
+from a ring (>= 1 GiB of weights in total), so expert weights come from HBM and not from
+the 256 MB memory-side cache.
+
+Prints ONE JSON line.  `value` = algorithmic bytes of a step (activated experts' weights +
+activation traffic) / step time, in GB/s; the `roofline` object prices the dominant kernel
+(the grouped FFN) alone, with its duration taken from HIP events recorded in the timed
+region on the launching stream; `cpu_baseline` times the CPU oracle on the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import statistics
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
+
+
+def make_cfg(name: str, T):
+    from paper_2512_13525_amd import workloads as W
+    if name == "dsv2lite":
+        return W.dsv2lite(T or 128)
+    if name == "qwen3":
+        return W.qwen3(T or 256)
+    if name == "dsv3":
+        return W.dsv3(T or 512)
+    if name == "stress":
+        return W.stress(T or 64, 1.25, 0.8)
+    raise SystemExit(f"unknown workload {name}")
+
+
+def main() -> None:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="dsv2lite", choices=["dsv2lite", "qwen3", "dsv3", "stress"])
+    ap.add_argument("--tokens", type=int, default=None)
+    ap.add_argument("--ring-bytes", type=float, default=1.25e9, help="minimum total bytes of rotating weight copies")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-events", action="store_true", help="do not record per-kernel events in the timed region")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        raise SystemExit("this build runs on ONE GPU: the other MoE instances exist only as replica placement "
+                         "seen by the scheduler; run with --gpus 1")
+
+    import numpy as np
+    import torch
+    from paper_2512_13525_amd import binding as B
+    from paper_2512_13525_amd import workloads as W
+    from paper_2512_13525_amd.layer import LayerStep, to_device_bf16
+
+    B.lib()                                   # fail loudly if the HIP library is missing
+    assert torch.cuda.is_available(), "bench.py needs an MI355X"
+    torch.cuda.set_device(0)
+    cfg = make_cfg(args.workload, args.tokens)
+    lay = W.build_placement(cfg)
+    T, k, C, d_h, d_e = cfg.T, cfg.k, cfg.C, cfg.d_h, cfg.d_e
+
+    # ---- ring of input batches and weight copies
+    per_copy = C * 3 * d_h * d_e * 2
+    n_ring = max(4, int(-(-args.ring_bytes // per_copy)))
+    logits = [torch.from_numpy(W.router_logits(cfg, sub=i)).cuda() for i in range(n_ring)]
+    Xs = [to_device_bf16(W.activations(cfg, sub=i)) for i in range(n_ring)]
+    gen = torch.Generator(device="cuda").manual_seed(cfg.seed)
+    W13s, W2s = [], []
+    for i in range(n_ring):
+        # packed layout is a fixed permutation of the canonical one: seeded N(0, 0.02) values
+        # drawn straight into it are the same workload
+        W13s.append((torch.randn((C, 2 * d_e, d_h), generator=gen, device="cuda") * 0.02).to(torch.bfloat16))
+        W2s.append((torch.randn((C, d_h, d_e), generator=gen, device="cuda") * 0.02).to(torch.bfloat16))
+
+    # ---- choose the straggler instance of batch 0 (set-up, not timed)
+    step = LayerStep(cfg, lay, 0)
+    step.route(logits[0]); step.schedule()
+    torch.cuda.synchronize()
+    g_self = int(torch.argmax(step.load).item())
+    step = LayerStep(cfg, lay, g_self)
+
+    def run_step(i):
+        j = i % n_ring
+        step.route(logits[j])
+        step.schedule()
+        step.permute()
+        step.ffn(Xs[j], W13=W13s[j], W2=W2s[j])
+        step.combine()
+
+    # per-ring-entry facts (a_g, n_local) for the byte count; read back outside the timed region
+    a_g, n_local, a_max = [], [], []
+    for j in range(n_ring):
+        run_step(j)
+        torch.cuda.synchronize()
+        cnt = step.slot_count.cpu().numpy()
+        a_g.append(int((cnt > 0).sum())); n_local.append(int(cnt.sum())); a_max.append(int(step.load.max().item()))
+
+    def bytes_ffn(j):
+        return a_g[j] * 3 * d_h * d_e * 2 + min(T, n_local[j]) * d_h * 2 + n_local[j] * d_h * 4
+
+    def bytes_step(j):
+        # + combine (read Yp, write Y) + routing/schedule index traffic
+        return (bytes_ffn(j) + n_local[j] * d_h * 4 + T * d_h * 2 + T * cfg.E * 4 + 6 * T * k * 4)
+
+    for i in range(args.warmup):
+        run_step(i)
+    torch.cuda.synchronize()
+
+    # ---- timed region: exactly K steps; one event pair per step around the FFN launch(es)
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        j = i % n_ring
+        step.route(logits[j])
+        step.schedule()
+        step.permute()
+        if not args.no_events:
+            ev[i][0].record()
+        step.ffn(Xs[j], W13=W13s[j], W2=W2s[j])
+        if not args.no_events:
+            ev[i][1].record()
+        step.combine()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    mean_bytes_step = statistics.mean(bytes_step(i % n_ring) for i in range(args.steps))
+    value = mean_bytes_step / (ms_per_step * 1e-3) / 1e9
+
+    if not args.no_events:
+        ffn_us = [a.elapsed_time(b) * 1e3 for a, b in ev]
+        ffn_avg_us = statistics.mean(ffn_us)
+        mean_bytes_ffn = statistics.mean(bytes_ffn(i % n_ring) for i in range(args.steps))
+        achieved = mean_bytes_ffn / (ffn_avg_us * 1e-6) / 1e9
+        roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                    "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+                    "kernel": "moe_grouped_ffn", "avg_us": round(ffn_avg_us, 2),
+                    "p50_us": round(statistics.median(ffn_us), 2),
+                    "algorithmic_bytes": int(mean_bytes_ffn)}
+    else:
+        roofline = None
+
+    # ---- per-stage times (separate instrumented pass; events between all stages)
+    stages = ["route", "schedule", "permute", "ffn", "combine"]
+    acc = {s: [] for s in stages}
+    n_inst_steps = min(args.steps, 100)
+    marks = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in range(n_inst_steps)]
+    torch.cuda.synchronize()
+    for i in range(n_inst_steps):
+        j = i % n_ring
+        m = marks[i]
+        m[0].record(); step.route(logits[j])
+        m[1].record(); step.schedule()
+        m[2].record(); step.permute()
+        m[3].record(); step.ffn(Xs[j], W13=W13s[j], W2=W2s[j])
+        m[4].record(); step.combine()
+        m[5].record()
+    torch.cuda.synchronize()
+    for m in marks:
+        for si, s in enumerate(stages):
+            acc[s].append(m[si].elapsed_time(m[si + 1]) * 1e3)
+    stage_us = {s: round(statistics.median(v), 2) for s, v in acc.items()}
+
+    out = {
+        "metric": "moe_layer_step_algorithmic_GBps", "value": round(value, 1), "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{cfg.name} MoE layer: E={cfg.E} k={k} d_h={d_h} d_e={d_e} T={T}, "
+                               f"{cfg.n_inst} instances x C={C} slots, Zipf s={cfg.zipf_s}, instance g_self={g_self} "
+                               f"(straggler of batch 0)",
+                   "ring_copies": n_ring, "ring_bytes": n_ring * per_copy},
+        "step_us": round(ms_per_step * 1e3, 2),
+        "pct_hbm_peak_whole_step": round(100 * value / HBM_PEAK_GBPS, 2),
+        "activated_experts_a_g": {"mean": round(statistics.mean(a_g), 2), "min": min(a_g), "max": max(a_g)},
+        "a_max_over_instances": {"mean": round(statistics.mean(a_max), 2), "max": max(a_max)},
+        "n_local_mean": round(statistics.mean(n_local), 1),
+        "stage_us_median": stage_us,
+        "sched_us": stage_us["schedule"],
+        "layer_us_permute_ffn_combine": round(stage_us["permute"] + stage_us["ffn"] + stage_us["combine"], 2),
+        "roofline": roofline,
+    }
+
+    # ---- CPU baseline: the oracle, as it stands, on this machine's host cores
+    if not args.no_cpu_baseline:
+        sys.path.insert(0, os.path.join(ROOT, "tests"))
+        from oracle import dispatch, ffn, scheduling
+        from helpers import oracle_route
+        try:
+            cores = len(os.sched_getaffinity(0))
+        except AttributeError:
+            cores = os.cpu_count() or 1
+        W13h, W2h = W.instance_weights(cfg, lay, g_self)           # untimed: input generation
+        lg, Xh = W.router_logits(cfg, sub=0), W.activations(cfg, sub=0)
+        opl = scheduling.make_placement(lay, cfg.E, cfg.n_inst, cfg.C)
+        reps, spent, sched_us = 0, 0.0, []
+        while spent < 10.0 and reps < 20:
+            c0 = time.perf_counter()
+            ids, w, _ = oracle_route(cfg, lg)
+            s0 = time.perf_counter()
+            O, _, _ = scheduling.aebs(ids, opl)
+            s1 = time.perf_counter()
+            _, off, perm = dispatch.permute(O, g_self, C)
+            Yp = ffn.grouped_ffn(Xh, W13h, W2h, off, perm, k)
+            dispatch.combine(Yp, perm, w, T, k)
+            c1 = time.perf_counter()
+            spent += c1 - c0; reps += 1; sched_us.append((s1 - s0) * 1e6)
+        cpu_s = spent / reps
+        out["cpu_baseline"] = {"value": round(bytes_step(0) / cpu_s / 1e9, 3), "unit": "GB/s", "cores": cores,
+                               "kind": "oracle",
+                               "sample": f"{reps} whole layer steps of the same workload (batch 0, instance {g_self}), "
+                                         f"NumPy fp64 oracle; {cpu_s * 1e3:.1f} ms per step, of which Alg. 1 "
+                                         f"{statistics.median(sched_us):.0f} us",
+                               "ms_per_step": round(cpu_s * 1e3, 2)}
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()
