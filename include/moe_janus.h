@@ -150,6 +150,7 @@ int moe_permute(const moe_placement_t *pl, int g_self, const int32_t *rid_dev, i
  * wavefront, so that the FFN kernel streams each expert with fully coalesced 128-bit
  * loads.  moe_pack_weights_bf16 converts canonical -> packed on the device
  * (dst and src must not overlap; sizes in elements are equal).
+ * The packed W2 groups output channels in pairs of 16-row tiles.
  * Needs d_h % 32 == 0 and d_e % 32 == 0 (MOE_ESHAPE otherwise).
  */
 int moe_pack_weights_bf16(const void *W13_dev, const void *W2_dev, int C, int d_h, int d_e,
@@ -165,12 +166,27 @@ int moe_pack_weights_bf16(const void *W13_dev, const void *W2_dev, int C, int d_
  *   X_dev  [T, d_h]  bf16 or f32 (dtype)
  *   W13_dev, W2_dev  packed (bf16) or canonical (f32), see above
  *   Yp_dev [T*k, d_h] float32, capacity T*k rows, rows >= n_local are left untouched
- *   workspace_dev    at least moe_workspace_bytes() bytes, 256-byte aligned; holds the
- *                    intermediate a (bf16 or f32) between the two GEMM stages
+ *   workspace_dev    at least moe_workspace_bytes() bytes, 256-byte aligned; holds a small
+ *                    header of progress counters and the intermediate a (bf16 or f32)
+ *                    between the two GEMM stages.  The header must have been cleared with
+ *                    moe_workspace_init() once after allocation; every call that runs to
+ *                    completion leaves it cleared for the next one.  Calls that share a
+ *                    workspace must not overlap in time.
  * bf16 inputs are multiplied on the matrix cores with fp32 accumulation; `a` is rounded
- * to bf16 once.  Limits: d_h % 32 == 0, d_e % 32 == 0 (bf16); d_h % 4 == 0, d_e % 4 == 0 (f32).
+ * to bf16 once.  The bf16 path is one persistent kernel whose second stage polls the
+ * counters of the first; the poll is bounded, and an overrun (which means the header was
+ * not cleared, or the GPU was shared with work that starved the kernel) is reported by
+ * moe_workspace_status() instead of hanging.
+ * Limits: d_h % 32 == 0, d_e % 32 == 0 (bf16); d_h % 4 == 0, d_e % 4 == 0 (f32; T*k <= 65535).
  */
 size_t moe_workspace_bytes(int T, int k, int C, int d_h, int d_e, int dtype);
+
+/* Clears the workspace header (asynchronous on `stream`). */
+int moe_workspace_init(void *workspace_dev, size_t workspace_bytes, void *stream);
+
+/* Synchronous read-back of the header's error word for tests and debugging (not for the hot
+ * path): *status_host = 0 if no poll of the fused kernel ever overran since the last init. */
+int moe_workspace_status(const void *workspace_dev, int *status_host);
 
 int moe_grouped_ffn(const void *X_dev, const void *W13_dev, const void *W2_dev,
                     int T, int k, int C, int d_h, int d_e, int dtype,

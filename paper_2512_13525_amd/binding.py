@@ -23,7 +23,7 @@ EXPORTS = [
     "moe_strerror", "moe_last_error",
     "moe_placement_create", "moe_placement_destroy", "moe_placement_replicas", "moe_placement_dims",
     "moe_route", "moe_schedule", "moe_permute", "moe_pack_weights_bf16",
-    "moe_workspace_bytes", "moe_grouped_ffn", "moe_combine",
+    "moe_workspace_bytes", "moe_workspace_init", "moe_workspace_status", "moe_grouped_ffn", "moe_combine",
 ]
 
 
@@ -73,6 +73,10 @@ def lib() -> ctypes.CDLL:
     L.moe_pack_weights_bf16.argtypes = [vp, vp, ci, ci, ci, vp, vp, vp]
     L.moe_workspace_bytes.restype = cs
     L.moe_workspace_bytes.argtypes = [ci, ci, ci, ci, ci, ci]
+    L.moe_workspace_init.restype = ci
+    L.moe_workspace_init.argtypes = [vp, cs, vp]
+    L.moe_workspace_status.restype = ci
+    L.moe_workspace_status.argtypes = [vp, ctypes.POINTER(ci)]
     L.moe_grouped_ffn.restype = ci
     L.moe_grouped_ffn.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, ci, vp, vp, vp, vp, cs, vp]
     L.moe_combine.restype = ci
@@ -160,6 +164,17 @@ def moe_pack_weights_bf16(W13, W2, C: int, d_h: int, d_e: int, W13_packed, W2_pa
 
 def moe_workspace_bytes(T: int, k: int, C: int, d_h: int, d_e: int, dtype: int) -> int:
     return int(lib().moe_workspace_bytes(T, k, C, d_h, d_e, dtype))
+
+
+def moe_workspace_init(workspace, stream=None) -> None:
+    _check(lib().moe_workspace_init(_ptr(workspace), workspace.numel() * workspace.element_size(),
+                                    _stream(stream)), "moe_workspace_init")
+
+
+def moe_workspace_status(workspace) -> int:
+    st = ctypes.c_int(-1)
+    _check(lib().moe_workspace_status(_ptr(workspace), ctypes.byref(st)), "moe_workspace_status")
+    return st.value
 
 
 def moe_grouped_ffn(X, W13, W2, T: int, k: int, C: int, d_h: int, d_e: int, dtype: int, slot_off, perm,

@@ -2,20 +2,48 @@
 // fused gate/up GEMM and a down GEMM; at decode sizes the layer is bound by streaming the
 // activated experts' weights from HBM, so latency follows the activated-expert count).
 //
-// bf16 path.  Weights are consumed in a tile-packed layout: every 16-row x 32-column tile
-// of a weight matrix is stored as the 1 KiB image of the MFMA A-operand of one wavefront
-// (lane l holds row l%16, columns (l/16)*8 .. +7), so a wavefront streams its tiles with
-// fully coalesced 128-bit loads straight into MFMA registers.  Tokens are the B operand
-// (lane l holds token l%16, the same 8 columns), gathered through `perm`; the 16x16 fp32
-// result tile leaves lane l with 4 consecutive output channels (l/16)*4.. of token l%16.
+// bf16 path: ONE persistent kernel for both GEMM stages.
 //
-//   stage 1  gateup_kernel: workgroup = (slot, 16 intermediate channels); its 4 wavefronts
-//            split K = d_h, partial tiles meet in LDS, SiLU(gate)*up is rounded to bf16 once
-//            and written to the workspace `act` [n_local, d_e].
-//   stage 2  down_kernel: wavefront = (slot, 16 output channels) over K = d_e, reading `act`.
-// Workgroups of slots without requests leave at once; their weights are never touched.
+// Weights are consumed in a tile-packed layout: a 16-row x 32-column tile of a weight matrix
+// is stored as the 1 KiB image of the MFMA A-operand of one wavefront (lane l holds row l%16,
+// columns (l/16)*8 .. +7), and the two 16-row tiles a work unit multiplies together
+// (16 gate + 16 up channels in stage 1, 32 output channels in stage 2) alternate per K-step,
+// so a unit is one contiguous run of 2 KiB steps read with fully coalesced 128-bit loads
+// straight into MFMA registers.  Tokens are the B operand (lane l holds token l%16, the same
+// 8 columns), fetched from L2 (X through `perm`, or the intermediate `act`) and shared by
+// both MFMAs of the step.  The 16x16 fp32 result leaves lane l with 4 consecutive output
+// channels (l/16)*4.. of token l%16.
 //
-// fp32 path (correctness configuration): plain wave-per-output-row dot products.
+// Work decomposition.  Nothing about the activated set is known on the host, so every
+// workgroup first compacts the activated slots from slot_off.  The work of a stage is the
+// flat sequence  slot -> pass (32 tokens) -> unit -> quad (4 K-steps, one per wavefront);
+// it is cut into gridDim equal ranges of quads, one per persistent workgroup, whatever the
+// number of activated experts (a perfectly balanced split: the layer's latency then follows
+// the activated-expert count down to a single expert).  A workgroup's 4 wavefronts take the
+// 4 K-steps of a quad (split-K), keep a ring of kRing steps of loads in flight and meet in
+// LDS at the end of a unit.  A unit cut by a range boundary is finished by whichever of its
+// workgroups arrives last: every part stores its fp32 partial tile in a private workspace
+// slot, bumps the unit's arrival counter, and the last one adds the parts in workgroup order
+// (so the sum is deterministic) and runs the epilogue.  Nobody ever waits for a partial.
+// SiLU(gate)*up is rounded to bf16 once and written to `act`.
+//
+// Stage 2 of a slot may start only when all stage-1 units of that slot are done: a per-slot
+// counter in the workspace header is bumped by every finished stage-1 unit and polled by
+// stage 2.  `act`, the partial tiles and the counters are written and read with agent-scope
+// (L2-coherent) accesses because the 8 XCDs do not share an L2, so no cache write-back or
+// invalidation is ever issued; a writer waits for its stores to be acknowledged before it
+// bumps a counter.  Every workgroup finishes all of its stage-1 work before it polls, and
+// the grid is never larger than what is resident at once, so every awaited unit belongs to
+// a running workgroup that never waits itself.  The poll is bounded all the same: on overrun
+// the workgroup raises the error word of the header and carries on, so that every wave
+// reaches the end of the kernel.  The last stage-2 unit of a slot clears that slot's
+// counters, and the finisher of a cut unit clears its arrival counter, for the next call.
+//
+// Slots without requests are never compacted into the work list: their weights are not read.
+//
+// fp32 path (correctness configuration): plain wave-per-output-row dot products, two kernels.
+#include <stdlib.h>
+
 #include "common.h"
 
 namespace {
@@ -23,7 +51,28 @@ namespace {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kTokTiles = 4;          // token tiles (of 16) a workgroup keeps in registers per pass
+constexpr int kTokTiles = 2;            // token tiles (of 16) per pass
+constexpr int kPassTok = kTokTiles * 16;
+constexpr int kRing = 2;                // K-steps of loads each wavefront keeps in flight
+constexpr int kFfnThreads = 256;
+constexpr int kFfnWgPerCu = 2;          // resident workgroups per CU the register budget is sized for
+constexpr int kMaxGrid = 1024;          // upper bound of the persistent grid
+constexpr int kTokCacheSlots = 64;      // activated slots whose first-pass token rows are cached in LDS
+
+// Workspace layout (bytes):
+//   [0, kCtrlBytes)            header: int [1] = error word; slot s owns the 128-byte line at int
+//                              offset kCtrlSlot0 + s*kCtrlStride ([0] stage-1 units done, [1] stage-2
+//                              units done); arrival counters of cut units at int offset kCtrlArrive0
+//                              + stage*kMaxGrid + (first workgroup of the unit)
+//   [kCtrlBytes, +kPartBytes)  partial tiles [stage][workgroup][2][kTokTiles][2][64] x 16 B
+//   [kCtrlBytes + kPartBytes, ...)  act
+constexpr int kCtrlStride = 32;
+constexpr int kCtrlSlot0 = 64;
+constexpr int kCtrlArrive0 = kCtrlSlot0 + MOE_MAX_SLOTS * kCtrlStride;
+constexpr int kCtrlInts = kCtrlArrive0 + 2 * kMaxGrid;
+constexpr size_t kCtrlBytes = (static_cast<size_t>(kCtrlInts) * 4 + 255) / 256 * 256;
+constexpr size_t kPartPerWg = 2 * 4 * kTokTiles * 2 * 64;              // f32x4 elements: 2 parts x (4 units x kTokTiles) x 2 halves
+constexpr size_t kPartBytes = 2 * static_cast<size_t>(kMaxGrid) * kPartPerWg * 16;
 
 __device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
     return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
@@ -49,153 +98,438 @@ __global__ void pack_w13_kernel(const uint4 *__restrict__ src, uint4 *__restrict
     }
 }
 
-// W2 [C, d_h, d_e] -> [C][d_h/16][d_e/32][64 lanes][8]
+// W2 [C, d_h, d_e] -> [C][d_h/32][d_e/32][2 (rows 0-15, rows 16-31)][64 lanes][8]
 __global__ void pack_w2_kernel(const uint4 *__restrict__ src, uint4 *__restrict__ dst,
                                int C, int d_h, int d_e) {
-    const int IT = d_h / 16, KS = d_e / 32;
-    const size_t n = static_cast<size_t>(C) * IT * KS * 64;
+    const int IT = d_h / 32, KS = d_e / 32;
+    const size_t n = static_cast<size_t>(C) * IT * KS * 2 * 64;
     for (size_t i = blockIdx.x * static_cast<size_t>(blockDim.x) + threadIdx.x; i < n;
          i += static_cast<size_t>(gridDim.x) * blockDim.x) {
         const int lane = i % 64;
         size_t r = i / 64;
+        const int half = r % 2; r /= 2;
         const int kk = r % KS; r /= KS;
         const int it = r % IT;
         const int s = r / IT;
-        const size_t row = static_cast<size_t>(s) * d_h + it * 16 + (lane & 15);
+        const size_t row = static_cast<size_t>(s) * d_h + it * 32 + half * 16 + (lane & 15);
         const size_t col = static_cast<size_t>(kk) * 32 + (lane >> 4) * 8;
         dst[i] = src[(row * d_e + col) / 8];
     }
 }
 
-// ------------------------------------------------------------------ stage 1 (bf16)
-template <int NT>
-__device__ __forceinline__ void gateup_accumulate(const bf16x8 *__restrict__ wp, const uint16_t *const *xp,
-                                                  int k_begin, int k_end, f32x4 *acc_g, f32x4 *acc_u) {
-#pragma unroll 4
-    for (int kk = k_begin; kk < k_end; ++kk) {
-        const bf16x8 a_g = wp[(static_cast<size_t>(kk) * 2 + 0) * 64];
-        const bf16x8 a_u = wp[(static_cast<size_t>(kk) * 2 + 1) * 64];
-#pragma unroll
-        for (int t = 0; t < NT; ++t) {
-            const bf16x8 b = *reinterpret_cast<const bf16x8 *>(xp[t] + kk * 32);
-            acc_g[t] = mfma16(a_g, b, acc_g[t]);
-            acc_u[t] = mfma16(a_u, b, acc_u[t]);
-        }
-    }
+__global__ void fill_zero_kernel(int *p, int n) {
+    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) p[i] = 0;
 }
 
-__global__ __launch_bounds__(256)
-void gateup_kernel(const uint16_t *__restrict__ X, const bf16x8 *__restrict__ W13p,
-                   const int32_t *__restrict__ slot_off, const int32_t *__restrict__ perm,
-                   uint16_t *__restrict__ act, int k, int d_h, int d_e) {
-    __shared__ f32x4 red[4][kTokTiles][2][64];          // [wave][token tile][gate|up][lane]
-    const int jt = blockIdx.x, s = blockIdx.y;
-    const int lo = slot_off[s];
-    const int m = slot_off[s + 1] - lo;
-    if (m <= 0) return;
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int n = lane & 15, q = lane >> 4;
-    const int JT = d_e / 16, KS = d_h / 32;
-    const int k_begin = wave * KS / 4, k_end = (wave + 1) * KS / 4;
-    const bf16x8 *wp = W13p + (static_cast<size_t>(s) * JT + jt) * KS * 2 * 64 + lane;
-    const int n_tiles = (m + 15) / 16;
+// ------------------------------------------------------------------ fused bf16 kernel
+struct FfnArgs {
+    const uint16_t *X;
+    const bf16x8 *W13p;
+    const bf16x8 *W2p;
+    const int32_t *slot_off;
+    const int32_t *perm;
+    int *ctrl;
+    f32x4 *part;
+    uint16_t *act;
+    float *Yp;
+    int k, C, d_h, d_e;
+    int act_stride;                      // elements between rows of act: a multiple of 64 (128-byte lines)
+    int spin_limit;
+};
 
-    for (int tile0 = 0; tile0 < n_tiles; tile0 += kTokTiles) {
-        const int nt = min(kTokTiles, n_tiles - tile0);
-        const uint16_t *xp[kTokTiles];
+// agent-scope (L2-coherent across XCDs) 16-byte accesses built from 64-bit relaxed atomics
+__device__ __forceinline__ void store_coherent(f32x4 *p, f32x4 v) {
+    union { f32x4 v; uint64_t u[2]; } r;
+    r.v = v;
+    uint64_t *q = reinterpret_cast<uint64_t *>(p);
+    __hip_atomic_store(q, r.u[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(q + 1, r.u[1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+__device__ __forceinline__ f32x4 load_coherent(const f32x4 *p) {
+    union { f32x4 v; uint64_t u[2]; } r;
+    const uint64_t *q = reinterpret_cast<const uint64_t *>(p);
+    r.u[0] = __hip_atomic_load(q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    r.u[1] = __hip_atomic_load(q + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return r.v;
+}
+
+// B-operand fragment (8 bf16 of one token row).  COHERENT = true reads the intermediate `act`,
+// which other XCDs wrote during this kernel.
+template <bool COHERENT>
+__device__ __forceinline__ bf16x8 load_b(const uint16_t *p) {
+    if (COHERENT) {
+        union { uint64_t u[2]; bf16x8 v; } r;
+        const uint64_t *q = reinterpret_cast<const uint64_t *>(p);
+        r.u[0] = __hip_atomic_load(q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        r.u[1] = __hip_atomic_load(q + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        return r.v;
+    }
+    return *reinterpret_cast<const bf16x8 *>(p);
+}
+
+__device__ __forceinline__ float silu_mul(float g, float u) { return g / (1.0f + __expf(-g)) * u; }
+
+constexpr int kMaxGroup = 4;             // units a workgroup multiplies together per K-step (B operand reuse)
+constexpr int kPairs = kMaxGroup * kTokTiles;
+
+struct FfnShared {
+    f32x4 red[4][kMaxGroup][kTokTiles][64];  // [wave][unit of the group][token tile][lane], one half at a time
+    int slot[MOE_MAX_SLOTS];                 // activated slots, ascending
+    int lo[MOE_MAX_SLOTS];                   // first request row of the slot
+    int m[MOE_MAX_SLOTS];                    // requests of the slot
+    int pre[MOE_MAX_SLOTS + 1];              // passes before activated slot j
+    int tok[kTokCacheSlots][kPassTok];       // token row of the first-pass requests
+    int a_g;
+    int flag;
+#ifdef MOE_FFN_TRACE
+    long long wait_ticks;
+#endif
+};
+
+// One segment = quads [qa, qb) of one group of R units for one pass of token tiles.  A K-step
+// of the group is R x 2 weight fragments (R x 2 KiB) against the same token fragment(s).
+// STAGE1: gate/up units (16 intermediate channels each); otherwise down units (32 output
+// channels each).
+template <bool STAGE1, int R>
+__device__ __forceinline__ void ffn_segment(const FfnArgs &a, FfnShared &sh, int j, int pass, int g_idx,
+                                            int qa, int qb, long long u0, long long Q, long long G,
+                                            int wave, int lane) {
+    const int n = lane & 15, q4 = lane >> 4;
+    const int n1 = a.d_e / 16, n2 = a.d_h / 32;
+    const int n_s = STAGE1 ? n1 : n2;
+    const int KS = (STAGE1 ? a.d_h : a.d_e) / 32;
+    const int QU = (KS + 3) >> 2;
+    const int s = sh.slot[j], lo = sh.lo[j], m = sh.m[j];
+    const int tile0 = pass * kTokTiles;
+    const int n_tiles = (m + 15) >> 4;
+    const int nt = min(kTokTiles, n_tiles - tile0);
+    int *slot_ctrl = a.ctrl + kCtrlSlot0 + s * kCtrlStride;
+    const size_t unit_stride = static_cast<size_t>(KS) * 128;      // 16-byte chunks between consecutive units
+
+    // this wave's K-steps: kk = 4*(qa+i) + wave, i in [0, n_i)
+    int n_i = qb - qa;
+    if (qb == QU && 4 * (QU - 1) + wave >= KS) n_i -= 1;
+    const bf16x8 *wp = (STAGE1 ? a.W13p : a.W2p) +
+                       ((static_cast<size_t>(s) * n_s + static_cast<size_t>(g_idx) * R) * KS + 4 * qa + wave) * 128 + lane;
+
+    // ---- weights first: their latency covers everything up to the first MFMA
+    bf16x8 wr[kRing][R][2];
 #pragma unroll
-        for (int t = 0; t < kTokTiles; ++t) {
-            const int idx = (tile0 + t) * 16 + n;
-            const int tok = perm[lo + (idx < m ? idx : 0)] / k;     // padding lanes reuse a valid row
-            xp[t] = X + static_cast<size_t>(tok) * d_h + q * 8;
-        }
-        f32x4 acc_g[kTokTiles], acc_u[kTokTiles];
+    for (int d = 0; d < kRing; ++d) {
+        if (d < n_i) {
 #pragma unroll
-        for (int t = 0; t < kTokTiles; ++t) { acc_g[t] = f32x4{0, 0, 0, 0}; acc_u[t] = f32x4{0, 0, 0, 0}; }
-        switch (nt) {
-            case 1: gateup_accumulate<1>(wp, xp, k_begin, k_end, acc_g, acc_u); break;
-            case 2: gateup_accumulate<2>(wp, xp, k_begin, k_end, acc_g, acc_u); break;
-            case 3: gateup_accumulate<3>(wp, xp, k_begin, k_end, acc_g, acc_u); break;
-            default: gateup_accumulate<4>(wp, xp, k_begin, k_end, acc_g, acc_u); break;
-        }
-#pragma unroll
-        for (int t = 0; t < kTokTiles; ++t) {
-            if (t < nt) { red[wave][t][0][lane] = acc_g[t]; red[wave][t][1][lane] = acc_u[t]; }
-        }
-        __syncthreads();
-        if (wave < nt) {                                 // wave t finishes token tile t
-            const int t = wave;
-            f32x4 g = red[0][t][0][lane], u = red[0][t][1][lane];
-#pragma unroll
-            for (int w = 1; w < 4; ++w) { g += red[w][t][0][lane]; u += red[w][t][1][lane]; }
-            const int idx = (tile0 + t) * 16 + n;
-            if (idx < m) {
-                ushort4 o;
-                o.x = moe::f32_to_bf16(g[0] / (1.0f + __expf(-g[0])) * u[0]);
-                o.y = moe::f32_to_bf16(g[1] / (1.0f + __expf(-g[1])) * u[1]);
-                o.z = moe::f32_to_bf16(g[2] / (1.0f + __expf(-g[2])) * u[2]);
-                o.w = moe::f32_to_bf16(g[3] / (1.0f + __expf(-g[3])) * u[3]);
-                *reinterpret_cast<ushort4 *>(act + static_cast<size_t>(lo + idx) * d_e + jt * 16 + q * 4) = o;
+            for (int r = 0; r < R; ++r) {
+                wr[d][r][0] = wp[r * unit_stride + static_cast<size_t>(d) * 512];
+                wr[d][r][1] = wp[r * unit_stride + static_cast<size_t>(d) * 512 + 64];
             }
         }
+    }
+
+    if (!STAGE1) {
+        // every stage-1 unit of this slot must have published its part of `act`
+        if (threadIdx.x == 0) {
+#ifdef MOE_FFN_TRACE
+            const long long w0 = wall_clock64();
+#endif
+            const int need = n1 * (sh.pre[j + 1] - sh.pre[j]);
+            int spins = 0;
+            while (__hip_atomic_load(&slot_ctrl[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < need) {
+                __builtin_amdgcn_s_sleep(16);
+                if (++spins > a.spin_limit) {
+                    __hip_atomic_store(&a.ctrl[1], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    break;
+                }
+            }
+#ifdef MOE_FFN_TRACE
+            sh.wait_ticks += wall_clock64() - w0;
+#endif
+        }
         __syncthreads();
     }
-}
 
-// ------------------------------------------------------------------ stage 2 (bf16)
-template <int NT>
-__device__ __forceinline__ void down_accumulate(const bf16x8 *__restrict__ wp, const uint16_t *const *ap,
-                                                int KS, f32x4 *acc) {
-#pragma unroll 4
-    for (int kk = 0; kk < KS; ++kk) {
-        const bf16x8 a = wp[static_cast<size_t>(kk) * 64];
+    // ---- token rows of this pass (B operand)
+    const uint16_t *bp[kTokTiles];
 #pragma unroll
-        for (int t = 0; t < NT; ++t) {
-            const bf16x8 b = *reinterpret_cast<const bf16x8 *>(ap[t] + kk * 32);
-            acc[t] = mfma16(a, b, acc[t]);
+    for (int t = 0; t < kTokTiles; ++t) {
+        const int idx = (tile0 + t) * 16 + n;
+        const int r = idx < m ? idx : tile0 * 16;                    // padding lanes reuse a valid row
+        if (STAGE1) {
+            int tok;
+            if (pass == 0 && j < kTokCacheSlots) tok = sh.tok[j][r];
+            else tok = a.perm[lo + r] / a.k;
+            bp[t] = a.X + static_cast<size_t>(tok) * a.d_h + (4 * qa + wave) * 32 + q4 * 8;
+        } else {
+            bp[t] = a.act + static_cast<size_t>(lo + r) * a.act_stride + (4 * qa + wave) * 32 + q4 * 8;
+        }
+    }
+    bf16x8 br[kRing][kTokTiles];
+#pragma unroll
+    for (int d = 0; d < kRing; ++d) {
+        if (d < n_i) {
+#pragma unroll
+            for (int t = 0; t < kTokTiles; ++t)
+                if (t < nt) br[d][t] = *reinterpret_cast<const bf16x8 *>(bp[t] + d * 128);
+        }
+    }
+
+    f32x4 acc[R][kTokTiles][2];
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int t = 0; t < kTokTiles; ++t) { acc[r][t][0] = f32x4{0, 0, 0, 0}; acc[r][t][1] = f32x4{0, 0, 0, 0}; }
+
+#define MOE_STEP(d, i, REFILL)                                                        \
+    {                                                                                 \
+        /* consume ring entry d, then refill the same registers (no copies) */         \
+        _Pragma("unroll") for (int r = 0; r < R; ++r) {                               \
+            _Pragma("unroll") for (int t = 0; t < kTokTiles; ++t) {                   \
+                if (t < NT_) {                                                        \
+                    acc[r][t][0] = mfma16(wr[d][r][0], br[d][t], acc[r][t][0]);       \
+                    acc[r][t][1] = mfma16(wr[d][r][1], br[d][t], acc[r][t][1]);       \
+                }                                                                     \
+            }                                                                         \
+        }                                                                             \
+        if (REFILL) {                                                                 \
+            const size_t o_ = static_cast<size_t>((i) + kRing);                       \
+            _Pragma("unroll") for (int r = 0; r < R; ++r) {                           \
+                wr[d][r][0] = wp[r * unit_stride + o_ * 512];                         \
+                wr[d][r][1] = wp[r * unit_stride + o_ * 512 + 64];                    \
+            }                                                                         \
+            _Pragma("unroll") for (int t = 0; t < kTokTiles; ++t)                     \
+                if (t < NT_) br[d][t] = *reinterpret_cast<const bf16x8 *>(bp[t] + o_ * 128); \
+        }                                                                             \
+    }
+#define MOE_STREAM(NTV)                                                               \
+    {                                                                                 \
+        constexpr int NT_ = NTV;                                                      \
+        int i0 = 0;                                                                   \
+        for (; i0 + 2 * kRing <= n_i; i0 += kRing) {                                  \
+            _Pragma("unroll") for (int d = 0; d < kRing; ++d) MOE_STEP(d, i0 + d, true) \
+        }                                                                             \
+        for (; i0 < n_i; i0 += kRing) {                                               \
+            _Pragma("unroll") for (int d = 0; d < kRing; ++d) {                       \
+                const int i = i0 + d;                                                 \
+                if (i < n_i) MOE_STEP(d, i, i + kRing < n_i)                          \
+            }                                                                         \
+        }                                                                             \
+    }
+    if (nt == 1) MOE_STREAM(1) else MOE_STREAM(2)
+#undef MOE_STREAM
+#undef MOE_STEP
+
+    // ---- the 4 wavefronts' partial tiles meet in LDS, one half (gate | up, rows 0-15 | 16-31) at a
+    // time; wave w then owns the (unit, token tile) pairs w and w+4
+    f32x4 res[2][2];                                                 // [pair slot][half]
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int t = 0; t < kTokTiles; ++t)
+                if (t < nt) sh.red[wave][r][t][lane] = acc[r][t][h];
+        __syncthreads();
+#pragma unroll
+        for (int ps = 0; ps < 2; ++ps) {
+            const int p = wave + 4 * ps;
+            const int r = p / kTokTiles, t = p % kTokTiles;
+            f32x4 v = f32x4{0, 0, 0, 0};
+            if (p < R * kTokTiles && t < nt) {
+                v = sh.red[0][r][t][lane];
+#pragma unroll
+                for (int w = 1; w < 4; ++w) v += sh.red[w][r][t][lane];
+            }
+            res[ps][h] = v;
+        }
+        __syncthreads();
+    }
+
+    const bool whole = qa == 0 && qb == QU;
+    bool finish = whole;
+    if (!whole) {
+        // a group cut by a range boundary: publish this part, the last part to arrive finishes
+        const int b_first = static_cast<int>(((u0 + 1) * G - 1) / Q);
+        const int b_last = static_cast<int>(((u0 + QU) * G - 1) / Q);
+        f32x4 *mine = a.part + ((STAGE1 ? 0 : static_cast<size_t>(kMaxGrid)) + blockIdx.x) * kPartPerWg +
+                      static_cast<size_t>(qa == 0 ? 1 : 0) * (kPairs * 2 * 64);
+#pragma unroll
+        for (int ps = 0; ps < 2; ++ps) {
+            const int p = wave + 4 * ps;
+            if (p < R * kTokTiles && p % kTokTiles < nt) {
+                store_coherent(mine + (p * 2 + 0) * 64 + lane, res[ps][0]);
+                store_coherent(mine + (p * 2 + 1) * 64 + lane, res[ps][1]);
+            }
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");             // stores acknowledged before the arrival
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            int *arrive = a.ctrl + kCtrlArrive0 + (STAGE1 ? 0 : kMaxGrid) + b_first;
+            const int old = __hip_atomic_fetch_add(arrive, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            sh.flag = old == b_last - b_first;
+            if (sh.flag) __hip_atomic_store(arrive, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        __syncthreads();
+        finish = sh.flag != 0;
+        if (finish) {
+#pragma unroll
+            for (int ps = 0; ps < 2; ++ps) {
+                const int p = wave + 4 * ps;
+                if (p < R * kTokTiles && p % kTokTiles < nt) {
+                    f32x4 v0 = f32x4{0, 0, 0, 0}, v1 = f32x4{0, 0, 0, 0};
+                    for (int b = b_first; b <= b_last; ++b) {        // fixed order: deterministic sum
+                        const f32x4 *q = a.part + ((STAGE1 ? 0 : static_cast<size_t>(kMaxGrid)) + b) * kPartPerWg +
+                                         static_cast<size_t>(b == b_first ? 1 : 0) * (kPairs * 2 * 64);
+                        v0 += load_coherent(q + (p * 2 + 0) * 64 + lane);
+                        v1 += load_coherent(q + (p * 2 + 1) * 64 + lane);
+                    }
+                    res[ps][0] = v0; res[ps][1] = v1;
+                }
+            }
+        }
+    }
+
+    if (finish) {
+#pragma unroll
+        for (int ps = 0; ps < 2; ++ps) {
+            const int p = wave + 4 * ps;
+            const int r = p / kTokTiles, t = p % kTokTiles;
+            const int idx = (tile0 + t) * 16 + n;
+            if (p < R * kTokTiles && t < nt && idx < m) {
+                const int t_idx = g_idx * R + r;
+                const f32x4 r0 = res[ps][0], r1 = res[ps][1];
+                if (STAGE1) {
+                    // agent-scope store: visible to the other XCDs once acknowledged
+                    const uint64_t o =
+                        static_cast<uint64_t>(moe::f32_to_bf16(silu_mul(r0[0], r1[0]))) |
+                        static_cast<uint64_t>(moe::f32_to_bf16(silu_mul(r0[1], r1[1]))) << 16 |
+                        static_cast<uint64_t>(moe::f32_to_bf16(silu_mul(r0[2], r1[2]))) << 32 |
+                        static_cast<uint64_t>(moe::f32_to_bf16(silu_mul(r0[3], r1[3]))) << 48;
+                    __hip_atomic_store(reinterpret_cast<uint64_t *>(a.act + static_cast<size_t>(lo + idx) * a.act_stride +
+                                                                    t_idx * 16 + q4 * 4),
+                                       o, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                } else {
+                    float *y = a.Yp + static_cast<size_t>(lo + idx) * a.d_h + t_idx * 32 + q4 * 4;
+                    *reinterpret_cast<f32x4 *>(y) = r0;
+                    *reinterpret_cast<f32x4 *>(y + 16) = r1;
+                }
+            }
+        }
+        // A workgroup barrier does not wait for global stores to be acknowledged; the counter
+        // bump below must not overtake this group's `act` stores on their way to memory.
+        if (STAGE1) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    }
+    __syncthreads();                                                 // flag is reused
+    if (finish && threadIdx.x == 0) {
+        if (STAGE1) {
+            __hip_atomic_fetch_add(&slot_ctrl[0], R, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        } else {
+            const int total2 = n2 * (sh.pre[j + 1] - sh.pre[j]);
+            if (__hip_atomic_fetch_add(&slot_ctrl[1], R, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == total2 - R) {
+                // last stage-2 group of the slot: every other group of the slot has passed its wait
+                __hip_atomic_store(&slot_ctrl[0], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(&slot_ctrl[1], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
         }
     }
 }
 
-__global__ __launch_bounds__(256)
-void down_kernel(const uint16_t *__restrict__ act, const bf16x8 *__restrict__ W2p,
-                 const int32_t *__restrict__ slot_off, float *__restrict__ Yp, int d_h, int d_e) {
-    const int s = blockIdx.y;
-    const int lo = slot_off[s];
-    const int m = slot_off[s + 1] - lo;
-    if (m <= 0) return;
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int n = lane & 15, q = lane >> 4;
-    const int IT = d_h / 16, KS = d_e / 32;
-    const int it = blockIdx.x * 4 + wave;
-    if (it >= IT) return;                                // no block barrier below
-    const bf16x8 *wp = W2p + (static_cast<size_t>(s) * IT + it) * KS * 64 + lane;
-    const int n_tiles = (m + 15) / 16;
+template <bool STAGE1, int R>
+__device__ __forceinline__ void ffn_stage(const FfnArgs &a, FfnShared &sh, int wave, int lane) {
+    const int a_g = sh.a_g;
+    const int n_g = (STAGE1 ? a.d_e / 16 : a.d_h / 32) / R;          // groups of R units per slot
+    const int KS = (STAGE1 ? a.d_h : a.d_e) / 32;
+    const int QU = (KS + 3) >> 2;
+    const long long per_pass = static_cast<long long>(n_g) * QU;     // quads of one pass of one slot
+    const long long Q = sh.pre[a_g] * per_pass;                      // quads of the stage
+    if (Q == 0) return;
+    // at most one workgroup per quad, so that no range is empty and every workgroup that a
+    // cut group counts on does arrive
+    const long long G = min(static_cast<long long>(gridDim.x), Q);
+    if (blockIdx.x >= G) return;
+    long long q = blockIdx.x * Q / G;
+    const long long q_hi = (blockIdx.x + 1LL) * Q / G;
+    int j = 0;
+    while (q < q_hi) {
+        while (sh.pre[j + 1] * per_pass <= q) ++j;
+        const long long rel = q - sh.pre[j] * per_pass;
+        const int pass = static_cast<int>(rel / per_pass);
+        const int rel2 = static_cast<int>(rel - pass * per_pass);
+        const int g_idx = rel2 / QU;
+        const int qa = rel2 - g_idx * QU;
+        const int qb = static_cast<int>(min(static_cast<long long>(QU), qa + (q_hi - q)));
+        ffn_segment<STAGE1, R>(a, sh, j, pass, g_idx, qa, qb, q - qa, Q, G, wave, lane);
+        q += qb - qa;
+    }
+}
 
-    for (int tile0 = 0; tile0 < n_tiles; tile0 += kTokTiles) {
-        const int nt = min(kTokTiles, n_tiles - tile0);
-        const uint16_t *ap[kTokTiles];
+__global__ __launch_bounds__(kFfnThreads, kFfnWgPerCu)
+void ffn_fused_kernel(FfnArgs a) {
+    __shared__ FfnShared sh;
+#ifdef MOE_FFN_TRACE
+    const long long t0 = wall_clock64();
+    if (threadIdx.x == 0) sh.wait_ticks = 0;
+#endif
+    // `act` is read with ordinary loads, and only after it is complete: nothing stale can be cached,
+    // because caches are invalidated at the kernel boundary and no line of `act` is read early
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform: scalar control flow
+    const int lane = threadIdx.x & 63;
+
+    // ---- activated slots in slot order, their request rows, and the pass prefix
+    if (wave == 0) {
+        int base = 0, passes = 0;
+        for (int s0 = 0; s0 < a.C; s0 += MOE_WAVE) {
+            const int s = s0 + lane;
+            const int lo = s < a.C ? a.slot_off[s] : 0;
+            const int m = s < a.C ? a.slot_off[s + 1] - lo : 0;
+            const bool on = m > 0;
+            const uint64_t mask = __ballot(on);
+            const int p = on ? (m + kPassTok - 1) / kPassTok : 0;
+            int incl = p;                                            // inclusive scan of passes over lanes
 #pragma unroll
-        for (int t = 0; t < kTokTiles; ++t) {
-            const int idx = (tile0 + t) * 16 + n;
-            ap[t] = act + static_cast<size_t>(lo + (idx < m ? idx : 0)) * d_e + q * 8;
+            for (int d = 1; d < MOE_WAVE; d <<= 1) {
+                const int o = __shfl_up(incl, d, MOE_WAVE);
+                if (lane >= d) incl += o;
+            }
+            if (on) {
+                const int jj = base + __popcll(mask & moe::lanemask_lt());
+                sh.slot[jj] = s; sh.lo[jj] = lo; sh.m[jj] = m;
+                sh.pre[jj] = passes + incl - p;
+            }
+            base += __popcll(mask);
+            passes += __shfl(incl, MOE_WAVE - 1, MOE_WAVE);
         }
-        f32x4 acc[kTokTiles];
-#pragma unroll
-        for (int t = 0; t < kTokTiles; ++t) acc[t] = f32x4{0, 0, 0, 0};
-        switch (nt) {
-            case 1: down_accumulate<1>(wp, ap, KS, acc); break;
-            case 2: down_accumulate<2>(wp, ap, KS, acc); break;
-            case 3: down_accumulate<3>(wp, ap, KS, acc); break;
-            default: down_accumulate<4>(wp, ap, KS, acc); break;
-        }
-#pragma unroll
-        for (int t = 0; t < kTokTiles; ++t) {
-            const int idx = (tile0 + t) * 16 + n;
-            if (t < nt && idx < m)
-                *reinterpret_cast<f32x4 *>(Yp + static_cast<size_t>(lo + idx) * d_h + it * 16 + q * 4) = acc[t];
+        if (lane == 0) { sh.a_g = base; sh.pre[base] = passes; }
+    }
+    __syncthreads();
+    {
+        const int n_cache = min(sh.a_g, kTokCacheSlots) * kPassTok;
+        for (int i = threadIdx.x; i < n_cache; i += kFfnThreads) {
+            const int j = i / kPassTok, r = i - j * kPassTok;
+            sh.tok[j][r] = a.perm[sh.lo[j] + (r < sh.m[j] ? r : 0)] / a.k;
         }
     }
+    __syncthreads();
+
+    // units are multiplied in groups of 4 (2, 1) against the same token fragments
+    const int n1 = a.d_e / 16, n2 = a.d_h / 32;
+#ifdef MOE_FFN_TRACE
+    const long long t1 = wall_clock64();
+#endif
+    if (n1 % 4 == 0) ffn_stage<true, 4>(a, sh, wave, lane);
+    else if (n1 % 2 == 0) ffn_stage<true, 2>(a, sh, wave, lane);
+    else ffn_stage<true, 1>(a, sh, wave, lane);
+#ifdef MOE_FFN_TRACE
+    const long long t2 = wall_clock64();
+#endif
+    if (n2 % 4 == 0) ffn_stage<false, 4>(a, sh, wave, lane);
+    else if (n2 % 2 == 0) ffn_stage<false, 2>(a, sh, wave, lane);
+    else ffn_stage<false, 1>(a, sh, wave, lane);
+#ifdef MOE_FFN_TRACE
+    if (threadIdx.x == 0) {
+        long long *tr = reinterpret_cast<long long *>(a.part + (2 * static_cast<size_t>(kMaxGrid) - 1 - blockIdx.x) * kPartPerWg);
+        tr[0] = t0; tr[1] = t1; tr[2] = t2; tr[3] = wall_clock64(); tr[4] = sh.wait_ticks;
+    }
+#endif
 }
 
 // ------------------------------------------------------------------ fp32 path
@@ -262,8 +596,25 @@ extern "C" size_t moe_workspace_bytes(int T, int k, int C, int d_h, int d_e, int
     (void)C; (void)d_h;
     if (T < 0 || k < 1 || d_e < 1) return 0;
     const size_t elt = dtype == MOE_DTYPE_F32 ? 4 : 2;
-    const size_t bytes = static_cast<size_t>(T) * k * d_e * elt;
-    return (bytes + 255) / 256 * 256 + 256;
+    const size_t bytes = static_cast<size_t>(T) * k * ((d_e + 63) / 64 * 64) * elt;
+    return kCtrlBytes + kPartBytes + (bytes + 255) / 256 * 256 + 256;
+}
+
+extern "C" int moe_workspace_init(void *workspace_dev, size_t workspace_bytes, void *stream) {
+    if (!workspace_dev || !moe::aligned(workspace_dev, 256)) return MOE_EINVAL;
+    if (workspace_bytes < kCtrlBytes) return MOE_EWORKSPACE;
+    hipLaunchKernelGGL(fill_zero_kernel, dim3(1), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       static_cast<int *>(workspace_dev), kCtrlInts);
+    return moe::check_launch("moe_workspace_init");
+}
+
+extern "C" int moe_workspace_status(const void *workspace_dev, int *status_host) {
+    if (!workspace_dev || !status_host) return MOE_EINVAL;
+    int hdr[2] = {0, 0};
+    hipError_t e = hipMemcpy(hdr, workspace_dev, sizeof(hdr), hipMemcpyDeviceToHost);
+    if (e != hipSuccess) { moe::set_hip_error(e, "moe_workspace_status"); return MOE_EHIP; }
+    *status_host = hdr[1];
+    return MOE_OK;
 }
 
 extern "C" int moe_pack_weights_bf16(const void *W13_dev, const void *W2_dev, int C, int d_h, int d_e,
@@ -281,6 +632,27 @@ extern "C" int moe_pack_weights_bf16(const void *W13_dev, const void *W2_dev, in
                        static_cast<const uint4 *>(W2_dev), static_cast<uint4 *>(W2_packed_dev), C, d_h, d_e);
     return moe::check_launch("moe_pack_weights_bf16");
 }
+
+namespace {
+// Persistent grid of the fused kernel: a multiple of the CU count that is resident at once
+// (kFfnWgPerCu workgroups of 256 threads per CU by __launch_bounds__).  MOE_JANUS_FFN_WG_PER_CU
+// (1..kFfnWgPerCu) overrides the default for tuning.
+int ffn_grid_blocks() {
+    static int cached = 0;
+    if (cached) return cached;
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
+        return 0;
+    int per_cu = kFfnWgPerCu;
+    if (const char *e = getenv("MOE_JANUS_FFN_WG_PER_CU")) {
+        const int v = atoi(e);
+        if (v >= 1 && v <= kFfnWgPerCu) per_cu = v;
+    }
+    cached = cus * per_cu < kMaxGrid ? cus * per_cu : kMaxGrid;
+    return cached;
+}
+}  // namespace
 
 extern "C" int moe_grouped_ffn(const void *X_dev, const void *W13_dev, const void *W2_dev,
                                int T, int k, int C, int d_h, int d_e, int dtype,
@@ -300,18 +672,29 @@ extern "C" int moe_grouped_ffn(const void *X_dev, const void *W13_dev, const voi
         return MOE_EINVAL;
     if (workspace_bytes < moe_workspace_bytes(T, k, C, d_h, d_e, dtype)) return MOE_EWORKSPACE;
     hipStream_t st = static_cast<hipStream_t>(stream);
+    char *ws = static_cast<char *>(workspace_dev);
     if (dtype == MOE_DTYPE_BF16) {
-        uint16_t *act = static_cast<uint16_t *>(workspace_dev);
-        hipLaunchKernelGGL(gateup_kernel, dim3(d_e / 16, C), dim3(256), 0, st,
-                           static_cast<const uint16_t *>(X_dev), static_cast<const bf16x8 *>(W13_dev),
-                           slot_off_dev, perm_dev, act, k, d_h, d_e);
-        hipLaunchKernelGGL(down_kernel, dim3((d_h / 16 + 3) / 4, C), dim3(256), 0, st,
-                           act, static_cast<const bf16x8 *>(W2_dev), slot_off_dev, Yp_dev, d_h, d_e);
+        const int blocks = ffn_grid_blocks();
+        if (blocks < 1) { moe::set_hip_error(hipErrorInvalidDevice, "moe_grouped_ffn/device query"); return MOE_EHIP; }
+        FfnArgs a;
+        a.X = static_cast<const uint16_t *>(X_dev);
+        a.W13p = static_cast<const bf16x8 *>(W13_dev);
+        a.W2p = static_cast<const bf16x8 *>(W2_dev);
+        a.slot_off = slot_off_dev;
+        a.perm = perm_dev;
+        a.ctrl = reinterpret_cast<int *>(ws);
+        a.part = reinterpret_cast<f32x4 *>(ws + kCtrlBytes);
+        a.act = reinterpret_cast<uint16_t *>(ws + kCtrlBytes + kPartBytes);
+        a.Yp = Yp_dev;
+        a.k = k; a.C = C; a.d_h = d_h; a.d_e = d_e;
+        a.act_stride = (d_e + 63) / 64 * 64;
+        a.spin_limit = 1 << 21;
+        hipLaunchKernelGGL(ffn_fused_kernel, dim3(blocks), dim3(kFfnThreads), 0, st, a);
     } else {
         // one grid row per possible request row; rows >= n_local leave at once
         const long long rows = static_cast<long long>(T) * k;
         if (rows > 65535) return MOE_ESHAPE;
-        float *act = static_cast<float *>(workspace_dev);
+        float *act = reinterpret_cast<float *>(ws + kCtrlBytes + kPartBytes);
         hipLaunchKernelGGL(gateup_f32_kernel, dim3((d_e + 3) / 4, rows), dim3(256), 0, st,
                            static_cast<const float *>(X_dev), static_cast<const float *>(W13_dev),
                            slot_off_dev, perm_dev, act, C, k, d_h, d_e);

@@ -41,6 +41,7 @@ class LayerStep:
         self.Y = torch.empty((T, cfg.d_h), dtype=self.tdtype, device=device)
         ws = B.moe_workspace_bytes(T, k, C, cfg.d_h, cfg.d_e, self.dtype)
         self.workspace = torch.empty((ws,), dtype=torch.uint8, device=device)
+        B.moe_workspace_init(self.workspace)
         self.W13 = None
         self.W2 = None
 

@@ -77,6 +77,8 @@ def test_argument_validation_without_launch():
     assert L.moe_combine(None, None, None, 4, 2, 130, B.MOE_DTYPE_F32, None, None) == B.MOE_ESHAPE
     assert L.moe_combine(None, None, None, 4, 2, 128, B.MOE_DTYPE_F32, None, None) == B.MOE_EINVAL
     assert L.moe_pack_weights_bf16(None, None, 2, 100, 64, None, None, None) == B.MOE_ESHAPE
+    assert L.moe_workspace_init(None, 0, None) == B.MOE_EINVAL
+    assert L.moe_workspace_status(None, None) == B.MOE_EINVAL
     ws = L.moe_workspace_bytes(128, 6, 17, 2048, 1408, B.MOE_DTYPE_BF16)
     assert ws >= 128 * 6 * 1408 * 2 and ws % 256 == 0
     assert L.moe_workspace_bytes(64, 2, 5, 256, 512, B.MOE_DTYPE_F32) >= 64 * 2 * 512 * 4

@@ -198,6 +198,13 @@ def test_layer_parity(cfg):
     # tokens without a local request are exactly zero
     no_local = (orc.O // cfg.C != orc.g_self).all(axis=1)
     assert not Y.float().cpu().numpy()[no_local].any()
+    assert B.moe_workspace_status(step.workspace) == 0
+    # a second step on the same buffers (counters were left cleared) gives the same bits
+    Yp1 = step.Yp.clone()
+    step.step(torch.from_numpy(orc.logits).cuda(), upload_x(cfg, orc.X))
+    torch.cuda.synchronize()
+    assert torch.equal(Yp1[:n_local], step.Yp[:n_local])
+    assert B.moe_workspace_status(step.workspace) == 0
 
 
 def test_all_instances_sum_to_dense_layer():
