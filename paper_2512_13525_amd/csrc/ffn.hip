@@ -53,6 +53,7 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kTokTiles = 2;            // token tiles (of 16) per pass
 constexpr int kPassTok = kTokTiles * 16;
+
 constexpr int kRing = 2;                // K-steps of loads each wavefront keeps in flight
 constexpr int kFfnThreads = 256;
 constexpr int kFfnWgPerCu = 2;          // resident workgroups per CU the register budget is sized for
@@ -137,35 +138,18 @@ struct FfnArgs {
     int spin_limit;
 };
 
-// agent-scope (L2-coherent across XCDs) 16-byte accesses built from 64-bit relaxed atomics
+// agent-scope (L2-coherent across XCDs) 16-byte accesses.  The compiler offers agent-scope
+// atomics up to 64 bits only; the 128-bit forms are the same instructions with the sc1 bit, so
+// that a wavefront moves a whole 1 KiB tile with one fully coalesced request.  The caller
+// waits (s_waitcnt vmcnt(0)) before it relies on a store having landed; the load waits itself.
 __device__ __forceinline__ void store_coherent(f32x4 *p, f32x4 v) {
-    union { f32x4 v; uint64_t u[2]; } r;
-    r.v = v;
-    uint64_t *q = reinterpret_cast<uint64_t *>(p);
-    __hip_atomic_store(q, r.u[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    __hip_atomic_store(q + 1, r.u[1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    asm volatile("global_store_dwordx4 %0, %1, off sc1" : : "v"(p), "v"(v) : "memory");
 }
 
 __device__ __forceinline__ f32x4 load_coherent(const f32x4 *p) {
-    union { f32x4 v; uint64_t u[2]; } r;
-    const uint64_t *q = reinterpret_cast<const uint64_t *>(p);
-    r.u[0] = __hip_atomic_load(q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    r.u[1] = __hip_atomic_load(q + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    return r.v;
-}
-
-// B-operand fragment (8 bf16 of one token row).  COHERENT = true reads the intermediate `act`,
-// which other XCDs wrote during this kernel.
-template <bool COHERENT>
-__device__ __forceinline__ bf16x8 load_b(const uint16_t *p) {
-    if (COHERENT) {
-        union { uint64_t u[2]; bf16x8 v; } r;
-        const uint64_t *q = reinterpret_cast<const uint64_t *>(p);
-        r.u[0] = __hip_atomic_load(q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        r.u[1] = __hip_atomic_load(q + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        return r.v;
-    }
-    return *reinterpret_cast<const bf16x8 *>(p);
+    f32x4 v;
+    asm volatile("global_load_dwordx4 %0, %1, off sc1\n\ts_waitcnt vmcnt(0)" : "=v"(v) : "v"(p) : "memory");
+    return v;
 }
 
 __device__ __forceinline__ float silu_mul(float g, float u) { return g / (1.0f + __expf(-g)) * u; }
@@ -191,30 +175,31 @@ struct FfnShared {
 // of the group is R x 2 weight fragments (R x 2 KiB) against the same token fragment(s).
 // STAGE1: gate/up units (16 intermediate channels each); otherwise down units (32 output
 // channels each).
+struct SegDesc {
+    int j, pass, g_idx, qa, qb;
+    long long u0;                            // first quad of the group in the stage's flat order
+};
+
+// This wave's K-steps of a segment: kk = 4*(qa+i) + wave, i in [0, n_i)
+__device__ __forceinline__ int seg_steps(const SegDesc &d, int KS, int QU, int wave) {
+    int n_i = d.qb - d.qa;
+    if (d.qb == QU && 4 * (QU - 1) + wave >= KS) n_i -= 1;
+    return n_i;
+}
+
 template <bool STAGE1, int R>
-__device__ __forceinline__ void ffn_segment(const FfnArgs &a, FfnShared &sh, int j, int pass, int g_idx,
-                                            int qa, int qb, long long u0, long long Q, long long G,
-                                            int wave, int lane) {
-    const int n = lane & 15, q4 = lane >> 4;
-    const int n1 = a.d_e / 16, n2 = a.d_h / 32;
-    const int n_s = STAGE1 ? n1 : n2;
+__device__ __forceinline__ const bf16x8 *seg_weights(const FfnArgs &a, const FfnShared &sh, const SegDesc &d,
+                                                     int wave, int lane) {
+    const int n_s = STAGE1 ? a.d_e / 16 : a.d_h / 32;
     const int KS = (STAGE1 ? a.d_h : a.d_e) / 32;
-    const int QU = (KS + 3) >> 2;
-    const int s = sh.slot[j], lo = sh.lo[j], m = sh.m[j];
-    const int tile0 = pass * kTokTiles;
-    const int n_tiles = (m + 15) >> 4;
-    const int nt = min(kTokTiles, n_tiles - tile0);
-    int *slot_ctrl = a.ctrl + kCtrlSlot0 + s * kCtrlStride;
-    const size_t unit_stride = static_cast<size_t>(KS) * 128;      // 16-byte chunks between consecutive units
+    return (STAGE1 ? a.W13p : a.W2p) +
+           ((static_cast<size_t>(sh.slot[d.j]) * n_s + static_cast<size_t>(d.g_idx) * R) * KS + 4 * d.qa + wave) * 128 + lane;
+}
 
-    // this wave's K-steps: kk = 4*(qa+i) + wave, i in [0, n_i)
-    int n_i = qb - qa;
-    if (qb == QU && 4 * (QU - 1) + wave >= KS) n_i -= 1;
-    const bf16x8 *wp = (STAGE1 ? a.W13p : a.W2p) +
-                       ((static_cast<size_t>(s) * n_s + static_cast<size_t>(g_idx) * R) * KS + 4 * qa + wave) * 128 + lane;
-
-    // ---- weights first: their latency covers everything up to the first MFMA
-    bf16x8 wr[kRing][R][2];
+// First kRing K-steps of a segment's weights into the ring (issued as early as possible: before
+// the previous segment's reduction and epilogue, so that their latency hides behind them).
+template <int R>
+__device__ __forceinline__ void seg_prefetch(const bf16x8 *wp, size_t unit_stride, int n_i, bf16x8 (*wr)[R][2]) {
 #pragma unroll
     for (int d = 0; d < kRing; ++d) {
         if (d < n_i) {
@@ -225,6 +210,26 @@ __device__ __forceinline__ void ffn_segment(const FfnArgs &a, FfnShared &sh, int
             }
         }
     }
+}
+
+template <bool STAGE1, int R>
+__device__ __forceinline__ void ffn_segment(const FfnArgs &a, FfnShared &sh, const SegDesc &cur, const SegDesc &nxt,
+                                            bool has_next, bf16x8 (*wr)[R][2], long long Q, long long G,
+                                            int wave, int lane) {
+    const int j = cur.j, pass = cur.pass, g_idx = cur.g_idx, qa = cur.qa, qb = cur.qb;
+    const long long u0 = cur.u0;
+    const int n = lane & 15, q4 = lane >> 4;
+    const int n1 = a.d_e / 16, n2 = a.d_h / 32;
+    const int KS = (STAGE1 ? a.d_h : a.d_e) / 32;
+    const int QU = (KS + 3) >> 2;
+    const int s = sh.slot[j], lo = sh.lo[j], m = sh.m[j];
+    const int tile0 = pass * kTokTiles;
+    const int n_tiles = (m + 15) >> 4;
+    const int nt = min(kTokTiles, n_tiles - tile0);
+    int *slot_ctrl = a.ctrl + kCtrlSlot0 + s * kCtrlStride;
+    const size_t unit_stride = static_cast<size_t>(KS) * 128;      // 16-byte chunks between consecutive units
+    const int n_i = seg_steps(cur, KS, QU, wave);
+    const bf16x8 *wp = seg_weights<STAGE1, R>(a, sh, cur, wave, lane);   // its first kRing steps are already in flight
 
     if (!STAGE1) {
         // every stage-1 unit of this slot must have published its part of `act`
@@ -317,6 +322,10 @@ __device__ __forceinline__ void ffn_segment(const FfnArgs &a, FfnShared &sh, int
     if (nt == 1) MOE_STREAM(1) else MOE_STREAM(2)
 #undef MOE_STREAM
 #undef MOE_STEP
+
+    // ---- the next segment's first weights go out before this one's reduction and epilogue
+    if (has_next)
+        seg_prefetch<R>(seg_weights<STAGE1, R>(a, sh, nxt, wave, lane), unit_stride, seg_steps(nxt, KS, QU, wave), wr);
 
     // ---- the 4 wavefronts' partial tiles meet in LDS, one half (gate | up, rows 0-15 | 16-31) at a
     // time; wave w then owns the (unit, token tile) pairs w and w+4
@@ -449,16 +458,31 @@ __device__ __forceinline__ void ffn_stage(const FfnArgs &a, FfnShared &sh, int w
     long long q = blockIdx.x * Q / G;
     const long long q_hi = (blockIdx.x + 1LL) * Q / G;
     int j = 0;
-    while (q < q_hi) {
-        while (sh.pre[j + 1] * per_pass <= q) ++j;
-        const long long rel = q - sh.pre[j] * per_pass;
-        const int pass = static_cast<int>(rel / per_pass);
-        const int rel2 = static_cast<int>(rel - pass * per_pass);
-        const int g_idx = rel2 / QU;
-        const int qa = rel2 - g_idx * QU;
-        const int qb = static_cast<int>(min(static_cast<long long>(QU), qa + (q_hi - q)));
-        ffn_segment<STAGE1, R>(a, sh, j, pass, g_idx, qa, qb, q - qa, Q, G, wave, lane);
-        q += qb - qa;
+    auto describe = [&](long long at) {
+        while (sh.pre[j + 1] * per_pass <= at) ++j;
+        const long long rel = at - sh.pre[j] * per_pass;
+        SegDesc d;
+        d.j = j;
+        d.pass = static_cast<int>(rel / per_pass);
+        const int rel2 = static_cast<int>(rel - d.pass * per_pass);
+        d.g_idx = rel2 / QU;
+        d.qa = rel2 - d.g_idx * QU;
+        d.qb = static_cast<int>(min(static_cast<long long>(QU), d.qa + (q_hi - at)));
+        d.u0 = at - d.qa;
+        return d;
+    };
+    bf16x8 wr[kRing][R][2];
+    SegDesc cur = describe(q);
+    seg_prefetch<R>(seg_weights<STAGE1, R>(a, sh, cur, wave, lane), static_cast<size_t>(KS) * 128,
+                    seg_steps(cur, KS, QU, wave), wr);
+    while (true) {
+        q += cur.qb - cur.qa;
+        const bool has_next = q < q_hi;
+        SegDesc nxt = cur;
+        if (has_next) nxt = describe(q);
+        ffn_segment<STAGE1, R>(a, sh, cur, nxt, has_next, wr, Q, G, wave, lane);
+        if (!has_next) break;
+        cur = nxt;
     }
 }
 
@@ -510,19 +534,23 @@ void ffn_fused_kernel(FfnArgs a) {
     }
     __syncthreads();
 
-    // units are multiplied in groups of 4 (2, 1) against the same token fragments
+    // Units are multiplied in groups of R = 4, 2 or 1 against the same token fragments: larger
+    // groups re-read the tokens less often, but a group is the unit of the cross-workgroup fix-up,
+    // so R is kept small enough that a workgroup's range spans at least ~2 groups.
     const int n1 = a.d_e / 16, n2 = a.d_h / 32;
+    const long long passes = sh.pre[sh.a_g];
+    const long long grid = gridDim.x;
 #ifdef MOE_FFN_TRACE
     const long long t1 = wall_clock64();
 #endif
-    if (n1 % 4 == 0) ffn_stage<true, 4>(a, sh, wave, lane);
-    else if (n1 % 2 == 0) ffn_stage<true, 2>(a, sh, wave, lane);
+    if (n1 % 4 == 0 && passes * n1 >= 8 * grid) ffn_stage<true, 4>(a, sh, wave, lane);
+    else if (n1 % 2 == 0 && passes * n1 >= 4 * grid) ffn_stage<true, 2>(a, sh, wave, lane);
     else ffn_stage<true, 1>(a, sh, wave, lane);
 #ifdef MOE_FFN_TRACE
     const long long t2 = wall_clock64();
 #endif
-    if (n2 % 4 == 0) ffn_stage<false, 4>(a, sh, wave, lane);
-    else if (n2 % 2 == 0) ffn_stage<false, 2>(a, sh, wave, lane);
+    if (n2 % 4 == 0 && passes * n2 >= 8 * grid) ffn_stage<false, 4>(a, sh, wave, lane);
+    else if (n2 % 2 == 0 && passes * n2 >= 4 * grid) ffn_stage<false, 2>(a, sh, wave, lane);
     else ffn_stage<false, 1>(a, sh, wave, lane);
 #ifdef MOE_FFN_TRACE
     if (threadIdx.x == 0) {
