@@ -3,7 +3,7 @@
 
 One step = route -> AEBS schedule -> permute -> grouped expert FFN -> combine for the
 straggler instance of a seeded synthetic batch, queued on one stream with no host
-synchronisation.  Consecutive steps use different weight copies and different batches
+synchronisation, as three launches (fused front, fused FFN, combine).  Consecutive steps use different weight copies and different batches
 from a ring (>= 1 GiB of weights in total), so expert weights come from HBM and not from
 the 256 MB memory-side cache.
 
@@ -50,6 +50,9 @@ def main() -> None:
     ap.add_argument("--ring-bytes", type=float, default=1.25e9, help="minimum total bytes of rotating weight copies")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-events", action="store_true", help="do not record per-kernel events in the timed region")
+    ap.add_argument("--mode", default="step", choices=["step", "sched", "act_sweep"],
+                    help="step: the headline line (default); sched: scheduler us and a_max vs optimum over the "
+                         "stress sweep; act_sweep: layer us vs number of activated experts")
     args = ap.parse_args()
     if args.gpus != 1:
         raise SystemExit("this build runs on ONE GPU: the other MoE instances exist only as replica placement "
@@ -64,6 +67,10 @@ def main() -> None:
     B.lib()                                   # fail loudly if the HIP library is missing
     assert torch.cuda.is_available(), "bench.py needs an MI355X"
     torch.cuda.set_device(0)
+    if args.mode == "sched":
+        return sched_sweep(args)
+    if args.mode == "act_sweep":
+        return act_sweep(args)
     cfg = make_cfg(args.workload, args.tokens)
     lay = W.build_placement(cfg)
     T, k, C, d_h, d_e = cfg.T, cfg.k, cfg.C, cfg.d_h, cfg.d_e
@@ -89,10 +96,9 @@ def main() -> None:
     step = LayerStep(cfg, lay, g_self)
 
     def run_step(i):
+        # three launches: front (route + Alg. 1 + dispatch), grouped FFN, combine
         j = i % n_ring
-        step.route(logits[j])
-        step.schedule()
-        step.permute()
+        step.front(logits[j])
         step.ffn(Xs[j], W13=W13s[j], W2=W2s[j])
         step.combine()
 
@@ -121,9 +127,7 @@ def main() -> None:
     t0 = time.perf_counter()
     for i in range(args.steps):
         j = i % n_ring
-        step.route(logits[j])
-        step.schedule()
-        step.permute()
+        step.front(logits[j])
         if not args.no_events:
             ev[i][0].record()
         step.ffn(Xs[j], W13=W13s[j], W2=W2s[j])
@@ -169,6 +173,13 @@ def main() -> None:
         for si, s in enumerate(stages):
             acc[s].append(m[si].elapsed_time(m[si + 1]) * 1e3)
     stage_us = {s: round(statistics.median(v), 2) for s, v in acc.items()}
+    # the fused front launch (what the timed region uses instead of route + schedule + permute)
+    fm = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_inst_steps)]
+    for i in range(n_inst_steps):
+        fm[i][0].record(); step.front(logits[i % n_ring]); fm[i][1].record()
+        step.ffn(Xs[i % n_ring], W13=W13s[i % n_ring], W2=W2s[i % n_ring]); step.combine()
+    torch.cuda.synchronize()
+    stage_us["front_fused"] = round(statistics.median(a.elapsed_time(b) * 1e3 for a, b in fm), 2)
 
     out = {
         "metric": "moe_layer_step_algorithmic_GBps", "value": round(value, 1), "unit": "GB/s",
@@ -184,6 +195,7 @@ def main() -> None:
         "a_max_over_instances": {"mean": round(statistics.mean(a_max), 2), "max": max(a_max)},
         "n_local_mean": round(statistics.mean(n_local), 1),
         "stage_us_median": stage_us,
+        "launches_per_step": 3,
         "sched_us": stage_us["schedule"],
         "layer_us_permute_ffn_combine": round(stage_us["permute"] + stage_us["ffn"] + stage_us["combine"], 2),
         "roofline": roofline,
@@ -221,6 +233,114 @@ def main() -> None:
                                          f"{statistics.median(sched_us):.0f} us",
                                "ms_per_step": round(cpu_s * 1e3, 2)}
     print(json.dumps(out), flush=True)
+
+
+def _time_us(fn, reps):
+    """Mean microseconds per call of fn over `reps` back-to-back launches (HIP events)."""
+    import torch
+    for _ in range(5):
+        fn()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    a.record()
+    for _ in range(reps):
+        fn()
+    b.record()
+    torch.cuda.synchronize()
+    return a.elapsed_time(b) * 1e3 / reps
+
+
+def sched_sweep(args) -> None:
+    """Scheduler-stress sweep: 256 experts, top-8, 16 instances; one JSON line per point with the
+    scheduler time (Alg. 1, one launch), a_max of AEBS on the GPU, the exact optimum and the
+    static home-replica policy from the CPU oracle."""
+    import numpy as np
+    import torch
+    from oracle import optimum, scheduling
+    from paper_2512_13525_amd import binding as B
+    from paper_2512_13525_amd import workloads as W
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    from helpers import oracle_route
+
+    for r in (1.0, 1.125, 1.25):
+        for s in (0.0, 0.8, 1.5):
+            for T in (64, 128, 256, 512, 1024, 2048, 4096, 8192):
+                cfg = W.stress(T, r, s)
+                lay = W.build_placement(cfg)
+                pl = B.Placement(lay, cfg.E, cfg.n_inst, cfg.C)
+                logits = W.router_logits(cfg)
+                d_logits = torch.from_numpy(logits).cuda()
+                ids = torch.empty((T, cfg.k), dtype=torch.int32, device="cuda")
+                w = torch.empty((T, cfg.k), dtype=torch.float32, device="cuda")
+                rid = torch.empty((T, cfg.k), dtype=torch.int32, device="cuda")
+                rep = torch.empty((cfg.E,), dtype=torch.int32, device="cuda")
+                load = torch.empty((cfg.n_inst,), dtype=torch.int32, device="cuda")
+                B.moe_route(d_logits, cfg.k, ids, w)
+                us = _time_us(lambda: B.moe_schedule(pl, ids, T, cfg.k, rid, rep, load), 200)
+                route_us = _time_us(lambda: B.moe_route(d_logits, cfg.k, ids, w), 200)
+                a_max = int(load.max().item())
+                o_ids, _, _ = oracle_route(cfg, logits)
+                opl = scheduling.make_placement(lay, cfg.E, cfg.n_inst, cfg.C)
+                act = sorted(set(o_ids.reshape(-1).tolist()))
+                opt = optimum.optimum_matching(act, opl)
+                home = int(scheduling.loads_of(scheduling.home_only(o_ids, opl), opl).max())
+                print(json.dumps({"mode": "sched", "T": T, "replication": r, "zipf_s": s, "sched_us": round(us, 2),
+                                  "route_us": round(route_us, 2), "activated": len(act), "a_max_aebs": a_max,
+                                  "a_max_optimum": opt, "a_max_home_only": home}), flush=True)
+
+
+def act_sweep(args) -> None:
+    """Layer time (permute + FFN + combine) against the number of activated experts at a fixed
+    batch (the paper's microbenchmark of Sec. 2.2: batch 64, requests spread evenly over exactly
+    `a` experts of the instance); fits t = beta*a + c_e (Eq. 1c)."""
+    import numpy as np
+    import torch
+    from paper_2512_13525_amd import workloads as W
+    from paper_2512_13525_amd.layer import LayerStep, to_device_bf16
+
+    cfg = make_cfg(args.workload, args.tokens or 64)
+    lay = W.build_placement(cfg)
+    T, k, C, d_h, d_e = cfg.T, cfg.k, cfg.C, cfg.d_h, cfg.d_e
+    step = LayerStep(cfg, lay, 0)
+    per_copy = C * 3 * d_h * d_e * 2
+    n_ring = max(4, int(-(-args.ring_bytes // per_copy)))
+    gen = torch.Generator(device="cuda").manual_seed(1)
+    W13s = [(torch.randn((C, 2 * d_e, d_h), generator=gen, device="cuda") * 0.02).to(torch.bfloat16) for _ in range(n_ring)]
+    W2s = [(torch.randn((C, d_h, d_e), generator=gen, device="cuda") * 0.02).to(torch.bfloat16) for _ in range(n_ring)]
+    X = to_device_bf16(W.activations(cfg))
+    step.topk_w.fill_(1.0 / k)
+    pts = []
+    for a in range(1, C + 1):
+        # every request goes to one of the first `a` local slots of instance 0, round-robin
+        rid = (np.arange(T * k, dtype=np.int32) % a).reshape(T, k)
+        step.rid.copy_(torch.from_numpy(rid))
+        i = [0]
+
+        def layer():
+            j = i[0] % n_ring
+            i[0] += 1
+            step.permute()
+            step.ffn(X, W13=W13s[j], W2=W2s[j])
+            step.combine()
+
+        def ffn_only():
+            j = i[0] % n_ring
+            i[0] += 1
+            step.ffn(X, W13=W13s[j], W2=W2s[j])
+
+        us = _time_us(layer, 100)
+        ffn_us = _time_us(ffn_only, 100)
+        gbps = a * 3 * d_h * d_e * 2 / (ffn_us * 1e-6) / 1e9
+        pts.append((a, us))
+        print(json.dumps({"mode": "act_sweep", "workload": cfg.name, "T": T, "activated": a, "layer_us": round(us, 2),
+                          "ffn_us": round(ffn_us, 2), "ffn_weight_GBps": round(gbps, 1),
+                          "pct_hbm_peak": round(100 * gbps / HBM_PEAK_GBPS, 1)}), flush=True)
+    xs = np.array([p[0] for p in pts], dtype=np.float64)
+    ys = np.array([p[1] for p in pts], dtype=np.float64)
+    beta, c_e = np.polyfit(xs, ys, 1)
+    print(json.dumps({"mode": "act_sweep_fit", "workload": cfg.name, "beta_us_per_expert": round(float(beta), 3),
+                      "c_e_us": round(float(c_e), 3),
+                      "beta_at_hbm_peak_us": round(3 * d_h * d_e * 2 / (HBM_PEAK_GBPS * 1e3), 3)}), flush=True)
 
 
 if __name__ == "__main__":

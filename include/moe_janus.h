@@ -140,6 +140,19 @@ int moe_permute(const moe_placement_t *pl, int g_self, const int32_t *rid_dev, i
                 int32_t *slot_count_dev, int32_t *slot_off_dev, int32_t *perm_dev,
                 int32_t *pos_dev, void *stream);
 
+/* ------------------------------------------------------------------ a0-a4 in one launch
+ * Same results, bit for bit, as moe_route + moe_schedule + moe_permute called one after the
+ * other with the same arguments (E is the placement's).  At decode sizes each of those steps is a
+ * few microseconds of work behind a launch of similar cost; this entry point pays one launch.
+ * sync_dev: one int32 of device memory, zero before the first call; every call leaves it zero.
+ * Calls that share sync_dev must not overlap in time.
+ */
+int moe_route_schedule_permute(const moe_placement_t *pl, int g_self, const float *logits_dev, int T, int k,
+                               const moe_route_cfg *cfg, int32_t *topk_ids_dev, float *topk_w_dev,
+                               int32_t *rid_dev, int32_t *act_rep_dev, int32_t *load_dev,
+                               int32_t *slot_count_dev, int32_t *slot_off_dev, int32_t *perm_dev,
+                               int32_t *pos_dev, int32_t *sync_dev, void *stream);
+
 /* ------------------------------------------------------------------ expert weights
  * Canonical layout of one instance's physical experts (what a checkpoint holds):
  *   W13 [C, 2*d_e, d_h]  rows 0..d_e-1 = gate projection, rows d_e..2*d_e-1 = up projection

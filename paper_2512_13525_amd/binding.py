@@ -22,7 +22,7 @@ MOE_ROUTE_SOFTMAX, MOE_ROUTE_SIGMOID_GROUP = 0, 1
 EXPORTS = [
     "moe_strerror", "moe_last_error",
     "moe_placement_create", "moe_placement_destroy", "moe_placement_replicas", "moe_placement_dims",
-    "moe_route", "moe_schedule", "moe_permute", "moe_pack_weights_bf16",
+    "moe_route", "moe_schedule", "moe_permute", "moe_route_schedule_permute", "moe_pack_weights_bf16",
     "moe_workspace_bytes", "moe_workspace_init", "moe_workspace_status", "moe_grouped_ffn", "moe_combine",
 ]
 
@@ -69,6 +69,8 @@ def lib() -> ctypes.CDLL:
     L.moe_schedule.argtypes = [vp, vp, ci, ci, vp, vp, vp, vp]
     L.moe_permute.restype = ci
     L.moe_permute.argtypes = [vp, ci, vp, ci, ci, vp, vp, vp, vp, vp]
+    L.moe_route_schedule_permute.restype = ci
+    L.moe_route_schedule_permute.argtypes = [vp, ci, vp, ci, ci, ctypes.POINTER(moe_route_cfg)] + [vp] * 11
     L.moe_pack_weights_bf16.restype = ci
     L.moe_pack_weights_bf16.argtypes = [vp, vp, ci, ci, ci, vp, vp, vp]
     L.moe_workspace_bytes.restype = cs
@@ -155,6 +157,18 @@ def moe_permute(pl: Placement, g_self: int, rid, T: int, k: int, slot_count, slo
                 stream=None) -> None:
     _check(lib().moe_permute(pl.handle, g_self, _ptr(rid), T, k, _ptr(slot_count), _ptr(slot_off),
                              _ptr(perm), _ptr(pos), _stream(stream)), "moe_permute")
+
+
+def moe_route_schedule_permute(pl: Placement, g_self: int, logits, k: int, topk_ids, topk_w, rid, act_rep, load,
+                               slot_count, slot_off, perm, pos, sync, mode: int = MOE_ROUTE_SOFTMAX,
+                               renormalize: bool = True, n_group: int = 1, topk_group: int = 1, scale: float = 1.0,
+                               stream=None) -> None:
+    T = logits.shape[0]
+    cfg = moe_route_cfg(mode, int(renormalize), n_group, topk_group, scale)
+    _check(lib().moe_route_schedule_permute(pl.handle, g_self, _ptr(logits), T, k, ctypes.byref(cfg),
+                                            _ptr(topk_ids), _ptr(topk_w), _ptr(rid), _ptr(act_rep), _ptr(load),
+                                            _ptr(slot_count), _ptr(slot_off), _ptr(perm), _ptr(pos), _ptr(sync),
+                                            _stream(stream)), "moe_route_schedule_permute")
 
 
 def moe_pack_weights_bf16(W13, W2, C: int, d_h: int, d_e: int, W13_packed, W2_packed, stream=None) -> None:

@@ -1,0 +1,400 @@
+// Device-side building blocks of a0-a4 (gating selection, Alg. 1, dispatch), shared by the
+// stand-alone kernels of moe_route / moe_schedule / moe_permute and by the fused front kernel.
+// Each block-level function is written for one workgroup of kFrontThreads threads.
+#pragma once
+
+#include "common.h"
+
+namespace moe {
+
+constexpr int kFrontThreads = 1024;
+constexpr int kFrontWaves = kFrontThreads / MOE_WAVE;
+
+// ------------------------------------------------------------------ a0: one token per wavefront
+__device__ __forceinline__ uint64_t wave_max_u64(uint64_t v) {
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        uint64_t o = __shfl_xor(v, off, MOE_WAVE);
+        v = o > v ? o : v;
+    }
+    return v;
+}
+
+__device__ __forceinline__ float wave_sum_f32(float v) {
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, MOE_WAVE);
+    return v;
+}
+
+__device__ __forceinline__ uint32_t orderable(float f) {
+    uint32_t u = __float_as_uint(f + 0.0f);            // -0.0 -> +0.0
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+__device__ __forceinline__ float from_orderable(uint32_t o) {
+    uint32_t u = (o & 0x80000000u) ? (o & 0x7fffffffu) : ~o;
+    return __uint_as_float(u);
+}
+
+__device__ __forceinline__ uint64_t make_key(float v, int id) {
+    return (static_cast<uint64_t>(orderable(v)) << 32) | static_cast<uint32_t>(0x7fffffff - id);
+}
+
+__device__ __forceinline__ float sigmoid_f32(float x) { return 1.0f / (1.0f + expf(-x)); }
+
+// Lane l owns experts l, l+64, ...; every logit becomes a 64-bit key (order-preserving float bits
+// in the high word, ~id in the low word) so that "largest logit, lower id on ties" is an unsigned
+// maximum found with a 6-step cross-lane butterfly; k selections are k such reductions.
+// row_lds: VPL*64 floats private to this wavefront.  COHERENT: results are written with agent-scope
+// stores (read by another workgroup of the same launch).
+template <int VPL, bool COHERENT>
+__device__ __forceinline__ void route_token(const float *__restrict__ row, int E, int k, const moe_route_cfg &cfg,
+                                            float *row_lds, int lane, int32_t *ids_out, float *w_out) {
+    float v[VPL];
+    uint64_t key[VPL];
+#pragma unroll
+    for (int i = 0; i < VPL; ++i) {
+        const int e = lane + i * MOE_WAVE;
+        v[i] = e < E ? row[e] : 0.0f;
+        key[i] = e < E ? make_key(v[i], e) : 0ull;
+    }
+
+    float denom_all = 0.0f;                              // softmax denominator over all experts
+    if (cfg.mode == MOE_ROUTE_SIGMOID_GROUP) {
+        // group score = sum of the two largest sigmoid scores of the group, in fp32
+        const int per = E / cfg.n_group;
+#pragma unroll
+        for (int i = 0; i < VPL; ++i) row_lds[lane + i * MOE_WAVE] = v[i];
+        // the row is private to this wave: a wavefront-scope fence orders its LDS writes
+        // before the reads below (no block barrier: waves may be on different tokens)
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        uint64_t gkey = 0ull;
+        if (lane < cfg.n_group) {
+            float a = -INFINITY, b = -INFINITY;          // a >= b: two largest logits of the group
+            for (int j = 0; j < per; ++j) {
+                const float x = row_lds[lane * per + j];
+                if (x > a) { b = a; a = x; }
+                else if (x > b) { b = x; }
+            }
+            const float score = sigmoid_f32(a) + sigmoid_f32(b);
+            gkey = make_key(score, lane);
+        }
+        uint64_t keep = 0ull;
+        for (int j = 0; j < cfg.topk_group; ++j) {
+            const uint64_t best = wave_max_u64(gkey);
+            const int g = 0x7fffffff - static_cast<int>(best & 0xffffffffu);
+            keep |= 1ull << g;
+            if (lane == g) gkey = 0ull;
+        }
+#pragma unroll
+        for (int i = 0; i < VPL; ++i) {
+            const int e = lane + i * MOE_WAVE;
+            if (e < E && !((keep >> (e / per)) & 1ull)) key[i] = 0ull;
+        }
+        __builtin_amdgcn_wave_barrier();                 // row_lds is reused by this wave's next token
+    } else if (!cfg.renormalize) {
+        uint64_t m = 0ull;
+#pragma unroll
+        for (int i = 0; i < VPL; ++i) m = key[i] > m ? key[i] : m;
+        const float vmax = from_orderable(static_cast<uint32_t>(wave_max_u64(m) >> 32));
+        float s = 0.0f;
+#pragma unroll
+        for (int i = 0; i < VPL; ++i)
+            if (lane + i * MOE_WAVE < E) s += expf(v[i] - vmax);
+        denom_all = wave_sum_f32(s);
+    }
+
+    // k rounds of "largest remaining"
+    float sel_v = 0.0f;            // lane j keeps the j-th selected logit
+    int sel_id = 0;
+    float vmax = 0.0f;
+    for (int j = 0; j < k; ++j) {
+        uint64_t m = 0ull;
+#pragma unroll
+        for (int i = 0; i < VPL; ++i) m = key[i] > m ? key[i] : m;
+        const uint64_t best = wave_max_u64(m);
+        const int id = 0x7fffffff - static_cast<int>(best & 0xffffffffu);
+        const float val = from_orderable(static_cast<uint32_t>(best >> 32));
+        if (j == 0) vmax = val;
+        if (lane == j) { sel_v = val; sel_id = id; }
+#pragma unroll
+        for (int i = 0; i < VPL; ++i)
+            if (lane + i * MOE_WAVE == id) key[i] = 0ull;
+    }
+
+    // weights of the k selected experts (lanes 0..k-1)
+    float score = 0.0f;
+    if (lane < k) {
+        score = cfg.mode == MOE_ROUTE_SIGMOID_GROUP ? sigmoid_f32(sel_v) : expf(sel_v - vmax);
+    }
+    const float denom_sel = wave_sum_f32(score);
+    if (lane < k) {
+        float w;
+        if (cfg.mode == MOE_ROUTE_SIGMOID_GROUP) w = score / denom_sel * cfg.scale;
+        else if (cfg.renormalize) w = score / denom_sel;
+        else w = score / denom_all;
+        if (COHERENT) {
+            __hip_atomic_store(ids_out + lane, sel_id, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        } else {
+            ids_out[lane] = sel_id;
+        }
+        w_out[lane] = w;
+    }
+}
+
+// ------------------------------------------------------------------ a1-a3: Alg. 1 in one workgroup
+struct SchedTables {
+    const uint64_t *host_mask;     // [E]
+    const int16_t  *slot_of;       // [E*n_inst]
+    const int32_t  *single_rid;    // [E]
+    const uint64_t *multi_mask;    // [n_words]
+    const uint64_t *single_mask;   // [n_inst*n_words]
+};
+
+struct SchedShared {
+    uint32_t flag[MOE_MAX_EXPERTS];
+    int32_t rep[MOE_MAX_EXPERTS];
+    uint64_t host_mask[MOE_MAX_EXPERTS];
+    int32_t single_rid[MOE_MAX_EXPERTS];
+    uint64_t multi_mask[MOE_MAX_EXPERTS / 64];
+    uint64_t single_mask[MOE_MAX_INSTANCES * (MOE_MAX_EXPERTS / 64)];
+};
+
+__device__ __forceinline__ uint64_t readlane_u64(uint64_t v, int l) {
+    const uint32_t lo = __builtin_amdgcn_readlane(static_cast<int>(v & 0xffffffffu), l);
+    const uint32_t hi = __builtin_amdgcn_readlane(static_cast<int>(v >> 32), l);
+    return (static_cast<uint64_t>(hi) << 32) | lo;
+}
+
+__device__ __forceinline__ uint64_t readfirstlane_u64(uint64_t v) {
+    const uint32_t lo = __builtin_amdgcn_readfirstlane(static_cast<int>(v & 0xffffffffu));
+    const uint32_t hi = __builtin_amdgcn_readfirstlane(static_cast<int>(v >> 32));
+    return (static_cast<uint64_t>(hi) << 32) | lo;
+}
+
+// 16-byte agent-scope (L2-coherent across XCDs) load of four request ids
+__device__ __forceinline__ int4 load_ids4(const int4 *p, bool coherent) {
+    if (coherent) {
+        int4 v;
+        asm volatile("global_load_dwordx4 %0, %1, off sc1\n\ts_waitcnt vmcnt(0)" : "=v"(v) : "v"(p) : "memory");
+        return v;
+    }
+    return *p;
+}
+
+__device__ __forceinline__ int load_id(const int32_t *p, bool coherent) {
+    return coherent ? __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : *p;
+}
+
+// One workgroup runs the whole algorithm, so the three steps need no grid-wide synchronisation
+// and the schedule is a pure function of (layout, activated set):
+//   Step 1 (collect)  every thread scans a strided share of the request ids and raises a flag per
+//                     expert in LDS (all writers store the same value);
+//   Step 2 (select)   one wavefront turns the flags into 64-bit ballots.  Loads of single-replica
+//                     experts are popcounts of (ballot & per-instance mask); lane g holds load[g]
+//                     in a register.  Multi-replica experts are walked in ascending id by peeling
+//                     bits off (ballot & multi-replica mask); the arg-min over the expert's hosts
+//                     reads the candidate lanes' loads with scalar-indexed lane reads, so one greedy
+//                     step costs a few scalar instructions per host;
+//   Step 3 (rewrite)  every thread maps its share of requests through actRep held in LDS.
+// The layout tables are staged into LDS first.  ids_coherent: the ids were written by other
+// workgroups of the same launch.
+__device__ __forceinline__ void aebs_block(const SchedTables &tb, SchedShared &sh, int E, int n_inst, int C,
+                                           int n_words, const int32_t *__restrict__ ids, int n_pairs, int vec_ok,
+                                           bool ids_coherent, int32_t *__restrict__ rid,
+                                           int32_t *__restrict__ act_rep, int32_t *__restrict__ load_out) {
+    const int tid = threadIdx.x;
+    for (int e = tid; e < E; e += kFrontThreads) {
+        sh.flag[e] = 0u;
+        sh.host_mask[e] = tb.host_mask[e];
+        sh.single_rid[e] = tb.single_rid[e];
+    }
+    for (int i = tid; i < n_words; i += kFrontThreads) sh.multi_mask[i] = tb.multi_mask[i];
+    for (int i = tid; i < n_inst * n_words; i += kFrontThreads) sh.single_mask[i] = tb.single_mask[i];
+    __syncthreads();
+
+    // ---- Step 1: collect the activated experts
+    if (vec_ok) {
+        const int n4 = n_pairs >> 2;
+        const int4 *ids4 = reinterpret_cast<const int4 *>(ids);
+        for (int i = tid; i < n4; i += kFrontThreads) {
+            const int4 v = load_ids4(ids4 + i, ids_coherent);
+            sh.flag[v.x] = 1u; sh.flag[v.y] = 1u; sh.flag[v.z] = 1u; sh.flag[v.w] = 1u;
+        }
+        for (int i = (n4 << 2) + tid; i < n_pairs; i += kFrontThreads) sh.flag[load_id(ids + i, ids_coherent)] = 1u;
+    } else {
+        for (int i = tid; i < n_pairs; i += kFrontThreads) sh.flag[load_id(ids + i, ids_coherent)] = 1u;
+    }
+    __syncthreads();
+
+    // ---- Step 2: select one replica per activated expert (first wavefront)
+    if (tid < MOE_WAVE) {
+        const int lane = tid;
+        int load = 0;                                   // lane g: load[g]
+        for (int w = 0; w < n_words; ++w) {
+            const int e = w * 64 + lane;
+            const uint64_t act = __ballot(e < E && sh.flag[e] != 0u);
+            if (lane < n_inst) load += __popcll(act & sh.single_mask[lane * n_words + w]);
+        }
+        for (int w = 0; w < n_words; ++w) {
+            const int e = w * 64 + lane;
+            const uint64_t act = __ballot(e < E && sh.flag[e] != 0u);
+            const uint64_t hm = e < E ? sh.host_mask[e] : 0ull;
+            uint64_t todo = act & readfirstlane_u64(sh.multi_mask[w]);   // wave-uniform: keep the loop scalar
+            int chosen = -1;                            // lane b: instance chosen for expert w*64+b
+            while (todo) {
+                const int b = __builtin_ctzll(todo);
+                todo &= todo - 1;
+                uint64_t hosts = readlane_u64(hm, b);
+                int best_g = __builtin_ctzll(hosts);
+                int best_load = __builtin_amdgcn_readlane(load, best_g);
+                hosts &= hosts - 1;
+                while (hosts) {                         // ascending instance id: strict '<' keeps the lowest on ties
+                    const int h = __builtin_ctzll(hosts);
+                    hosts &= hosts - 1;
+                    const int l = __builtin_amdgcn_readlane(load, h);
+                    if (l < best_load) { best_load = l; best_g = h; }
+                }
+                if (lane == best_g) load += 1;
+                if (lane == b) chosen = best_g;
+            }
+            if (e < E) {
+                int rep = -1;
+                if ((act >> lane) & 1ull) {
+                    if (chosen >= 0) rep = chosen * C + tb.slot_of[e * n_inst + chosen];
+                    else rep = sh.single_rid[e];
+                }
+                sh.rep[e] = rep;
+                act_rep[e] = rep;
+            }
+        }
+        if (lane < n_inst) load_out[lane] = load;
+    }
+    __syncthreads();
+
+    // ---- Step 3: rewrite every request
+    if (vec_ok) {
+        const int n4 = n_pairs >> 2;
+        const int4 *ids4 = reinterpret_cast<const int4 *>(ids);
+        int4 *rid4 = reinterpret_cast<int4 *>(rid);
+        for (int i = tid; i < n4; i += kFrontThreads) {
+            const int4 v = load_ids4(ids4 + i, ids_coherent);
+            int4 r;
+            r.x = sh.rep[v.x]; r.y = sh.rep[v.y]; r.z = sh.rep[v.z]; r.w = sh.rep[v.w];
+            rid4[i] = r;
+        }
+        for (int i = (n4 << 2) + tid; i < n_pairs; i += kFrontThreads) rid[i] = sh.rep[load_id(ids + i, ids_coherent)];
+    } else {
+        for (int i = tid; i < n_pairs; i += kFrontThreads) rid[i] = sh.rep[load_id(ids + i, ids_coherent)];
+    }
+}
+
+// ------------------------------------------------------------------ a4: dispatch in one workgroup
+struct PermShared {
+    int cnt[kFrontWaves][MOE_MAX_SLOTS];     // pass A: counts; pass B: running bases
+    int total[MOE_MAX_SLOTS];
+    int off[MOE_MAX_SLOTS + 1];
+};
+
+// A stable counting sort of the local requests by slot.  Each wavefront owns a contiguous range of
+// request ids, so "ascending request id inside a slot" follows from (wave order, group order, lane
+// order) and never from the arrival order of atomics:
+//   pass A  per-(wave, slot) histograms in LDS;
+//   scan    per-slot exclusive prefix over waves, then an exclusive scan over slots;
+//   pass B  each wave walks its range again; the lanes of a 64-request group that share a slot are
+//           found with a ballot, ranked with a popcount of the lower lanes, and written at the
+//           wave's running base for that slot.
+__device__ __forceinline__ void permute_block(PermShared &sh, const int32_t *__restrict__ rid, int n_pairs,
+                                              int g_self, int C, int32_t *__restrict__ slot_count,
+                                              int32_t *__restrict__ slot_off, int32_t *__restrict__ perm,
+                                              int32_t *__restrict__ pos) {
+    const int tid = threadIdx.x;
+    const int wave = tid / MOE_WAVE;
+    const int lane = tid % MOE_WAVE;
+    for (int i = tid; i < kFrontWaves * MOE_MAX_SLOTS; i += kFrontThreads) (&sh.cnt[0][0])[i] = 0;
+    __syncthreads();
+
+    const int n_groups = (n_pairs + MOE_WAVE - 1) / MOE_WAVE;
+    const int gpw = (n_groups + kFrontWaves - 1) / kFrontWaves;
+    const int g_begin = wave * gpw;
+    const int g_end = min(n_groups, g_begin + gpw);
+    const int rid_lo = g_self * C;
+
+    // ---- pass A
+    for (int grp = g_begin; grp < g_end; ++grp) {
+        const int p = grp * MOE_WAVE + lane;
+        const int s = (p < n_pairs ? rid[p] : -1) - rid_lo;
+        if (p < n_pairs && s >= 0 && s < C) atomicAdd(&sh.cnt[wave][s], 1);
+    }
+    __syncthreads();
+
+    // ---- per-slot exclusive prefix over waves
+    for (int s = tid; s < C; s += kFrontThreads) {
+        int run = 0;
+#pragma unroll
+        for (int w = 0; w < kFrontWaves; ++w) {
+            const int c = sh.cnt[w][s];
+            sh.cnt[w][s] = run;
+            run += c;
+        }
+        sh.total[s] = run;
+        slot_count[s] = run;
+    }
+    __syncthreads();
+
+    // ---- exclusive scan over slots (first wavefront, 64 slots per round)
+    if (wave == 0) {
+        int carry = 0;
+        for (int s0 = 0; s0 < C; s0 += MOE_WAVE) {
+            const int s = s0 + lane;
+            const int v = s < C ? sh.total[s] : 0;
+            int incl = v;
+#pragma unroll
+            for (int d = 1; d < MOE_WAVE; d <<= 1) {
+                const int o = __shfl_up(incl, d, MOE_WAVE);
+                if (lane >= d) incl += o;
+            }
+            if (s < C) {
+                sh.off[s] = carry + incl - v;
+                slot_off[s] = carry + incl - v;
+            }
+            carry += __shfl(incl, MOE_WAVE - 1, MOE_WAVE);
+        }
+        if (lane == 0) {
+            sh.off[C] = carry;
+            slot_off[C] = carry;
+        }
+    }
+    __syncthreads();
+
+    // ---- pass B
+    volatile int *base = &sh.cnt[wave][0];
+    for (int grp = g_begin; grp < g_end; ++grp) {
+        const int p = grp * MOE_WAVE + lane;
+        const int s = (p < n_pairs ? rid[p] : -1) - rid_lo;
+        const bool local = p < n_pairs && s >= 0 && s < C;
+        int row = -1;
+        uint64_t todo = __ballot(local);
+        while (todo) {
+            const int lead = __builtin_ctzll(todo);
+            const int s0 = __builtin_amdgcn_readlane(s, lead);
+            const uint64_t same = __ballot(local && s == s0);
+            const int b = base[s0] + sh.off[s0];
+            if (local && s == s0) row = b + __popcll(same & lanemask_lt());
+            __builtin_amdgcn_wave_barrier();
+            if (lane == lead) base[s0] += __popcll(same);
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            todo &= ~same;
+        }
+        if (p < n_pairs) {
+            pos[p] = row;
+            if (local) perm[row] = p;
+        }
+    }
+}
+
+}  // namespace moe

@@ -16,7 +16,7 @@
 //
 // Work decomposition.  Nothing about the activated set is known on the host, so every
 // workgroup first compacts the activated slots from slot_off.  The work of a stage is the
-// flat sequence  slot -> pass (32 tokens) -> unit -> quad (4 K-steps, one per wavefront);
+// flat sequence  slot -> unit -> pass (32 tokens) -> quad (4 K-steps, one per wavefront);
 // it is cut into gridDim equal ranges of quads, one per persistent workgroup, whatever the
 // number of activated experts (a perfectly balanced split: the layer's latency then follows
 // the activated-expert count down to a single expert).  A workgroup's 4 wavefronts take the
@@ -460,13 +460,16 @@ __device__ __forceinline__ void ffn_stage(const FfnArgs &a, FfnShared &sh, int w
     int j = 0;
     auto describe = [&](long long at) {
         while (sh.pre[j + 1] * per_pass <= at) ++j;
-        const long long rel = at - sh.pre[j] * per_pass;
+        // inside a slot: group -> pass -> quad, so that the passes of a group (more than 32 tokens
+        // on one expert) re-read its weights back to back, from L2 rather than from HBM
+        const int rel = static_cast<int>(at - sh.pre[j] * per_pass);
+        const int per_group = (sh.pre[j + 1] - sh.pre[j]) * QU;
         SegDesc d;
         d.j = j;
-        d.pass = static_cast<int>(rel / per_pass);
-        const int rel2 = static_cast<int>(rel - d.pass * per_pass);
-        d.g_idx = rel2 / QU;
-        d.qa = rel2 - d.g_idx * QU;
+        d.g_idx = rel / per_group;
+        const int rel2 = rel - d.g_idx * per_group;
+        d.pass = rel2 / QU;
+        d.qa = rel2 - d.pass * QU;
         d.qb = static_cast<int>(min(static_cast<long long>(QU), d.qa + (q_hi - at)));
         d.u0 = at - d.qa;
         return d;

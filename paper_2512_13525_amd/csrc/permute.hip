@@ -1,116 +1,18 @@
 // a4: this instance's share of the dispatch (Janus Sec. 3.4, Step 4) and
 // a6: the weighted top-k combine that produces the instance-partial output entering the
-// reverse-path reduction (Sec. 3.3).
-//
-// permute: a stable counting sort of the local requests by slot, one workgroup of 16
-// wavefronts.  Each wavefront owns a contiguous range of request ids, so "ascending request
-// id inside a slot" follows from (wave order, group order, lane order) and never from the
-// arrival order of atomics:
-//   pass A  per-(wave, slot) histograms in LDS;
-//   scan    per-slot exclusive prefix over waves, then an exclusive scan over slots;
-//   pass B  each wave walks its range again; the lanes of a 64-request group that share a
-//           slot are found with a ballot, ranked with a popcount of the lower lanes, and
-//           written at the wave's running base for that slot.
-#include "common.h"
+// reverse-path reduction (Sec. 3.3).  The counting sort lives in dispatch_dev.h (permute_block).
+#include "dispatch_dev.h"
 
 namespace {
 
-constexpr int kPermThreads = 1024;
-constexpr int kPermWaves = kPermThreads / MOE_WAVE;
+constexpr int kPermThreads = moe::kFrontThreads;
 
 __global__ __launch_bounds__(kPermThreads)
 void permute_kernel(const int32_t *__restrict__ rid, int n_pairs, int g_self, int C,
                     int32_t *__restrict__ slot_count, int32_t *__restrict__ slot_off,
                     int32_t *__restrict__ perm, int32_t *__restrict__ pos) {
-    __shared__ int cnt[kPermWaves][MOE_MAX_SLOTS];     // pass A: counts; pass B: running bases
-    __shared__ int total[MOE_MAX_SLOTS];
-    __shared__ int off_lds[MOE_MAX_SLOTS + 1];
-
-    const int tid = threadIdx.x;
-    const int wave = tid / MOE_WAVE;
-    const int lane = tid % MOE_WAVE;
-    for (int i = tid; i < kPermWaves * MOE_MAX_SLOTS; i += kPermThreads) (&cnt[0][0])[i] = 0;
-    __syncthreads();
-
-    const int n_groups = (n_pairs + MOE_WAVE - 1) / MOE_WAVE;
-    const int gpw = (n_groups + kPermWaves - 1) / kPermWaves;
-    const int g_begin = wave * gpw;
-    const int g_end = min(n_groups, g_begin + gpw);
-    const int rid_lo = g_self * C;
-
-    // ---- pass A
-    for (int grp = g_begin; grp < g_end; ++grp) {
-        const int p = grp * MOE_WAVE + lane;
-        const int s = (p < n_pairs ? rid[p] : -1) - rid_lo;
-        if (p < n_pairs && s >= 0 && s < C) atomicAdd(&cnt[wave][s], 1);
-    }
-    __syncthreads();
-
-    // ---- per-slot exclusive prefix over waves
-    for (int s = tid; s < C; s += kPermThreads) {
-        int run = 0;
-#pragma unroll
-        for (int w = 0; w < kPermWaves; ++w) {
-            const int c = cnt[w][s];
-            cnt[w][s] = run;
-            run += c;
-        }
-        total[s] = run;
-        slot_count[s] = run;
-    }
-    __syncthreads();
-
-    // ---- exclusive scan over slots (first wavefront, 64 slots per round)
-    if (wave == 0) {
-        int carry = 0;
-        for (int s0 = 0; s0 < C; s0 += MOE_WAVE) {
-            const int s = s0 + lane;
-            const int v = s < C ? total[s] : 0;
-            int incl = v;
-#pragma unroll
-            for (int d = 1; d < MOE_WAVE; d <<= 1) {
-                const int o = __shfl_up(incl, d, MOE_WAVE);
-                if (lane >= d) incl += o;
-            }
-            if (s < C) {
-                off_lds[s] = carry + incl - v;
-                slot_off[s] = carry + incl - v;
-            }
-            carry += __shfl(incl, MOE_WAVE - 1, MOE_WAVE);
-        }
-        if (lane == 0) {
-            off_lds[C] = carry;
-            slot_off[C] = carry;
-        }
-    }
-    __syncthreads();
-
-    // ---- pass B
-    volatile int *base = &cnt[wave][0];
-    for (int grp = g_begin; grp < g_end; ++grp) {
-        const int p = grp * MOE_WAVE + lane;
-        const int s = (p < n_pairs ? rid[p] : -1) - rid_lo;
-        const bool local = p < n_pairs && s >= 0 && s < C;
-        int row = -1;
-        uint64_t todo = __ballot(local);
-        while (todo) {
-            const int lead = __builtin_ctzll(todo);
-            const int s0 = __builtin_amdgcn_readlane(s, lead);
-            const uint64_t same = __ballot(local && s == s0);
-            const int b = base[s0] + off_lds[s0];
-            if (local && s == s0) row = b + __popcll(same & moe::lanemask_lt());
-            __builtin_amdgcn_wave_barrier();
-            if (lane == lead) base[s0] += __popcll(same);
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-            todo &= ~same;
-        }
-        if (p < n_pairs) {
-            pos[p] = row;
-            if (local) perm[row] = p;
-        }
-    }
+    __shared__ moe::PermShared sh;
+    moe::permute_block(sh, rid, n_pairs, g_self, C, slot_count, slot_off, perm, pos);
 }
 
 // One workgroup per (token, 1024-column chunk); each thread owns 4 consecutive columns.

@@ -42,6 +42,7 @@ class LayerStep:
         ws = B.moe_workspace_bytes(T, k, C, cfg.d_h, cfg.d_e, self.dtype)
         self.workspace = torch.empty((ws,), dtype=torch.uint8, device=device)
         B.moe_workspace_init(self.workspace)
+        self.sync = torch.zeros((64,), **i32)
         self.W13 = None
         self.W2 = None
 
@@ -77,6 +78,15 @@ class LayerStep:
         B.moe_permute(self.pl, self.g_self, self.rid, c.T, c.k, self.slot_count, self.slot_off,
                       self.perm, self.pos, stream=stream)
 
+    def front(self, logits, stream=None):
+        """route + schedule + permute in one launch."""
+        c = self.cfg
+        group = c.route != "softmax"
+        B.moe_route_schedule_permute(self.pl, self.g_self, logits, c.k, self.topk_ids, self.topk_w, self.rid,
+                                     self.act_rep, self.load, self.slot_count, self.slot_off, self.perm, self.pos,
+                                     self.sync, B.MOE_ROUTE_SIGMOID_GROUP if group else B.MOE_ROUTE_SOFTMAX, True,
+                                     c.n_group if group else 1, c.topk_group if group else 1, 1.0, stream=stream)
+
     def ffn(self, X, stream=None, W13=None, W2=None):
         c = self.cfg
         B.moe_grouped_ffn(X, self.W13 if W13 is None else W13, self.W2 if W2 is None else W2,
@@ -88,9 +98,17 @@ class LayerStep:
         B.moe_combine(self.Yp, self.pos, self.topk_w, c.T, c.k, c.d_h, self.dtype, self.Y, stream=stream)
 
     def step(self, logits, X, stream=None, W13=None, W2=None):
+        """The layer step through the four separate entry points (five launches)."""
         self.route(logits, stream)
         self.schedule(stream)
         self.permute(stream)
+        self.ffn(X, stream, W13, W2)
+        self.combine(stream)
+        return self.Y
+
+    def step_fused(self, logits, X, stream=None, W13=None, W2=None):
+        """The same step in three launches: front (a0-a4), FFN, combine."""
+        self.front(logits, stream)
         self.ffn(X, stream, W13, W2)
         self.combine(stream)
         return self.Y

@@ -207,6 +207,27 @@ def test_layer_parity(cfg):
     assert B.moe_workspace_status(step.workspace) == 0
 
 
+@pytest.mark.parametrize("cfg", [W.tiny(), W.dsv2lite(), W.qwen3(1024), W.dsv3(512), small("ragged", k=5, T=77),
+                                 W.stress(8192, 1.25, 0.8), small("k1", k=1, T=1)], ids=lambda c: f"{c.name}-T{c.T}")
+def test_fused_front_equals_separate_calls(cfg):
+    """moe_route_schedule_permute gives the bits of the three separate calls, call after call."""
+    lay = W.build_placement(cfg)
+    logits = torch.from_numpy(W.router_logits(cfg)).cuda()
+    a = LayerStep(cfg, lay, cfg.n_inst - 1)
+    b = LayerStep(cfg, lay, cfg.n_inst - 1)
+    a.route(logits); a.schedule(); a.permute()
+    for rep in range(3):
+        for t in (b.topk_ids, b.rid, b.act_rep, b.load, b.slot_count, b.slot_off, b.perm, b.pos):
+            t.fill_(-5)
+        b.front(logits)
+        torch.cuda.synchronize()
+        n_local = int(a.slot_off[-1].item())
+        for name in ("topk_ids", "topk_w", "rid", "act_rep", "load", "slot_count", "slot_off", "pos"):
+            assert torch.equal(getattr(a, name), getattr(b, name)), (name, rep)
+        assert torch.equal(a.perm[:n_local], b.perm[:n_local])
+        assert int(b.sync[0].item()) == 0
+
+
 def test_all_instances_sum_to_dense_layer():
     """Tiny configuration: the instance partials of both instances add up to the dense
     per-token layer (replicas hold identical weights, so scheduling never changes the output)."""
