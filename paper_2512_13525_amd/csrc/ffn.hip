@@ -21,10 +21,13 @@
 // number of activated experts (a perfectly balanced split: the layer's latency then follows
 // the activated-expert count down to a single expert).  A workgroup's 4 wavefronts take the
 // 4 K-steps of a quad (split-K), keep a ring of kRing steps of loads in flight and meet in
-// LDS at the end of a unit.  A unit cut by a range boundary is finished by whichever of its
-// workgroups arrives last: every part stores its fp32 partial tile in a private workspace
-// slot, bumps the unit's arrival counter, and the last one adds the parts in workgroup order
-// (so the sum is deterministic) and runs the epilogue.  Nobody ever waits for a partial.
+// LDS at the end of a unit.  A unit cut by a range boundary is finished by the workgroup that
+// holds its first quad (the last segment of that workgroup's range): every other part is the
+// first segment of a later workgroup's range, stores its fp32 partial tile in a private
+// workspace slot and bumps the unit's arrival counter; the finisher polls the counter (the
+// parts are ready long before), adds the parts in workgroup order (so the sum is deterministic)
+// and runs the epilogue.  Counter bumps are sent one segment late, when the stores they
+// announce are known to be acknowledged, so no wavefront stalls on a store round trip.
 // SiLU(gate)*up is rounded to bf16 once and written to `act`.
 //
 // Stage 2 of a slot may start only when all stage-1 units of that slot are done: a per-slot
@@ -56,7 +59,6 @@ constexpr int kPassTok = kTokTiles * 16;
 
 constexpr int kRing = 2;                // K-steps of loads each wavefront keeps in flight
 constexpr int kFfnThreads = 256;
-constexpr int kFfnWgPerCu = 2;          // resident workgroups per CU the register budget is sized for
 constexpr int kMaxGrid = 1024;          // upper bound of the persistent grid
 constexpr int kTokCacheSlots = 64;      // activated slots whose first-pass token rows are cached in LDS
 
@@ -152,13 +154,17 @@ __device__ __forceinline__ f32x4 load_coherent(const f32x4 *p) {
     return v;
 }
 
+// Workgroup barrier for LDS exchange only: waits for this wavefront's LDS traffic, not for its
+// global loads (the prefetched weights of the next segment stay in flight across it).
+__device__ __forceinline__ void lds_barrier() {
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
 __device__ __forceinline__ float silu_mul(float g, float u) { return g / (1.0f + __expf(-g)) * u; }
 
-constexpr int kMaxGroup = 4;             // units a workgroup multiplies together per K-step (B operand reuse)
-constexpr int kPairs = kMaxGroup * kTokTiles;
 
 struct FfnShared {
-    f32x4 red[4][kMaxGroup][kTokTiles][64];  // [wave][unit of the group][token tile][lane], one half at a time
+    f32x4 *red;                              // [wave][unit of the group][token tile][lane], one half at a time
     int slot[MOE_MAX_SLOTS];                 // activated slots, ascending
     int lo[MOE_MAX_SLOTS];                   // first request row of the slot
     int m[MOE_MAX_SLOTS];                    // requests of the slot
@@ -168,6 +174,7 @@ struct FfnShared {
     int flag;
 #ifdef MOE_FFN_TRACE
     long long wait_ticks;
+    int tr_n;
 #endif
 };
 
@@ -175,10 +182,40 @@ struct FfnShared {
 // of the group is R x 2 weight fragments (R x 2 KiB) against the same token fragment(s).
 // STAGE1: gate/up units (16 intermediate channels each); otherwise down units (32 output
 // channels each).
+#ifdef MOE_FFN_TRACE
+// debug build only: thread 0 of every workgroup logs (tag, time) pairs into the unused second
+// partial slot of its workgroup
+#define MOE_TR(tag)                                                                              \
+    if (threadIdx.x == 0) {                                                                      \
+        long long *tr_ = reinterpret_cast<long long *>(a.part + blockIdx.x * kPartPerWg + kPartPerWg / 2); \
+        const int n_ = sh.tr_n;                                                                  \
+        if (n_ < 250) { tr_[2 + 2 * n_] = (tag); tr_[3 + 2 * n_] = wall_clock64(); sh.tr_n = n_ + 1; tr_[0] = n_ + 1; } \
+    }
+#else
+#define MOE_TR(tag)
+#endif
+
 struct SegDesc {
     int j, pass, g_idx, qa, qb;
-    long long u0;                            // first quad of the group in the stage's flat order
+    int u0;                                  // first quad of the group in the stage's flat order
 };
+
+// Signals a workgroup owes for stores it has issued but not yet seen acknowledged.  They are sent
+// one segment later, after the next streaming loop has drained (s_waitcnt vmcnt(0) is free there),
+// so that no wavefront ever stalls on a store round trip.
+struct Pending {
+    int *arrive;       // arrival counter of a cut group this workgroup contributed a part to
+    int *slot_done;    // stage-1 counter of a slot ...
+    int slot_units;    // ... and the units finished for it
+};
+
+__device__ __forceinline__ void flush_pending(Pending &pd) {
+    if (pd.arrive) __hip_atomic_fetch_add(pd.arrive, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (pd.slot_done) __hip_atomic_fetch_add(pd.slot_done, pd.slot_units, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    pd.arrive = nullptr;
+    pd.slot_done = nullptr;
+    pd.slot_units = 0;
+}
 
 // This wave's K-steps of a segment: kk = 4*(qa+i) + wave, i in [0, n_i)
 __device__ __forceinline__ int seg_steps(const SegDesc &d, int KS, int QU, int wave) {
@@ -214,10 +251,10 @@ __device__ __forceinline__ void seg_prefetch(const bf16x8 *wp, size_t unit_strid
 
 template <bool STAGE1, int R>
 __device__ __forceinline__ void ffn_segment(const FfnArgs &a, FfnShared &sh, const SegDesc &cur, const SegDesc &nxt,
-                                            bool has_next, bf16x8 (*wr)[R][2], long long Q, long long G,
+                                            bool has_next, bf16x8 (*wr)[R][2], Pending &pd, int Q, int G,
                                             int wave, int lane) {
     const int j = cur.j, pass = cur.pass, g_idx = cur.g_idx, qa = cur.qa, qb = cur.qb;
-    const long long u0 = cur.u0;
+    const int u0 = cur.u0;
     const int n = lane & 15, q4 = lane >> 4;
     const int n1 = a.d_e / 16, n2 = a.d_h / 32;
     const int KS = (STAGE1 ? a.d_h : a.d_e) / 32;
@@ -230,6 +267,7 @@ __device__ __forceinline__ void ffn_segment(const FfnArgs &a, FfnShared &sh, con
     const size_t unit_stride = static_cast<size_t>(KS) * 128;      // 16-byte chunks between consecutive units
     const int n_i = seg_steps(cur, KS, QU, wave);
     const bf16x8 *wp = seg_weights<STAGE1, R>(a, sh, cur, wave, lane);   // its first kRing steps are already in flight
+    MOE_TR((STAGE1 ? 100 : 200) + 0)
 
     if (!STAGE1) {
         // every stage-1 unit of this slot must have published its part of `act`
@@ -250,7 +288,7 @@ __device__ __forceinline__ void ffn_segment(const FfnArgs &a, FfnShared &sh, con
             sh.wait_ticks += wall_clock64() - w0;
 #endif
         }
-        __syncthreads();
+        lds_barrier();
     }
 
     // ---- token rows of this pass (B operand)
@@ -278,6 +316,7 @@ __device__ __forceinline__ void ffn_segment(const FfnArgs &a, FfnShared &sh, con
         }
     }
 
+    MOE_TR((STAGE1 ? 100 : 200) + 1)
     f32x4 acc[R][kTokTiles][2];
 #pragma unroll
     for (int r = 0; r < R; ++r)
@@ -323,6 +362,11 @@ __device__ __forceinline__ void ffn_segment(const FfnArgs &a, FfnShared &sh, con
 #undef MOE_STREAM
 #undef MOE_STEP
 
+    // every load of this segment has been consumed, so this costs nothing; it also means that the
+    // stores of the previous segment (partial tiles, `act`) have been acknowledged
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    MOE_TR((STAGE1 ? 100 : 200) + 2)
+
     // ---- the next segment's first weights go out before this one's reduction and epilogue
     if (has_next)
         seg_prefetch<R>(seg_weights<STAGE1, R>(a, sh, nxt, wave, lane), unit_stride, seg_steps(nxt, KS, QU, wave), wr);
@@ -330,64 +374,97 @@ __device__ __forceinline__ void ffn_segment(const FfnArgs &a, FfnShared &sh, con
     // ---- the 4 wavefronts' partial tiles meet in LDS, one half (gate | up, rows 0-15 | 16-31) at a
     // time; wave w then owns the (unit, token tile) pairs w and w+4
     f32x4 res[2][2];                                                 // [pair slot][half]
+    if (R == 1) {
+        // both halves at once: red is [wave][half][token tile][lane]
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
-#pragma unroll
-        for (int r = 0; r < R; ++r)
+        for (int h = 0; h < 2; ++h)
 #pragma unroll
             for (int t = 0; t < kTokTiles; ++t)
-                if (t < nt) sh.red[wave][r][t][lane] = acc[r][t][h];
-        __syncthreads();
+                if (t < nt) sh.red[((wave * 2 + h) * kTokTiles + t) * 64 + lane] = acc[0][t][h];
+        lds_barrier();
+        // past this barrier every wavefront has seen its earlier stores acknowledged
+        if (threadIdx.x == 0) flush_pending(pd);
 #pragma unroll
-        for (int ps = 0; ps < 2; ++ps) {
-            const int p = wave + 4 * ps;
-            const int r = p / kTokTiles, t = p % kTokTiles;
+        for (int h = 0; h < 2; ++h) {
             f32x4 v = f32x4{0, 0, 0, 0};
-            if (p < R * kTokTiles && t < nt) {
-                v = sh.red[0][r][t][lane];
+            if (wave < nt) {
+                v = sh.red[(h * kTokTiles + wave) * 64 + lane];
 #pragma unroll
-                for (int w = 1; w < 4; ++w) v += sh.red[w][r][t][lane];
+                for (int w = 1; w < 4; ++w) v += sh.red[((w * 2 + h) * kTokTiles + wave) * 64 + lane];
             }
-            res[ps][h] = v;
+            res[0][h] = v;
+            res[1][h] = f32x4{0, 0, 0, 0};
         }
-        __syncthreads();
+        lds_barrier();
+    } else {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+#pragma unroll
+                for (int t = 0; t < kTokTiles; ++t)
+                    if (t < nt) sh.red[((wave * R + r) * kTokTiles + t) * 64 + lane] = acc[r][t][h];
+            lds_barrier();
+            if (h == 0 && threadIdx.x == 0) flush_pending(pd);
+#pragma unroll
+            for (int ps = 0; ps < 2; ++ps) {
+                const int p = wave + 4 * ps;
+                const int r = p / kTokTiles, t = p % kTokTiles;
+                f32x4 v = f32x4{0, 0, 0, 0};
+                if (p < R * kTokTiles && t < nt) {
+                    v = sh.red[(r * kTokTiles + t) * 64 + lane];
+#pragma unroll
+                    for (int w = 1; w < 4; ++w) v += sh.red[((w * R + r) * kTokTiles + t) * 64 + lane];
+                }
+                res[ps][h] = v;
+            }
+            lds_barrier();
+        }
     }
 
+    MOE_TR((STAGE1 ? 100 : 200) + 3)
     const bool whole = qa == 0 && qb == QU;
     bool finish = whole;
     if (!whole) {
-        // a group cut by a range boundary: publish this part, the last part to arrive finishes
-        const int b_first = static_cast<int>(((u0 + 1) * G - 1) / Q);
-        const int b_last = static_cast<int>(((u0 + QU) * G - 1) / Q);
-        f32x4 *mine = a.part + ((STAGE1 ? 0 : static_cast<size_t>(kMaxGrid)) + blockIdx.x) * kPartPerWg +
-                      static_cast<size_t>(qa == 0 ? 1 : 0) * (kPairs * 2 * 64);
-#pragma unroll
-        for (int ps = 0; ps < 2; ++ps) {
-            const int p = wave + 4 * ps;
-            if (p < R * kTokTiles && p % kTokTiles < nt) {
-                store_coherent(mine + (p * 2 + 0) * 64 + lane, res[ps][0]);
-                store_coherent(mine + (p * 2 + 1) * 64 + lane, res[ps][1]);
-            }
-        }
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");             // stores acknowledged before the arrival
-        __syncthreads();
-        if (threadIdx.x == 0) {
-            int *arrive = a.ctrl + kCtrlArrive0 + (STAGE1 ? 0 : kMaxGrid) + b_first;
-            const int old = __hip_atomic_fetch_add(arrive, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            sh.flag = old == b_last - b_first;
-            if (sh.flag) __hip_atomic_store(arrive, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
-        __syncthreads();
-        finish = sh.flag != 0;
-        if (finish) {
+        // A group cut by a range boundary.  The part that holds the group's first quad finishes it:
+        // that part is the last segment of its workgroup's range, while every other part is the
+        // first segment of a later workgroup's range, so the others are ready long before.
+        const int b_first = static_cast<int>(((u0 + 1LL) * G - 1) / Q);
+        const int b_last = static_cast<int>((static_cast<long long>(u0 + QU) * G - 1) / Q);
+        int *arrive = a.ctrl + kCtrlArrive0 + (STAGE1 ? 0 : kMaxGrid) + b_first;
+        const size_t part0 = STAGE1 ? 0 : static_cast<size_t>(kMaxGrid);
+        if (qa != 0) {
+            f32x4 *mine = a.part + (part0 + blockIdx.x) * kPartPerWg;
 #pragma unroll
             for (int ps = 0; ps < 2; ++ps) {
                 const int p = wave + 4 * ps;
                 if (p < R * kTokTiles && p % kTokTiles < nt) {
-                    f32x4 v0 = f32x4{0, 0, 0, 0}, v1 = f32x4{0, 0, 0, 0};
-                    for (int b = b_first; b <= b_last; ++b) {        // fixed order: deterministic sum
-                        const f32x4 *q = a.part + ((STAGE1 ? 0 : static_cast<size_t>(kMaxGrid)) + b) * kPartPerWg +
-                                         static_cast<size_t>(b == b_first ? 1 : 0) * (kPairs * 2 * 64);
+                    store_coherent(mine + (p * 2 + 0) * 64 + lane, res[ps][0]);
+                    store_coherent(mine + (p * 2 + 1) * 64 + lane, res[ps][1]);
+                }
+            }
+            if (threadIdx.x == 0) pd.arrive = arrive;                // sent once the stores are acknowledged
+        } else {
+            if (threadIdx.x == 0) {
+                int spins = 0;
+                while (__hip_atomic_load(arrive, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < b_last - b_first) {
+                    __builtin_amdgcn_s_sleep(8);
+                    if (++spins > a.spin_limit) {
+                        __hip_atomic_store(&a.ctrl[1], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        break;
+                    }
+                }
+                __hip_atomic_store(arrive, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // for the next call
+            }
+            lds_barrier();
+            finish = true;
+#pragma unroll
+            for (int ps = 0; ps < 2; ++ps) {
+                const int p = wave + 4 * ps;
+                if (p < R * kTokTiles && p % kTokTiles < nt) {
+                    f32x4 v0 = res[ps][0], v1 = res[ps][1];
+                    for (int b = b_first + 1; b <= b_last; ++b) {    // fixed order: deterministic sum
+                        const f32x4 *q = a.part + (part0 + b) * kPartPerWg;
                         v0 += load_coherent(q + (p * 2 + 0) * 64 + lane);
                         v1 += load_coherent(q + (p * 2 + 1) * 64 + lane);
                     }
@@ -423,20 +500,19 @@ __device__ __forceinline__ void ffn_segment(const FfnArgs &a, FfnShared &sh, con
                 }
             }
         }
-        // A workgroup barrier does not wait for global stores to be acknowledged; the counter
-        // bump below must not overtake this group's `act` stores on their way to memory.
-        if (STAGE1) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    }
-    __syncthreads();                                                 // flag is reused
-    if (finish && threadIdx.x == 0) {
-        if (STAGE1) {
-            __hip_atomic_fetch_add(&slot_ctrl[0], R, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        } else {
-            const int total2 = n2 * (sh.pre[j + 1] - sh.pre[j]);
-            if (__hip_atomic_fetch_add(&slot_ctrl[1], R, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == total2 - R) {
-                // last stage-2 group of the slot: every other group of the slot has passed its wait
-                __hip_atomic_store(&slot_ctrl[0], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                __hip_atomic_store(&slot_ctrl[1], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        MOE_TR((STAGE1 ? 100 : 200) + (whole ? 4 : 5))
+        if (threadIdx.x == 0) {
+            if (STAGE1) {
+                // the slot's counter is bumped once these `act` stores are acknowledged
+                pd.slot_done = &slot_ctrl[0];
+                pd.slot_units = R;
+            } else {
+                const int total2 = n2 * (sh.pre[j + 1] - sh.pre[j]);
+                if (__hip_atomic_fetch_add(&slot_ctrl[1], R, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == total2 - R) {
+                    // last stage-2 group of the slot: every other group of the slot has passed its wait
+                    __hip_atomic_store(&slot_ctrl[0], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    __hip_atomic_store(&slot_ctrl[1], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
             }
         }
     }
@@ -448,21 +524,21 @@ __device__ __forceinline__ void ffn_stage(const FfnArgs &a, FfnShared &sh, int w
     const int n_g = (STAGE1 ? a.d_e / 16 : a.d_h / 32) / R;          // groups of R units per slot
     const int KS = (STAGE1 ? a.d_h : a.d_e) / 32;
     const int QU = (KS + 3) >> 2;
-    const long long per_pass = static_cast<long long>(n_g) * QU;     // quads of one pass of one slot
-    const long long Q = sh.pre[a_g] * per_pass;                      // quads of the stage
+    const int per_pass = n_g * QU;                                   // quads of one pass of one slot
+    const int Q = sh.pre[a_g] * per_pass;                            // quads of the stage (the host bounds it below 2^31)
     if (Q == 0) return;
     // at most one workgroup per quad, so that no range is empty and every workgroup that a
     // cut group counts on does arrive
-    const long long G = min(static_cast<long long>(gridDim.x), Q);
-    if (blockIdx.x >= G) return;
-    long long q = blockIdx.x * Q / G;
-    const long long q_hi = (blockIdx.x + 1LL) * Q / G;
+    const int G = min(static_cast<int>(gridDim.x), Q);
+    if (static_cast<int>(blockIdx.x) >= G) return;
+    int q = static_cast<int>(static_cast<long long>(blockIdx.x) * Q / G);
+    const int q_hi = static_cast<int>((blockIdx.x + 1LL) * Q / G);
     int j = 0;
-    auto describe = [&](long long at) {
+    auto describe = [&](int at) {
         while (sh.pre[j + 1] * per_pass <= at) ++j;
         // inside a slot: group -> pass -> quad, so that the passes of a group (more than 32 tokens
         // on one expert) re-read its weights back to back, from L2 rather than from HBM
-        const int rel = static_cast<int>(at - sh.pre[j] * per_pass);
+        const int rel = at - sh.pre[j] * per_pass;
         const int per_group = (sh.pre[j + 1] - sh.pre[j]) * QU;
         SegDesc d;
         d.j = j;
@@ -470,11 +546,12 @@ __device__ __forceinline__ void ffn_stage(const FfnArgs &a, FfnShared &sh, int w
         const int rel2 = rel - d.g_idx * per_group;
         d.pass = rel2 / QU;
         d.qa = rel2 - d.pass * QU;
-        d.qb = static_cast<int>(min(static_cast<long long>(QU), d.qa + (q_hi - at)));
+        d.qb = min(QU, d.qa + (q_hi - at));
         d.u0 = at - d.qa;
         return d;
     };
     bf16x8 wr[kRing][R][2];
+    Pending pd{nullptr, nullptr, 0};                                 // meaningful in thread 0 only
     SegDesc cur = describe(q);
     seg_prefetch<R>(seg_weights<STAGE1, R>(a, sh, cur, wave, lane), static_cast<size_t>(KS) * 128,
                     seg_steps(cur, KS, QU, wave), wr);
@@ -483,18 +560,28 @@ __device__ __forceinline__ void ffn_stage(const FfnArgs &a, FfnShared &sh, int w
         const bool has_next = q < q_hi;
         SegDesc nxt = cur;
         if (has_next) nxt = describe(q);
-        ffn_segment<STAGE1, R>(a, sh, cur, nxt, has_next, wr, Q, G, wave, lane);
+        ffn_segment<STAGE1, R>(a, sh, cur, nxt, has_next, wr, pd, Q, G, wave, lane);
         if (!has_next) break;
         cur = nxt;
     }
+    // the last segment's signals
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (threadIdx.x == 0) flush_pending(pd);
 }
 
-__global__ __launch_bounds__(kFfnThreads, kFfnWgPerCu)
+// RMAX: largest group size compiled in; WGPC: resident workgroups per CU the register budget
+// is sized for.  <4, 2> for layers with many large units, <1, 4> for small layers, where more
+// resident wavefronts matter more than token-operand reuse.
+template <int RMAX, int WGPC>
+__global__ __launch_bounds__(kFfnThreads, WGPC)
 void ffn_fused_kernel(FfnArgs a) {
     __shared__ FfnShared sh;
+    __shared__ f32x4 red_lds[4 * (RMAX > 2 ? RMAX : 2) * kTokTiles * 64];
+    if (threadIdx.x == 0) sh.red = red_lds;
 #ifdef MOE_FFN_TRACE
     const long long t0 = wall_clock64();
-    if (threadIdx.x == 0) sh.wait_ticks = 0;
+    if (threadIdx.x == 0) { sh.wait_ticks = 0; sh.tr_n = 0; }
 #endif
     // `act` is read with ordinary loads, and only after it is complete: nothing stale can be cached,
     // because caches are invalidated at the kernel boundary and no line of `act` is read early
@@ -546,14 +633,14 @@ void ffn_fused_kernel(FfnArgs a) {
 #ifdef MOE_FFN_TRACE
     const long long t1 = wall_clock64();
 #endif
-    if (n1 % 4 == 0 && passes * n1 >= 8 * grid) ffn_stage<true, 4>(a, sh, wave, lane);
-    else if (n1 % 2 == 0 && passes * n1 >= 4 * grid) ffn_stage<true, 2>(a, sh, wave, lane);
+    if (RMAX >= 4 && n1 % 4 == 0 && passes * n1 >= 8 * grid) ffn_stage<true, (RMAX >= 4 ? 4 : 1)>(a, sh, wave, lane);
+    else if (RMAX >= 2 && n1 % 2 == 0 && passes * n1 >= 4 * grid) ffn_stage<true, (RMAX >= 2 ? 2 : 1)>(a, sh, wave, lane);
     else ffn_stage<true, 1>(a, sh, wave, lane);
 #ifdef MOE_FFN_TRACE
     const long long t2 = wall_clock64();
 #endif
-    if (n2 % 4 == 0 && passes * n2 >= 8 * grid) ffn_stage<false, 4>(a, sh, wave, lane);
-    else if (n2 % 2 == 0 && passes * n2 >= 4 * grid) ffn_stage<false, 2>(a, sh, wave, lane);
+    if (RMAX >= 4 && n2 % 4 == 0 && passes * n2 >= 8 * grid) ffn_stage<false, (RMAX >= 4 ? 4 : 1)>(a, sh, wave, lane);
+    else if (RMAX >= 2 && n2 % 2 == 0 && passes * n2 >= 4 * grid) ffn_stage<false, (RMAX >= 2 ? 2 : 1)>(a, sh, wave, lane);
     else ffn_stage<false, 1>(a, sh, wave, lane);
 #ifdef MOE_FFN_TRACE
     if (threadIdx.x == 0) {
@@ -665,23 +752,24 @@ extern "C" int moe_pack_weights_bf16(const void *W13_dev, const void *W2_dev, in
 }
 
 namespace {
-// Persistent grid of the fused kernel: a multiple of the CU count that is resident at once
-// (kFfnWgPerCu workgroups of 256 threads per CU by __launch_bounds__).  MOE_JANUS_FFN_WG_PER_CU
-// (1..kFfnWgPerCu) overrides the default for tuning.
-int ffn_grid_blocks() {
-    static int cached = 0;
-    if (cached) return cached;
-    int dev = 0, cus = 0;
-    if (hipGetDevice(&dev) != hipSuccess ||
-        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
-        return 0;
-    int per_cu = kFfnWgPerCu;
+// Persistent grid of the fused kernel: a multiple of the CU count that is resident at once.
+// MOE_JANUS_FFN_WG_PER_CU overrides the workgroups per CU (1..limit) for tuning.
+int ffn_grid_blocks(int limit_per_cu) {
+    static int cus = 0;
+    if (!cus) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1)
+            return 0;
+        cus = n;
+    }
+    int per_cu = limit_per_cu;
     if (const char *e = getenv("MOE_JANUS_FFN_WG_PER_CU")) {
         const int v = atoi(e);
-        if (v >= 1 && v <= kFfnWgPerCu) per_cu = v;
+        if (v >= 1 && v <= limit_per_cu) per_cu = v;
     }
-    cached = cus * per_cu < kMaxGrid ? cus * per_cu : kMaxGrid;
-    return cached;
+    const int g = cus * per_cu;
+    return g < kMaxGrid ? g : kMaxGrid;
 }
 }  // namespace
 
@@ -702,10 +790,20 @@ extern "C" int moe_grouped_ffn(const void *X_dev, const void *W13_dev, const voi
         !moe::aligned(perm_dev, 4))
         return MOE_EINVAL;
     if (workspace_bytes < moe_workspace_bytes(T, k, C, d_h, d_e, dtype)) return MOE_EWORKSPACE;
+    if (dtype == MOE_DTYPE_BF16) {
+        // the kernel numbers its work (passes x units x quads of 4 K-steps) in 32 bits
+        const long long passes = static_cast<long long>(T) * k / 32 + C;
+        const long long q1 = passes * (d_e / 16) * ((d_h / 32 + 3) / 4), q2 = passes * (d_h / 32) * ((d_e / 32 + 3) / 4);
+        if (q1 > 0x3fffffffLL || q2 > 0x3fffffffLL) return MOE_ESHAPE;
+    }
     hipStream_t st = static_cast<hipStream_t>(stream);
     char *ws = static_cast<char *>(workspace_dev);
     if (dtype == MOE_DTYPE_BF16) {
-        const int blocks = ffn_grid_blocks();
+        // many large units (deep K, many slots): favour token-operand reuse; otherwise favour more
+        // resident wavefronts.  MOE_JANUS_FFN_VARIANT=small|large overrides the choice.
+        bool large = static_cast<long long>(C) * (d_e / 16) * (d_h / 32) >= (1LL << 19);
+        if (const char *e = getenv("MOE_JANUS_FFN_VARIANT")) large = e[0] == 'l';
+        const int blocks = ffn_grid_blocks(large ? 2 : 4);
         if (blocks < 1) { moe::set_hip_error(hipErrorInvalidDevice, "moe_grouped_ffn/device query"); return MOE_EHIP; }
         FfnArgs a;
         a.X = static_cast<const uint16_t *>(X_dev);
@@ -720,7 +818,8 @@ extern "C" int moe_grouped_ffn(const void *X_dev, const void *W13_dev, const voi
         a.k = k; a.C = C; a.d_h = d_h; a.d_e = d_e;
         a.act_stride = (d_e + 63) / 64 * 64;
         a.spin_limit = 1 << 21;
-        hipLaunchKernelGGL(ffn_fused_kernel, dim3(blocks), dim3(kFfnThreads), 0, st, a);
+        if (large) hipLaunchKernelGGL((ffn_fused_kernel<4, 2>), dim3(blocks), dim3(kFfnThreads), 0, st, a);
+        else hipLaunchKernelGGL((ffn_fused_kernel<1, 4>), dim3(blocks), dim3(kFfnThreads), 0, st, a);
     } else {
         // one grid row per possible request row; rows >= n_local leave at once
         const long long rows = static_cast<long long>(T) * k;

@@ -19,7 +19,7 @@ def oracle_route(cfg, logits):
 class OracleRun:
     """Everything the oracle computes for (cfg, g_self) on the seeded inputs."""
 
-    def __init__(self, cfg, g_self=None, with_ffn=True, weights=None):
+    def __init__(self, cfg, g_self=None, with_ffn=True, weights=None, only_activated=False):
         self.cfg = cfg
         self.lay = W.build_placement(cfg)
         self.pl = scheduling.make_placement(self.lay, cfg.E, cfg.n_inst, cfg.C)
@@ -35,7 +35,15 @@ class OracleRun:
         self.pos[self.perm] = np.arange(len(self.perm), dtype=np.int32)
         if with_ffn:
             if weights is None:
-                weights = W.instance_weights(cfg, self.lay, g_self)
+                if only_activated:
+                    # slots without a request hold NaN: the HIP path must never read them
+                    W13 = np.full((cfg.C, 2 * cfg.d_e, cfg.d_h), np.nan, dtype=np.float32)
+                    W2 = np.full((cfg.C, cfg.d_h, cfg.d_e), np.nan, dtype=np.float32)
+                    for s in np.nonzero(self.slot_count > 0)[0]:
+                        W13[s], W2[s] = W.expert_weights(cfg, int(self.lay[g_self * cfg.C + s]))
+                    weights = (W13, W2)
+                else:
+                    weights = W.instance_weights(cfg, self.lay, g_self)
             self.W13, self.W2 = weights
             self.Yp = ffn.grouped_ffn(self.X, self.W13, self.W2, self.slot_off, self.perm, cfg.k)
             self.Y = dispatch.combine(self.Yp, self.perm, self.w, cfg.T, cfg.k)
