@@ -10,6 +10,18 @@ namespace moe {
 constexpr int kFrontThreads = 1024;
 constexpr int kFrontWaves = kFrontThreads / MOE_WAVE;
 
+__device__ __forceinline__ uint64_t readlane_u64(uint64_t v, int l) {
+    const uint32_t lo = __builtin_amdgcn_readlane(static_cast<int>(v & 0xffffffffu), l);
+    const uint32_t hi = __builtin_amdgcn_readlane(static_cast<int>(v >> 32), l);
+    return (static_cast<uint64_t>(hi) << 32) | lo;
+}
+
+__device__ __forceinline__ uint64_t readfirstlane_u64(uint64_t v) {
+    const uint32_t lo = __builtin_amdgcn_readfirstlane(static_cast<int>(v & 0xffffffffu));
+    const uint32_t hi = __builtin_amdgcn_readfirstlane(static_cast<int>(v >> 32));
+    return (static_cast<uint64_t>(hi) << 32) | lo;
+}
+
 // ------------------------------------------------------------------ a0: one token per wavefront
 __device__ __forceinline__ uint64_t wave_max_u64(uint64_t v) {
 #pragma unroll
@@ -44,7 +56,9 @@ __device__ __forceinline__ float sigmoid_f32(float x) { return 1.0f / (1.0f + ex
 
 // Lane l owns experts l, l+64, ...; every logit becomes a 64-bit key (order-preserving float bits
 // in the high word, ~id in the low word) so that "largest logit, lower id on ties" is an unsigned
-// maximum found with a 6-step cross-lane butterfly; k selections are k such reductions.
+// comparison.  With one key per lane (E <= 64) the top-k are the keys that fewer than k other keys
+// exceed (rank counting with scalar lane broadcasts, no shuffles); with more keys per lane the k
+// selections are k maxima, each found with a 6-step cross-lane butterfly.
 // row_lds: VPL*64 floats private to this wavefront.  COHERENT: results are written with agent-scope
 // stores (read by another workgroup of the same launch).
 template <int VPL, bool COHERENT>
@@ -106,41 +120,90 @@ __device__ __forceinline__ void route_token(const float *__restrict__ row, int E
         denom_all = wave_sum_f32(s);
     }
 
-    // k rounds of "largest remaining"
-    float sel_v = 0.0f;            // lane j keeps the j-th selected logit
-    int sel_id = 0;
-    float vmax = 0.0f;
-    for (int j = 0; j < k; ++j) {
-        uint64_t m = 0ull;
-#pragma unroll
-        for (int i = 0; i < VPL; ++i) m = key[i] > m ? key[i] : m;
-        const uint64_t best = wave_max_u64(m);
-        const int id = 0x7fffffff - static_cast<int>(best & 0xffffffffu);
-        const float val = from_orderable(static_cast<uint32_t>(best >> 32));
-        if (j == 0) vmax = val;
-        if (lane == j) { sel_v = val; sel_id = id; }
-#pragma unroll
-        for (int i = 0; i < VPL; ++i)
-            if (lane + i * MOE_WAVE == id) key[i] = 0ull;
-    }
-
-    // weights of the k selected experts (lanes 0..k-1)
-    float score = 0.0f;
-    if (lane < k) {
-        score = cfg.mode == MOE_ROUTE_SIGMOID_GROUP ? sigmoid_f32(sel_v) : expf(sel_v - vmax);
-    }
-    const float denom_sel = wave_sum_f32(score);
-    if (lane < k) {
-        float w;
-        if (cfg.mode == MOE_ROUTE_SIGMOID_GROUP) w = score / denom_sel * cfg.scale;
-        else if (cfg.renormalize) w = score / denom_sel;
-        else w = score / denom_all;
-        if (COHERENT) {
-            __hip_atomic_store(ids_out + lane, sel_id, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        } else {
-            ids_out[lane] = sel_id;
+    if (VPL == 1) {
+        // Rank of every key among all keys of the row (keys are distinct: the id is part of the key):
+        // lane j's keys are broadcast one after the other with scalar lane reads and every lane counts
+        // the keys greater than its own.  The k keys with rank < k are the selection, already in
+        // output order; dropped or padding keys are 0 and never rank below k.
+        int rank[VPL];
+    #pragma unroll
+        for (int i = 0; i < VPL; ++i) rank[i] = 0;
+        for (int j = 0; j < MOE_WAVE; ++j) {
+    #pragma unroll
+            for (int i2 = 0; i2 < VPL; ++i2) {
+                const uint64_t other = readlane_u64(key[i2], j);
+    #pragma unroll
+                for (int i = 0; i < VPL; ++i) rank[i] += other > key[i] ? 1 : 0;
+            }
         }
-        w_out[lane] = w;
+        float vmax = 0.0f;                                   // largest surviving logit (rank 0)
+    #pragma unroll
+        for (int i = 0; i < VPL; ++i) {
+            const uint64_t top = __ballot(rank[i] == 0 && key[i] != 0ull);
+            if (top) vmax = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(v[i]), __builtin_ctzll(top)));
+        }
+        float score[VPL];
+        float local = 0.0f;
+    #pragma unroll
+        for (int i = 0; i < VPL; ++i) {
+            const bool sel = rank[i] < k && key[i] != 0ull;
+            score[i] = sel ? (cfg.mode == MOE_ROUTE_SIGMOID_GROUP ? sigmoid_f32(v[i]) : expf(v[i] - vmax)) : 0.0f;
+            local += score[i];
+        }
+        const float denom_sel = wave_sum_f32(local);
+    #pragma unroll
+        for (int i = 0; i < VPL; ++i) {
+            if (rank[i] < k && key[i] != 0ull) {
+                float w;
+                if (cfg.mode == MOE_ROUTE_SIGMOID_GROUP) w = score[i] / denom_sel * cfg.scale;
+                else if (cfg.renormalize) w = score[i] / denom_sel;
+                else w = score[i] / denom_all;
+                const int e = lane + i * MOE_WAVE;
+                if (COHERENT) {
+                    __hip_atomic_store(ids_out + rank[i], e, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                } else {
+                    ids_out[rank[i]] = e;
+                }
+                w_out[rank[i]] = w;
+            }
+        }
+    } else {
+        // k rounds of "largest remaining"
+        float sel_v = 0.0f;            // lane j keeps the j-th selected logit
+        int sel_id = 0;
+        float vmax = 0.0f;
+        for (int j = 0; j < k; ++j) {
+            uint64_t m = 0ull;
+    #pragma unroll
+            for (int i = 0; i < VPL; ++i) m = key[i] > m ? key[i] : m;
+            const uint64_t best = wave_max_u64(m);
+            const int id = 0x7fffffff - static_cast<int>(best & 0xffffffffu);
+            const float val = from_orderable(static_cast<uint32_t>(best >> 32));
+            if (j == 0) vmax = val;
+            if (lane == j) { sel_v = val; sel_id = id; }
+    #pragma unroll
+            for (int i = 0; i < VPL; ++i)
+                if (lane + i * MOE_WAVE == id) key[i] = 0ull;
+        }
+
+        // weights of the k selected experts (lanes 0..k-1)
+        float score = 0.0f;
+        if (lane < k) {
+            score = cfg.mode == MOE_ROUTE_SIGMOID_GROUP ? sigmoid_f32(sel_v) : expf(sel_v - vmax);
+        }
+        const float denom_sel = wave_sum_f32(score);
+        if (lane < k) {
+            float w;
+            if (cfg.mode == MOE_ROUTE_SIGMOID_GROUP) w = score / denom_sel * cfg.scale;
+            else if (cfg.renormalize) w = score / denom_sel;
+            else w = score / denom_all;
+            if (COHERENT) {
+                __hip_atomic_store(ids_out + lane, sel_id, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            } else {
+                ids_out[lane] = sel_id;
+            }
+            w_out[lane] = w;
+        }
     }
 }
 
@@ -161,18 +224,6 @@ struct SchedShared {
     uint64_t multi_mask[MOE_MAX_EXPERTS / 64];
     uint64_t single_mask[MOE_MAX_INSTANCES * (MOE_MAX_EXPERTS / 64)];
 };
-
-__device__ __forceinline__ uint64_t readlane_u64(uint64_t v, int l) {
-    const uint32_t lo = __builtin_amdgcn_readlane(static_cast<int>(v & 0xffffffffu), l);
-    const uint32_t hi = __builtin_amdgcn_readlane(static_cast<int>(v >> 32), l);
-    return (static_cast<uint64_t>(hi) << 32) | lo;
-}
-
-__device__ __forceinline__ uint64_t readfirstlane_u64(uint64_t v) {
-    const uint32_t lo = __builtin_amdgcn_readfirstlane(static_cast<int>(v & 0xffffffffu));
-    const uint32_t hi = __builtin_amdgcn_readfirstlane(static_cast<int>(v >> 32));
-    return (static_cast<uint64_t>(hi) << 32) | lo;
-}
 
 // 16-byte agent-scope (L2-coherent across XCDs) load of four request ids
 __device__ __forceinline__ int4 load_ids4(const int4 *p, bool coherent) {

@@ -570,24 +570,10 @@ __device__ __forceinline__ void ffn_stage(const FfnArgs &a, FfnShared &sh, int w
     if (threadIdx.x == 0) flush_pending(pd);
 }
 
-// RMAX: largest group size compiled in; WGPC: resident workgroups per CU the register budget
-// is sized for.  <4, 2> for layers with many large units, <1, 4> for small layers, where more
-// resident wavefronts matter more than token-operand reuse.
-template <int RMAX, int WGPC>
-__global__ __launch_bounds__(kFfnThreads, WGPC)
-void ffn_fused_kernel(FfnArgs a) {
-    __shared__ FfnShared sh;
-    __shared__ f32x4 red_lds[4 * (RMAX > 2 ? RMAX : 2) * kTokTiles * 64];
-    if (threadIdx.x == 0) sh.red = red_lds;
-#ifdef MOE_FFN_TRACE
-    const long long t0 = wall_clock64();
-    if (threadIdx.x == 0) { sh.wait_ticks = 0; sh.tr_n = 0; }
-#endif
-    // `act` is read with ordinary loads, and only after it is complete: nothing stale can be cached,
-    // because caches are invalidated at the kernel boundary and no line of `act` is read early
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform: scalar control flow
-    const int lane = threadIdx.x & 63;
-
+// Activated slots in slot order, their request rows, the prefix of passes (PT tokens per pass)
+// and the token rows of each slot's first requests.
+template <int PT>
+__device__ __forceinline__ void ffn_prologue(const FfnArgs &a, FfnShared &sh, int wave, int lane) {
     // ---- activated slots in slot order, their request rows, and the pass prefix
     if (wave == 0) {
         int base = 0, passes = 0;
@@ -597,7 +583,7 @@ void ffn_fused_kernel(FfnArgs a) {
             const int m = s < a.C ? a.slot_off[s + 1] - lo : 0;
             const bool on = m > 0;
             const uint64_t mask = __ballot(on);
-            const int p = on ? (m + kPassTok - 1) / kPassTok : 0;
+            const int p = on ? (m + PT - 1) / PT : 0;
             int incl = p;                                            // inclusive scan of passes over lanes
 #pragma unroll
             for (int d = 1; d < MOE_WAVE; d <<= 1) {
@@ -623,6 +609,27 @@ void ffn_fused_kernel(FfnArgs a) {
         }
     }
     __syncthreads();
+
+}
+
+constexpr int kFfnWgPerCu = 2;          // resident workgroups per CU the register budget is sized for
+constexpr int RMAX = 4;                 // largest group of units multiplied against the same token fragments
+
+__global__ __launch_bounds__(kFfnThreads, kFfnWgPerCu)
+void ffn_fused_kernel(FfnArgs a) {
+    __shared__ FfnShared sh;
+    __shared__ f32x4 red_lds[4 * (RMAX > 2 ? RMAX : 2) * kTokTiles * 64];
+    if (threadIdx.x == 0) sh.red = red_lds;
+#ifdef MOE_FFN_TRACE
+    const long long t0 = wall_clock64();
+    if (threadIdx.x == 0) { sh.wait_ticks = 0; sh.tr_n = 0; }
+#endif
+    // `act` is read with ordinary loads, and only after it is complete: nothing stale can be cached,
+    // because caches are invalidated at the kernel boundary and no line of `act` is read early
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform: scalar control flow
+    const int lane = threadIdx.x & 63;
+
+    ffn_prologue<kPassTok>(a, sh, wave, lane);
 
     // Units are multiplied in groups of R = 4, 2 or 1 against the same token fragments: larger
     // groups re-read the tokens less often, but a group is the unit of the cross-workgroup fix-up,
@@ -792,18 +799,14 @@ extern "C" int moe_grouped_ffn(const void *X_dev, const void *W13_dev, const voi
     if (workspace_bytes < moe_workspace_bytes(T, k, C, d_h, d_e, dtype)) return MOE_EWORKSPACE;
     if (dtype == MOE_DTYPE_BF16) {
         // the kernel numbers its work (passes x units x quads of 4 K-steps) in 32 bits
-        const long long passes = static_cast<long long>(T) * k / 32 + C;
+        const long long passes = static_cast<long long>(T) * k / 16 + C;
         const long long q1 = passes * (d_e / 16) * ((d_h / 32 + 3) / 4), q2 = passes * (d_h / 32) * ((d_e / 32 + 3) / 4);
         if (q1 > 0x3fffffffLL || q2 > 0x3fffffffLL) return MOE_ESHAPE;
     }
     hipStream_t st = static_cast<hipStream_t>(stream);
     char *ws = static_cast<char *>(workspace_dev);
     if (dtype == MOE_DTYPE_BF16) {
-        // many large units (deep K, many slots): favour token-operand reuse; otherwise favour more
-        // resident wavefronts.  MOE_JANUS_FFN_VARIANT=small|large overrides the choice.
-        bool large = static_cast<long long>(C) * (d_e / 16) * (d_h / 32) >= (1LL << 19);
-        if (const char *e = getenv("MOE_JANUS_FFN_VARIANT")) large = e[0] == 'l';
-        const int blocks = ffn_grid_blocks(large ? 2 : 4);
+        const int blocks = ffn_grid_blocks(kFfnWgPerCu);
         if (blocks < 1) { moe::set_hip_error(hipErrorInvalidDevice, "moe_grouped_ffn/device query"); return MOE_EHIP; }
         FfnArgs a;
         a.X = static_cast<const uint16_t *>(X_dev);
@@ -818,8 +821,7 @@ extern "C" int moe_grouped_ffn(const void *X_dev, const void *W13_dev, const voi
         a.k = k; a.C = C; a.d_h = d_h; a.d_e = d_e;
         a.act_stride = (d_e + 63) / 64 * 64;
         a.spin_limit = 1 << 21;
-        if (large) hipLaunchKernelGGL((ffn_fused_kernel<4, 2>), dim3(blocks), dim3(kFfnThreads), 0, st, a);
-        else hipLaunchKernelGGL((ffn_fused_kernel<1, 4>), dim3(blocks), dim3(kFfnThreads), 0, st, a);
+        hipLaunchKernelGGL(ffn_fused_kernel, dim3(blocks), dim3(kFfnThreads), 0, st, a);
     } else {
         // one grid row per possible request row; rows >= n_local leave at once
         const long long rows = static_cast<long long>(T) * k;
