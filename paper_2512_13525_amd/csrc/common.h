@@ -38,6 +38,11 @@ inline int check_launch(const char *where) {
     return MOE_OK;
 }
 
+// bf16 grouped FFN as two streaming launches (ffn_stream.hip); shapes validated by the caller
+void launch_ffn_stream(const void *X, const void *W13p, const void *W2p, int T, int k, int C, int d_h, int d_e,
+                       const int32_t *slot_off, const int32_t *perm, uint16_t *act, int act_stride,
+                       float *Yp, hipStream_t st);
+
 inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 
 __device__ __forceinline__ int lane_id() { return threadIdx.x & (MOE_WAVE - 1); }

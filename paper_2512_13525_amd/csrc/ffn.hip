@@ -806,6 +806,13 @@ extern "C" int moe_grouped_ffn(const void *X_dev, const void *W13_dev, const voi
     hipStream_t st = static_cast<hipStream_t>(stream);
     char *ws = static_cast<char *>(workspace_dev);
     if (dtype == MOE_DTYPE_BF16) {
+        static const bool use_stream = getenv("MOE_JANUS_FFN_FUSED") == nullptr;
+        if (use_stream) {
+            moe::launch_ffn_stream(X_dev, W13_dev, W2_dev, T, k, C, d_h, d_e, slot_off_dev, perm_dev,
+                                   reinterpret_cast<uint16_t *>(ws + kCtrlBytes + kPartBytes), (d_e + 63) / 64 * 64,
+                                   Yp_dev, st);
+            return moe::check_launch("moe_grouped_ffn");
+        }
         const int blocks = ffn_grid_blocks(kFfnWgPerCu);
         if (blocks < 1) { moe::set_hip_error(hipErrorInvalidDevice, "moe_grouped_ffn/device query"); return MOE_EHIP; }
         FfnArgs a;

@@ -1,0 +1,215 @@
+// a5, bf16 path: the grouped expert FFN as two streaming launches (gate/up + SiLU*up, then down).
+//
+// Janus Sec. 2.2: at decode sizes an expert is two skinny GEMMs whose cost is the weight bytes
+// streamed from HBM, so the layer's latency follows the number of activated experts.  The
+// kernels below are plain oversubscribed streamers: one workgroup per (slot, 16- or 32-channel
+// tile of the output) and K-split part, dispatched by the hardware; a workgroup of a slot
+// without requests leaves at once and never touches that slot's weights.
+//
+// The 4 wavefronts of a workgroup split the K-steps (32 columns each) of the tile round-robin,
+// keep kDepth steps of 128-bit loads in flight each (weights: 1 KiB MFMA A-operand images,
+// fully coalesced; tokens: B operand fetched from L2), and meet in LDS once per pass of 32
+// tokens.  The sum over wavefronts is taken in a fixed order, so results are reproducible.
+#include "common.h"
+
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kDepth = 4;               // K-steps of loads each wavefront keeps in flight
+constexpr int kThreads = 256;
+constexpr int kWaves = kThreads / MOE_WAVE;
+constexpr int kMaxTiles = 2;            // token tiles (of 16) per pass
+
+struct StreamArgs {
+    const uint16_t *B;                   // token operand rows: X (stage 1, through perm) or act (stage 2)
+    const bf16x8 *Wp;                    // packed weights: [C][tiles][KS][2][64] fragments
+    const int32_t *slot_off;
+    const int32_t *perm;
+    uint16_t *act;                       // stage-1 output
+    float *Yp;                           // stage-2 output
+    int k, tiles, KS;
+    int n_tiles_total;                   // C * tiles
+    int b_stride;                        // elements between rows of B
+    int out_stride;                      // elements between rows of the output
+};
+
+__device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+}
+
+__device__ __forceinline__ float silu_mul(float g, float u) { return g / (1.0f + __expf(-g)) * u; }
+
+// One pass: tokens [row0, row0 + NT*16) of the slot (rows >= row_end are padding) against the
+// workgroup's tile.  `w` points at K-step 0 of the tile (wave-uniform).  A wavefront advances in
+// super-steps of SS consecutive K-steps (SS*2 KiB of weights, SS*64 contiguous bytes of every
+// token row: SS = 2 reads whole 128-byte lines of the token rows) and keeps D super-steps in flight.
+template <bool STAGE1, int NT, int SS>
+__device__ __forceinline__ void stream_pass(const StreamArgs &a, f32x4 (*red)[2][kMaxTiles][MOE_WAVE],
+                                            const char *w, int tile, int row0, int row_end,
+                                            int wave, int lane) {
+    constexpr int D = kDepth / SS;
+    // B operand: lane l reads 8 columns (l/16)*8.. of token row l%16 of every token tile.  Weights
+    // and tokens are both addressed as a wave-uniform base (scalar registers, advanced per K-step)
+    // plus a constant 32-bit per-lane byte offset.
+    const uint32_t aoff = lane * 16;
+    uint32_t boff[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+        int r = row0 + t * 16 + (lane & 15);
+        r = r < row_end ? r : row_end - 1;
+        const uint32_t src = STAGE1 ? static_cast<uint32_t>(a.perm[r] / a.k) : static_cast<uint32_t>(r);
+        boff[t] = (src * static_cast<uint32_t>(a.b_stride) + (lane >> 4) * 8) * 2;
+    }
+    const char *bbase = reinterpret_cast<const char *>(a.B);
+    const int n = (a.KS / SS - wave + kWaves - 1) / kWaves;     // super-steps wave, wave+4, ... of this wavefront
+    f32x4 acc[2][NT];
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+        for (int t = 0; t < NT; ++t) acc[h][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    if (n > 0) {
+        // Ring entry d holds super-step i+d.  The steady-state loop has no branch, so the compiler
+        // counts outstanding loads exactly and each MFMA waits only for its own entry.  Loads past
+        // the last super-step fetch the last one again (a cache hit): every load is unconditional.
+        bf16x8 wr[D][SS][2], br[D][SS][NT];
+        const int last = n - 1;
+        // Workgroups start their K loop at different places (and wrap around) so that they do not
+        // march through equally aligned tiles in lockstep.
+        const int rot = static_cast<int>(blockIdx.x % static_cast<unsigned>(n));
+#define MOE_LOAD_STEP(d, step)                                                                   \
+        do {                                                                                     \
+            const int q_ = (step);                                                               \
+            int r_ = (q_ < last ? q_ : last) + rot;                                              \
+            r_ = r_ >= n ? r_ - n : r_;                                                          \
+            const int s_ = wave + kWaves * r_;                                                   \
+            const char *ws_ = w + static_cast<size_t>(s_) * (2048 * SS);                         \
+            const char *bs_ = bbase + static_cast<size_t>(s_) * (64 * SS);                       \
+            _Pragma("unroll") for (int ss = 0; ss < SS; ++ss) {                                  \
+                wr[d][ss][0] = *reinterpret_cast<const bf16x8 *>(ws_ + ss * 2048 + aoff);        \
+                wr[d][ss][1] = *reinterpret_cast<const bf16x8 *>(ws_ + ss * 2048 + 1024 + aoff); \
+            }                                                                                    \
+            _Pragma("unroll") for (int t = 0; t < NT; ++t)                                       \
+                _Pragma("unroll") for (int ss = 0; ss < SS; ++ss)                                \
+                    br[d][ss][t] = *reinterpret_cast<const bf16x8 *>(bs_ + ss * 64 + boff[t]);   \
+            asm volatile("" ::: "memory");                                                       \
+        } while (0)
+#define MOE_MMA_STEP(d)                                                                          \
+        do {                                                                                     \
+            _Pragma("unroll") for (int ss = 0; ss < SS; ++ss)                                    \
+                _Pragma("unroll") for (int t = 0; t < NT; ++t) {                                 \
+                    acc[0][t] = mfma16(wr[d][ss][0], br[d][ss][t], acc[0][t]);                   \
+                    acc[1][t] = mfma16(wr[d][ss][1], br[d][ss][t], acc[1][t]);                   \
+                }                                                                                \
+        } while (0)
+#pragma unroll
+        for (int d = 0; d < D; ++d) MOE_LOAD_STEP(d, d);
+        int i = 0;
+        for (; i + 2 * D <= n; i += D) {
+#pragma unroll
+            for (int d = 0; d < D; ++d) {
+                MOE_MMA_STEP(d);
+                MOE_LOAD_STEP(d, i + d + D);
+            }
+        }
+        const int rem = n - i;                                   // 1 .. 2*D-1 super-steps left
+#pragma unroll
+        for (int d = 0; d < D; ++d) {
+            if (d < rem) MOE_MMA_STEP(d);
+            if (d < D - 1) MOE_LOAD_STEP(d, i + d + D);
+        }
+#pragma unroll
+        for (int d = 0; d < D - 1; ++d)
+            if (D + d < rem) MOE_MMA_STEP(d);
+#undef MOE_LOAD_STEP
+#undef MOE_MMA_STEP
+    }
+
+    // split-K reduction over the 4 wavefronts in LDS, fixed order
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+        for (int t = 0; t < NT; ++t) red[wave][h][t][lane] = acc[h][t];
+    __syncthreads();
+    if (STAGE1) {
+        // lane-slot (t, l) holds gate/up channels tile*16 + (l/16)*4 .. +3 of token row0 + t*16 + l%16
+        for (int item = threadIdx.x; item < NT * MOE_WAVE; item += kThreads) {
+            const int t = item / MOE_WAVE, l = item % MOE_WAVE;
+            f32x4 g = red[0][0][t][l], u = red[0][1][t][l];
+#pragma unroll
+            for (int wv = 1; wv < kWaves; ++wv) { g += red[wv][0][t][l]; u += red[wv][1][t][l]; }
+            const int r = row0 + t * 16 + (l & 15);
+            if (r < row_end) {
+                ushort4 o;
+                o.x = moe::f32_to_bf16(silu_mul(g[0], u[0]));
+                o.y = moe::f32_to_bf16(silu_mul(g[1], u[1]));
+                o.z = moe::f32_to_bf16(silu_mul(g[2], u[2]));
+                o.w = moe::f32_to_bf16(silu_mul(g[3], u[3]));
+                *reinterpret_cast<ushort4 *>(a.act + static_cast<size_t>(r) * a.out_stride + tile * 16 + (l >> 4) * 4) = o;
+            }
+        }
+    } else {
+        // lane-slot (h, t, l) holds output channels tile*32 + h*16 + (l/16)*4 .. +3
+        for (int item = threadIdx.x; item < 2 * NT * MOE_WAVE; item += kThreads) {
+            const int h = item / (NT * MOE_WAVE), t = item / MOE_WAVE % NT, l = item % MOE_WAVE;
+            f32x4 y = red[0][h][t][l];
+#pragma unroll
+            for (int wv = 1; wv < kWaves; ++wv) y += red[wv][h][t][l];
+            const int r = row0 + t * 16 + (l & 15);
+            if (r < row_end)
+                *reinterpret_cast<f32x4 *>(a.Yp + static_cast<size_t>(r) * a.out_stride + tile * 32 + h * 16 + (l >> 4) * 4) = y;
+        }
+    }
+}
+
+// grid (x: slot*tiles + tile, padded to a multiple of 8; y: block of 32 tokens of the slot).  The
+// padding keeps all token blocks of a tile on one XCD (workgroups go to XCDs round-robin in linear
+// order), so the tile's weights are fetched from HBM once and shared through that XCD's L2.
+template <bool STAGE1, int SS>
+__global__ __launch_bounds__(kThreads, 4)
+void ffn_stream_kernel(StreamArgs a) {
+    __shared__ f32x4 red[kWaves][2][kMaxTiles][MOE_WAVE];
+    if (blockIdx.x >= static_cast<unsigned>(a.n_tiles_total)) return;
+    const int slot = blockIdx.x / a.tiles, tile = blockIdx.x % a.tiles;
+    const int lo = a.slot_off[slot], hi = a.slot_off[slot + 1];
+    const int row0 = lo + blockIdx.y * (kMaxTiles * 16);
+    if (row0 >= hi) return;                  // no such token block (or slot not activated: its weights stay unread)
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / MOE_WAVE), lane = threadIdx.x % MOE_WAVE;
+    const char *w = reinterpret_cast<const char *>(a.Wp) + (static_cast<size_t>(slot) * a.tiles + tile) * a.KS * 2048;
+    if (hi - row0 <= 16) stream_pass<STAGE1, 1, SS>(a, red, w, tile, row0, hi, wave, lane);
+    else stream_pass<STAGE1, 2, SS>(a, red, w, tile, row0, hi, wave, lane);
+}
+
+template <bool STAGE1>
+void launch_stage(const StreamArgs &a, int C, int T, hipStream_t st) {
+    const dim3 grid((a.n_tiles_total + 7) / 8 * 8, (T + kMaxTiles * 16 - 1) / (kMaxTiles * 16));
+    if (a.KS % 2 == 0) hipLaunchKernelGGL((ffn_stream_kernel<STAGE1, 2>), grid, dim3(kThreads), 0, st, a);
+    else hipLaunchKernelGGL((ffn_stream_kernel<STAGE1, 1>), grid, dim3(kThreads), 0, st, a);
+}
+
+}  // namespace
+
+namespace moe {
+
+// Launches both stages on `st`.  Shapes were validated by the caller (d_h, d_e multiples of 32).
+void launch_ffn_stream(const void *X, const void *W13p, const void *W2p, int T, int k, int C, int d_h, int d_e,
+                       const int32_t *slot_off, const int32_t *perm, uint16_t *act, int act_stride,
+                       float *Yp, hipStream_t st) {
+    // a slot receives at most one request per token, so T bounds its rows
+    StreamArgs a;
+    a.slot_off = slot_off; a.perm = perm; a.act = act; a.Yp = Yp; a.k = k;
+    a.B = static_cast<const uint16_t *>(X);
+    a.Wp = static_cast<const bf16x8 *>(W13p);
+    a.tiles = d_e / 16; a.KS = d_h / 32; a.b_stride = d_h; a.out_stride = act_stride;
+    a.n_tiles_total = C * a.tiles;
+    launch_stage<true>(a, C, T, st);
+    a.B = act;
+    a.Wp = static_cast<const bf16x8 *>(W2p);
+    a.tiles = d_h / 32; a.KS = d_e / 32; a.b_stride = act_stride; a.out_stride = d_h;
+    a.n_tiles_total = C * a.tiles;
+    launch_stage<false>(a, C, T, st);
+}
+
+}  // namespace moe
