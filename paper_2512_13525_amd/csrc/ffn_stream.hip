@@ -22,6 +22,11 @@ constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / MOE_WAVE;
 constexpr int kMaxTiles = 2;            // token tiles (of 16) per pass
 
+#ifdef MOE_STREAM_TRACE
+// timeline of every workgroup (debug builds only): [stage][linear id][start, first data, end, xcc/cu]
+__device__ long long g_trace[2][1 << 15][4];
+#endif
+
 struct StreamArgs {
     const uint16_t *B;                   // token operand rows: X (stage 1, through perm) or act (stage 2)
     const bf16x8 *Wp;                    // packed weights: [C][tiles][KS][2][64] fragments
@@ -30,7 +35,6 @@ struct StreamArgs {
     uint16_t *act;                       // stage-1 output
     float *Yp;                           // stage-2 output
     int k, tiles, KS;
-    int n_tiles_total;                   // C * tiles
     int b_stride;                        // elements between rows of B
     int out_stride;                      // elements between rows of the output
 };
@@ -40,6 +44,49 @@ __device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
 }
 
 __device__ __forceinline__ float silu_mul(float g, float u) { return g / (1.0f + __expf(-g)) * u; }
+
+// Split-K reduction over the 4 wavefronts in LDS (fixed order), then the epilogue: SiLU(gate)*up
+// rounded once to bf16 (stage 1) or the fp32 partial output rows (stage 2).
+template <bool STAGE1, int NT>
+__device__ __forceinline__ void reduce_store(const StreamArgs &a, f32x4 (*red)[2][kMaxTiles][MOE_WAVE],
+                                             f32x4 (&acc)[2][NT], int tile, int row0, int row_end,
+                                             int wave, int lane) {
+    // split-K reduction over the 4 wavefronts in LDS, fixed order
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+        for (int t = 0; t < NT; ++t) red[wave][h][t][lane] = acc[h][t];
+    __syncthreads();
+    if (STAGE1) {
+        // lane-slot (t, l) holds gate/up channels tile*16 + (l/16)*4 .. +3 of token row0 + t*16 + l%16
+        for (int item = threadIdx.x; item < NT * MOE_WAVE; item += kThreads) {
+            const int t = item / MOE_WAVE, l = item % MOE_WAVE;
+            f32x4 g = red[0][0][t][l], u = red[0][1][t][l];
+#pragma unroll
+            for (int wv = 1; wv < kWaves; ++wv) { g += red[wv][0][t][l]; u += red[wv][1][t][l]; }
+            const int r = row0 + t * 16 + (l & 15);
+            if (r < row_end) {
+                ushort4 o;
+                o.x = moe::f32_to_bf16(silu_mul(g[0], u[0]));
+                o.y = moe::f32_to_bf16(silu_mul(g[1], u[1]));
+                o.z = moe::f32_to_bf16(silu_mul(g[2], u[2]));
+                o.w = moe::f32_to_bf16(silu_mul(g[3], u[3]));
+                *reinterpret_cast<ushort4 *>(a.act + static_cast<size_t>(r) * a.out_stride + tile * 16 + (l >> 4) * 4) = o;
+            }
+        }
+    } else {
+        // lane-slot (h, t, l) holds output channels tile*32 + h*16 + (l/16)*4 .. +3
+        for (int item = threadIdx.x; item < 2 * NT * MOE_WAVE; item += kThreads) {
+            const int h = item / (NT * MOE_WAVE), t = item / MOE_WAVE % NT, l = item % MOE_WAVE;
+            f32x4 y = red[0][h][t][l];
+#pragma unroll
+            for (int wv = 1; wv < kWaves; ++wv) y += red[wv][h][t][l];
+            const int r = row0 + t * 16 + (l & 15);
+            if (r < row_end)
+                *reinterpret_cast<f32x4 *>(a.Yp + static_cast<size_t>(r) * a.out_stride + tile * 32 + h * 16 + (l >> 4) * 4) = y;
+        }
+    }
+}
 
 // One pass: tokens [row0, row0 + NT*16) of the slot (rows >= row_end are padding) against the
 // workgroup's tile.  `w` points at K-step 0 of the tile (wave-uniform).  A wavefront advances in
@@ -127,66 +174,149 @@ __device__ __forceinline__ void stream_pass(const StreamArgs &a, f32x4 (*red)[2]
 #undef MOE_MMA_STEP
     }
 
-    // split-K reduction over the 4 wavefronts in LDS, fixed order
+    reduce_store<STAGE1, NT>(a, red, acc, tile, row0, row_end, wave, lane);
+}
+
+// The same pass for an even number of K-steps, with whole-line token reads.  A super-step is two
+// K-steps = 64 columns = one 128-byte line of every token row.  A load instruction fetches 8 rows
+// x 128 bytes (lane l: row l/8, 16-byte chunk l%8), so no line is requested twice and none by
+// halves; the MFMA layout (lane l: row l%16, chunk 4*step + l/16) is produced by a round trip
+// through a wave-private 2 KiB LDS tile per 16 rows (chunks XOR-swizzled by row so that both the
+// row-major writes and the column-wise reads spread over the banks).  NH = number of 8-row halves
+// that hold requests (rows past the end repeat the last row; halves past it are not loaded and
+// leave unspecified values in token columns whose results are never stored).
+template <bool STAGE1, int NH>
+__device__ __forceinline__ void stream_pass_lines(const StreamArgs &a, char *lds, const char *w, int tile,
+                                                  int row0, int row_end, int wave, int lane) {
+    constexpr int NT = (NH + 1) / 2;
+    constexpr int D = kDepth / 2;
+    f32x4 (*red)[2][kMaxTiles][MOE_WAVE] = reinterpret_cast<f32x4 (*)[2][kMaxTiles][MOE_WAVE]>(lds);
+    char *stg = lds + wave * (kMaxTiles * 2048);
+    const uint32_t aoff = lane * 16;
+    uint32_t boff[NH];
+#pragma unroll
+    for (int h = 0; h < NH; ++h) {
+        int r = row0 + h * 8 + (lane >> 3);
+        r = r < row_end ? r : row_end - 1;
+        const uint32_t src = STAGE1 ? static_cast<uint32_t>(a.perm[r] / a.k) : static_cast<uint32_t>(r);
+        boff[h] = src * static_cast<uint32_t>(a.b_stride) * 2 + (lane & 7) * 16;
+    }
+    // LDS addresses: write row (h%2)*8 + l/8 of tile h/2, chunk l%8; read row l%16, chunk 4*ss + l/16
+    const uint32_t wr_lds = ((lane >> 3) * 128) + (((lane & 7) ^ (lane >> 3)) * 16);
+    const uint32_t rd_row = (lane & 15) * 128, rd_sw = lane & 7, rd_g = lane >> 4;
+    const char *bbase = reinterpret_cast<const char *>(a.B);
+    const int n = (a.KS / 2 - wave + kWaves - 1) / kWaves;      // super-steps wave, wave+4, ... of this wavefront
+    f32x4 acc[2][NT];
 #pragma unroll
     for (int h = 0; h < 2; ++h)
 #pragma unroll
-        for (int t = 0; t < NT; ++t) red[wave][h][t][lane] = acc[h][t];
-    __syncthreads();
-    if (STAGE1) {
-        // lane-slot (t, l) holds gate/up channels tile*16 + (l/16)*4 .. +3 of token row0 + t*16 + l%16
-        for (int item = threadIdx.x; item < NT * MOE_WAVE; item += kThreads) {
-            const int t = item / MOE_WAVE, l = item % MOE_WAVE;
-            f32x4 g = red[0][0][t][l], u = red[0][1][t][l];
+        for (int t = 0; t < NT; ++t) acc[h][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    if (n > 0) {
+        bf16x8 wr[D][2][2], br[D][NH];
+        const int last = n - 1;
+        const int rot = static_cast<int>(blockIdx.x % static_cast<unsigned>(n));
+#define MOE_LOAD_STEP(d, step)                                                                   \
+        do {                                                                                     \
+            const int q_ = (step);                                                               \
+            int r_ = (q_ < last ? q_ : last) + rot;                                              \
+            r_ = r_ >= n ? r_ - n : r_;                                                          \
+            const int s_ = wave + kWaves * r_;                                                   \
+            const char *ws_ = w + static_cast<size_t>(s_) * 4096;                                \
+            const char *bs_ = bbase + static_cast<size_t>(s_) * 128;                             \
+            _Pragma("unroll") for (int ss = 0; ss < 2; ++ss) {                                   \
+                wr[d][ss][0] = *reinterpret_cast<const bf16x8 *>(ws_ + ss * 2048 + aoff);        \
+                wr[d][ss][1] = *reinterpret_cast<const bf16x8 *>(ws_ + ss * 2048 + 1024 + aoff); \
+            }                                                                                    \
+            _Pragma("unroll") for (int h = 0; h < NH; ++h)                                       \
+                br[d][h] = *reinterpret_cast<const bf16x8 *>(bs_ + boff[h]);                     \
+            asm volatile("" ::: "memory");                                                       \
+        } while (0)
+#define MOE_MMA_STEP(d)                                                                          \
+        do {                                                                                     \
+            _Pragma("unroll") for (int h = 0; h < NH; ++h)                                       \
+                *reinterpret_cast<bf16x8 *>(stg + (h / 2) * 2048 + (h % 2) * 1024 + wr_lds) = br[d][h]; \
+            _Pragma("unroll") for (int ss = 0; ss < 2; ++ss)                                     \
+                _Pragma("unroll") for (int t = 0; t < NT; ++t) {                                 \
+                    const bf16x8 bf_ = *reinterpret_cast<const bf16x8 *>(                        \
+                        stg + t * 2048 + rd_row + (((4 * ss + rd_g) ^ rd_sw) * 16));             \
+                    acc[0][t] = mfma16(wr[d][ss][0], bf_, acc[0][t]);                            \
+                    acc[1][t] = mfma16(wr[d][ss][1], bf_, acc[1][t]);                            \
+                }                                                                                \
+        } while (0)
 #pragma unroll
-            for (int wv = 1; wv < kWaves; ++wv) { g += red[wv][0][t][l]; u += red[wv][1][t][l]; }
-            const int r = row0 + t * 16 + (l & 15);
-            if (r < row_end) {
-                ushort4 o;
-                o.x = moe::f32_to_bf16(silu_mul(g[0], u[0]));
-                o.y = moe::f32_to_bf16(silu_mul(g[1], u[1]));
-                o.z = moe::f32_to_bf16(silu_mul(g[2], u[2]));
-                o.w = moe::f32_to_bf16(silu_mul(g[3], u[3]));
-                *reinterpret_cast<ushort4 *>(a.act + static_cast<size_t>(r) * a.out_stride + tile * 16 + (l >> 4) * 4) = o;
+        for (int d = 0; d < D; ++d) MOE_LOAD_STEP(d, d);
+        int i = 0;
+        for (; i + 2 * D <= n; i += D) {
+#pragma unroll
+            for (int d = 0; d < D; ++d) {
+                MOE_MMA_STEP(d);
+                MOE_LOAD_STEP(d, i + d + D);
             }
         }
-    } else {
-        // lane-slot (h, t, l) holds output channels tile*32 + h*16 + (l/16)*4 .. +3
-        for (int item = threadIdx.x; item < 2 * NT * MOE_WAVE; item += kThreads) {
-            const int h = item / (NT * MOE_WAVE), t = item / MOE_WAVE % NT, l = item % MOE_WAVE;
-            f32x4 y = red[0][h][t][l];
+        const int rem = n - i;                                   // 1 .. 2*D-1 super-steps left
 #pragma unroll
-            for (int wv = 1; wv < kWaves; ++wv) y += red[wv][h][t][l];
-            const int r = row0 + t * 16 + (l & 15);
-            if (r < row_end)
-                *reinterpret_cast<f32x4 *>(a.Yp + static_cast<size_t>(r) * a.out_stride + tile * 32 + h * 16 + (l >> 4) * 4) = y;
+        for (int d = 0; d < D; ++d) {
+            if (d < rem) MOE_MMA_STEP(d);
+            if (d < D - 1) MOE_LOAD_STEP(d, i + d + D);
         }
+#pragma unroll
+        for (int d = 0; d < D - 1; ++d)
+            if (D + d < rem) MOE_MMA_STEP(d);
+#undef MOE_LOAD_STEP
+#undef MOE_MMA_STEP
     }
+    __syncthreads();                                             // the staging tiles are reused for the reduction
+    reduce_store<STAGE1, NT>(a, red, acc, tile, row0, row_end, wave, lane);
 }
 
-// grid (x: slot*tiles + tile, padded to a multiple of 8; y: block of 32 tokens of the slot).  The
-// padding keeps all token blocks of a tile on one XCD (workgroups go to XCDs round-robin in linear
-// order), so the tile's weights are fetched from HBM once and shared through that XCD's L2.
-template <bool STAGE1, int SS>
+// grid (x: slot*tiles + tile; y: block of 32 tokens of the slot).  LINES selects the whole-line
+// token path (even number of K-steps).
+template <bool STAGE1, bool LINES>
 __global__ __launch_bounds__(kThreads, 4)
 void ffn_stream_kernel(StreamArgs a) {
-    __shared__ f32x4 red[kWaves][2][kMaxTiles][MOE_WAVE];
-    if (blockIdx.x >= static_cast<unsigned>(a.n_tiles_total)) return;
+    // split-K reduction buffer [4 waves][2][kMaxTiles][64] x 16 B, which the whole-line path also
+    // uses as its per-wavefront staging tiles during the K loop
+    __shared__ __attribute__((aligned(16))) char lds[kWaves * 2 * kMaxTiles * MOE_WAVE * 16];
+    static_assert(kWaves * kMaxTiles * 2048 <= sizeof(lds), "staging tiles must fit in the reduction buffer");
+#ifdef MOE_STREAM_TRACE
+    const long long t_start = wall_clock64();
+    const unsigned lin = blockIdx.y * gridDim.x + blockIdx.x;
+#endif
     const int slot = blockIdx.x / a.tiles, tile = blockIdx.x % a.tiles;
     const int lo = a.slot_off[slot], hi = a.slot_off[slot + 1];
     const int row0 = lo + blockIdx.y * (kMaxTiles * 16);
     if (row0 >= hi) return;                  // no such token block (or slot not activated: its weights stay unread)
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / MOE_WAVE), lane = threadIdx.x % MOE_WAVE;
-    const char *w = reinterpret_cast<const char *>(a.Wp) + (static_cast<size_t>(slot) * a.tiles + tile) * a.KS * 2048;
-    if (hi - row0 <= 16) stream_pass<STAGE1, 1, SS>(a, red, w, tile, row0, hi, wave, lane);
-    else stream_pass<STAGE1, 2, SS>(a, red, w, tile, row0, hi, wave, lane);
+    const char *w = reinterpret_cast<const char *>(a.Wp) + static_cast<size_t>(blockIdx.x) * a.KS * 2048;
+    const int m = hi - row0;
+    if (LINES) {
+        if (m <= 8) stream_pass_lines<STAGE1, 1>(a, lds, w, tile, row0, hi, wave, lane);
+        else if (m <= 16) stream_pass_lines<STAGE1, 2>(a, lds, w, tile, row0, hi, wave, lane);
+        else if (m <= 24) stream_pass_lines<STAGE1, 3>(a, lds, w, tile, row0, hi, wave, lane);
+        else stream_pass_lines<STAGE1, 4>(a, lds, w, tile, row0, hi, wave, lane);
+    } else {
+        f32x4 (*red)[2][kMaxTiles][MOE_WAVE] = reinterpret_cast<f32x4 (*)[2][kMaxTiles][MOE_WAVE]>(lds);
+        if (m <= 16) stream_pass<STAGE1, 1, 1>(a, red, w, tile, row0, hi, wave, lane);
+        else stream_pass<STAGE1, 2, 1>(a, red, w, tile, row0, hi, wave, lane);
+    }
+#ifdef MOE_STREAM_TRACE
+    if (threadIdx.x == 0 && lin < (1u << 15)) {
+        unsigned hwid;
+        asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(hwid));
+        unsigned hw2;
+        asm volatile("s_getreg_b32 %0, hwreg(HW_REG_HW_ID)" : "=s"(hw2));
+        long long *tr = g_trace[STAGE1 ? 0 : 1][lin];
+        tr[0] = t_start; tr[1] = hi - row0; tr[2] = wall_clock64(); tr[3] = (static_cast<long long>(hwid) << 32) | hw2;
+    }
+#endif
 }
 
 template <bool STAGE1>
 void launch_stage(const StreamArgs &a, int C, int T, hipStream_t st) {
-    const dim3 grid((a.n_tiles_total + 7) / 8 * 8, (T + kMaxTiles * 16 - 1) / (kMaxTiles * 16));
-    if (a.KS % 2 == 0) hipLaunchKernelGGL((ffn_stream_kernel<STAGE1, 2>), grid, dim3(kThreads), 0, st, a);
-    else hipLaunchKernelGGL((ffn_stream_kernel<STAGE1, 1>), grid, dim3(kThreads), 0, st, a);
+    const dim3 grid(C * a.tiles, (T + kMaxTiles * 16 - 1) / (kMaxTiles * 16));
+    if (a.KS % 2 == 0) hipLaunchKernelGGL((ffn_stream_kernel<STAGE1, true>), grid, dim3(kThreads), 0, st, a);
+    else hipLaunchKernelGGL((ffn_stream_kernel<STAGE1, false>), grid, dim3(kThreads), 0, st, a);
 }
 
 }  // namespace
@@ -203,13 +333,17 @@ void launch_ffn_stream(const void *X, const void *W13p, const void *W2p, int T, 
     a.B = static_cast<const uint16_t *>(X);
     a.Wp = static_cast<const bf16x8 *>(W13p);
     a.tiles = d_e / 16; a.KS = d_h / 32; a.b_stride = d_h; a.out_stride = act_stride;
-    a.n_tiles_total = C * a.tiles;
     launch_stage<true>(a, C, T, st);
     a.B = act;
     a.Wp = static_cast<const bf16x8 *>(W2p);
     a.tiles = d_h / 32; a.KS = d_e / 32; a.b_stride = act_stride; a.out_stride = d_h;
-    a.n_tiles_total = C * a.tiles;
     launch_stage<false>(a, C, T, st);
 }
 
 }  // namespace moe
+
+#ifdef MOE_STREAM_TRACE
+extern "C" int moe_debug_stream_trace(long long *host, size_t bytes) {
+    return hipMemcpyFromSymbol(host, HIP_SYMBOL(g_trace), bytes) == hipSuccess ? 0 : 1;
+}
+#endif
