@@ -20,7 +20,8 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 constexpr int kDepth = 4;               // K-steps of loads each wavefront keeps in flight
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / MOE_WAVE;
-constexpr int kMaxTiles = 2;            // token tiles (of 16) per pass
+constexpr int kMaxTiles = 2;            // token tiles (of 16) per workgroup
+constexpr int kBlockTok = kMaxTiles * 16; // tokens of a slot one workgroup takes
 
 #ifdef MOE_STREAM_TRACE
 // timeline of every workgroup (debug builds only): [stage][linear id][start, first data, end, xcc/cu]
@@ -34,7 +35,8 @@ struct StreamArgs {
     const int32_t *perm;
     uint16_t *act;                       // stage-1 output
     float *Yp;                           // stage-2 output
-    int k, tiles, KS;
+    int k, C, tiles, KS;
+    int tiles_pad;                       // tiles rounded up to a multiple of 8
     int b_stride;                        // elements between rows of B
     int out_stride;                      // elements between rows of the output
 };
@@ -125,7 +127,7 @@ __device__ __forceinline__ void stream_pass(const StreamArgs &a, f32x4 (*red)[2]
         const int last = n - 1;
         // Workgroups start their K loop at different places (and wrap around) so that they do not
         // march through equally aligned tiles in lockstep.
-        const int rot = static_cast<int>(blockIdx.x % static_cast<unsigned>(n));
+        const int rot = static_cast<int>(static_cast<unsigned>(tile) % static_cast<unsigned>(n));
 #define MOE_LOAD_STEP(d, step)                                                                   \
         do {                                                                                     \
             const int q_ = (step);                                                               \
@@ -213,29 +215,43 @@ __device__ __forceinline__ void stream_pass_lines(const StreamArgs &a, char *lds
         for (int t = 0; t < NT; ++t) acc[h][t] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     if (n > 0) {
-        bf16x8 wr[D][2][2], br[D][NH];
+        // Weights run D super-steps ahead (ring wr); the token rows, which come from L2, only one:
+        // the loads of super-step q+1 are issued in iteration q *before* the weights of q+D, so that
+        // waiting for them (loads return in order) leaves those weights in flight.
+        bf16x8 wr[D][2][2], br[NH];
         const int last = n - 1;
-        const int rot = static_cast<int>(blockIdx.x % static_cast<unsigned>(n));
-#define MOE_LOAD_STEP(d, step)                                                                   \
-        do {                                                                                     \
+        const int rot = static_cast<int>(static_cast<unsigned>(tile) % static_cast<unsigned>(n));
+#define MOE_STEP_INDEX(step)                                                                     \
             const int q_ = (step);                                                               \
             int r_ = (q_ < last ? q_ : last) + rot;                                              \
             r_ = r_ >= n ? r_ - n : r_;                                                          \
-            const int s_ = wave + kWaves * r_;                                                   \
+            const int s_ = wave + kWaves * r_;
+#define MOE_LOAD_A(d, step)                                                                      \
+        do {                                                                                     \
+            MOE_STEP_INDEX(step)                                                                 \
             const char *ws_ = w + static_cast<size_t>(s_) * 4096;                                \
-            const char *bs_ = bbase + static_cast<size_t>(s_) * 128;                             \
             _Pragma("unroll") for (int ss = 0; ss < 2; ++ss) {                                   \
                 wr[d][ss][0] = *reinterpret_cast<const bf16x8 *>(ws_ + ss * 2048 + aoff);        \
                 wr[d][ss][1] = *reinterpret_cast<const bf16x8 *>(ws_ + ss * 2048 + 1024 + aoff); \
             }                                                                                    \
+            asm volatile("" ::: "memory");                                                       \
+        } while (0)
+#define MOE_LOAD_B(step)                                                                         \
+        do {                                                                                     \
+            MOE_STEP_INDEX(step)                                                                 \
+            const char *bs_ = bbase + static_cast<size_t>(s_) * 128;                             \
             _Pragma("unroll") for (int h = 0; h < NH; ++h)                                       \
-                br[d][h] = *reinterpret_cast<const bf16x8 *>(bs_ + boff[h]);                     \
+                br[h] = *reinterpret_cast<const bf16x8 *>(bs_ + boff[h]);                        \
+            asm volatile("" ::: "memory");                                                       \
+        } while (0)
+#define MOE_STAGE_B()                                                                            \
+        do {                                                                                     \
+            _Pragma("unroll") for (int h = 0; h < NH; ++h)                                       \
+                *reinterpret_cast<bf16x8 *>(stg + (h / 2) * 2048 + (h % 2) * 1024 + wr_lds) = br[h]; \
             asm volatile("" ::: "memory");                                                       \
         } while (0)
 #define MOE_MMA_STEP(d)                                                                          \
         do {                                                                                     \
-            _Pragma("unroll") for (int h = 0; h < NH; ++h)                                       \
-                *reinterpret_cast<bf16x8 *>(stg + (h / 2) * 2048 + (h % 2) * 1024 + wr_lds) = br[d][h]; \
             _Pragma("unroll") for (int ss = 0; ss < 2; ++ss)                                     \
                 _Pragma("unroll") for (int t = 0; t < NT; ++t) {                                 \
                     const bf16x8 bf_ = *reinterpret_cast<const bf16x8 *>(                        \
@@ -243,35 +259,83 @@ __device__ __forceinline__ void stream_pass_lines(const StreamArgs &a, char *lds
                     acc[0][t] = mfma16(wr[d][ss][0], bf_, acc[0][t]);                            \
                     acc[1][t] = mfma16(wr[d][ss][1], bf_, acc[1][t]);                            \
                 }                                                                                \
+            asm volatile("" ::: "memory");                                                       \
         } while (0)
+        MOE_LOAD_B(0);
 #pragma unroll
-        for (int d = 0; d < D; ++d) MOE_LOAD_STEP(d, d);
+        for (int d = 0; d < D; ++d) MOE_LOAD_A(d, d);
         int i = 0;
         for (; i + 2 * D <= n; i += D) {
 #pragma unroll
             for (int d = 0; d < D; ++d) {
+                MOE_STAGE_B();
+                MOE_LOAD_B(i + d + 1);
                 MOE_MMA_STEP(d);
-                MOE_LOAD_STEP(d, i + d + D);
+                MOE_LOAD_A(d, i + d + D);
             }
         }
         const int rem = n - i;                                   // 1 .. 2*D-1 super-steps left
 #pragma unroll
         for (int d = 0; d < D; ++d) {
+            MOE_STAGE_B();
+            MOE_LOAD_B(i + d + 1);
             if (d < rem) MOE_MMA_STEP(d);
-            if (d < D - 1) MOE_LOAD_STEP(d, i + d + D);
+            if (d < D - 1) MOE_LOAD_A(d, i + d + D);
         }
 #pragma unroll
-        for (int d = 0; d < D - 1; ++d)
+        for (int d = 0; d < D - 1; ++d) {
+            MOE_STAGE_B();
+            if (d < D - 2) MOE_LOAD_B(i + D + d + 1);
             if (D + d < rem) MOE_MMA_STEP(d);
-#undef MOE_LOAD_STEP
+        }
+#undef MOE_STEP_INDEX
+#undef MOE_LOAD_A
+#undef MOE_LOAD_B
+#undef MOE_STAGE_B
 #undef MOE_MMA_STEP
     }
     __syncthreads();                                             // the staging tiles are reused for the reduction
     reduce_store<STAGE1, NT>(a, red, acc, tile, row0, row_end, wave, lane);
 }
 
-// grid (x: slot*tiles + tile; y: block of 32 tokens of the slot).  LINES selects the whole-line
-// token path (even number of K-steps).
+__device__ __forceinline__ int wave_scan_inclusive(int v, int lane) {
+#pragma unroll
+    for (int off = 1; off < MOE_WAVE; off <<= 1) {
+        const int o = __shfl_up(v, off, MOE_WAVE);
+        if (lane >= off) v += o;
+    }
+    return v;
+}
+
+// Work item j of the launch: the j-th block of kBlockTok tokens when the blocks of all slots are
+// listed in slot order (blocks of a slot adjacent).  Every wavefront works this out for itself
+// from slot_off (C <= 256 slots, 4 per lane).  Returns false past the last block.
+__device__ __forceinline__ bool find_item(const int32_t *__restrict__ slot_off, int C, int j, int lane,
+                                          int *slot, int *blk) {
+    int base = 0;
+    for (int c0 = 0; c0 < C; c0 += MOE_WAVE) {
+        const int sidx = c0 + lane;
+        const int cnt = sidx < C ? slot_off[sidx + 1] - slot_off[sidx] : 0;
+        const int v = (cnt + kBlockTok - 1) / kBlockTok;
+        const int incl = wave_scan_inclusive(v, lane);
+        const int lo = base + incl - v;
+        const uint64_t hit = __ballot(v > 0 && j >= lo && j < lo + v);
+        if (hit) {
+            const int l = __builtin_ctzll(hit);
+            *slot = c0 + l;
+            *blk = j - __builtin_amdgcn_readlane(lo, l);
+            return true;
+        }
+        base += __builtin_amdgcn_readlane(incl, MOE_WAVE - 1);
+    }
+    return false;
+}
+
+// 1-D grid: workgroup id = item * tiles_pad + tile (tiles_pad = tiles rounded up to a multiple of
+// 8).  Workgroups are dispatched in id order and go to the XCDs round-robin, so the token blocks
+// of one tile of a slot (ids tiles_pad apart) run on the same XCD at about the same time: the
+// tile's weights come from HBM once and are shared through that XCD's L2.  LINES selects the
+// whole-line token path (even number of K-steps).
 template <bool STAGE1, bool LINES>
 __global__ __launch_bounds__(kThreads, 4)
 void ffn_stream_kernel(StreamArgs a) {
@@ -281,14 +345,16 @@ void ffn_stream_kernel(StreamArgs a) {
     static_assert(kWaves * kMaxTiles * 2048 <= sizeof(lds), "staging tiles must fit in the reduction buffer");
 #ifdef MOE_STREAM_TRACE
     const long long t_start = wall_clock64();
-    const unsigned lin = blockIdx.y * gridDim.x + blockIdx.x;
+    const unsigned lin = blockIdx.x;
 #endif
-    const int slot = blockIdx.x / a.tiles, tile = blockIdx.x % a.tiles;
-    const int lo = a.slot_off[slot], hi = a.slot_off[slot + 1];
-    const int row0 = lo + blockIdx.y * (kMaxTiles * 16);
-    if (row0 >= hi) return;                  // no such token block (or slot not activated: its weights stay unread)
+    const int tile = blockIdx.x % a.tiles_pad, item = blockIdx.x / a.tiles_pad;
+    if (tile >= a.tiles) return;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / MOE_WAVE), lane = threadIdx.x % MOE_WAVE;
-    const char *w = reinterpret_cast<const char *>(a.Wp) + static_cast<size_t>(blockIdx.x) * a.KS * 2048;
+    int slot, blk;
+    if (!find_item(a.slot_off, a.C, item, lane, &slot, &blk)) return;   // past the last block: nothing is read
+    const int lo = a.slot_off[slot], hi = a.slot_off[slot + 1];
+    const int row0 = lo + blk * kBlockTok;
+    const char *w = reinterpret_cast<const char *>(a.Wp) + (static_cast<size_t>(slot) * a.tiles + tile) * a.KS * 2048;
     const int m = hi - row0;
     if (LINES) {
         if (m <= 8) stream_pass_lines<STAGE1, 1>(a, lds, w, tile, row0, hi, wave, lane);
@@ -296,6 +362,7 @@ void ffn_stream_kernel(StreamArgs a) {
         else if (m <= 24) stream_pass_lines<STAGE1, 3>(a, lds, w, tile, row0, hi, wave, lane);
         else stream_pass_lines<STAGE1, 4>(a, lds, w, tile, row0, hi, wave, lane);
     } else {
+        // odd number of K-steps: half-line token reads
         f32x4 (*red)[2][kMaxTiles][MOE_WAVE] = reinterpret_cast<f32x4 (*)[2][kMaxTiles][MOE_WAVE]>(lds);
         if (m <= 16) stream_pass<STAGE1, 1, 1>(a, red, w, tile, row0, hi, wave, lane);
         else stream_pass<STAGE1, 2, 1>(a, red, w, tile, row0, hi, wave, lane);
@@ -312,9 +379,16 @@ void ffn_stream_kernel(StreamArgs a) {
 #endif
 }
 
+// A slot receives at most one request per token (a token's k experts are distinct), so the
+// launch has at most min(C * ceil(T/kBlockTok), C + T*k/kBlockTok) token blocks.
 template <bool STAGE1>
-void launch_stage(const StreamArgs &a, int C, int T, hipStream_t st) {
-    const dim3 grid(C * a.tiles, (T + kMaxTiles * 16 - 1) / (kMaxTiles * 16));
+void launch_stage(StreamArgs &a, int T, hipStream_t st) {
+    const long long per_slot = (T + kBlockTok - 1) / kBlockTok;
+    long long items = a.C * per_slot;
+    const long long by_rows = a.C + static_cast<long long>(T) * a.k / kBlockTok;
+    if (by_rows < items) items = by_rows;
+    a.tiles_pad = (a.tiles + 7) / 8 * 8;
+    const dim3 grid(static_cast<unsigned>(items * a.tiles_pad));
     if (a.KS % 2 == 0) hipLaunchKernelGGL((ffn_stream_kernel<STAGE1, true>), grid, dim3(kThreads), 0, st, a);
     else hipLaunchKernelGGL((ffn_stream_kernel<STAGE1, false>), grid, dim3(kThreads), 0, st, a);
 }
@@ -329,15 +403,15 @@ void launch_ffn_stream(const void *X, const void *W13p, const void *W2p, int T, 
                        float *Yp, hipStream_t st) {
     // a slot receives at most one request per token, so T bounds its rows
     StreamArgs a;
-    a.slot_off = slot_off; a.perm = perm; a.act = act; a.Yp = Yp; a.k = k;
+    a.slot_off = slot_off; a.perm = perm; a.act = act; a.Yp = Yp; a.k = k; a.C = C;
     a.B = static_cast<const uint16_t *>(X);
     a.Wp = static_cast<const bf16x8 *>(W13p);
     a.tiles = d_e / 16; a.KS = d_h / 32; a.b_stride = d_h; a.out_stride = act_stride;
-    launch_stage<true>(a, C, T, st);
+    launch_stage<true>(a, T, st);
     a.B = act;
     a.Wp = static_cast<const bf16x8 *>(W2p);
     a.tiles = d_h / 32; a.KS = d_e / 32; a.b_stride = act_stride; a.out_stride = d_h;
-    launch_stage<false>(a, C, T, st);
+    launch_stage<false>(a, T, st);
 }
 
 }  // namespace moe
