@@ -38,10 +38,24 @@ inline int check_launch(const char *where) {
     return MOE_OK;
 }
 
-// bf16 grouped FFN as two streaming launches (ffn_stream.hip); shapes validated by the caller
-void launch_ffn_stream(const void *X, const void *W13p, const void *W2p, int T, int k, int C, int d_h, int d_e,
-                       const int32_t *slot_off, const int32_t *perm, uint16_t *act, int act_stride,
-                       float *Yp, hipStream_t st);
+// Control region at the start of the FFN workspace: error word + hand-off counters (ffn_stream.hip)
+constexpr size_t kFfnCtrlBytes = 4u << 20;
+
+// Upper bound of the number of blocks of kFfnBlockRows request rows over all slots: a slot
+// receives at most one request per token (a token's k experts are distinct).
+constexpr int kFfnBlockRows = 32;
+inline long long ffn_max_blocks(int T, int k, int C) {
+    const long long per_slot = (T + kFfnBlockRows - 1) / kFfnBlockRows;
+    const long long a = C * per_slot, b = C + static_cast<long long>(T) * k / kFfnBlockRows;
+    return a < b ? a : b;
+}
+
+// bf16 grouped FFN (ffn_stream.hip); shapes validated by the caller.  `ctrl` is the zero-initialised
+// control region of the workspace, `act` holds ffn_max_blocks(T, k, C) blocks of kFfnBlockRows x d_e
+// bf16.  Returns MOE_OK or MOE_ESHAPE (too many blocks).
+int launch_ffn_stream(const void *X, const void *W13p, const void *W2p, int T, int k, int C, int d_h, int d_e,
+                      const int32_t *slot_off, const int32_t *perm, int *ctrl, uint16_t *act, float *Yp,
+                      hipStream_t st);
 
 inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 

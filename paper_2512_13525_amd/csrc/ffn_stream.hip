@@ -1,15 +1,33 @@
-// a5, bf16 path: the grouped expert FFN as two streaming launches (gate/up + SiLU*up, then down).
+// a5, bf16 path: the grouped expert FFN (gate/up + SiLU*up, then down) as oversubscribed streaming
+// workgroups.
 //
 // Janus Sec. 2.2: at decode sizes an expert is two skinny GEMMs whose cost is the weight bytes
-// streamed from HBM, so the layer's latency follows the number of activated experts.  The
-// kernels below are plain oversubscribed streamers: one workgroup per (slot, 16- or 32-channel
-// tile of the output) and K-split part, dispatched by the hardware; a workgroup of a slot
-// without requests leaves at once and never touches that slot's weights.
+// streamed from HBM, so the layer's latency follows the number of activated experts.  The work
+// of a stage is cut into items = (block of up to 32 request rows of one slot) x (tile of 16
+// gate+up channels in stage 1, 32 output channels in stage 2); one workgroup per item, in plain
+// grid order, dispatched by the hardware.  Slots without requests own no item: their weights are
+// never read.  Nothing about the activated set is known on the host, so the grid is sized for
+// the largest possible number of blocks and every wavefront finds its item from slot_off;
+// workgroups past the last block leave at once.
 //
-// The 4 wavefronts of a workgroup split the K-steps (32 columns each) of the tile round-robin,
-// keep kDepth steps of 128-bit loads in flight each (weights: 1 KiB MFMA A-operand images,
-// fully coalesced; tokens: B operand fetched from L2), and meet in LDS once per pass of 32
-// tokens.  The sum over wavefronts is taken in a fixed order, so results are reproducible.
+// The 4 wavefronts of a workgroup split the K dimension of the tile round-robin in super-steps
+// of 64 columns and meet in LDS once, at the end (fixed summation order: results are
+// reproducible).  Per super-step a wavefront reads 4 KiB of weights (packed MFMA A-operand
+// images, fully coalesced 128-bit loads, two super-steps ahead) and one 128-byte line of each
+// token row (the B operand, from L2, one super-step ahead).
+//
+// Both stages run in ONE launch: the stage-2 workgroups have the higher ids, so the hardware
+// starts them only after every stage-1 workgroup has been started, and they fill the compute
+// units that the tail of stage 1 leaves idle.  A stage-2 workgroup first puts its weight loads in
+// flight and then waits until the 16-channel tiles of its block of `act` rows are all written: a
+// counter per block in the workspace is bumped by each stage-1 workgroup once its stores are
+// acknowledged, and polled (bounded; an overrun raises the workspace's error word and the
+// workgroup carries on, so every wave reaches the end of the kernel).  `act` is written with
+// agent-scope stores and read with agent-scope loads, and the counters are agent-scope atomics,
+// because the 8 XCDs do not share an L2.  The last stage-2 workgroup of a block to get through
+// the wait clears the block's counters for the next call.
+#include <stdlib.h>
+
 #include "common.h"
 
 namespace {
@@ -17,28 +35,45 @@ namespace {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kDepth = 4;               // K-steps of loads each wavefront keeps in flight
+constexpr int kDepthA = 2;              // super-steps of weight loads each wavefront keeps in flight
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / MOE_WAVE;
 constexpr int kMaxTiles = 2;            // token tiles (of 16) per workgroup
-constexpr int kBlockTok = kMaxTiles * 16; // tokens of a slot one workgroup takes
+constexpr int kBlockTok = kMaxTiles * 16; // request rows of a slot one workgroup takes
+
+// Control region of the workspace (ints): [1] error word; block j owns the 8 lines of 128 bytes
+// at int offset (j+1)*kCtrlBlockInts: line 0 = {stage-1 tiles done, stage-2 workgroups through},
+// lines 1..7 = copies of the block's ready flag (same-address accesses from many workgroups
+// serialise in the memory system, so the pollers are spread over the copies).
+constexpr int kCtrlLineInts = 32;
+constexpr int kCtrlCopies = 7;
+constexpr int kCtrlBlockInts = (1 + kCtrlCopies) * kCtrlLineInts;
+constexpr int kMaxItems = static_cast<int>(moe::kFfnCtrlBytes / 4) / kCtrlBlockInts - 1;
 
 #ifdef MOE_STREAM_TRACE
-// timeline of every workgroup (debug builds only): [stage][linear id][start, first data, end, xcc/cu]
-__device__ long long g_trace[2][1 << 15][4];
+// timeline of every workgroup (debug builds only): [linear id][start, stage, end, xcc/cu]
+__device__ long long g_trace[1 << 15][4];
 #endif
 
+struct StageArgs {
+    const uint16_t *B;                   // token operand: X (stage 1, rows through perm) or act (stage 2, blocks)
+    const char *Wp;                      // packed weights: [C][tiles][KS][2][64] fragments of 16 bytes
+    int tiles, tiles_pad, KS;            // tiles_pad = tiles rounded up to a multiple of 8
+    int b_stride;                        // elements between rows of X (stage 1)
+    int out_stride;                      // elements between rows of Yp (stage 2)
+};
+
 struct StreamArgs {
-    const uint16_t *B;                   // token operand rows: X (stage 1, through perm) or act (stage 2)
-    const bf16x8 *Wp;                    // packed weights: [C][tiles][KS][2][64] fragments
+    StageArgs s[2];
     const int32_t *slot_off;
     const int32_t *perm;
     uint16_t *act;                       // stage-1 output
     float *Yp;                           // stage-2 output
-    int k, C, tiles, KS;
-    int tiles_pad;                       // tiles rounded up to a multiple of 8
-    int b_stride;                        // elements between rows of B
-    int out_stride;                      // elements between rows of the output
+    int *ctrl;
+    int k, C;
+    unsigned n1;                         // workgroups of stage 1 (ids below n1)
+    int mode;                            // 0: both stages in this launch; 1 / 2: that stage alone
+    int spin_limit;
 };
 
 __device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
@@ -47,13 +82,18 @@ __device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
 
 __device__ __forceinline__ float silu_mul(float g, float u) { return g / (1.0f + __expf(-g)) * u; }
 
+// Workgroup barrier for LDS exchange only: waits for this wavefront's LDS traffic, not for its
+// global loads (prefetched weights stay in flight across it).
+__device__ __forceinline__ void lds_barrier() {
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
 // Split-K reduction over the 4 wavefronts in LDS (fixed order), then the epilogue: SiLU(gate)*up
-// rounded once to bf16 (stage 1) or the fp32 partial output rows (stage 2).
+// rounded once to bf16 (stage 1, agent-scope stores) or the fp32 partial output rows (stage 2).
 template <bool STAGE1, int NT>
-__device__ __forceinline__ void reduce_store(const StreamArgs &a, f32x4 (*red)[2][kMaxTiles][MOE_WAVE],
-                                             f32x4 (&acc)[2][NT], int tile, int row0, int row_end,
-                                             int wave, int lane) {
-    // split-K reduction over the 4 wavefronts in LDS, fixed order
+__device__ __forceinline__ void reduce_store(const StreamArgs &a, const StageArgs &g,
+                                             f32x4 (*red)[2][kMaxTiles][MOE_WAVE], f32x4 (&acc)[2][NT],
+                                             int item_id, int tile, int row0, int row_end, int wave, int lane) {
 #pragma unroll
     for (int h = 0; h < 2; ++h)
 #pragma unroll
@@ -63,17 +103,20 @@ __device__ __forceinline__ void reduce_store(const StreamArgs &a, f32x4 (*red)[2
         // lane-slot (t, l) holds gate/up channels tile*16 + (l/16)*4 .. +3 of token row0 + t*16 + l%16
         for (int item = threadIdx.x; item < NT * MOE_WAVE; item += kThreads) {
             const int t = item / MOE_WAVE, l = item % MOE_WAVE;
-            f32x4 g = red[0][0][t][l], u = red[0][1][t][l];
+            f32x4 gt = red[0][0][t][l], up = red[0][1][t][l];
 #pragma unroll
-            for (int wv = 1; wv < kWaves; ++wv) { g += red[wv][0][t][l]; u += red[wv][1][t][l]; }
+            for (int wv = 1; wv < kWaves; ++wv) { gt += red[wv][0][t][l]; up += red[wv][1][t][l]; }
             const int r = row0 + t * 16 + (l & 15);
             if (r < row_end) {
-                ushort4 o;
-                o.x = moe::f32_to_bf16(silu_mul(g[0], u[0]));
-                o.y = moe::f32_to_bf16(silu_mul(g[1], u[1]));
-                o.z = moe::f32_to_bf16(silu_mul(g[2], u[2]));
-                o.w = moe::f32_to_bf16(silu_mul(g[3], u[3]));
-                *reinterpret_cast<ushort4 *>(a.act + static_cast<size_t>(r) * a.out_stride + tile * 16 + (l >> 4) * 4) = o;
+                const uint64_t o = static_cast<uint64_t>(moe::f32_to_bf16(silu_mul(gt[0], up[0]))) |
+                                   static_cast<uint64_t>(moe::f32_to_bf16(silu_mul(gt[1], up[1]))) << 16 |
+                                   static_cast<uint64_t>(moe::f32_to_bf16(silu_mul(gt[2], up[2]))) << 32 |
+                                   static_cast<uint64_t>(moe::f32_to_bf16(silu_mul(gt[3], up[3]))) << 48;
+                // act block of this item: [tile][32 rows][16 channels], one writer per 128-byte line
+                uint64_t *dst = reinterpret_cast<uint64_t *>(
+                    reinterpret_cast<char *>(a.act) + (static_cast<size_t>(item_id) * g.tiles + tile) * 1024 +
+                    (t * 16 + (l & 15)) * 32 + (l >> 4) * 8);
+                __hip_atomic_store(dst, o, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
         }
     } else {
@@ -85,185 +128,148 @@ __device__ __forceinline__ void reduce_store(const StreamArgs &a, f32x4 (*red)[2
             for (int wv = 1; wv < kWaves; ++wv) y += red[wv][h][t][l];
             const int r = row0 + t * 16 + (l & 15);
             if (r < row_end)
-                *reinterpret_cast<f32x4 *>(a.Yp + static_cast<size_t>(r) * a.out_stride + tile * 32 + h * 16 + (l >> 4) * 4) = y;
+                *reinterpret_cast<f32x4 *>(a.Yp + static_cast<size_t>(r) * g.out_stride + tile * 32 + h * 16 + (l >> 4) * 4) = y;
         }
     }
 }
 
-// One pass: tokens [row0, row0 + NT*16) of the slot (rows >= row_end are padding) against the
-// workgroup's tile.  `w` points at K-step 0 of the tile (wave-uniform).  A wavefront advances in
-// super-steps of SS consecutive K-steps (SS*2 KiB of weights, SS*64 contiguous bytes of every
-// token row: SS = 2 reads whole 128-byte lines of the token rows) and keeps D super-steps in flight.
-template <bool STAGE1, int NT, int SS>
-__device__ __forceinline__ void stream_pass(const StreamArgs &a, f32x4 (*red)[2][kMaxTiles][MOE_WAVE],
-                                            const char *w, int tile, int row0, int row_end,
-                                            int wave, int lane) {
-    constexpr int D = kDepth / SS;
-    // B operand: lane l reads 8 columns (l/16)*8.. of token row l%16 of every token tile.  Weights
-    // and tokens are both addressed as a wave-uniform base (scalar registers, advanced per K-step)
-    // plus a constant 32-bit per-lane byte offset.
-    const uint32_t aoff = lane * 16;
-    uint32_t boff[NT];
-#pragma unroll
-    for (int t = 0; t < NT; ++t) {
-        int r = row0 + t * 16 + (lane & 15);
-        r = r < row_end ? r : row_end - 1;
-        const uint32_t src = STAGE1 ? static_cast<uint32_t>(a.perm[r] / a.k) : static_cast<uint32_t>(r);
-        boff[t] = (src * static_cast<uint32_t>(a.b_stride) + (lane >> 4) * 8) * 2;
-    }
-    const char *bbase = reinterpret_cast<const char *>(a.B);
-    const int n = (a.KS / SS - wave + kWaves - 1) / kWaves;     // super-steps wave, wave+4, ... of this wavefront
-    f32x4 acc[2][NT];
-#pragma unroll
-    for (int h = 0; h < 2; ++h)
-#pragma unroll
-        for (int t = 0; t < NT; ++t) acc[h][t] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-    if (n > 0) {
-        // Ring entry d holds super-step i+d.  The steady-state loop has no branch, so the compiler
-        // counts outstanding loads exactly and each MFMA waits only for its own entry.  Loads past
-        // the last super-step fetch the last one again (a cache hit): every load is unconditional.
-        bf16x8 wr[D][SS][2], br[D][SS][NT];
-        const int last = n - 1;
-        // Workgroups start their K loop at different places (and wrap around) so that they do not
-        // march through equally aligned tiles in lockstep.
-        const int rot = static_cast<int>(static_cast<unsigned>(tile) % static_cast<unsigned>(n));
-#define MOE_LOAD_STEP(d, step)                                                                   \
-        do {                                                                                     \
-            const int q_ = (step);                                                               \
-            int r_ = (q_ < last ? q_ : last) + rot;                                              \
-            r_ = r_ >= n ? r_ - n : r_;                                                          \
-            const int s_ = wave + kWaves * r_;                                                   \
-            const char *ws_ = w + static_cast<size_t>(s_) * (2048 * SS);                         \
-            const char *bs_ = bbase + static_cast<size_t>(s_) * (64 * SS);                       \
-            _Pragma("unroll") for (int ss = 0; ss < SS; ++ss) {                                  \
-                wr[d][ss][0] = *reinterpret_cast<const bf16x8 *>(ws_ + ss * 2048 + aoff);        \
-                wr[d][ss][1] = *reinterpret_cast<const bf16x8 *>(ws_ + ss * 2048 + 1024 + aoff); \
-            }                                                                                    \
-            _Pragma("unroll") for (int t = 0; t < NT; ++t)                                       \
-                _Pragma("unroll") for (int ss = 0; ss < SS; ++ss)                                \
-                    br[d][ss][t] = *reinterpret_cast<const bf16x8 *>(bs_ + ss * 64 + boff[t]);   \
-            asm volatile("" ::: "memory");                                                       \
-        } while (0)
-#define MOE_MMA_STEP(d)                                                                          \
-        do {                                                                                     \
-            _Pragma("unroll") for (int ss = 0; ss < SS; ++ss)                                    \
-                _Pragma("unroll") for (int t = 0; t < NT; ++t) {                                 \
-                    acc[0][t] = mfma16(wr[d][ss][0], br[d][ss][t], acc[0][t]);                   \
-                    acc[1][t] = mfma16(wr[d][ss][1], br[d][ss][t], acc[1][t]);                   \
-                }                                                                                \
-        } while (0)
-#pragma unroll
-        for (int d = 0; d < D; ++d) MOE_LOAD_STEP(d, d);
-        int i = 0;
-        for (; i + 2 * D <= n; i += D) {
-#pragma unroll
-            for (int d = 0; d < D; ++d) {
-                MOE_MMA_STEP(d);
-                MOE_LOAD_STEP(d, i + d + D);
+// Stage 2 of a block may read `act` only when all stage-1 tiles of the block are written: the
+// stage-1 workgroup that completes the count raises the block's ready flags.  Called by the whole
+// workgroup; thread 0 polls one copy of the flag.  The second counter of the block counts the
+// stage-2 workgroups that got through: the last one clears the block's control lines for the
+// next call.
+__device__ __forceinline__ void wait_block_ready(const StreamArgs &a, int item, int tile, int n_readers) {
+    if (threadIdx.x == 0) {
+        int *blk = a.ctrl + (item + 1) * kCtrlBlockInts;
+        const int *flag = blk + (1 + tile % kCtrlCopies) * kCtrlLineInts;
+        int spins = 0;
+        while (__hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0) {
+            if (++spins > a.spin_limit) {
+                __hip_atomic_fetch_or(a.ctrl + 1, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                break;
             }
+            __builtin_amdgcn_s_sleep(32);
         }
-        const int rem = n - i;                                   // 1 .. 2*D-1 super-steps left
+        if (__hip_atomic_fetch_add(blk + 1, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == n_readers - 1) {
+            __hip_atomic_store(blk, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(blk + 1, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 #pragma unroll
-        for (int d = 0; d < D; ++d) {
-            if (d < rem) MOE_MMA_STEP(d);
-            if (d < D - 1) MOE_LOAD_STEP(d, i + d + D);
+            for (int c = 1; c <= kCtrlCopies; ++c)
+                __hip_atomic_store(blk + c * kCtrlLineInts, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
-#pragma unroll
-        for (int d = 0; d < D - 1; ++d)
-            if (D + d < rem) MOE_MMA_STEP(d);
-#undef MOE_LOAD_STEP
-#undef MOE_MMA_STEP
     }
-
-    reduce_store<STAGE1, NT>(a, red, acc, tile, row0, row_end, wave, lane);
+    lds_barrier();
 }
 
-// The same pass for an even number of K-steps, with whole-line token reads.  A super-step is two
-// K-steps = 64 columns = one 128-byte line of every token row.  A load instruction fetches 8 rows
-// x 128 bytes (lane l: row l/8, 16-byte chunk l%8), so no line is requested twice and none by
-// halves; the MFMA layout (lane l: row l%16, chunk 4*step + l/16) is produced by a round trip
-// through a wave-private 2 KiB LDS tile per 16 rows (chunks XOR-swizzled by row so that both the
-// row-major writes and the column-wise reads spread over the banks).  NH = number of 8-row halves
-// that hold requests (rows past the end repeat the last row; halves past it are not loaded and
-// leave unspecified values in token columns whose results are never stored).
-template <bool STAGE1, int NH>
-__device__ __forceinline__ void stream_pass_lines(const StreamArgs &a, char *lds, const char *w, int tile,
-                                                  int row0, int row_end, int wave, int lane) {
+// One item with an even number of K-steps.  A super-step is two K-steps = 64 columns = one
+// 128-byte line of every token row (in stage 2: the 32-byte pieces of 4 consecutive stage-1 tiles).
+// A token load instruction fetches whole lines (lane l: row l/8, 16-byte chunk l%8), so no line
+// is requested twice and none by halves; the MFMA layout (lane l: row l%16, 16-byte chunk 4*step + l/16) is produced by a
+// round trip through a wave-private 2 KiB LDS tile per 16 rows (chunks XOR-swizzled by row so
+// that both the row-major writes and the column-wise reads spread over the banks).  NH = number
+// of 8-row halves that hold requests (rows past the end repeat the last row; halves past it are
+// not loaded and leave unspecified values in token columns whose results are never stored).
+// WAIT: the token rows are `act` rows that other workgroups of this launch produce.
+template <bool STAGE1, int NH, bool WAIT>
+__device__ __forceinline__ void stream_item_lines(const StreamArgs &a, const StageArgs &g, char *lds,
+                                                  const char *w, int item, int tile, int row0, int row_end,
+                                                  int wave, int lane) {
     constexpr int NT = (NH + 1) / 2;
-    constexpr int D = kDepth / 2;
+    constexpr int D = kDepthA;
     f32x4 (*red)[2][kMaxTiles][MOE_WAVE] = reinterpret_cast<f32x4 (*)[2][kMaxTiles][MOE_WAVE]>(lds);
     char *stg = lds + wave * (kMaxTiles * 2048);
     const uint32_t aoff = lane * 16;
+    // token rows: wave-uniform base (advanced per super-step) + constant 32-bit per-lane byte offset
     uint32_t boff[NH];
 #pragma unroll
     for (int h = 0; h < NH; ++h) {
-        int r = row0 + h * 8 + (lane >> 3);
-        r = r < row_end ? r : row_end - 1;
-        const uint32_t src = STAGE1 ? static_cast<uint32_t>(a.perm[r] / a.k) : static_cast<uint32_t>(r);
-        boff[h] = src * static_cast<uint32_t>(a.b_stride) * 2 + (lane & 7) * 16;
+        if (STAGE1) {
+            int r = row0 + h * 8 + (lane >> 3);
+            r = r < row_end ? r : row_end - 1;
+            boff[h] = static_cast<uint32_t>(a.perm[r] / a.k) * static_cast<uint32_t>(g.b_stride) * 2 + (lane & 7) * 16;
+        } else {
+            // act block: [tile][32 rows][16 channels]; chunk c of a super-step = tile c/2, half c%2
+            boff[h] = ((lane & 7) >> 1) * 1024 + (h * 8 + (lane >> 3)) * 32 + (lane & 1) * 16;
+        }
     }
-    // LDS addresses: write row (h%2)*8 + l/8 of tile h/2, chunk l%8; read row l%16, chunk 4*ss + l/16
+    // LDS: row R of a tile at R*128, its 16-byte chunk c at ((c ^ (R & 7)) * 16)
     const uint32_t wr_lds = ((lane >> 3) * 128) + (((lane & 7) ^ (lane >> 3)) * 16);
     const uint32_t rd_row = (lane & 15) * 128, rd_sw = lane & 7, rd_g = lane >> 4;
-    const char *bbase = reinterpret_cast<const char *>(a.B);
-    const int n = (a.KS / 2 - wave + kWaves - 1) / kWaves;      // super-steps wave, wave+4, ... of this wavefront
+    const char *bbase = STAGE1 ? reinterpret_cast<const char *>(g.B)
+                               : reinterpret_cast<const char *>(g.B) + static_cast<size_t>(item) * a.s[0].tiles * 1024;
+    constexpr int kBStep = STAGE1 ? 128 : 4096;                  // bytes a super-step advances the token operand
+    const int n = (g.KS / 2 - wave + kWaves - 1) / kWaves;      // super-steps wave, wave+4, ... of this wavefront
     f32x4 acc[2][NT];
 #pragma unroll
     for (int h = 0; h < 2; ++h)
 #pragma unroll
         for (int t = 0; t < NT; ++t) acc[h][t] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    if (n > 0) {
-        // Weights run D super-steps ahead (ring wr); the token rows, which come from L2, only one:
-        // the loads of super-step q+1 are issued in iteration q *before* the weights of q+D, so that
-        // waiting for them (loads return in order) leaves those weights in flight.
-        bf16x8 wr[D][2][2], br[NH];
-        const int last = n - 1;
-        const int rot = static_cast<int>(static_cast<unsigned>(tile) % static_cast<unsigned>(n));
+    // Weights run D super-steps ahead (ring wr); the token rows, which come from L2, only one:
+    // the loads of super-step q+1 are issued in iteration q *before* the weights of q+D, so that
+    // waiting for them (loads return in order) leaves those weights in flight.  The steady-state
+    // loop has no branch, so the compiler counts outstanding loads exactly.  Loads past the last
+    // super-step fetch the last one again (a cache hit): every load is unconditional.
+    bf16x8 wr[D][2][2];
+    bf16x8 br[NH];
+    const int last = n > 0 ? n - 1 : 0;
+    // Workgroups start their K loop at different places (and wrap around) so that they do not
+    // march through equally aligned tiles in lockstep.
+    const int rot = n > 0 ? static_cast<int>(static_cast<unsigned>(tile) % static_cast<unsigned>(n)) : 0;
 #define MOE_STEP_INDEX(step)                                                                     \
-            const int q_ = (step);                                                               \
-            int r_ = (q_ < last ? q_ : last) + rot;                                              \
-            r_ = r_ >= n ? r_ - n : r_;                                                          \
-            const int s_ = wave + kWaves * r_;
+        const int q_ = (step);                                                                   \
+        int r_ = (q_ < last ? q_ : last) + rot;                                                  \
+        r_ = r_ >= n ? r_ - n : r_;                                                              \
+        const int s_ = wave + kWaves * r_;
 #define MOE_LOAD_A(d, step)                                                                      \
-        do {                                                                                     \
-            MOE_STEP_INDEX(step)                                                                 \
-            const char *ws_ = w + static_cast<size_t>(s_) * 4096;                                \
-            _Pragma("unroll") for (int ss = 0; ss < 2; ++ss) {                                   \
-                wr[d][ss][0] = *reinterpret_cast<const bf16x8 *>(ws_ + ss * 2048 + aoff);        \
-                wr[d][ss][1] = *reinterpret_cast<const bf16x8 *>(ws_ + ss * 2048 + 1024 + aoff); \
-            }                                                                                    \
-            asm volatile("" ::: "memory");                                                       \
-        } while (0)
+    do {                                                                                         \
+        MOE_STEP_INDEX(step)                                                                     \
+        const char *ws_ = w + static_cast<size_t>(s_) * 4096;                                    \
+        _Pragma("unroll") for (int ss = 0; ss < 2; ++ss) {                                       \
+            wr[d][ss][0] = *reinterpret_cast<const bf16x8 *>(ws_ + ss * 2048 + aoff);            \
+            wr[d][ss][1] = *reinterpret_cast<const bf16x8 *>(ws_ + ss * 2048 + 1024 + aoff);     \
+        }                                                                                        \
+        asm volatile("" ::: "memory");                                                           \
+    } while (0)
 #define MOE_LOAD_B(step)                                                                         \
-        do {                                                                                     \
-            MOE_STEP_INDEX(step)                                                                 \
-            const char *bs_ = bbase + static_cast<size_t>(s_) * 128;                             \
-            _Pragma("unroll") for (int h = 0; h < NH; ++h)                                       \
-                br[h] = *reinterpret_cast<const bf16x8 *>(bs_ + boff[h]);                        \
-            asm volatile("" ::: "memory");                                                       \
-        } while (0)
+    do {                                                                                         \
+        MOE_STEP_INDEX(step)                                                                     \
+        const char *bs_ = bbase + static_cast<size_t>(s_) * kBStep;                              \
+        _Pragma("unroll") for (int h = 0; h < NH; ++h)                                           \
+            br[h] = *reinterpret_cast<const bf16x8 *>(bs_ + boff[h]);                            \
+        asm volatile("" ::: "memory");                                                           \
+    } while (0)
 #define MOE_STAGE_B()                                                                            \
-        do {                                                                                     \
-            _Pragma("unroll") for (int h = 0; h < NH; ++h)                                       \
-                *reinterpret_cast<bf16x8 *>(stg + (h / 2) * 2048 + (h % 2) * 1024 + wr_lds) = br[h]; \
-            asm volatile("" ::: "memory");                                                       \
-        } while (0)
+    do {                                                                                         \
+        _Pragma("unroll") for (int h = 0; h < NH; ++h)                                           \
+            *reinterpret_cast<bf16x8 *>(stg + (h / 2) * 2048 + (h % 2) * 1024 + wr_lds) = br[h]; \
+        asm volatile("" ::: "memory");                                                           \
+    } while (0)
 #define MOE_MMA_STEP(d)                                                                          \
-        do {                                                                                     \
-            _Pragma("unroll") for (int ss = 0; ss < 2; ++ss)                                     \
-                _Pragma("unroll") for (int t = 0; t < NT; ++t) {                                 \
-                    const bf16x8 bf_ = *reinterpret_cast<const bf16x8 *>(                        \
-                        stg + t * 2048 + rd_row + (((4 * ss + rd_g) ^ rd_sw) * 16));             \
-                    acc[0][t] = mfma16(wr[d][ss][0], bf_, acc[0][t]);                            \
-                    acc[1][t] = mfma16(wr[d][ss][1], bf_, acc[1][t]);                            \
-                }                                                                                \
-            asm volatile("" ::: "memory");                                                       \
-        } while (0)
-        MOE_LOAD_B(0);
+    do {                                                                                         \
+        _Pragma("unroll") for (int ss = 0; ss < 2; ++ss)                                         \
+            _Pragma("unroll") for (int t = 0; t < NT; ++t) {                                     \
+                const bf16x8 bf_ = *reinterpret_cast<const bf16x8 *>(                            \
+                    stg + t * 2048 + rd_row + (((4 * ss + rd_g) ^ rd_sw) * 16));                 \
+                acc[0][t] = mfma16(wr[d][ss][0], bf_, acc[0][t]);                                \
+                acc[1][t] = mfma16(wr[d][ss][1], bf_, acc[1][t]);                                \
+            }                                                                                    \
+        asm volatile("" ::: "memory");                                                           \
+    } while (0)
+    if (WAIT) {
+        // weights first: they do not depend on stage 1
+        if (n > 0) {
 #pragma unroll
-        for (int d = 0; d < D; ++d) MOE_LOAD_A(d, d);
+            for (int d = 0; d < D; ++d) MOE_LOAD_A(d, d);
+        }
+        wait_block_ready(a, item, tile, g.tiles);
+    }
+    if (n > 0) {
+        MOE_LOAD_B(0);
+        if (!WAIT) {
+#pragma unroll
+            for (int d = 0; d < D; ++d) MOE_LOAD_A(d, d);
+        }
         int i = 0;
         for (; i + 2 * D <= n; i += D) {
 #pragma unroll
@@ -288,14 +294,97 @@ __device__ __forceinline__ void stream_pass_lines(const StreamArgs &a, char *lds
             if (d < D - 2) MOE_LOAD_B(i + D + d + 1);
             if (D + d < rem) MOE_MMA_STEP(d);
         }
+    }
 #undef MOE_STEP_INDEX
 #undef MOE_LOAD_A
 #undef MOE_LOAD_B
 #undef MOE_STAGE_B
 #undef MOE_MMA_STEP
-    }
     __syncthreads();                                             // the staging tiles are reused for the reduction
-    reduce_store<STAGE1, NT>(a, red, acc, tile, row0, row_end, wave, lane);
+    reduce_store<STAGE1, NT>(a, g, red, acc, item, tile, row0, row_end, wave, lane);
+}
+
+// One item with an odd number of K-steps (shapes that are multiples of 32 but not of 64): single
+// K-steps, token rows read 64 bytes at a time straight into the MFMA layout (lane l: row l%16,
+// 16 bytes at (l/16)*16), four steps of weights and tokens in flight.
+template <bool STAGE1, int NT, bool WAIT>
+__device__ __forceinline__ void stream_item_steps(const StreamArgs &a, const StageArgs &g, char *lds,
+                                                  const char *w, int item, int tile, int row0, int row_end,
+                                                  int wave, int lane) {
+    constexpr int D = 2 * kDepthA;
+    f32x4 (*red)[2][kMaxTiles][MOE_WAVE] = reinterpret_cast<f32x4 (*)[2][kMaxTiles][MOE_WAVE]>(lds);
+    const uint32_t aoff = lane * 16;
+    uint32_t boff[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+        if (STAGE1) {
+            int r = row0 + t * 16 + (lane & 15);
+            r = r < row_end ? r : row_end - 1;
+            boff[t] = (static_cast<uint32_t>(a.perm[r] / a.k) * static_cast<uint32_t>(g.b_stride) + (lane >> 4) * 8) * 2;
+        } else {
+            // act block: [tile][32 rows][16 channels]; a K-step = 2 tiles, chunk l/16 = tile (l/16)/2, half (l/16)%2
+            boff[t] = (lane >> 5) * 1024 + (t * 16 + (lane & 15)) * 32 + ((lane >> 4) & 1) * 16;
+        }
+    }
+    const char *bbase = STAGE1 ? reinterpret_cast<const char *>(g.B)
+                               : reinterpret_cast<const char *>(g.B) + static_cast<size_t>(item) * a.s[0].tiles * 1024;
+    constexpr int kBStep = STAGE1 ? 64 : 2048;                   // bytes a K-step advances the token operand
+    const int n = (g.KS - wave + kWaves - 1) / kWaves;          // K-steps wave, wave+4, ... of this wavefront
+    f32x4 acc[2][NT];
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+        for (int t = 0; t < NT; ++t) acc[h][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    if (WAIT) wait_block_ready(a, item, tile, g.tiles);
+    if (n > 0) {
+        bf16x8 wr[D][2], br[D][NT];
+        const int last = n - 1;
+        const int rot = static_cast<int>(static_cast<unsigned>(tile) % static_cast<unsigned>(n));
+#define MOE_LOAD_STEP(d, step)                                                                   \
+        do {                                                                                     \
+            const int q_ = (step);                                                               \
+            int r_ = (q_ < last ? q_ : last) + rot;                                              \
+            r_ = r_ >= n ? r_ - n : r_;                                                          \
+            const int s_ = wave + kWaves * r_;                                                   \
+            const char *ws_ = w + static_cast<size_t>(s_) * 2048;                                \
+            const char *bs_ = bbase + static_cast<size_t>(s_) * kBStep;                            \
+            wr[d][0] = *reinterpret_cast<const bf16x8 *>(ws_ + aoff);                            \
+            wr[d][1] = *reinterpret_cast<const bf16x8 *>(ws_ + 1024 + aoff);                     \
+            _Pragma("unroll") for (int t = 0; t < NT; ++t)                                       \
+                br[d][t] = *reinterpret_cast<const bf16x8 *>(bs_ + boff[t]);                     \
+            asm volatile("" ::: "memory");                                                       \
+        } while (0)
+#define MOE_MMA_STEP(d)                                                                          \
+        do {                                                                                     \
+            _Pragma("unroll") for (int t = 0; t < NT; ++t) {                                     \
+                acc[0][t] = mfma16(wr[d][0], br[d][t], acc[0][t]);                               \
+                acc[1][t] = mfma16(wr[d][1], br[d][t], acc[1][t]);                               \
+            }                                                                                    \
+        } while (0)
+#pragma unroll
+        for (int d = 0; d < D; ++d) MOE_LOAD_STEP(d, d);
+        int i = 0;
+        for (; i + 2 * D <= n; i += D) {
+#pragma unroll
+            for (int d = 0; d < D; ++d) {
+                MOE_MMA_STEP(d);
+                MOE_LOAD_STEP(d, i + d + D);
+            }
+        }
+        const int rem = n - i;                                   // 1 .. 2*D-1 steps left
+#pragma unroll
+        for (int d = 0; d < D; ++d) {
+            if (d < rem) MOE_MMA_STEP(d);
+            if (d < D - 1) MOE_LOAD_STEP(d, i + d + D);
+        }
+#pragma unroll
+        for (int d = 0; d < D - 1; ++d)
+            if (D + d < rem) MOE_MMA_STEP(d);
+#undef MOE_LOAD_STEP
+#undef MOE_MMA_STEP
+    }
+    reduce_store<STAGE1, NT>(a, g, red, acc, item, tile, row0, row_end, wave, lane);
 }
 
 __device__ __forceinline__ int wave_scan_inclusive(int v, int lane) {
@@ -307,11 +396,11 @@ __device__ __forceinline__ int wave_scan_inclusive(int v, int lane) {
     return v;
 }
 
-// Work item j of the launch: the j-th block of kBlockTok tokens when the blocks of all slots are
-// listed in slot order (blocks of a slot adjacent).  Every wavefront works this out for itself
-// from slot_off (C <= 256 slots, 4 per lane).  Returns false past the last block.
-__device__ __forceinline__ bool find_item(const int32_t *__restrict__ slot_off, int C, int j, int lane,
-                                          int *slot, int *blk) {
+// Block j of the launch: the j-th block of kBlockTok request rows when the blocks of all slots
+// are listed in slot order (blocks of a slot adjacent).  Every wavefront works this out for
+// itself from slot_off (64 slots per round).  Returns false past the last block.
+__device__ __forceinline__ bool find_block(const int32_t *__restrict__ slot_off, int C, int j, int lane,
+                                           int *slot, int *blk) {
     int base = 0;
     for (int c0 = 0; c0 < C; c0 += MOE_WAVE) {
         const int sidx = c0 + lane;
@@ -331,12 +420,50 @@ __device__ __forceinline__ bool find_item(const int32_t *__restrict__ slot_off, 
     return false;
 }
 
-// 1-D grid: workgroup id = item * tiles_pad + tile (tiles_pad = tiles rounded up to a multiple of
-// 8).  Workgroups are dispatched in id order and go to the XCDs round-robin, so the token blocks
-// of one tile of a slot (ids tiles_pad apart) run on the same XCD at about the same time: the
-// tile's weights come from HBM once and are shared through that XCD's L2.  LINES selects the
-// whole-line token path (even number of K-steps).
-template <bool STAGE1, bool LINES>
+template <bool STAGE1, bool LINES, bool WAIT>
+__device__ __forceinline__ void run_item(const StreamArgs &a, const StageArgs &g, char *lds, unsigned id) {
+    const int tile = id % g.tiles_pad, item = id / g.tiles_pad;
+    if (tile >= g.tiles) return;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / MOE_WAVE), lane = threadIdx.x % MOE_WAVE;
+    int slot, blk;
+    if (!find_block(a.slot_off, a.C, item, lane, &slot, &blk)) return;   // past the last block: nothing is read
+    const int lo = a.slot_off[slot], hi = a.slot_off[slot + 1];
+    const int row0 = lo + blk * kBlockTok;
+    const char *w = g.Wp + (static_cast<size_t>(slot) * g.tiles + tile) * g.KS * 2048;
+    const int m = hi - row0;
+    if (LINES) {
+        if (m <= 8) stream_item_lines<STAGE1, 1, WAIT>(a, g, lds, w, item, tile, row0, hi, wave, lane);
+        else if (m <= 16) stream_item_lines<STAGE1, 2, WAIT>(a, g, lds, w, item, tile, row0, hi, wave, lane);
+        else if (m <= 24) stream_item_lines<STAGE1, 3, WAIT>(a, g, lds, w, item, tile, row0, hi, wave, lane);
+        else stream_item_lines<STAGE1, 4, WAIT>(a, g, lds, w, item, tile, row0, hi, wave, lane);
+    } else {
+        if (m <= 16) stream_item_steps<STAGE1, 1, WAIT>(a, g, lds, w, item, tile, row0, hi, wave, lane);
+        else stream_item_steps<STAGE1, 2, WAIT>(a, g, lds, w, item, tile, row0, hi, wave, lane);
+    }
+    if (STAGE1 && a.mode == 0) {
+        // announce the tile: every thread waits for its own act stores to be acknowledged, then
+        // one thread bumps the block's counter and, if it completes the count, raises the ready flags
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            int *blk = a.ctrl + (item + 1) * kCtrlBlockInts;
+            if (__hip_atomic_fetch_add(blk, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == g.tiles - 1) {
+                // last tile of the block: every other tile's stores were acknowledged before its bump
+#pragma unroll
+                for (int c = 1; c <= kCtrlCopies; ++c)
+                    __hip_atomic_store(blk + c * kCtrlLineInts, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+    }
+}
+
+// 1-D grid: stage-1 workgroups (ids below n1), then stage-2 workgroups; within a stage, id =
+// block * tiles_pad + tile.  Workgroups are dispatched in id order, so a stage-2 workgroup is
+// started after every stage-1 workgroup, and go to the XCDs round-robin, so the blocks of one tile
+// of a slot (ids tiles_pad apart, a multiple of 8) run on the same XCD at about the same time: the
+// tile's weights come from HBM once and are shared through that XCD's L2.  LINES1 / LINES2 select
+// the whole-line token path of a stage (even number of K-steps).
+template <bool LINES1, bool LINES2>
 __global__ __launch_bounds__(kThreads, 4)
 void ffn_stream_kernel(StreamArgs a) {
     // split-K reduction buffer [4 waves][2][kMaxTiles][64] x 16 B, which the whole-line path also
@@ -345,73 +472,70 @@ void ffn_stream_kernel(StreamArgs a) {
     static_assert(kWaves * kMaxTiles * 2048 <= sizeof(lds), "staging tiles must fit in the reduction buffer");
 #ifdef MOE_STREAM_TRACE
     const long long t_start = wall_clock64();
-    const unsigned lin = blockIdx.x;
 #endif
-    const int tile = blockIdx.x % a.tiles_pad, item = blockIdx.x / a.tiles_pad;
-    if (tile >= a.tiles) return;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / MOE_WAVE), lane = threadIdx.x % MOE_WAVE;
-    int slot, blk;
-    if (!find_item(a.slot_off, a.C, item, lane, &slot, &blk)) return;   // past the last block: nothing is read
-    const int lo = a.slot_off[slot], hi = a.slot_off[slot + 1];
-    const int row0 = lo + blk * kBlockTok;
-    const char *w = reinterpret_cast<const char *>(a.Wp) + (static_cast<size_t>(slot) * a.tiles + tile) * a.KS * 2048;
-    const int m = hi - row0;
-    if (LINES) {
-        if (m <= 8) stream_pass_lines<STAGE1, 1>(a, lds, w, tile, row0, hi, wave, lane);
-        else if (m <= 16) stream_pass_lines<STAGE1, 2>(a, lds, w, tile, row0, hi, wave, lane);
-        else if (m <= 24) stream_pass_lines<STAGE1, 3>(a, lds, w, tile, row0, hi, wave, lane);
-        else stream_pass_lines<STAGE1, 4>(a, lds, w, tile, row0, hi, wave, lane);
+    if (a.mode == 1) {
+        run_item<true, LINES1, false>(a, a.s[0], lds, blockIdx.x);
+    } else if (a.mode == 2) {
+        run_item<false, LINES2, false>(a, a.s[1], lds, blockIdx.x);
     } else {
-        // odd number of K-steps: half-line token reads
-        f32x4 (*red)[2][kMaxTiles][MOE_WAVE] = reinterpret_cast<f32x4 (*)[2][kMaxTiles][MOE_WAVE]>(lds);
-        if (m <= 16) stream_pass<STAGE1, 1, 1>(a, red, w, tile, row0, hi, wave, lane);
-        else stream_pass<STAGE1, 2, 1>(a, red, w, tile, row0, hi, wave, lane);
+        if (blockIdx.x < a.n1) run_item<true, LINES1, false>(a, a.s[0], lds, blockIdx.x);
+        else run_item<false, LINES2, true>(a, a.s[1], lds, blockIdx.x - a.n1);
     }
 #ifdef MOE_STREAM_TRACE
-    if (threadIdx.x == 0 && lin < (1u << 15)) {
-        unsigned hwid;
+    if (threadIdx.x == 0 && blockIdx.x < (1u << 15)) {
+        unsigned hwid, hw2;
         asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(hwid));
-        unsigned hw2;
         asm volatile("s_getreg_b32 %0, hwreg(HW_REG_HW_ID)" : "=s"(hw2));
-        long long *tr = g_trace[STAGE1 ? 0 : 1][lin];
-        tr[0] = t_start; tr[1] = hi - row0; tr[2] = wall_clock64(); tr[3] = (static_cast<long long>(hwid) << 32) | hw2;
+        long long *tr = g_trace[blockIdx.x];
+        tr[0] = t_start; tr[1] = blockIdx.x < a.n1; tr[2] = wall_clock64(); tr[3] = (static_cast<long long>(hwid) << 32) | hw2;
     }
 #endif
 }
 
-// A slot receives at most one request per token (a token's k experts are distinct), so the
-// launch has at most min(C * ceil(T/kBlockTok), C + T*k/kBlockTok) token blocks.
-template <bool STAGE1>
-void launch_stage(StreamArgs &a, int T, hipStream_t st) {
-    const long long per_slot = (T + kBlockTok - 1) / kBlockTok;
-    long long items = a.C * per_slot;
-    const long long by_rows = a.C + static_cast<long long>(T) * a.k / kBlockTok;
-    if (by_rows < items) items = by_rows;
-    a.tiles_pad = (a.tiles + 7) / 8 * 8;
-    const dim3 grid(static_cast<unsigned>(items * a.tiles_pad));
-    if (a.KS % 2 == 0) hipLaunchKernelGGL((ffn_stream_kernel<STAGE1, true>), grid, dim3(kThreads), 0, st, a);
-    else hipLaunchKernelGGL((ffn_stream_kernel<STAGE1, false>), grid, dim3(kThreads), 0, st, a);
+template <bool L1, bool L2>
+void launch(const StreamArgs &a, unsigned blocks, hipStream_t st) {
+    hipLaunchKernelGGL((ffn_stream_kernel<L1, L2>), dim3(blocks), dim3(kThreads), 0, st, a);
+}
+
+void launch_lines(const StreamArgs &a, unsigned blocks, hipStream_t st) {
+    const bool l1 = a.s[0].KS % 2 == 0, l2 = a.s[1].KS % 2 == 0;
+    if (l1 && l2) launch<true, true>(a, blocks, st);
+    else if (l1) launch<true, false>(a, blocks, st);
+    else if (l2) launch<false, true>(a, blocks, st);
+    else launch<false, false>(a, blocks, st);
 }
 
 }  // namespace
 
 namespace moe {
 
-// Launches both stages on `st`.  Shapes were validated by the caller (d_h, d_e multiples of 32).
-void launch_ffn_stream(const void *X, const void *W13p, const void *W2p, int T, int k, int C, int d_h, int d_e,
-                       const int32_t *slot_off, const int32_t *perm, uint16_t *act, int act_stride,
-                       float *Yp, hipStream_t st) {
-    // a slot receives at most one request per token, so T bounds its rows
+int launch_ffn_stream(const void *X, const void *W13p, const void *W2p, int T, int k, int C, int d_h, int d_e,
+                      const int32_t *slot_off, const int32_t *perm, int *ctrl, uint16_t *act, float *Yp,
+                      hipStream_t st) {
+    static_assert(kBlockTok == kFfnBlockRows, "block size is part of the workspace layout");
+    const long long items = ffn_max_blocks(T, k, C);
+    if (items > kMaxItems) return MOE_ESHAPE;
     StreamArgs a;
-    a.slot_off = slot_off; a.perm = perm; a.act = act; a.Yp = Yp; a.k = k; a.C = C;
-    a.B = static_cast<const uint16_t *>(X);
-    a.Wp = static_cast<const bf16x8 *>(W13p);
-    a.tiles = d_e / 16; a.KS = d_h / 32; a.b_stride = d_h; a.out_stride = act_stride;
-    launch_stage<true>(a, T, st);
-    a.B = act;
-    a.Wp = static_cast<const bf16x8 *>(W2p);
-    a.tiles = d_h / 32; a.KS = d_e / 32; a.b_stride = act_stride; a.out_stride = d_h;
-    launch_stage<false>(a, T, st);
+    a.slot_off = slot_off; a.perm = perm; a.act = act; a.Yp = Yp; a.ctrl = ctrl; a.k = k; a.C = C;
+    a.spin_limit = 1 << 20;
+    a.s[0].B = static_cast<const uint16_t *>(X);
+    a.s[0].Wp = static_cast<const char *>(W13p);
+    a.s[0].tiles = d_e / 16; a.s[0].KS = d_h / 32; a.s[0].b_stride = d_h; a.s[0].out_stride = 0;
+    a.s[1].B = act;
+    a.s[1].Wp = static_cast<const char *>(W2p);
+    a.s[1].tiles = d_h / 32; a.s[1].KS = d_e / 32; a.s[1].b_stride = 0; a.s[1].out_stride = d_h;
+    for (int i = 0; i < 2; ++i) a.s[i].tiles_pad = (a.s[i].tiles + 7) / 8 * 8;
+    const long long n1 = items * a.s[0].tiles_pad, n2 = items * a.s[1].tiles_pad;
+    if (n1 + n2 > 0x7fffffffLL) return MOE_ESHAPE;
+    a.n1 = static_cast<unsigned>(n1);
+    static const bool two_launches = getenv("MOE_JANUS_FFN_TWO_LAUNCHES") != nullptr;
+    if (two_launches) {
+        a.mode = 1; launch_lines(a, static_cast<unsigned>(n1), st);
+        a.mode = 2; launch_lines(a, static_cast<unsigned>(n2), st);
+    } else {
+        a.mode = 0; launch_lines(a, static_cast<unsigned>(n1 + n2), st);
+    }
+    return MOE_OK;
 }
 
 }  // namespace moe
