@@ -58,6 +58,7 @@ extern "C" {
 #define MOE_MAX_INSTANCES    64   /* n_inst */
 #define MOE_MAX_SLOTS       256   /* C */
 #define MOE_MAX_TOPK         32   /* k */
+#define MOE_FFN_BLOCK_ROWS   32   /* request rows of one slot per entry of the FFN work list */
 
 const char *moe_strerror(int code);
 const char *moe_last_error(void);
@@ -134,11 +135,22 @@ int moe_schedule(const moe_placement_t *pl, const int32_t *topk_ids_dev, int T, 
  *   slot_off_dev   [C+1]  int32  exclusive scan of slot_count; slot_off[C] = n_local
  *   perm_dev       [T*k]  int32  capacity T*k; the first n_local entries are request ids
  *   pos_dev        [T*k]  int32  pos[p] = row of request p in perm, or -1 if p is not local
- * n_local stays on the device (slot_off_dev[C]); nothing is read back.
+ *   blocks_dev     [moe_block_list_len(T, k, C)] int32, 16-byte aligned: the work list of
+ *                  moe_grouped_ffn.  The rows of every slot are cut into blocks of at most
+ *                  MOE_FFN_BLOCK_ROWS rows, slots in ascending order.  Four int32 per entry:
+ *                  entry 0 = {number of blocks B, 0, 0, 0}; entry 1+j = {slot, first row of the
+ *                  block, slot_off[slot+1], 0}.  Entries past B are left untouched.
+ * n_local and B stay on the device; nothing is read back.  The grouped FFN cannot size its
+ * launch by them, so it sizes it for moe_max_blocks() and lets the surplus leave at once.
  */
 int moe_permute(const moe_placement_t *pl, int g_self, const int32_t *rid_dev, int T, int k,
                 int32_t *slot_count_dev, int32_t *slot_off_dev, int32_t *perm_dev,
-                int32_t *pos_dev, void *stream);
+                int32_t *pos_dev, int32_t *blocks_dev, void *stream);
+
+/* Largest number of blocks a batch of T tokens can produce on an instance with C slots (a slot
+ * receives at most one request per token), and the int32 length of blocks_dev. */
+size_t moe_max_blocks(int T, int k, int C);
+size_t moe_block_list_len(int T, int k, int C);
 
 /* ------------------------------------------------------------------ a0-a4 in one launch
  * Same results, bit for bit, as moe_route + moe_schedule + moe_permute called one after the
@@ -151,7 +163,7 @@ int moe_route_schedule_permute(const moe_placement_t *pl, int g_self, const floa
                                const moe_route_cfg *cfg, int32_t *topk_ids_dev, float *topk_w_dev,
                                int32_t *rid_dev, int32_t *act_rep_dev, int32_t *load_dev,
                                int32_t *slot_count_dev, int32_t *slot_off_dev, int32_t *perm_dev,
-                               int32_t *pos_dev, int32_t *sync_dev, void *stream);
+                               int32_t *pos_dev, int32_t *blocks_dev, int32_t *sync_dev, void *stream);
 
 /* ------------------------------------------------------------------ expert weights
  * Canonical layout of one instance's physical experts (what a checkpoint holds):
@@ -179,31 +191,34 @@ int moe_pack_weights_bf16(const void *W13_dev, const void *W2_dev, int C, int d_
  *   X_dev  [T, d_h]  bf16 or f32 (dtype)
  *   W13_dev, W2_dev  packed (bf16) or canonical (f32), see above
  *   Yp_dev [T*k, d_h] float32, capacity T*k rows, rows >= n_local are left untouched
- *   workspace_dev    at least moe_workspace_bytes() bytes, 256-byte aligned; holds a small
- *                    header of progress counters and the intermediate a (bf16 or f32)
- *                    between the two GEMM stages.  The header must have been cleared with
+ *   blocks_dev       the work list moe_permute wrote for this batch (bf16 path; the f32 path
+ *                    does not read it and accepts NULL)
+ *   workspace_dev    at least moe_workspace_bytes() bytes, 256-byte aligned; holds a control
+ *                    region of hand-off flags and the intermediate a (bf16 or f32) between
+ *                    the two GEMM stages.  The control region must have been cleared with
  *                    moe_workspace_init() once after allocation; every call that runs to
  *                    completion leaves it cleared for the next one.  Calls that share a
  *                    workspace must not overlap in time.
  * bf16 inputs are multiplied on the matrix cores with fp32 accumulation; `a` is rounded
- * to bf16 once.  The bf16 path is one persistent kernel whose second stage polls the
- * counters of the first; the poll is bounded, and an overrun (which means the header was
- * not cleared, or the GPU was shared with work that starved the kernel) is reported by
- * moe_workspace_status() instead of hanging.
- * Limits: d_h % 32 == 0, d_e % 32 == 0 (bf16); d_h % 4 == 0, d_e % 4 == 0 (f32; T*k <= 65535).
+ * to bf16 once.  The bf16 path is one launch in which the workgroups of the second stage
+ * wait for flags raised by the first; the wait is bounded, and an overrun (which means the
+ * control region was not cleared, or the GPU was shared with work that starved the kernel)
+ * is reported by moe_workspace_status() instead of hanging.
+ * Limits: d_h % 32 == 0, d_e % 32 == 0 (bf16); d_h % 4 == 0, d_e % 4 == 0 (f32; T*k <= 65535);
+ * moe_max_blocks(T, k, C) <= 4095 (bf16).
  */
 size_t moe_workspace_bytes(int T, int k, int C, int d_h, int d_e, int dtype);
 
-/* Clears the workspace header (asynchronous on `stream`). */
+/* Clears the workspace's control region (asynchronous on `stream`). */
 int moe_workspace_init(void *workspace_dev, size_t workspace_bytes, void *stream);
 
 /* Synchronous read-back of the header's error word for tests and debugging (not for the hot
- * path): *status_host = 0 if no poll of the fused kernel ever overran since the last init. */
+ * path): *status_host = 0 if no wait of the bf16 kernel ever overran since the last init. */
 int moe_workspace_status(const void *workspace_dev, int *status_host);
 
 int moe_grouped_ffn(const void *X_dev, const void *W13_dev, const void *W2_dev,
                     int T, int k, int C, int d_h, int d_e, int dtype,
-                    const int32_t *slot_off_dev, const int32_t *perm_dev,
+                    const int32_t *slot_off_dev, const int32_t *perm_dev, const int32_t *blocks_dev,
                     float *Yp_dev, void *workspace_dev, size_t workspace_bytes, void *stream);
 
 /* ------------------------------------------------------------------ a6: combine

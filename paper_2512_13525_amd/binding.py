@@ -22,7 +22,8 @@ MOE_ROUTE_SOFTMAX, MOE_ROUTE_SIGMOID_GROUP = 0, 1
 EXPORTS = [
     "moe_strerror", "moe_last_error",
     "moe_placement_create", "moe_placement_destroy", "moe_placement_replicas", "moe_placement_dims",
-    "moe_route", "moe_schedule", "moe_permute", "moe_route_schedule_permute", "moe_pack_weights_bf16",
+    "moe_route", "moe_schedule", "moe_permute", "moe_max_blocks", "moe_block_list_len",
+    "moe_route_schedule_permute", "moe_pack_weights_bf16",
     "moe_workspace_bytes", "moe_workspace_init", "moe_workspace_status", "moe_grouped_ffn", "moe_combine",
 ]
 
@@ -68,9 +69,13 @@ def lib() -> ctypes.CDLL:
     L.moe_schedule.restype = ci
     L.moe_schedule.argtypes = [vp, vp, ci, ci, vp, vp, vp, vp]
     L.moe_permute.restype = ci
-    L.moe_permute.argtypes = [vp, ci, vp, ci, ci, vp, vp, vp, vp, vp]
+    L.moe_permute.argtypes = [vp, ci, vp, ci, ci, vp, vp, vp, vp, vp, vp]
+    L.moe_max_blocks.restype = cs
+    L.moe_max_blocks.argtypes = [ci, ci, ci]
+    L.moe_block_list_len.restype = cs
+    L.moe_block_list_len.argtypes = [ci, ci, ci]
     L.moe_route_schedule_permute.restype = ci
-    L.moe_route_schedule_permute.argtypes = [vp, ci, vp, ci, ci, ctypes.POINTER(moe_route_cfg)] + [vp] * 11
+    L.moe_route_schedule_permute.argtypes = [vp, ci, vp, ci, ci, ctypes.POINTER(moe_route_cfg)] + [vp] * 12
     L.moe_pack_weights_bf16.restype = ci
     L.moe_pack_weights_bf16.argtypes = [vp, vp, ci, ci, ci, vp, vp, vp]
     L.moe_workspace_bytes.restype = cs
@@ -80,7 +85,7 @@ def lib() -> ctypes.CDLL:
     L.moe_workspace_status.restype = ci
     L.moe_workspace_status.argtypes = [vp, ctypes.POINTER(ci)]
     L.moe_grouped_ffn.restype = ci
-    L.moe_grouped_ffn.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, ci, vp, vp, vp, vp, cs, vp]
+    L.moe_grouped_ffn.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, ci, vp, vp, vp, vp, vp, cs, vp]
     L.moe_combine.restype = ci
     L.moe_combine.argtypes = [vp, vp, vp, ci, ci, ci, ci, vp, vp]
     _lib = L
@@ -153,22 +158,30 @@ def moe_schedule(pl: Placement, topk_ids, T: int, k: int, rid, act_rep, load, st
                               _stream(stream)), "moe_schedule")
 
 
-def moe_permute(pl: Placement, g_self: int, rid, T: int, k: int, slot_count, slot_off, perm, pos,
+def moe_permute(pl: Placement, g_self: int, rid, T: int, k: int, slot_count, slot_off, perm, pos, blocks,
                 stream=None) -> None:
     _check(lib().moe_permute(pl.handle, g_self, _ptr(rid), T, k, _ptr(slot_count), _ptr(slot_off),
-                             _ptr(perm), _ptr(pos), _stream(stream)), "moe_permute")
+                             _ptr(perm), _ptr(pos), _ptr(blocks), _stream(stream)), "moe_permute")
+
+
+def moe_max_blocks(T: int, k: int, C: int) -> int:
+    return int(lib().moe_max_blocks(T, k, C))
+
+
+def moe_block_list_len(T: int, k: int, C: int) -> int:
+    return int(lib().moe_block_list_len(T, k, C))
 
 
 def moe_route_schedule_permute(pl: Placement, g_self: int, logits, k: int, topk_ids, topk_w, rid, act_rep, load,
-                               slot_count, slot_off, perm, pos, sync, mode: int = MOE_ROUTE_SOFTMAX,
+                               slot_count, slot_off, perm, pos, blocks, sync, mode: int = MOE_ROUTE_SOFTMAX,
                                renormalize: bool = True, n_group: int = 1, topk_group: int = 1, scale: float = 1.0,
                                stream=None) -> None:
     T = logits.shape[0]
     cfg = moe_route_cfg(mode, int(renormalize), n_group, topk_group, scale)
     _check(lib().moe_route_schedule_permute(pl.handle, g_self, _ptr(logits), T, k, ctypes.byref(cfg),
                                             _ptr(topk_ids), _ptr(topk_w), _ptr(rid), _ptr(act_rep), _ptr(load),
-                                            _ptr(slot_count), _ptr(slot_off), _ptr(perm), _ptr(pos), _ptr(sync),
-                                            _stream(stream)), "moe_route_schedule_permute")
+                                            _ptr(slot_count), _ptr(slot_off), _ptr(perm), _ptr(pos), _ptr(blocks),
+                                            _ptr(sync),                                             _stream(stream)), "moe_route_schedule_permute")
 
 
 def moe_pack_weights_bf16(W13, W2, C: int, d_h: int, d_e: int, W13_packed, W2_packed, stream=None) -> None:
@@ -192,10 +205,10 @@ def moe_workspace_status(workspace) -> int:
 
 
 def moe_grouped_ffn(X, W13, W2, T: int, k: int, C: int, d_h: int, d_e: int, dtype: int, slot_off, perm,
-                    Yp, workspace, stream=None) -> None:
+                    blocks, Yp, workspace, stream=None) -> None:
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib().moe_grouped_ffn(_ptr(X), _ptr(W13), _ptr(W2), T, k, C, d_h, d_e, dtype, _ptr(slot_off),
-                                 _ptr(perm), _ptr(Yp), _ptr(workspace), ws_bytes, _stream(stream)),
+                                 _ptr(perm), _ptr(blocks), _ptr(Yp), _ptr(workspace), ws_bytes, _stream(stream)),
            "moe_grouped_ffn")
 
 

@@ -43,7 +43,7 @@ constexpr size_t kFfnCtrlBytes = 4u << 20;
 
 // Upper bound of the number of blocks of kFfnBlockRows request rows over all slots: a slot
 // receives at most one request per token (a token's k experts are distinct).
-constexpr int kFfnBlockRows = 32;
+constexpr int kFfnBlockRows = MOE_FFN_BLOCK_ROWS;
 inline long long ffn_max_blocks(int T, int k, int C) {
     const long long per_slot = (T + kFfnBlockRows - 1) / kFfnBlockRows;
     const long long a = C * per_slot, b = C + static_cast<long long>(T) * k / kFfnBlockRows;
@@ -54,7 +54,7 @@ inline long long ffn_max_blocks(int T, int k, int C) {
 // control region of the workspace, `act` holds ffn_max_blocks(T, k, C) blocks of kFfnBlockRows x d_e
 // bf16.  Returns MOE_OK or MOE_ESHAPE (too many blocks).
 int launch_ffn_stream(const void *X, const void *W13p, const void *W2p, int T, int k, int C, int d_h, int d_e,
-                      const int32_t *slot_off, const int32_t *perm, int *ctrl, uint16_t *act, float *Yp,
+                      const int32_t *blocks, const int32_t *perm, int *ctrl, uint16_t *act, float *Yp,
                       hipStream_t st);
 
 inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }

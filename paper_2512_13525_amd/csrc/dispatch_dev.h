@@ -347,7 +347,56 @@ struct PermShared {
     int cnt[kFrontWaves][MOE_MAX_SLOTS];     // pass A: counts; pass B: running bases
     int total[MOE_MAX_SLOTS];
     int off[MOE_MAX_SLOTS + 1];
+    int blk_base[MOE_MAX_SLOTS + 1];         // exclusive scan of the slots' block counts
 };
+
+// Exclusive scan over slots of the request totals (sh.total -> sh.off, slot_off) and of the block
+// counts ceil(total / MOE_FFN_BLOCK_ROWS) (-> sh.blk_base).  First wavefront, 64 slots per round.
+__device__ __forceinline__ void scan_slots(PermShared &sh, int C, int32_t *__restrict__ slot_off, int lane) {
+    int carry = 0, bcarry = 0;
+    for (int s0 = 0; s0 < C; s0 += MOE_WAVE) {
+        const int s = s0 + lane;
+        const int v = s < C ? sh.total[s] : 0;
+        const int nb = (v + MOE_FFN_BLOCK_ROWS - 1) / MOE_FFN_BLOCK_ROWS;
+        int incl = v, bincl = nb;
+#pragma unroll
+        for (int d = 1; d < MOE_WAVE; d <<= 1) {
+            const int o = __shfl_up(incl, d, MOE_WAVE);
+            const int bo = __shfl_up(bincl, d, MOE_WAVE);
+            if (lane >= d) { incl += o; bincl += bo; }
+        }
+        if (s < C) {
+            sh.off[s] = carry + incl - v;
+            slot_off[s] = carry + incl - v;
+            sh.blk_base[s] = bcarry + bincl - nb;
+        }
+        carry += __shfl(incl, MOE_WAVE - 1, MOE_WAVE);
+        bcarry += __shfl(bincl, MOE_WAVE - 1, MOE_WAVE);
+    }
+    if (lane == 0) {
+        sh.off[C] = carry;
+        slot_off[C] = carry;
+        sh.blk_base[C] = bcarry;
+    }
+}
+
+// Work list of the grouped FFN (a5): the local request rows cut into blocks of at most
+// MOE_FFN_BLOCK_ROWS rows of one slot, slots in index order.  Entry 0 = {number of blocks, 0, 0, 0};
+// entry 1+j = {slot, first row, end of the slot's rows, 0}.  All threads, after scan_slots and a
+// barrier.
+__device__ __forceinline__ void list_blocks(const PermShared &sh, int C, int32_t *__restrict__ blocks) {
+    const int n_blocks = sh.blk_base[C];
+    int4 *out = reinterpret_cast<int4 *>(blocks);
+    if (threadIdx.x == 0) out[0] = make_int4(n_blocks, 0, 0, 0);
+    for (int j = threadIdx.x; j < n_blocks; j += blockDim.x) {
+        int lo = 0, hi = C;                       // last slot whose first block is <= j
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (sh.blk_base[mid] <= j) lo = mid; else hi = mid;
+        }
+        out[1 + j] = make_int4(lo, sh.off[lo] + (j - sh.blk_base[lo]) * MOE_FFN_BLOCK_ROWS, sh.off[lo + 1], 0);
+    }
+}
 
 // A stable counting sort of the local requests by slot.  Each wavefront owns a contiguous range of
 // request ids, so "ascending request id inside a slot" follows from (wave order, group order, lane
@@ -360,7 +409,7 @@ struct PermShared {
 __device__ __forceinline__ void permute_block(PermShared &sh, const int32_t *__restrict__ rid, int n_pairs,
                                               int g_self, int C, int32_t *__restrict__ slot_count,
                                               int32_t *__restrict__ slot_off, int32_t *__restrict__ perm,
-                                              int32_t *__restrict__ pos) {
+                                              int32_t *__restrict__ pos, int32_t *__restrict__ blocks) {
     const int tid = threadIdx.x;
     const int wave = tid / MOE_WAVE;
     const int lane = tid % MOE_WAVE;
@@ -395,30 +444,10 @@ __device__ __forceinline__ void permute_block(PermShared &sh, const int32_t *__r
     }
     __syncthreads();
 
-    // ---- exclusive scan over slots (first wavefront, 64 slots per round)
-    if (wave == 0) {
-        int carry = 0;
-        for (int s0 = 0; s0 < C; s0 += MOE_WAVE) {
-            const int s = s0 + lane;
-            const int v = s < C ? sh.total[s] : 0;
-            int incl = v;
-#pragma unroll
-            for (int d = 1; d < MOE_WAVE; d <<= 1) {
-                const int o = __shfl_up(incl, d, MOE_WAVE);
-                if (lane >= d) incl += o;
-            }
-            if (s < C) {
-                sh.off[s] = carry + incl - v;
-                slot_off[s] = carry + incl - v;
-            }
-            carry += __shfl(incl, MOE_WAVE - 1, MOE_WAVE);
-        }
-        if (lane == 0) {
-            sh.off[C] = carry;
-            slot_off[C] = carry;
-        }
-    }
+    // ---- exclusive scan over slots, then the FFN's work list
+    if (wave == 0) scan_slots(sh, C, slot_off, lane);
     __syncthreads();
+    list_blocks(sh, C, blocks);
 
     // ---- pass B
     volatile int *base = &sh.cnt[wave][0];

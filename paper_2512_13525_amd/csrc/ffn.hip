@@ -175,7 +175,7 @@ extern "C" int moe_pack_weights_bf16(const void *W13_dev, const void *W2_dev, in
 
 extern "C" int moe_grouped_ffn(const void *X_dev, const void *W13_dev, const void *W2_dev,
                                int T, int k, int C, int d_h, int d_e, int dtype,
-                               const int32_t *slot_off_dev, const int32_t *perm_dev,
+                               const int32_t *slot_off_dev, const int32_t *perm_dev, const int32_t *blocks_dev,
                                float *Yp_dev, void *workspace_dev, size_t workspace_bytes, void *stream) {
     if (T < 0 || k < 1 || C < 1 || d_h < 1 || d_e < 1) return MOE_EINVAL;
     if (dtype != MOE_DTYPE_BF16 && dtype != MOE_DTYPE_F32) return MOE_EINVAL;
@@ -189,13 +189,14 @@ extern "C" int moe_grouped_ffn(const void *X_dev, const void *W13_dev, const voi
         !moe::aligned(Yp_dev, 16) || !moe::aligned(workspace_dev, 256) || !moe::aligned(slot_off_dev, 4) ||
         !moe::aligned(perm_dev, 4))
         return MOE_EINVAL;
+    if (dtype == MOE_DTYPE_BF16 && (!blocks_dev || !moe::aligned(blocks_dev, 16))) return MOE_EINVAL;
     if (workspace_bytes < moe_workspace_bytes(T, k, C, d_h, d_e, dtype)) return MOE_EWORKSPACE;
     hipStream_t st = static_cast<hipStream_t>(stream);
     char *ws = static_cast<char *>(workspace_dev);
     if (dtype == MOE_DTYPE_BF16) {
         // the kernels address token rows with 32-bit byte offsets
         if (static_cast<long long>(T) * d_h * 2 > 0xffffffffLL) return MOE_ESHAPE;
-        const int rc = moe::launch_ffn_stream(X_dev, W13_dev, W2_dev, T, k, C, d_h, d_e, slot_off_dev, perm_dev,
+        const int rc = moe::launch_ffn_stream(X_dev, W13_dev, W2_dev, T, k, C, d_h, d_e, blocks_dev, perm_dev,
                                               reinterpret_cast<int *>(ws), reinterpret_cast<uint16_t *>(ws + kCtrlBytes),
                                               Yp_dev, st);
         if (rc != MOE_OK) return rc;

@@ -7,8 +7,9 @@
 // gate+up channels in stage 1, 32 output channels in stage 2); one workgroup per item, in plain
 // grid order, dispatched by the hardware.  Slots without requests own no item: their weights are
 // never read.  Nothing about the activated set is known on the host, so the grid is sized for
-// the largest possible number of blocks and every wavefront finds its item from slot_off;
-// workgroups past the last block leave at once.
+// the largest possible number of blocks; the dispatch step leaves the list of blocks in device
+// memory, a workgroup reads its entry with two scalar loads, and workgroups past the last block
+// leave at once.
 //
 // The 4 wavefronts of a workgroup split the K dimension of the tile round-robin in super-steps
 // of 64 columns and meet in LDS once, at the end (fixed summation order: results are
@@ -65,7 +66,7 @@ struct StageArgs {
 
 struct StreamArgs {
     StageArgs s[2];
-    const int32_t *slot_off;
+    const int32_t *blocks;               // work list written by the dispatch step
     const int32_t *perm;
     uint16_t *act;                       // stage-1 output
     float *Yp;                           // stage-2 output
@@ -387,48 +388,18 @@ __device__ __forceinline__ void stream_item_steps(const StreamArgs &a, const Sta
     reduce_store<STAGE1, NT>(a, g, red, acc, item, tile, row0, row_end, wave, lane);
 }
 
-__device__ __forceinline__ int wave_scan_inclusive(int v, int lane) {
-#pragma unroll
-    for (int off = 1; off < MOE_WAVE; off <<= 1) {
-        const int o = __shfl_up(v, off, MOE_WAVE);
-        if (lane >= off) v += o;
-    }
-    return v;
-}
-
-// Block j of the launch: the j-th block of kBlockTok request rows when the blocks of all slots
-// are listed in slot order (blocks of a slot adjacent).  Every wavefront works this out for
-// itself from slot_off (64 slots per round).  Returns false past the last block.
-__device__ __forceinline__ bool find_block(const int32_t *__restrict__ slot_off, int C, int j, int lane,
-                                           int *slot, int *blk) {
-    int base = 0;
-    for (int c0 = 0; c0 < C; c0 += MOE_WAVE) {
-        const int sidx = c0 + lane;
-        const int cnt = sidx < C ? slot_off[sidx + 1] - slot_off[sidx] : 0;
-        const int v = (cnt + kBlockTok - 1) / kBlockTok;
-        const int incl = wave_scan_inclusive(v, lane);
-        const int lo = base + incl - v;
-        const uint64_t hit = __ballot(v > 0 && j >= lo && j < lo + v);
-        if (hit) {
-            const int l = __builtin_ctzll(hit);
-            *slot = c0 + l;
-            *blk = j - __builtin_amdgcn_readlane(lo, l);
-            return true;
-        }
-        base += __builtin_amdgcn_readlane(incl, MOE_WAVE - 1);
-    }
-    return false;
-}
-
 template <bool STAGE1, bool LINES, bool WAIT>
 __device__ __forceinline__ void run_item(const StreamArgs &a, const StageArgs &g, char *lds, unsigned id) {
     const int tile = id % g.tiles_pad, item = id / g.tiles_pad;
     if (tile >= g.tiles) return;
+    // work list entry: {slot, first row, end of the slot's rows}; entry 0 holds the number of blocks
+    // (both are wave-uniform scalar loads issued together; an entry past the end is never used)
+    const int4 *list = reinterpret_cast<const int4 *>(a.blocks);
+    const int n_blocks = list[0].x;
+    const int4 ent = list[1 + item];
+    if (item >= n_blocks) return;                                // past the last block: nothing else is read
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / MOE_WAVE), lane = threadIdx.x % MOE_WAVE;
-    int slot, blk;
-    if (!find_block(a.slot_off, a.C, item, lane, &slot, &blk)) return;   // past the last block: nothing is read
-    const int lo = a.slot_off[slot], hi = a.slot_off[slot + 1];
-    const int row0 = lo + blk * kBlockTok;
+    const int slot = ent.x, row0 = ent.y, hi = ent.z;
     const char *w = g.Wp + (static_cast<size_t>(slot) * g.tiles + tile) * g.KS * 2048;
     const int m = hi - row0;
     if (LINES) {
@@ -510,13 +481,13 @@ void launch_lines(const StreamArgs &a, unsigned blocks, hipStream_t st) {
 namespace moe {
 
 int launch_ffn_stream(const void *X, const void *W13p, const void *W2p, int T, int k, int C, int d_h, int d_e,
-                      const int32_t *slot_off, const int32_t *perm, int *ctrl, uint16_t *act, float *Yp,
+                      const int32_t *blocks, const int32_t *perm, int *ctrl, uint16_t *act, float *Yp,
                       hipStream_t st) {
     static_assert(kBlockTok == kFfnBlockRows, "block size is part of the workspace layout");
     const long long items = ffn_max_blocks(T, k, C);
     if (items > kMaxItems) return MOE_ESHAPE;
     StreamArgs a;
-    a.slot_off = slot_off; a.perm = perm; a.act = act; a.Yp = Yp; a.ctrl = ctrl; a.k = k; a.C = C;
+    a.blocks = blocks; a.perm = perm; a.act = act; a.Yp = Yp; a.ctrl = ctrl; a.k = k; a.C = C;
     a.spin_limit = 1 << 20;
     a.s[0].B = static_cast<const uint16_t *>(X);
     a.s[0].Wp = static_cast<const char *>(W13p);

@@ -18,7 +18,7 @@ struct FrontArgs {
     float *w;
     moe::SchedTables tb;
     int n_inst, C, n_words, g_self;
-    int32_t *rid, *act_rep, *load, *slot_count, *slot_off, *perm, *pos;
+    int32_t *rid, *act_rep, *load, *slot_count, *slot_off, *perm, *pos, *blocks;
     int32_t *ticket;
 };
 
@@ -158,29 +158,9 @@ __device__ __forceinline__ void front_tail_small(const FrontArgs &a, SmallShared
         a.slot_count[s] = run;
     }
     __syncthreads();
-    if (wave == 0) {
-        int carry = 0;
-        for (int s0 = 0; s0 < C; s0 += MOE_WAVE) {
-            const int s = s0 + lane;
-            const int v = s < C ? sh.perm.total[s] : 0;
-            int incl = v;
-#pragma unroll
-            for (int d = 1; d < MOE_WAVE; d <<= 1) {
-                const int o = __shfl_up(incl, d, MOE_WAVE);
-                if (lane >= d) incl += o;
-            }
-            if (s < C) {
-                sh.perm.off[s] = carry + incl - v;
-                a.slot_off[s] = carry + incl - v;
-            }
-            carry += __shfl(incl, MOE_WAVE - 1, MOE_WAVE);
-        }
-        if (lane == 0) {
-            sh.perm.off[C] = carry;
-            a.slot_off[C] = carry;
-        }
-    }
+    if (wave == 0) moe::scan_slots(sh.perm, C, a.slot_off, lane);
     __syncthreads();
+    moe::list_blocks(sh.perm, C, a.blocks);
 
     // ---- pass B
     volatile int *base = &sh.perm.cnt[wave][0];
@@ -258,7 +238,7 @@ void front_kernel(FrontArgs a) {
     // rid is re-read below by other wavefronts of this workgroup
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
-    moe::permute_block(sh.perm, a.rid, n_pairs, a.g_self, a.C, a.slot_count, a.slot_off, a.perm, a.pos);
+    moe::permute_block(sh.perm, a.rid, n_pairs, a.g_self, a.C, a.slot_count, a.slot_off, a.perm, a.pos, a.blocks);
 }
 
 template <int VPL>
@@ -274,7 +254,7 @@ extern "C" int moe_route_schedule_permute(const moe_placement_t *pl, int g_self,
                                           const moe_route_cfg *cfg, int32_t *topk_ids_dev, float *topk_w_dev,
                                           int32_t *rid_dev, int32_t *act_rep_dev, int32_t *load_dev,
                                           int32_t *slot_count_dev, int32_t *slot_off_dev, int32_t *perm_dev,
-                                          int32_t *pos_dev, int32_t *sync_dev, void *stream) {
+                                          int32_t *pos_dev, int32_t *blocks_dev, int32_t *sync_dev, void *stream) {
     if (!pl || !cfg || T < 0 || k < 1) return MOE_EINVAL;
     const int E = pl->E;
     if (k > E) return MOE_EINVAL;
@@ -287,19 +267,20 @@ extern "C" int moe_route_schedule_permute(const moe_placement_t *pl, int g_self,
         if (cfg->n_group > 64 || E % cfg->n_group != 0 || E / cfg->n_group < 2) return MOE_ESHAPE;
         if (k > cfg->topk_group * (E / cfg->n_group)) return MOE_EINVAL;
     }
-    if (!act_rep_dev || !load_dev || !slot_count_dev || !slot_off_dev || !sync_dev) return MOE_EINVAL;
+    if (!act_rep_dev || !load_dev || !slot_count_dev || !slot_off_dev || !blocks_dev || !sync_dev) return MOE_EINVAL;
     if (T > 0 && (!logits_dev || !topk_ids_dev || !topk_w_dev || !rid_dev || !perm_dev || !pos_dev)) return MOE_EINVAL;
     const void *ptrs[] = {logits_dev, topk_ids_dev, topk_w_dev, rid_dev, act_rep_dev, load_dev,
                           slot_count_dev, slot_off_dev, perm_dev, pos_dev, sync_dev};
     for (const void *p : ptrs)
         if (!moe::aligned(p, 4)) return MOE_EINVAL;
+    if (!moe::aligned(blocks_dev, 16)) return MOE_EINVAL;
     FrontArgs a;
     a.logits = logits_dev; a.T = T; a.E = E; a.k = k; a.cfg = *cfg;
     a.ids = topk_ids_dev; a.w = topk_w_dev;
     a.tb = moe::SchedTables{pl->host_mask_d, pl->slot_of_d, pl->single_rid_d, pl->multi_mask_d, pl->single_mask_d};
     a.n_inst = pl->n_inst; a.C = pl->C; a.n_words = pl->n_words; a.g_self = g_self;
     a.rid = rid_dev; a.act_rep = act_rep_dev; a.load = load_dev;
-    a.slot_count = slot_count_dev; a.slot_off = slot_off_dev; a.perm = perm_dev; a.pos = pos_dev;
+    a.slot_count = slot_count_dev; a.slot_off = slot_off_dev; a.perm = perm_dev; a.pos = pos_dev; a.blocks = blocks_dev;
     a.ticket = sync_dev;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int vpl = (E + MOE_WAVE - 1) / MOE_WAVE;

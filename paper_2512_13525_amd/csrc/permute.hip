@@ -10,9 +10,9 @@ constexpr int kPermThreads = moe::kFrontThreads;
 __global__ __launch_bounds__(kPermThreads)
 void permute_kernel(const int32_t *__restrict__ rid, int n_pairs, int g_self, int C,
                     int32_t *__restrict__ slot_count, int32_t *__restrict__ slot_off,
-                    int32_t *__restrict__ perm, int32_t *__restrict__ pos) {
+                    int32_t *__restrict__ perm, int32_t *__restrict__ pos, int32_t *__restrict__ blocks) {
     __shared__ moe::PermShared sh;
-    moe::permute_block(sh, rid, n_pairs, g_self, C, slot_count, slot_off, perm, pos);
+    moe::permute_block(sh, rid, n_pairs, g_self, C, slot_count, slot_off, perm, pos, blocks);
 }
 
 // One workgroup per (token, 1024-column chunk); each thread owns 4 consecutive columns.
@@ -45,19 +45,29 @@ void combine_kernel(const float *__restrict__ Yp, const int32_t *__restrict__ po
 
 extern "C" int moe_permute(const moe_placement_t *pl, int g_self, const int32_t *rid_dev, int T, int k,
                            int32_t *slot_count_dev, int32_t *slot_off_dev, int32_t *perm_dev,
-                           int32_t *pos_dev, void *stream) {
+                           int32_t *pos_dev, int32_t *blocks_dev, void *stream) {
     if (!pl || T < 0 || k < 1) return MOE_EINVAL;
     if (g_self < 0 || g_self >= pl->n_inst) return MOE_EINVAL;
     if (k > MOE_MAX_TOPK) return MOE_ESHAPE;
     if (static_cast<long long>(T) * k > 0x7fffffffLL) return MOE_ESHAPE;
-    if (!slot_count_dev || !slot_off_dev) return MOE_EINVAL;
+    if (!slot_count_dev || !slot_off_dev || !blocks_dev) return MOE_EINVAL;
     if (T > 0 && (!rid_dev || !perm_dev || !pos_dev)) return MOE_EINVAL;
     if (!moe::aligned(rid_dev, 4) || !moe::aligned(slot_count_dev, 4) || !moe::aligned(slot_off_dev, 4) ||
-        !moe::aligned(perm_dev, 4) || !moe::aligned(pos_dev, 4))
+        !moe::aligned(perm_dev, 4) || !moe::aligned(pos_dev, 4) || !moe::aligned(blocks_dev, 16))
         return MOE_EINVAL;
     hipLaunchKernelGGL(permute_kernel, dim3(1), dim3(kPermThreads), 0, static_cast<hipStream_t>(stream),
-                       rid_dev, T * k, g_self, pl->C, slot_count_dev, slot_off_dev, perm_dev, pos_dev);
+                       rid_dev, T * k, g_self, pl->C, slot_count_dev, slot_off_dev, perm_dev, pos_dev, blocks_dev);
     return moe::check_launch("moe_permute");
+}
+
+extern "C" size_t moe_max_blocks(int T, int k, int C) {
+    if (T < 0 || k < 1 || C < 1) return 0;
+    return static_cast<size_t>(moe::ffn_max_blocks(T, k, C));
+}
+
+extern "C" size_t moe_block_list_len(int T, int k, int C) {
+    if (T < 0 || k < 1 || C < 1) return 0;
+    return 4 * (1 + static_cast<size_t>(moe::ffn_max_blocks(T, k, C)));
 }
 
 extern "C" int moe_combine(const float *Yp_dev, const int32_t *pos_dev, const float *topk_w_dev,

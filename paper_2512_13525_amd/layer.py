@@ -37,6 +37,7 @@ class LayerStep:
         self.slot_off = torch.empty((C + 1,), **i32)
         self.perm = torch.empty((T * k,), **i32)
         self.pos = torch.empty((T * k,), **i32)
+        self.blocks = torch.empty((B.moe_block_list_len(T, k, C),), **i32)
         self.Yp = torch.empty((T * k, cfg.d_h), dtype=torch.float32, device=device)
         self.Y = torch.empty((T, cfg.d_h), dtype=self.tdtype, device=device)
         ws = B.moe_workspace_bytes(T, k, C, cfg.d_h, cfg.d_e, self.dtype)
@@ -76,7 +77,7 @@ class LayerStep:
     def permute(self, stream=None):
         c = self.cfg
         B.moe_permute(self.pl, self.g_self, self.rid, c.T, c.k, self.slot_count, self.slot_off,
-                      self.perm, self.pos, stream=stream)
+                      self.perm, self.pos, self.blocks, stream=stream)
 
     def front(self, logits, stream=None):
         """route + schedule + permute in one launch."""
@@ -84,13 +85,13 @@ class LayerStep:
         group = c.route != "softmax"
         B.moe_route_schedule_permute(self.pl, self.g_self, logits, c.k, self.topk_ids, self.topk_w, self.rid,
                                      self.act_rep, self.load, self.slot_count, self.slot_off, self.perm, self.pos,
-                                     self.sync, B.MOE_ROUTE_SIGMOID_GROUP if group else B.MOE_ROUTE_SOFTMAX, True,
+                                     self.blocks, self.sync, B.MOE_ROUTE_SIGMOID_GROUP if group else B.MOE_ROUTE_SOFTMAX, True,
                                      c.n_group if group else 1, c.topk_group if group else 1, 1.0, stream=stream)
 
     def ffn(self, X, stream=None, W13=None, W2=None):
         c = self.cfg
         B.moe_grouped_ffn(X, self.W13 if W13 is None else W13, self.W2 if W2 is None else W2,
-                          c.T, c.k, c.C, c.d_h, c.d_e, self.dtype, self.slot_off, self.perm,
+                          c.T, c.k, c.C, c.d_h, c.d_e, self.dtype, self.slot_off, self.perm, self.blocks,
                           self.Yp, self.workspace, stream=stream)
 
     def combine(self, stream=None):

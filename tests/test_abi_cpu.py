@@ -65,19 +65,23 @@ def test_argument_validation_without_launch():
     g = B.moe_route_cfg(B.MOE_ROUTE_SIGMOID_GROUP, 1, 3, 2, 1.0)
     assert L.moe_route(None, 4, 8, 2, ctypes.byref(g), None, None, None) == B.MOE_ESHAPE       # 8 % 3
     assert L.moe_schedule(None, None, 4, 2, None, None, None, None) == B.MOE_EINVAL
-    assert L.moe_permute(None, 0, None, 4, 2, None, None, None, None, None) == B.MOE_EINVAL
+    assert L.moe_permute(None, 0, None, 4, 2, None, None, None, None, None, None) == B.MOE_EINVAL
     # FFN: shapes first, then pointers
-    assert L.moe_grouped_ffn(None, None, None, 4, 2, 5, 100, 64, B.MOE_DTYPE_BF16, None, None, None, None, 0,
+    assert L.moe_grouped_ffn(None, None, None, 4, 2, 5, 100, 64, B.MOE_DTYPE_BF16, None, None, None, None, None, 0,
                              None) == B.MOE_ESHAPE
-    assert L.moe_grouped_ffn(None, None, None, 4, 2, 5, 128, 64, B.MOE_DTYPE_BF16, None, None, None, None, 0,
+    assert L.moe_grouped_ffn(None, None, None, 4, 2, 5, 128, 64, B.MOE_DTYPE_BF16, None, None, None, None, None, 0,
                              None) == B.MOE_EINVAL
-    assert L.moe_grouped_ffn(None, None, None, 4, 2, 5, 128, 64, 7, None, None, None, None, 0, None) == B.MOE_EINVAL
-    assert L.moe_grouped_ffn(None, None, None, 0, 2, 5, 128, 64, B.MOE_DTYPE_BF16, None, None, None, None, 0,
+    assert L.moe_grouped_ffn(None, None, None, 4, 2, 5, 128, 64, 7, None, None, None, None, None, 0, None) == B.MOE_EINVAL
+    assert L.moe_grouped_ffn(None, None, None, 0, 2, 5, 128, 64, B.MOE_DTYPE_BF16, None, None, None, None, None, 0,
                              None) == B.MOE_OK
     assert L.moe_combine(None, None, None, 4, 2, 130, B.MOE_DTYPE_F32, None, None) == B.MOE_ESHAPE
     assert L.moe_combine(None, None, None, 4, 2, 128, B.MOE_DTYPE_F32, None, None) == B.MOE_EINVAL
     assert L.moe_pack_weights_bf16(None, None, 2, 100, 64, None, None, None) == B.MOE_ESHAPE
     assert L.moe_workspace_init(None, 0, None) == B.MOE_EINVAL
+    # a slot gets at most one request per token: min(C*ceil(T/32), C + T*k/32) blocks
+    assert L.moe_max_blocks(128, 6, 17) == 17 + 128 * 6 // 32
+    assert L.moe_max_blocks(16, 8, 36) == 36
+    assert L.moe_block_list_len(128, 6, 17) == 4 * (1 + 41)
     assert L.moe_workspace_status(None, None) == B.MOE_EINVAL
     ws = L.moe_workspace_bytes(128, 6, 17, 2048, 1408, B.MOE_DTYPE_BF16)
     assert ws >= 128 * 6 * 1408 * 2 and ws % 256 == 0

@@ -11,7 +11,7 @@ from paper_2512_13525_amd import workloads as W
 from paper_2512_13525_amd.layer import LayerStep, to_device_bf16
 from oracle import dispatch, ffn, scheduling
 
-from helpers import OracleRun, oracle_route, rel_fro
+from helpers import OracleRun, expected_blocks, oracle_route, rel_fro
 
 pytestmark = pytest.mark.gpu
 
@@ -131,8 +131,14 @@ def test_schedule_and_permute_parity(cfg):
         d_off = torch.full((cfg.C + 1,), -9, dtype=torch.int32, device="cuda")
         d_perm = torch.full((n,), -9, dtype=torch.int32, device="cuda")
         d_pos = torch.full((n,), -9, dtype=torch.int32, device="cuda")
-        B.moe_permute(pl, g, d_rid, cfg.T, cfg.k, d_cnt, d_off, d_perm, d_pos)
+        d_blk = torch.full((B.moe_block_list_len(cfg.T, cfg.k, cfg.C),), -9, dtype=torch.int32, device="cuda")
+        B.moe_permute(pl, g, d_rid, cfg.T, cfg.k, d_cnt, d_off, d_perm, d_pos, d_blk)
         torch.cuda.synchronize()
+        blk = expected_blocks(off)
+        assert blk[0] <= B.moe_max_blocks(cfg.T, cfg.k, cfg.C)
+        g_blk = d_blk.cpu().numpy()
+        np.testing.assert_array_equal(g_blk[:len(blk)], blk)
+        assert (g_blk[len(blk):] == -9).all()                   # entries past the last block untouched
         np.testing.assert_array_equal(d_cnt.cpu().numpy(), cnt)
         np.testing.assert_array_equal(d_off.cpu().numpy(), off)
         g_perm = d_perm.cpu().numpy()
@@ -220,7 +226,7 @@ def test_fused_front_equals_separate_calls(cfg):
     b = LayerStep(cfg, lay, cfg.n_inst - 1)
     a.route(logits); a.schedule(); a.permute()
     for rep in range(3):
-        for t in (b.topk_ids, b.rid, b.act_rep, b.load, b.slot_count, b.slot_off, b.perm, b.pos):
+        for t in (b.topk_ids, b.rid, b.act_rep, b.load, b.slot_count, b.slot_off, b.perm, b.pos, b.blocks):
             t.fill_(-5)
         b.front(logits)
         torch.cuda.synchronize()
@@ -228,6 +234,8 @@ def test_fused_front_equals_separate_calls(cfg):
         for name in ("topk_ids", "topk_w", "rid", "act_rep", "load", "slot_count", "slot_off", "pos"):
             assert torch.equal(getattr(a, name), getattr(b, name)), (name, rep)
         assert torch.equal(a.perm[:n_local], b.perm[:n_local])
+        n_blk = 4 * (1 + int(a.blocks[0].item()))
+        assert torch.equal(a.blocks[:n_blk], b.blocks[:n_blk])
         assert int(b.sync[0].item()) == 0
 
 
@@ -271,5 +279,5 @@ def test_ffn_rejects_small_workspace():
     step = LayerStep(cfg, W.build_placement(cfg), 0)
     with pytest.raises(B.MoeError) as ei:
         B.moe_grouped_ffn(step.Y, step.Y, step.Y, cfg.T, cfg.k, cfg.C, cfg.d_h, cfg.d_e, step.dtype,
-                          step.slot_off, step.perm, step.Yp, step.workspace[:256])
+                          step.slot_off, step.perm, step.blocks, step.Yp, step.workspace[:256])
     assert ei.value.code == B.MOE_EWORKSPACE
