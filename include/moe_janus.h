@@ -137,7 +137,8 @@ int moe_schedule(const moe_placement_t *pl, const int32_t *topk_ids_dev, int T, 
  *   pos_dev        [T*k]  int32  pos[p] = row of request p in perm, or -1 if p is not local
  *   blocks_dev     [moe_block_list_len(T, k, C)] int32, 16-byte aligned: the work list of
  *                  moe_grouped_ffn.  The rows of every slot are cut into blocks of at most
- *                  MOE_FFN_BLOCK_ROWS rows, slots in ascending order.  Four int32 per entry:
+ *                  MOE_FFN_BLOCK_ROWS rows; slots with more than 16 requests come first (their
+ *                  work takes longest), ascending slot order otherwise.  Four int32 per entry:
  *                  entry 0 = {number of blocks B, 0, 0, 0}; entry 1+j = {slot, first row of the
  *                  block, slot_off[slot+1], 0}.  Entries past B are left untouched.
  * n_local and B stay on the device; nothing is read back.  The grouped FFN cannot size its

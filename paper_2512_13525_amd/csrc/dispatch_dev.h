@@ -350,51 +350,56 @@ struct PermShared {
     int blk_base[MOE_MAX_SLOTS + 1];         // exclusive scan of the slots' block counts
 };
 
-// Exclusive scan over slots of the request totals (sh.total -> sh.off, slot_off) and of the block
-// counts ceil(total / MOE_FFN_BLOCK_ROWS) (-> sh.blk_base).  First wavefront, 64 slots per round.
+// Exclusive scan over slots of the request totals (sh.total -> sh.off, slot_off), and the place of
+// every slot's first block in the FFN work list (-> sh.blk_base; sh.blk_base[C] = number of blocks):
+// slots with more than kHeavyRows requests come first, slot order within each class.  First
+// wavefront, 64 slots per round.
+constexpr int kHeavyRows = 16;
 __device__ __forceinline__ void scan_slots(PermShared &sh, int C, int32_t *__restrict__ slot_off, int lane) {
-    int carry = 0, bcarry = 0;
+    int carry = 0, hcarry = 0, lcarry = 0;
     for (int s0 = 0; s0 < C; s0 += MOE_WAVE) {
         const int s = s0 + lane;
         const int v = s < C ? sh.total[s] : 0;
         const int nb = (v + MOE_FFN_BLOCK_ROWS - 1) / MOE_FFN_BLOCK_ROWS;
-        int incl = v, bincl = nb;
+        const int hb = v > kHeavyRows ? nb : 0, lb = nb - hb;
+        int incl = v, hincl = hb, lincl = lb;
 #pragma unroll
         for (int d = 1; d < MOE_WAVE; d <<= 1) {
             const int o = __shfl_up(incl, d, MOE_WAVE);
-            const int bo = __shfl_up(bincl, d, MOE_WAVE);
-            if (lane >= d) { incl += o; bincl += bo; }
+            const int ho = __shfl_up(hincl, d, MOE_WAVE);
+            const int lo = __shfl_up(lincl, d, MOE_WAVE);
+            if (lane >= d) { incl += o; hincl += ho; lincl += lo; }
         }
         if (s < C) {
             sh.off[s] = carry + incl - v;
             slot_off[s] = carry + incl - v;
-            sh.blk_base[s] = bcarry + bincl - nb;
+            // light slots are placed relative to the end of the heavy class, added below
+            sh.blk_base[s] = hb ? hcarry + hincl - hb : -(lcarry + lincl - lb) - 1;
         }
         carry += __shfl(incl, MOE_WAVE - 1, MOE_WAVE);
-        bcarry += __shfl(bincl, MOE_WAVE - 1, MOE_WAVE);
+        hcarry += __shfl(hincl, MOE_WAVE - 1, MOE_WAVE);
+        lcarry += __shfl(lincl, MOE_WAVE - 1, MOE_WAVE);
     }
+    for (int s = lane; s < C; s += MOE_WAVE)
+        if (sh.blk_base[s] < 0) sh.blk_base[s] = hcarry + (-sh.blk_base[s] - 1);
     if (lane == 0) {
         sh.off[C] = carry;
         slot_off[C] = carry;
-        sh.blk_base[C] = bcarry;
+        sh.blk_base[C] = hcarry + lcarry;
     }
 }
 
 // Work list of the grouped FFN (a5): the local request rows cut into blocks of at most
-// MOE_FFN_BLOCK_ROWS rows of one slot, slots in index order.  Entry 0 = {number of blocks, 0, 0, 0};
-// entry 1+j = {slot, first row, end of the slot's rows, 0}.  All threads, after scan_slots and a
-// barrier.
+// MOE_FFN_BLOCK_ROWS rows of one slot, in the order scan_slots fixed.  Entry 0 = {number of blocks,
+// 0, 0, 0}; entry 1+j = {slot, first row, end of the slot's rows, 0}.  All threads, after
+// scan_slots and a barrier; one thread per slot writes that slot's entries.
 __device__ __forceinline__ void list_blocks(const PermShared &sh, int C, int32_t *__restrict__ blocks) {
-    const int n_blocks = sh.blk_base[C];
     int4 *out = reinterpret_cast<int4 *>(blocks);
-    if (threadIdx.x == 0) out[0] = make_int4(n_blocks, 0, 0, 0);
-    for (int j = threadIdx.x; j < n_blocks; j += blockDim.x) {
-        int lo = 0, hi = C;                       // last slot whose first block is <= j
-        while (hi - lo > 1) {
-            const int mid = (lo + hi) >> 1;
-            if (sh.blk_base[mid] <= j) lo = mid; else hi = mid;
-        }
-        out[1 + j] = make_int4(lo, sh.off[lo] + (j - sh.blk_base[lo]) * MOE_FFN_BLOCK_ROWS, sh.off[lo + 1], 0);
+    if (threadIdx.x == 0) out[0] = make_int4(sh.blk_base[C], 0, 0, 0);
+    for (int s = threadIdx.x; s < C; s += blockDim.x) {
+        const int lo = sh.off[s], hi = sh.off[s + 1];
+        int j = sh.blk_base[s];
+        for (int r = lo; r < hi; r += MOE_FFN_BLOCK_ROWS) out[1 + j++] = make_int4(s, r, hi, 0);
     }
 }
 

@@ -27,8 +27,6 @@
 // agent-scope stores and read with agent-scope loads, and the counters are agent-scope atomics,
 // because the 8 XCDs do not share an L2.  The last stage-2 workgroup of a block to get through
 // the wait clears the block's counters for the next call.
-#include <stdlib.h>
-
 #include "common.h"
 
 namespace {
@@ -72,8 +70,6 @@ struct StreamArgs {
     float *Yp;                           // stage-2 output
     int *ctrl;
     int k, C;
-    unsigned n1;                         // workgroups of stage 1 (ids below n1)
-    int mode;                            // 0: both stages in this launch; 1 / 2: that stage alone
     int spin_limit;
 };
 
@@ -411,7 +407,7 @@ __device__ __forceinline__ void run_item(const StreamArgs &a, const StageArgs &g
         if (m <= 16) stream_item_steps<STAGE1, 1, WAIT>(a, g, lds, w, item, tile, row0, hi, wave, lane);
         else stream_item_steps<STAGE1, 2, WAIT>(a, g, lds, w, item, tile, row0, hi, wave, lane);
     }
-    if (STAGE1 && a.mode == 0) {
+    if (STAGE1) {
         // announce the tile: every thread waits for its own act stores to be acknowledged, then
         // one thread bumps the block's counter and, if it completes the count, raises the ready flags
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -428,12 +424,13 @@ __device__ __forceinline__ void run_item(const StreamArgs &a, const StageArgs &g
     }
 }
 
-// 1-D grid: stage-1 workgroups (ids below n1), then stage-2 workgroups; within a stage, id =
-// block * tiles_pad + tile.  Workgroups are dispatched in id order, so a stage-2 workgroup is
-// started after every stage-1 workgroup, and go to the XCDs round-robin, so the blocks of one tile
-// of a slot (ids tiles_pad apart, a multiple of 8) run on the same XCD at about the same time: the
-// tile's weights come from HBM once and are shared through that XCD's L2.  LINES1 / LINES2 select
-// the whole-line token path of a stage (even number of K-steps).
+// 1-D grid sized for the worst case.  With B = the batch's number of blocks, ids below B*tiles_pad(1)
+// are the stage-1 workgroups (id = block * tiles_pad + tile), the next B*tiles_pad(2) ids the
+// stage-2 workgroups, and the rest leave at once.  Workgroups are dispatched in id order, so a
+// stage-2 workgroup is started after every stage-1 workgroup, and go to the XCDs round-robin, so
+// the blocks of one tile of a slot (ids tiles_pad apart, a multiple of 8) run on the same XCD at
+// about the same time: the tile's weights come from HBM once and are shared through that XCD's
+// L2.  LINES1 / LINES2 select the whole-line token path of a stage (even number of K-steps).
 template <bool LINES1, bool LINES2>
 __global__ __launch_bounds__(kThreads, 4)
 void ffn_stream_kernel(StreamArgs a) {
@@ -444,13 +441,13 @@ void ffn_stream_kernel(StreamArgs a) {
 #ifdef MOE_STREAM_TRACE
     const long long t_start = wall_clock64();
 #endif
-    if (a.mode == 1) {
-        run_item<true, LINES1, false>(a, a.s[0], lds, blockIdx.x);
-    } else if (a.mode == 2) {
-        run_item<false, LINES2, false>(a, a.s[1], lds, blockIdx.x);
-    } else {
-        if (blockIdx.x < a.n1) run_item<true, LINES1, false>(a, a.s[0], lds, blockIdx.x);
-        else run_item<false, LINES2, true>(a, a.s[1], lds, blockIdx.x - a.n1);
+    {
+        // ids are decoded with the number of blocks the batch really has, so that the surplus of
+        // the worst-case grid comes after all the work of both stages
+        const unsigned n_blocks = static_cast<unsigned>(reinterpret_cast<const int4 *>(a.blocks)[0].x);
+        const unsigned n1 = n_blocks * a.s[0].tiles_pad;
+        if (blockIdx.x < n1) run_item<true, LINES1, false>(a, a.s[0], lds, blockIdx.x);
+        else if (blockIdx.x - n1 < n_blocks * a.s[1].tiles_pad) run_item<false, LINES2, true>(a, a.s[1], lds, blockIdx.x - n1);
     }
 #ifdef MOE_STREAM_TRACE
     if (threadIdx.x == 0 && blockIdx.x < (1u << 15)) {
@@ -458,7 +455,7 @@ void ffn_stream_kernel(StreamArgs a) {
         asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(hwid));
         asm volatile("s_getreg_b32 %0, hwreg(HW_REG_HW_ID)" : "=s"(hw2));
         long long *tr = g_trace[blockIdx.x];
-        tr[0] = t_start; tr[1] = blockIdx.x < a.n1; tr[2] = wall_clock64(); tr[3] = (static_cast<long long>(hwid) << 32) | hw2;
+        tr[0] = t_start; tr[1] = blockIdx.x < static_cast<unsigned>(reinterpret_cast<const int4 *>(a.blocks)[0].x) * a.s[0].tiles_pad; tr[2] = wall_clock64(); tr[3] = (static_cast<long long>(hwid) << 32) | hw2;
     }
 #endif
 }
@@ -498,14 +495,7 @@ int launch_ffn_stream(const void *X, const void *W13p, const void *W2p, int T, i
     for (int i = 0; i < 2; ++i) a.s[i].tiles_pad = (a.s[i].tiles + 7) / 8 * 8;
     const long long n1 = items * a.s[0].tiles_pad, n2 = items * a.s[1].tiles_pad;
     if (n1 + n2 > 0x7fffffffLL) return MOE_ESHAPE;
-    a.n1 = static_cast<unsigned>(n1);
-    static const bool two_launches = getenv("MOE_JANUS_FFN_TWO_LAUNCHES") != nullptr;
-    if (two_launches) {
-        a.mode = 1; launch_lines(a, static_cast<unsigned>(n1), st);
-        a.mode = 2; launch_lines(a, static_cast<unsigned>(n2), st);
-    } else {
-        a.mode = 0; launch_lines(a, static_cast<unsigned>(n1 + n2), st);
-    }
+    launch_lines(a, static_cast<unsigned>(n1 + n2), st);
     return MOE_OK;
 }
 
