@@ -24,6 +24,10 @@ import time
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
+# HBM bytes per FFN launch from rocprofv3 FETCH_SIZE / WRITE_SIZE runs of this command, scaled by a plain
+# copy (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0); see profiles/ffn_stream_kernel_dsv2lite_T128_hbm_traffic.txt.
+# Workloads without such a run report null.
+MEASURED_TRAFFIC = {("dsv2lite", 128): 215035800}
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
 
 
@@ -146,7 +150,8 @@ def main() -> None:
         mean_bytes_ffn = statistics.mean(bytes_ffn(i % n_ring) for i in range(args.steps))
         achieved = mean_bytes_ffn / (ffn_avg_us * 1e-6) / 1e9
         roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                    "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+                    "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": MEASURED_TRAFFIC.get((args.workload, T)),
+                    "traffic_unit": "bytes per launch",
                     "kernel": "moe_grouped_ffn", "avg_us": round(ffn_avg_us, 2),
                     "p50_us": round(statistics.median(ffn_us), 2),
                     "algorithmic_bytes": int(mean_bytes_ffn)}
