@@ -274,6 +274,45 @@ def test_unactivated_slots_are_not_read_bf16():
     assert np.isfinite(Y).all() and rel_fro(Y, orc.Y) < TOL_BF16
 
 
+@pytest.mark.parametrize("d_h,d_e", [(256, 192), (160, 96), (192, 160)], ids=["even-even", "odd-odd", "even-odd"])
+def test_ffn_block_boundaries(d_h, d_e):
+    """The grouped FFN alone on a hand-made dispatch whose slots hold 0, 1, 8, 9, 16, 17, 24, 25,
+    32, 33 and 65 rows (every number of 8-row halves, one and several blocks per slot), for even and
+    odd numbers of K-steps in either stage, against the oracle's grouped FFN."""
+    counts = [8, 9, 0, 16, 17, 24, 1, 25, 32, 33, 0, 65]
+    C, k, T = len(counts), 4, 70
+    cfg = W.MoEConfig("blocks", E=C, k=k, d_h=d_h, d_e=d_e, T=T, n_inst=1, C=C, zipf_s=0.0, seed=11)
+    rng = np.random.default_rng(3)
+    slot_off = np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
+    n_local = int(slot_off[-1])
+    perm = rng.permutation(T * k)[:n_local].astype(np.int32)
+    X = W.activations(cfg)
+    W13 = np.stack([W.expert_weights(cfg, e)[0] for e in range(C)])
+    W2 = np.stack([W.expert_weights(cfg, e)[1] for e in range(C)])
+    Yp_ref = ffn.grouped_ffn(X, W13, W2, slot_off, perm, k)
+    blk = expected_blocks(slot_off)
+    assert blk[0] <= B.moe_max_blocks(T, k, C)
+    d_blk = torch.zeros((B.moe_block_list_len(T, k, C),), dtype=torch.int32)
+    d_blk[:len(blk)] = torch.from_numpy(blk)
+    d_blk = d_blk.cuda()
+    W13p, W2p = torch.empty_like(to_device_bf16(W13)), torch.empty_like(to_device_bf16(W2))
+    B.moe_pack_weights_bf16(to_device_bf16(W13), to_device_bf16(W2), C, d_h, d_e, W13p, W2p)
+    ws = torch.empty((B.moe_workspace_bytes(T, k, C, d_h, d_e, B.MOE_DTYPE_BF16),), dtype=torch.uint8, device="cuda")
+    B.moe_workspace_init(ws)
+    Yp = torch.full((T * k, d_h), 123.0, dtype=torch.float32, device="cuda")
+    for rep in range(2):
+        B.moe_grouped_ffn(to_device_bf16(X), W13p, W2p, T, k, C, d_h, d_e, B.MOE_DTYPE_BF16,
+                          torch.from_numpy(slot_off).cuda(), torch.from_numpy(perm).cuda(), d_blk, Yp, ws)
+        torch.cuda.synchronize()
+        got = Yp.cpu().numpy()
+        assert (got[n_local:] == 123.0).all()
+        num = np.linalg.norm(got[:n_local] - Yp_ref, axis=1)
+        den = np.linalg.norm(Yp_ref, axis=1)
+        assert (num <= 2.5 * TOL_BF16 * den + 1e-30).all(), (rep, int(np.argmax(num / den)))
+        assert rel_fro(got[:n_local], Yp_ref) < TOL_BF16
+        assert B.moe_workspace_status(ws) == 0
+
+
 def test_ffn_rejects_small_workspace():
     cfg = small()
     step = LayerStep(cfg, W.build_placement(cfg), 0)
