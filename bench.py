@@ -54,9 +54,11 @@ def main() -> None:
     ap.add_argument("--ring-bytes", type=float, default=1.25e9, help="minimum total bytes of rotating weight copies")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-events", action="store_true", help="do not record per-kernel events in the timed region")
-    ap.add_argument("--mode", default="step", choices=["step", "sched", "act_sweep"],
+    ap.add_argument("--mode", default="step", choices=["step", "sched", "act_sweep", "skew", "batch_sweep"],
                     help="step: the headline line (default); sched: scheduler us and a_max vs optimum over the "
-                         "stress sweep; act_sweep: layer us vs number of activated experts")
+                         "stress sweep; act_sweep: layer us vs number of activated experts; skew: same "
+                         "activated set with an even and a Zipf split of the requests; batch_sweep: layer "
+                         "us vs batch size with every slot activated")
     args = ap.parse_args()
     if args.gpus != 1:
         raise SystemExit("this build runs on ONE GPU: the other MoE instances exist only as replica placement "
@@ -75,6 +77,8 @@ def main() -> None:
         return sched_sweep(args)
     if args.mode == "act_sweep":
         return act_sweep(args)
+    if args.mode in ("skew", "batch_sweep"):
+        return split_sweeps(args)
     cfg = make_cfg(args.workload, args.tokens)
     lay = W.build_placement(cfg)
     T, k, C, d_h, d_e = cfg.T, cfg.k, cfg.C, cfg.d_h, cfg.d_e
@@ -153,7 +157,10 @@ def main() -> None:
                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": MEASURED_TRAFFIC.get((args.workload, T)),
                     "traffic_unit": "bytes per launch",
                     "kernel": "moe_grouped_ffn", "avg_us": round(ffn_avg_us, 2),
+                    "p10_us": round(float(np.percentile(ffn_us, 10)), 2),
                     "p50_us": round(statistics.median(ffn_us), 2),
+                    "p90_us": round(float(np.percentile(ffn_us, 90)), 2),
+                    "read_probe_GBps": round(read_probe_gbps(W13s), 1),
                     "algorithmic_bytes": int(mean_bytes_ffn)}
     else:
         roofline = None
@@ -255,6 +262,24 @@ def _time_us(fn, reps):
     return a.elapsed_time(b) * 1e3 / reps
 
 
+def read_probe_gbps(bufs) -> float:
+    """A plain streaming read (moe_read_probe) over the ring of weight copies: the practical
+    HBM read ceiling on this machine, in GB/s (median of one pass per copy)."""
+    import torch
+    from paper_2512_13525_amd import binding as B
+    sink = torch.zeros((64,), dtype=torch.int32, device="cuda")
+    ts = []
+    for rep in range(3):
+        for t in bufs:
+            n = t.numel() * t.element_size()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record(); B.moe_read_probe(t, n, sink); b.record()
+            torch.cuda.synchronize()
+            if rep:
+                ts.append(n / (a.elapsed_time(b) * 1e-3) / 1e9)
+    return statistics.median(ts)
+
+
 def sched_sweep(args) -> None:
     """Scheduler-stress sweep: 256 experts, top-8, 16 instances; one JSON line per point with the
     scheduler time (Alg. 1, one launch), a_max of AEBS on the GPU, the exact optimum and the
@@ -346,6 +371,66 @@ def act_sweep(args) -> None:
     print(json.dumps({"mode": "act_sweep_fit", "workload": cfg.name, "beta_us_per_expert": round(float(beta), 3),
                       "c_e_us": round(float(c_e), 3),
                       "beta_at_hbm_peak_us": round(3 * d_h * d_e * 2 / (HBM_PEAK_GBPS * 1e3), 3)}), flush=True)
+
+
+def split_sweeps(args) -> None:
+    """skew: the paper's check that the layer time follows the activated set, not how the tokens
+    are split over it (Sec. 2.2): all C slots activated, T*k requests split evenly or Zipf(1.2).
+    batch_sweep: layer time against the batch size with all C slots activated and an even split
+    (Sec. 2.2: flat until the batch reaches thousands of tokens)."""
+    import numpy as np
+    import torch
+    from paper_2512_13525_amd import workloads as W
+    from paper_2512_13525_amd.layer import LayerStep, to_device_bf16
+
+    Ts = [args.tokens or 64] if args.mode == "skew" else [16, 32, 64, 128, 256, 512, 1024, 2048, 4096]
+    for T in Ts:
+        cfg = make_cfg(args.workload, T)
+        lay = W.build_placement(cfg)
+        k, C, d_h, d_e = cfg.k, cfg.C, cfg.d_h, cfg.d_e
+        step = LayerStep(cfg, lay, 0)
+        per_copy = C * 3 * d_h * d_e * 2
+        n_ring = max(4, int(-(-args.ring_bytes // per_copy)))
+        gen = torch.Generator(device="cuda").manual_seed(1)
+        W13s = [(torch.randn((C, 2 * d_e, d_h), generator=gen, device="cuda") * 0.02).to(torch.bfloat16) for _ in range(n_ring)]
+        W2s = [(torch.randn((C, d_h, d_e), generator=gen, device="cuda") * 0.02).to(torch.bfloat16) for _ in range(n_ring)]
+        X = to_device_bf16(W.activations(cfg))
+        step.topk_w.fill_(1.0 / k)
+        splits = {"even": None}
+        if args.mode == "skew":
+            p = 1.0 / np.arange(1, C + 1) ** 1.2
+            splits["zipf1.2"] = p / p.sum()
+        for name, p in splits.items():
+            n = T * k
+            if p is None:
+                slot = np.arange(n, dtype=np.int32) % C
+            else:
+                # every slot keeps at least one request; a slot gets at most one request per token
+                cnt = np.maximum(1, np.floor(p * (n - C)).astype(np.int64) + 1)
+                cnt = np.minimum(cnt, T)
+                while cnt.sum() > n:
+                    cnt[np.argmax(cnt)] -= 1
+                slot = np.repeat(np.arange(C, dtype=np.int32), cnt)
+                slot = np.concatenate([slot, np.full(n - len(slot), C * 1000, dtype=np.int32)])  # not local
+            rid = slot.reshape(T, k) if p is None else slot[np.argsort(np.arange(n) % T, kind="stable")].reshape(T, k)
+            step.rid.copy_(torch.from_numpy(np.ascontiguousarray(rid)))
+            i = [0]
+
+            def layer():
+                j = i[0] % n_ring
+                i[0] += 1
+                step.permute()
+                step.ffn(X, W13=W13s[j], W2=W2s[j])
+                step.combine()
+
+            us = _time_us(layer, 100)
+            cnts = step.slot_count.cpu().numpy()
+            print(json.dumps({"mode": args.mode, "workload": cfg.name, "T": T, "split": name,
+                              "activated": int((cnts > 0).sum()), "n_local": int(cnts.sum()),
+                              "max_rows_per_slot": int(cnts.max()), "layer_us": round(us, 2),
+                              "weight_GBps": round(C * 3 * d_h * d_e * 2 / (us * 1e-6) / 1e9, 1)}), flush=True)
+        del W13s, W2s, step
+        torch.cuda.empty_cache()
 
 
 if __name__ == "__main__":

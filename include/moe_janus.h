@@ -222,6 +222,15 @@ int moe_grouped_ffn(const void *X_dev, const void *W13_dev, const void *W2_dev,
                     const int32_t *slot_off_dev, const int32_t *perm_dev, const int32_t *blocks_dev,
                     float *Yp_dev, void *workspace_dev, size_t workspace_bytes, void *stream);
 
+/* ------------------------------------------------------------------ measurement helper
+ * Streams `bytes` (rounded down to 16) from src_dev with plain coalesced 128-bit loads and
+ * discards them: the practical read-bandwidth ceiling that the weight stream of
+ * moe_grouped_ffn (Sec. 2.2: the layer is bound by reading the activated experts' weights) is
+ * reported against.  sink_dev: 256 bytes of device memory (written practically never).
+ * src_dev 16-byte aligned.  Not a step of the layer.
+ */
+int moe_read_probe(const void *src_dev, size_t bytes, void *sink_dev, void *stream);
+
 /* ------------------------------------------------------------------ a6: combine
  * Y[i,:] = sum over j with pos[i*k+j] >= 0, in ascending j, of topk_w[i,j] * Yp[pos[i*k+j],:]
  * accumulated in fp32; tokens without a local request get zeros.  This is the instance's

@@ -25,6 +25,7 @@ EXPORTS = [
     "moe_route", "moe_schedule", "moe_permute", "moe_max_blocks", "moe_block_list_len",
     "moe_route_schedule_permute", "moe_pack_weights_bf16",
     "moe_workspace_bytes", "moe_workspace_init", "moe_workspace_status", "moe_grouped_ffn", "moe_combine",
+    "moe_read_probe",
 ]
 
 
@@ -86,6 +87,8 @@ def lib() -> ctypes.CDLL:
     L.moe_workspace_status.argtypes = [vp, ctypes.POINTER(ci)]
     L.moe_grouped_ffn.restype = ci
     L.moe_grouped_ffn.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, ci, vp, vp, vp, vp, vp, cs, vp]
+    L.moe_read_probe.restype = ci
+    L.moe_read_probe.argtypes = [vp, cs, vp, vp]
     L.moe_combine.restype = ci
     L.moe_combine.argtypes = [vp, vp, vp, ci, ci, ci, ci, vp, vp]
     _lib = L
@@ -210,6 +213,10 @@ def moe_grouped_ffn(X, W13, W2, T: int, k: int, C: int, d_h: int, d_e: int, dtyp
     _check(lib().moe_grouped_ffn(_ptr(X), _ptr(W13), _ptr(W2), T, k, C, d_h, d_e, dtype, _ptr(slot_off),
                                  _ptr(perm), _ptr(blocks), _ptr(Yp), _ptr(workspace), ws_bytes, _stream(stream)),
            "moe_grouped_ffn")
+
+
+def moe_read_probe(src, nbytes: int, sink, stream=None) -> None:
+    _check(lib().moe_read_probe(_ptr(src), nbytes, _ptr(sink), _stream(stream)), "moe_read_probe")
 
 
 def moe_combine(Yp, pos, topk_w, T: int, k: int, d_h: int, dtype: int, Y, stream=None) -> None:
