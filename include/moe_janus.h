@@ -58,7 +58,7 @@ extern "C" {
 #define MOE_MAX_INSTANCES    64   /* n_inst */
 #define MOE_MAX_SLOTS       256   /* C */
 #define MOE_MAX_TOPK         32   /* k */
-#define MOE_FFN_BLOCK_ROWS   32   /* request rows of one slot per entry of the FFN work list */
+#define MOE_FFN_BLOCK_ROWS   64   /* most request rows of one slot per entry of the FFN work list */
 
 const char *moe_strerror(int code);
 const char *moe_last_error(void);
@@ -137,10 +137,11 @@ int moe_schedule(const moe_placement_t *pl, const int32_t *topk_ids_dev, int T, 
  *   pos_dev        [T*k]  int32  pos[p] = row of request p in perm, or -1 if p is not local
  *   blocks_dev     [moe_block_list_len(T, k, C)] int32, 16-byte aligned: the work list of
  *                  moe_grouped_ffn.  The rows of every slot are cut into blocks of at most
- *                  MOE_FFN_BLOCK_ROWS rows; slots with more than 16 requests come first (their
- *                  work takes longest), ascending slot order otherwise.  Four int32 per entry:
- *                  entry 0 = {number of blocks B, 0, 0, 0}; entry 1+j = {slot, first row of the
- *                  block, slot_off[slot+1], 0}.  Entries past B are left untouched.
+ *                  R = moe_block_rows(T) rows (32 for small batches, MOE_FFN_BLOCK_ROWS otherwise);
+ *                  slots with more than 16 requests come first (their work takes longest),
+ *                  ascending slot order otherwise.  Four int32 per entry: entry 0 = {number of
+ *                  blocks B, R, 0, 0}; entry 1+j = {slot, first row of the block,
+ *                  slot_off[slot+1], 0}.  Entries past B are left untouched.
  * n_local and B stay on the device; nothing is read back.  The grouped FFN cannot size its
  * launch by them, so it sizes it for moe_max_blocks() and lets the surplus leave at once.
  */
@@ -150,6 +151,7 @@ int moe_permute(const moe_placement_t *pl, int g_self, const int32_t *rid_dev, i
 
 /* Largest number of blocks a batch of T tokens can produce on an instance with C slots (a slot
  * receives at most one request per token), and the int32 length of blocks_dev. */
+int moe_block_rows(int T);
 size_t moe_max_blocks(int T, int k, int C);
 size_t moe_block_list_len(int T, int k, int C);
 
@@ -192,8 +194,9 @@ int moe_pack_weights_bf16(const void *W13_dev, const void *W2_dev, int C, int d_
  *   X_dev  [T, d_h]  bf16 or f32 (dtype)
  *   W13_dev, W2_dev  packed (bf16) or canonical (f32), see above
  *   Yp_dev [T*k, d_h] float32, capacity T*k rows, rows >= n_local are left untouched
- *   blocks_dev       the work list moe_permute wrote for this batch (bf16 path; the f32 path
- *                    does not read it and accepts NULL)
+ *   blocks_dev       the work list moe_permute wrote for a batch of the same T (bf16 path; a
+ *                    list cut for another block size is refused: bit 1 of the status word;
+ *                    the f32 path does not read it and accepts NULL)
  *   workspace_dev    at least moe_workspace_bytes() bytes, 256-byte aligned; holds a control
  *                    region of hand-off flags and the intermediate a (bf16 or f32) between
  *                    the two GEMM stages.  The control region must have been cleared with

@@ -18,11 +18,12 @@ MOE_OK = 0
 MOE_EINVAL, MOE_ESHAPE, MOE_EPLACEMENT, MOE_EHIP, MOE_ENOMEM, MOE_EWORKSPACE = -1, -2, -3, -4, -5, -6
 MOE_DTYPE_BF16, MOE_DTYPE_F32 = 0, 1
 MOE_ROUTE_SOFTMAX, MOE_ROUTE_SIGMOID_GROUP = 0, 1
+MOE_FFN_BLOCK_ROWS = 64
 
 EXPORTS = [
     "moe_strerror", "moe_last_error",
     "moe_placement_create", "moe_placement_destroy", "moe_placement_replicas", "moe_placement_dims",
-    "moe_route", "moe_schedule", "moe_permute", "moe_max_blocks", "moe_block_list_len",
+    "moe_route", "moe_schedule", "moe_permute", "moe_block_rows", "moe_max_blocks", "moe_block_list_len",
     "moe_route_schedule_permute", "moe_pack_weights_bf16",
     "moe_workspace_bytes", "moe_workspace_init", "moe_workspace_status", "moe_grouped_ffn", "moe_combine",
     "moe_read_probe",
@@ -71,6 +72,8 @@ def lib() -> ctypes.CDLL:
     L.moe_schedule.argtypes = [vp, vp, ci, ci, vp, vp, vp, vp]
     L.moe_permute.restype = ci
     L.moe_permute.argtypes = [vp, ci, vp, ci, ci, vp, vp, vp, vp, vp, vp]
+    L.moe_block_rows.restype = ci
+    L.moe_block_rows.argtypes = [ci]
     L.moe_max_blocks.restype = cs
     L.moe_max_blocks.argtypes = [ci, ci, ci]
     L.moe_block_list_len.restype = cs
@@ -165,6 +168,10 @@ def moe_permute(pl: Placement, g_self: int, rid, T: int, k: int, slot_count, slo
                 stream=None) -> None:
     _check(lib().moe_permute(pl.handle, g_self, _ptr(rid), T, k, _ptr(slot_count), _ptr(slot_off),
                              _ptr(perm), _ptr(pos), _ptr(blocks), _stream(stream)), "moe_permute")
+
+
+def moe_block_rows(T: int) -> int:
+    return int(lib().moe_block_rows(T))
 
 
 def moe_max_blocks(T: int, k: int, C: int) -> int:

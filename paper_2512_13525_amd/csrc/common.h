@@ -41,17 +41,21 @@ inline int check_launch(const char *where) {
 // Control region at the start of the FFN workspace: error word + hand-off counters (ffn_stream.hip)
 constexpr size_t kFfnCtrlBytes = 4u << 20;
 
-// Upper bound of the number of blocks of kFfnBlockRows request rows over all slots: a slot
-// receives at most one request per token (a token's k experts are distinct).
-constexpr int kFfnBlockRows = MOE_FFN_BLOCK_ROWS;
+// Request rows per block of the FFN work list: small batches take blocks of 32 rows (more, shorter
+// workgroups), larger ones blocks of 64 (hot slots then re-read their expert half as often).
+inline int ffn_block_rows(int T) { return T < 384 ? 32 : MOE_FFN_BLOCK_ROWS; }
+
+// Upper bound of the number of blocks over all slots: a slot receives at most one request per
+// token (a token's k experts are distinct).
 inline long long ffn_max_blocks(int T, int k, int C) {
-    const long long per_slot = (T + kFfnBlockRows - 1) / kFfnBlockRows;
-    const long long a = C * per_slot, b = C + static_cast<long long>(T) * k / kFfnBlockRows;
+    const int rows = ffn_block_rows(T);
+    const long long per_slot = (T + rows - 1) / rows;
+    const long long a = C * per_slot, b = C + static_cast<long long>(T) * k / rows;
     return a < b ? a : b;
 }
 
 // bf16 grouped FFN (ffn_stream.hip); shapes validated by the caller.  `ctrl` is the zero-initialised
-// control region of the workspace, `act` holds ffn_max_blocks(T, k, C) blocks of kFfnBlockRows x d_e
+// control region of the workspace, `act` holds ffn_max_blocks(T, k, C) blocks of ffn_block_rows(T) x d_e
 // bf16.  Returns MOE_OK or MOE_ESHAPE (too many blocks).
 int launch_ffn_stream(const void *X, const void *W13p, const void *W2p, int T, int k, int C, int d_h, int d_e,
                       const int32_t *blocks, const int32_t *perm, int *ctrl, uint16_t *act, float *Yp,

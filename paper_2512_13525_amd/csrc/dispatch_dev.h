@@ -355,12 +355,13 @@ struct PermShared {
 // slots with more than kHeavyRows requests come first, slot order within each class.  First
 // wavefront, 64 slots per round.
 constexpr int kHeavyRows = 16;
-__device__ __forceinline__ void scan_slots(PermShared &sh, int C, int32_t *__restrict__ slot_off, int lane) {
+__device__ __forceinline__ void scan_slots(PermShared &sh, int C, int block_rows, int32_t *__restrict__ slot_off,
+                                           int lane) {
     int carry = 0, hcarry = 0, lcarry = 0;
     for (int s0 = 0; s0 < C; s0 += MOE_WAVE) {
         const int s = s0 + lane;
         const int v = s < C ? sh.total[s] : 0;
-        const int nb = (v + MOE_FFN_BLOCK_ROWS - 1) / MOE_FFN_BLOCK_ROWS;
+        const int nb = (v + block_rows - 1) / block_rows;
         const int hb = v > kHeavyRows ? nb : 0, lb = nb - hb;
         int incl = v, hincl = hb, lincl = lb;
 #pragma unroll
@@ -390,16 +391,17 @@ __device__ __forceinline__ void scan_slots(PermShared &sh, int C, int32_t *__res
 }
 
 // Work list of the grouped FFN (a5): the local request rows cut into blocks of at most
-// MOE_FFN_BLOCK_ROWS rows of one slot, in the order scan_slots fixed.  Entry 0 = {number of blocks,
-// 0, 0, 0}; entry 1+j = {slot, first row, end of the slot's rows, 0}.  All threads, after
+// block_rows rows of one slot, in the order scan_slots fixed.  Entry 0 = {number of blocks,
+// block_rows, 0, 0}; entry 1+j = {slot, first row, end of the slot's rows, 0}.  All threads, after
 // scan_slots and a barrier; one thread per slot writes that slot's entries.
-__device__ __forceinline__ void list_blocks(const PermShared &sh, int C, int32_t *__restrict__ blocks) {
+__device__ __forceinline__ void list_blocks(const PermShared &sh, int C, int block_rows,
+                                            int32_t *__restrict__ blocks) {
     int4 *out = reinterpret_cast<int4 *>(blocks);
-    if (threadIdx.x == 0) out[0] = make_int4(sh.blk_base[C], 0, 0, 0);
+    if (threadIdx.x == 0) out[0] = make_int4(sh.blk_base[C], block_rows, 0, 0);
     for (int s = threadIdx.x; s < C; s += blockDim.x) {
         const int lo = sh.off[s], hi = sh.off[s + 1];
         int j = sh.blk_base[s];
-        for (int r = lo; r < hi; r += MOE_FFN_BLOCK_ROWS) out[1 + j++] = make_int4(s, r, hi, 0);
+        for (int r = lo; r < hi; r += block_rows) out[1 + j++] = make_int4(s, r, hi, 0);
     }
 }
 
@@ -414,7 +416,8 @@ __device__ __forceinline__ void list_blocks(const PermShared &sh, int C, int32_t
 __device__ __forceinline__ void permute_block(PermShared &sh, const int32_t *__restrict__ rid, int n_pairs,
                                               int g_self, int C, int32_t *__restrict__ slot_count,
                                               int32_t *__restrict__ slot_off, int32_t *__restrict__ perm,
-                                              int32_t *__restrict__ pos, int32_t *__restrict__ blocks) {
+                                              int32_t *__restrict__ pos, int32_t *__restrict__ blocks,
+                                              int block_rows) {
     const int tid = threadIdx.x;
     const int wave = tid / MOE_WAVE;
     const int lane = tid % MOE_WAVE;
@@ -450,9 +453,9 @@ __device__ __forceinline__ void permute_block(PermShared &sh, const int32_t *__r
     __syncthreads();
 
     // ---- exclusive scan over slots, then the FFN's work list
-    if (wave == 0) scan_slots(sh, C, slot_off, lane);
+    if (wave == 0) scan_slots(sh, C, block_rows, slot_off, lane);
     __syncthreads();
-    list_blocks(sh, C, blocks);
+    list_blocks(sh, C, block_rows, blocks);
 
     // ---- pass B
     volatile int *base = &sh.cnt[wave][0];

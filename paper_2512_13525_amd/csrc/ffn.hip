@@ -24,7 +24,7 @@ namespace {
 //                        int [1] = error word, then the per-block hand-off counters of the bf16
 //                        kernels (see ffn_stream.hip)
 //   [kCtrlBytes, ...)    act: SiLU(gate)*up of every local request row (fp32: [row][d_e];
-//                        bf16: per block of 32 rows, [d_e/16 tiles][32 rows][16 channels])
+//                        bf16: per block of R = 32 or 64 rows, [d_e/16 tiles][R rows][16 channels])
 constexpr size_t kCtrlBytes = moe::kFfnCtrlBytes;
 
 // ------------------------------------------------------------------ packing
@@ -136,7 +136,7 @@ extern "C" size_t moe_workspace_bytes(int T, int k, int C, int d_h, int d_e, int
     // fp32: one row per request; bf16: whole blocks of rows (at most C partly filled ones)
     const size_t bytes = dtype == MOE_DTYPE_F32
         ? static_cast<size_t>(T) * k * d_e * 4
-        : static_cast<size_t>(moe::ffn_max_blocks(T, k, C)) * moe::kFfnBlockRows * d_e * 2;
+        : static_cast<size_t>(moe::ffn_max_blocks(T, k, C)) * moe::ffn_block_rows(T) * d_e * 2;
     return kCtrlBytes + (bytes + 255) / 256 * 256 + 256;
 }
 

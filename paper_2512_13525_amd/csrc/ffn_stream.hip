@@ -3,7 +3,7 @@
 //
 // Janus Sec. 2.2: at decode sizes an expert is two skinny GEMMs whose cost is the weight bytes
 // streamed from HBM, so the layer's latency follows the number of activated experts.  The work
-// of a stage is cut into items = (block of up to 32 request rows of one slot) x (tile of 16
+// of a stage is cut into items = (block of up to 32 or 64 request rows of one slot) x (tile of 16
 // gate+up channels in stage 1, 32 output channels in stage 2); one workgroup per item, in plain
 // grid order, dispatched by the hardware.  Slots without requests own no item: their weights are
 // never read.  Nothing about the activated set is known on the host, so the grid is sized for
@@ -37,8 +37,8 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 constexpr int kDepthA = 2;              // super-steps of weight loads each wavefront keeps in flight
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / MOE_WAVE;
-constexpr int kMaxTiles = 2;            // token tiles (of 16) per workgroup
-constexpr int kBlockTok = kMaxTiles * 16; // request rows of a slot one workgroup takes
+// A launch is compiled for blocks of TT token tiles of 16 rows (TT = 2 or 4: blocks of 32 or 64
+// request rows); one 16-channel tile of a block of act takes TT*16 rows x 32 bytes.
 
 // Control region of the workspace (ints): [1] error word; block j owns the 8 lines of 128 bytes
 // at int offset (j+1)*kCtrlBlockInts: line 0 = {stage-1 tiles done, stage-2 workgroups through},
@@ -87,10 +87,10 @@ __device__ __forceinline__ void lds_barrier() {
 
 // Split-K reduction over the 4 wavefronts in LDS (fixed order), then the epilogue: SiLU(gate)*up
 // rounded once to bf16 (stage 1, agent-scope stores) or the fp32 partial output rows (stage 2).
-template <bool STAGE1, int NT>
+template <bool STAGE1, int NT, int TT>
 __device__ __forceinline__ void reduce_store(const StreamArgs &a, const StageArgs &g,
-                                             f32x4 (*red)[2][kMaxTiles][MOE_WAVE], f32x4 (&acc)[2][NT],
-                                             int item_id, int tile, int row0, int row_end, int wave, int lane) {
+                                             f32x4 (*red)[2][TT][MOE_WAVE], f32x4 (&acc)[2][NT],
+                                             int item_id, int brow, int tile, int row0, int row_end, int wave, int lane) {
 #pragma unroll
     for (int h = 0; h < 2; ++h)
 #pragma unroll
@@ -109,10 +109,10 @@ __device__ __forceinline__ void reduce_store(const StreamArgs &a, const StageArg
                                    static_cast<uint64_t>(moe::f32_to_bf16(silu_mul(gt[1], up[1]))) << 16 |
                                    static_cast<uint64_t>(moe::f32_to_bf16(silu_mul(gt[2], up[2]))) << 32 |
                                    static_cast<uint64_t>(moe::f32_to_bf16(silu_mul(gt[3], up[3]))) << 48;
-                // act block of this item: [tile][32 rows][16 channels], one writer per 128-byte line
+                // act block of this item: [tile][TT*16 rows][16 channels], one writer per 128-byte line
                 uint64_t *dst = reinterpret_cast<uint64_t *>(
-                    reinterpret_cast<char *>(a.act) + (static_cast<size_t>(item_id) * g.tiles + tile) * 1024 +
-                    (t * 16 + (l & 15)) * 32 + (l >> 4) * 8);
+                    reinterpret_cast<char *>(a.act) + (static_cast<size_t>(item_id) * g.tiles + tile) * (TT * 512) +
+                    (brow + t * 16 + (l & 15)) * 32 + (l >> 4) * 8);
                 __hip_atomic_store(dst, o, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
         }
@@ -167,14 +167,14 @@ __device__ __forceinline__ void wait_block_ready(const StreamArgs &a, int item, 
 // of 8-row halves that hold requests (rows past the end repeat the last row; halves past it are
 // not loaded and leave unspecified values in token columns whose results are never stored).
 // WAIT: the token rows are `act` rows that other workgroups of this launch produce.
-template <bool STAGE1, int NH, bool WAIT>
+template <bool STAGE1, int NH, bool WAIT, int TT>
 __device__ __forceinline__ void stream_item_lines(const StreamArgs &a, const StageArgs &g, char *lds,
                                                   const char *w, int item, int tile, int row0, int row_end,
                                                   int wave, int lane) {
     constexpr int NT = (NH + 1) / 2;
     constexpr int D = kDepthA;
-    f32x4 (*red)[2][kMaxTiles][MOE_WAVE] = reinterpret_cast<f32x4 (*)[2][kMaxTiles][MOE_WAVE]>(lds);
-    char *stg = lds + wave * (kMaxTiles * 2048);
+    f32x4 (*red)[2][TT][MOE_WAVE] = reinterpret_cast<f32x4 (*)[2][TT][MOE_WAVE]>(lds);
+    char *stg = lds + wave * (TT * 2048);
     const uint32_t aoff = lane * 16;
     // token rows: wave-uniform base (advanced per super-step) + constant 32-bit per-lane byte offset
     uint32_t boff[NH];
@@ -185,16 +185,16 @@ __device__ __forceinline__ void stream_item_lines(const StreamArgs &a, const Sta
             r = r < row_end ? r : row_end - 1;
             boff[h] = static_cast<uint32_t>(a.perm[r] / a.k) * static_cast<uint32_t>(g.b_stride) * 2 + (lane & 7) * 16;
         } else {
-            // act block: [tile][32 rows][16 channels]; chunk c of a super-step = tile c/2, half c%2
-            boff[h] = ((lane & 7) >> 1) * 1024 + (h * 8 + (lane >> 3)) * 32 + (lane & 1) * 16;
+            // act block: [tile][TT*16 rows][16 channels]; chunk c of a super-step = tile c/2, half c%2
+            boff[h] = ((lane & 7) >> 1) * (TT * 512) + (h * 8 + (lane >> 3)) * 32 + (lane & 1) * 16;
         }
     }
     // LDS: row R of a tile at R*128, its 16-byte chunk c at ((c ^ (R & 7)) * 16)
     const uint32_t wr_lds = ((lane >> 3) * 128) + (((lane & 7) ^ (lane >> 3)) * 16);
     const uint32_t rd_row = (lane & 15) * 128, rd_sw = lane & 7, rd_g = lane >> 4;
     const char *bbase = STAGE1 ? reinterpret_cast<const char *>(g.B)
-                               : reinterpret_cast<const char *>(g.B) + static_cast<size_t>(item) * a.s[0].tiles * 1024;
-    constexpr int kBStep = STAGE1 ? 128 : 4096;                  // bytes a super-step advances the token operand
+                               : reinterpret_cast<const char *>(g.B) + static_cast<size_t>(item) * a.s[0].tiles * (TT * 512);
+    constexpr int kBStep = STAGE1 ? 128 : 4 * TT * 512;                  // bytes a super-step advances the token operand
     const int n = (g.KS / 2 - wave + kWaves - 1) / kWaves;      // super-steps wave, wave+4, ... of this wavefront
     f32x4 acc[2][NT];
 #pragma unroll
@@ -298,18 +298,18 @@ __device__ __forceinline__ void stream_item_lines(const StreamArgs &a, const Sta
 #undef MOE_STAGE_B
 #undef MOE_MMA_STEP
     __syncthreads();                                             // the staging tiles are reused for the reduction
-    reduce_store<STAGE1, NT>(a, g, red, acc, item, tile, row0, row_end, wave, lane);
+    reduce_store<STAGE1, NT, TT>(a, g, red, acc, item, 0, tile, row0, row_end, wave, lane);
 }
 
 // One item with an odd number of K-steps (shapes that are multiples of 32 but not of 64): single
 // K-steps, token rows read 64 bytes at a time straight into the MFMA layout (lane l: row l%16,
 // 16 bytes at (l/16)*16), four steps of weights and tokens in flight.
-template <bool STAGE1, int NT, bool WAIT>
+template <bool STAGE1, int NT, bool WAIT, int TT>
 __device__ __forceinline__ void stream_item_steps(const StreamArgs &a, const StageArgs &g, char *lds,
-                                                  const char *w, int item, int tile, int row0, int row_end,
+                                                  const char *w, int item, int brow, int tile, int row0, int row_end,
                                                   int wave, int lane) {
     constexpr int D = 2 * kDepthA;
-    f32x4 (*red)[2][kMaxTiles][MOE_WAVE] = reinterpret_cast<f32x4 (*)[2][kMaxTiles][MOE_WAVE]>(lds);
+    f32x4 (*red)[2][TT][MOE_WAVE] = reinterpret_cast<f32x4 (*)[2][TT][MOE_WAVE]>(lds);
     const uint32_t aoff = lane * 16;
     uint32_t boff[NT];
 #pragma unroll
@@ -319,13 +319,13 @@ __device__ __forceinline__ void stream_item_steps(const StreamArgs &a, const Sta
             r = r < row_end ? r : row_end - 1;
             boff[t] = (static_cast<uint32_t>(a.perm[r] / a.k) * static_cast<uint32_t>(g.b_stride) + (lane >> 4) * 8) * 2;
         } else {
-            // act block: [tile][32 rows][16 channels]; a K-step = 2 tiles, chunk l/16 = tile (l/16)/2, half (l/16)%2
-            boff[t] = (lane >> 5) * 1024 + (t * 16 + (lane & 15)) * 32 + ((lane >> 4) & 1) * 16;
+            // act block: [tile][TT*16 rows][16 channels]; a K-step = 2 tiles, chunk l/16 = tile (l/16)/2, half (l/16)%2
+            boff[t] = (lane >> 5) * (TT * 512) + (brow + t * 16 + (lane & 15)) * 32 + ((lane >> 4) & 1) * 16;
         }
     }
     const char *bbase = STAGE1 ? reinterpret_cast<const char *>(g.B)
-                               : reinterpret_cast<const char *>(g.B) + static_cast<size_t>(item) * a.s[0].tiles * 1024;
-    constexpr int kBStep = STAGE1 ? 64 : 2048;                   // bytes a K-step advances the token operand
+                               : reinterpret_cast<const char *>(g.B) + static_cast<size_t>(item) * a.s[0].tiles * (TT * 512);
+    constexpr int kBStep = STAGE1 ? 64 : 2 * TT * 512;                   // bytes a K-step advances the token operand
     const int n = (g.KS - wave + kWaves - 1) / kWaves;          // K-steps wave, wave+4, ... of this wavefront
     f32x4 acc[2][NT];
 #pragma unroll
@@ -333,7 +333,7 @@ __device__ __forceinline__ void stream_item_steps(const StreamArgs &a, const Sta
 #pragma unroll
         for (int t = 0; t < NT; ++t) acc[h][t] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    if (WAIT) wait_block_ready(a, item, tile, g.tiles);
+    if (WAIT && brow == 0) wait_block_ready(a, item, tile, g.tiles);
     if (n > 0) {
         bf16x8 wr[D][2], br[D][NT];
         const int last = n - 1;
@@ -381,10 +381,10 @@ __device__ __forceinline__ void stream_item_steps(const StreamArgs &a, const Sta
 #undef MOE_LOAD_STEP
 #undef MOE_MMA_STEP
     }
-    reduce_store<STAGE1, NT>(a, g, red, acc, item, tile, row0, row_end, wave, lane);
+    reduce_store<STAGE1, NT, TT>(a, g, red, acc, item, brow, tile, row0, row_end, wave, lane);
 }
 
-template <bool STAGE1, bool LINES, bool WAIT>
+template <bool STAGE1, bool LINES, bool WAIT, int TT>
 __device__ __forceinline__ void run_item(const StreamArgs &a, const StageArgs &g, char *lds, unsigned id) {
     const int tile = id % g.tiles_pad, item = id / g.tiles_pad;
     if (tile >= g.tiles) return;
@@ -399,13 +399,22 @@ __device__ __forceinline__ void run_item(const StreamArgs &a, const StageArgs &g
     const char *w = g.Wp + (static_cast<size_t>(slot) * g.tiles + tile) * g.KS * 2048;
     const int m = hi - row0;
     if (LINES) {
-        if (m <= 8) stream_item_lines<STAGE1, 1, WAIT>(a, g, lds, w, item, tile, row0, hi, wave, lane);
-        else if (m <= 16) stream_item_lines<STAGE1, 2, WAIT>(a, g, lds, w, item, tile, row0, hi, wave, lane);
-        else if (m <= 24) stream_item_lines<STAGE1, 3, WAIT>(a, g, lds, w, item, tile, row0, hi, wave, lane);
-        else stream_item_lines<STAGE1, 4, WAIT>(a, g, lds, w, item, tile, row0, hi, wave, lane);
+        const int halves = ((m < TT * 16 ? m : TT * 16) + 7) >> 3;     // 8-row halves that hold requests
+#define MOE_CASE(NH) case NH: stream_item_lines<STAGE1, NH, WAIT, TT>(a, g, lds, w, item, tile, row0, hi, wave, lane); break;
+        if constexpr (TT == 2) {
+            switch (halves) { MOE_CASE(1) MOE_CASE(2) MOE_CASE(3) MOE_CASE(4) }
+        } else {
+            switch (halves) { MOE_CASE(1) MOE_CASE(2) MOE_CASE(3) MOE_CASE(4) MOE_CASE(5) MOE_CASE(6) MOE_CASE(7) MOE_CASE(8) }
+        }
+#undef MOE_CASE
     } else {
-        if (m <= 16) stream_item_steps<STAGE1, 1, WAIT>(a, g, lds, w, item, tile, row0, hi, wave, lane);
-        else stream_item_steps<STAGE1, 2, WAIT>(a, g, lds, w, item, tile, row0, hi, wave, lane);
+        // passes of 32 rows (rows [row0 + brow, ...) of the block)
+        const int end = m < TT * 16 ? hi : row0 + TT * 16;
+        for (int brow = 0; row0 + brow < end; brow += 32) {
+            if (brow) __syncthreads();                           // the reduction buffer is reused
+            if (end - (row0 + brow) <= 16) stream_item_steps<STAGE1, 1, WAIT, TT>(a, g, lds, w, item, brow, tile, row0 + brow, end, wave, lane);
+            else stream_item_steps<STAGE1, 2, WAIT, TT>(a, g, lds, w, item, brow, tile, row0 + brow, end, wave, lane);
+        }
     }
     if (STAGE1) {
         // announce the tile: every thread waits for its own act stores to be acknowledged, then
@@ -431,23 +440,32 @@ __device__ __forceinline__ void run_item(const StreamArgs &a, const StageArgs &g
 // the blocks of one tile of a slot (ids tiles_pad apart, a multiple of 8) run on the same XCD at
 // about the same time: the tile's weights come from HBM once and are shared through that XCD's
 // L2.  LINES1 / LINES2 select the whole-line token path of a stage (even number of K-steps).
-template <bool LINES1, bool LINES2>
-__global__ __launch_bounds__(kThreads, 4)
+// TT = token tiles per block (2: blocks of 32 rows, 4 workgroups per CU; 4: blocks of 64 rows, whose
+// larger register set allows 3 per CU).
+template <bool LINES1, bool LINES2, int TT>
+__global__ __launch_bounds__(kThreads, TT == 2 ? 4 : 3)
 void ffn_stream_kernel(StreamArgs a) {
-    // split-K reduction buffer [4 waves][2][kMaxTiles][64] x 16 B, which the whole-line path also
-    // uses as its per-wavefront staging tiles during the K loop
-    __shared__ __attribute__((aligned(16))) char lds[kWaves * 2 * kMaxTiles * MOE_WAVE * 16];
-    static_assert(kWaves * kMaxTiles * 2048 <= sizeof(lds), "staging tiles must fit in the reduction buffer");
+    // split-K reduction buffer [4 waves][2][TT][64] x 16 B, which the whole-line path also uses as
+    // its per-wavefront staging tiles during the K loop
+    __shared__ __attribute__((aligned(16))) char lds[kWaves * 2 * TT * MOE_WAVE * 16];
+    static_assert(kWaves * TT * 2048 <= sizeof(lds), "staging tiles must fit in the reduction buffer");
 #ifdef MOE_STREAM_TRACE
     const long long t_start = wall_clock64();
 #endif
     {
         // ids are decoded with the number of blocks the batch really has, so that the surplus of
         // the worst-case grid comes after all the work of both stages
-        const unsigned n_blocks = static_cast<unsigned>(reinterpret_cast<const int4 *>(a.blocks)[0].x);
+        const int4 head = reinterpret_cast<const int4 *>(a.blocks)[0];
+        if (head.y != TT * 16) {
+            // the list was cut for another block size (made for a different T): refuse, visibly
+            if (threadIdx.x == 0 && blockIdx.x == 0)
+                __hip_atomic_fetch_or(a.ctrl + 1, 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            return;
+        }
+        const unsigned n_blocks = static_cast<unsigned>(head.x);
         const unsigned n1 = n_blocks * a.s[0].tiles_pad;
-        if (blockIdx.x < n1) run_item<true, LINES1, false>(a, a.s[0], lds, blockIdx.x);
-        else if (blockIdx.x - n1 < n_blocks * a.s[1].tiles_pad) run_item<false, LINES2, true>(a, a.s[1], lds, blockIdx.x - n1);
+        if (blockIdx.x < n1) run_item<true, LINES1, false, TT>(a, a.s[0], lds, blockIdx.x);
+        else if (blockIdx.x - n1 < n_blocks * a.s[1].tiles_pad) run_item<false, LINES2, true, TT>(a, a.s[1], lds, blockIdx.x - n1);
     }
 #ifdef MOE_STREAM_TRACE
     if (threadIdx.x == 0 && blockIdx.x < (1u << 15)) {
@@ -461,16 +479,17 @@ void ffn_stream_kernel(StreamArgs a) {
 }
 
 template <bool L1, bool L2>
-void launch(const StreamArgs &a, unsigned blocks, hipStream_t st) {
-    hipLaunchKernelGGL((ffn_stream_kernel<L1, L2>), dim3(blocks), dim3(kThreads), 0, st, a);
+void launch(const StreamArgs &a, int block_rows, unsigned blocks, hipStream_t st) {
+    if (block_rows == 32) hipLaunchKernelGGL((ffn_stream_kernel<L1, L2, 2>), dim3(blocks), dim3(kThreads), 0, st, a);
+    else hipLaunchKernelGGL((ffn_stream_kernel<L1, L2, 4>), dim3(blocks), dim3(kThreads), 0, st, a);
 }
 
-void launch_lines(const StreamArgs &a, unsigned blocks, hipStream_t st) {
+void launch_lines(const StreamArgs &a, int block_rows, unsigned blocks, hipStream_t st) {
     const bool l1 = a.s[0].KS % 2 == 0, l2 = a.s[1].KS % 2 == 0;
-    if (l1 && l2) launch<true, true>(a, blocks, st);
-    else if (l1) launch<true, false>(a, blocks, st);
-    else if (l2) launch<false, true>(a, blocks, st);
-    else launch<false, false>(a, blocks, st);
+    if (l1 && l2) launch<true, true>(a, block_rows, blocks, st);
+    else if (l1) launch<true, false>(a, block_rows, blocks, st);
+    else if (l2) launch<false, true>(a, block_rows, blocks, st);
+    else launch<false, false>(a, block_rows, blocks, st);
 }
 
 }  // namespace
@@ -480,7 +499,7 @@ namespace moe {
 int launch_ffn_stream(const void *X, const void *W13p, const void *W2p, int T, int k, int C, int d_h, int d_e,
                       const int32_t *blocks, const int32_t *perm, int *ctrl, uint16_t *act, float *Yp,
                       hipStream_t st) {
-    static_assert(kBlockTok == kFfnBlockRows, "block size is part of the workspace layout");
+    const int block_rows = ffn_block_rows(T);
     const long long items = ffn_max_blocks(T, k, C);
     if (items > kMaxItems) return MOE_ESHAPE;
     StreamArgs a;
@@ -495,7 +514,7 @@ int launch_ffn_stream(const void *X, const void *W13p, const void *W2p, int T, i
     for (int i = 0; i < 2; ++i) a.s[i].tiles_pad = (a.s[i].tiles + 7) / 8 * 8;
     const long long n1 = items * a.s[0].tiles_pad, n2 = items * a.s[1].tiles_pad;
     if (n1 + n2 > 0x7fffffffLL) return MOE_ESHAPE;
-    launch_lines(a, static_cast<unsigned>(n1 + n2), st);
+    launch_lines(a, block_rows, static_cast<unsigned>(n1 + n2), st);
     return MOE_OK;
 }
 

@@ -20,6 +20,7 @@ struct FrontArgs {
     int n_inst, C, n_words, g_self;
     int32_t *rid, *act_rep, *load, *slot_count, *slot_off, *perm, *pos, *blocks;
     int32_t *ticket;
+    int block_rows;
 };
 
 // Decode-size tail (up to kRegPairs requests): Alg. 1 and the counting sort with every request id
@@ -158,9 +159,9 @@ __device__ __forceinline__ void front_tail_small(const FrontArgs &a, SmallShared
         a.slot_count[s] = run;
     }
     __syncthreads();
-    if (wave == 0) moe::scan_slots(sh.perm, C, a.slot_off, lane);
+    if (wave == 0) moe::scan_slots(sh.perm, C, a.block_rows, a.slot_off, lane);
     __syncthreads();
-    moe::list_blocks(sh.perm, C, a.blocks);
+    moe::list_blocks(sh.perm, C, a.block_rows, a.blocks);
 
     // ---- pass B
     volatile int *base = &sh.perm.cnt[wave][0];
@@ -238,7 +239,7 @@ void front_kernel(FrontArgs a) {
     // rid is re-read below by other wavefronts of this workgroup
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
-    moe::permute_block(sh.perm, a.rid, n_pairs, a.g_self, a.C, a.slot_count, a.slot_off, a.perm, a.pos, a.blocks);
+    moe::permute_block(sh.perm, a.rid, n_pairs, a.g_self, a.C, a.slot_count, a.slot_off, a.perm, a.pos, a.blocks, a.block_rows);
 }
 
 template <int VPL>
@@ -282,6 +283,7 @@ extern "C" int moe_route_schedule_permute(const moe_placement_t *pl, int g_self,
     a.rid = rid_dev; a.act_rep = act_rep_dev; a.load = load_dev;
     a.slot_count = slot_count_dev; a.slot_off = slot_off_dev; a.perm = perm_dev; a.pos = pos_dev; a.blocks = blocks_dev;
     a.ticket = sync_dev;
+    a.block_rows = moe::ffn_block_rows(T);
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int vpl = (E + MOE_WAVE - 1) / MOE_WAVE;
     if (vpl <= 1) return launch_front<1>(a, st);

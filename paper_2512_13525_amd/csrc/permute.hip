@@ -10,9 +10,10 @@ constexpr int kPermThreads = moe::kFrontThreads;
 __global__ __launch_bounds__(kPermThreads)
 void permute_kernel(const int32_t *__restrict__ rid, int n_pairs, int g_self, int C,
                     int32_t *__restrict__ slot_count, int32_t *__restrict__ slot_off,
-                    int32_t *__restrict__ perm, int32_t *__restrict__ pos, int32_t *__restrict__ blocks) {
+                    int32_t *__restrict__ perm, int32_t *__restrict__ pos, int32_t *__restrict__ blocks,
+                    int block_rows) {
     __shared__ moe::PermShared sh;
-    moe::permute_block(sh, rid, n_pairs, g_self, C, slot_count, slot_off, perm, pos, blocks);
+    moe::permute_block(sh, rid, n_pairs, g_self, C, slot_count, slot_off, perm, pos, blocks, block_rows);
 }
 
 // One workgroup per (token, 1024-column chunk); each thread owns 4 consecutive columns.
@@ -56,7 +57,8 @@ extern "C" int moe_permute(const moe_placement_t *pl, int g_self, const int32_t 
         !moe::aligned(perm_dev, 4) || !moe::aligned(pos_dev, 4) || !moe::aligned(blocks_dev, 16))
         return MOE_EINVAL;
     hipLaunchKernelGGL(permute_kernel, dim3(1), dim3(kPermThreads), 0, static_cast<hipStream_t>(stream),
-                       rid_dev, T * k, g_self, pl->C, slot_count_dev, slot_off_dev, perm_dev, pos_dev, blocks_dev);
+                       rid_dev, T * k, g_self, pl->C, slot_count_dev, slot_off_dev, perm_dev, pos_dev, blocks_dev,
+                       moe::ffn_block_rows(T));
     return moe::check_launch("moe_permute");
 }
 
@@ -64,6 +66,8 @@ extern "C" size_t moe_max_blocks(int T, int k, int C) {
     if (T < 0 || k < 1 || C < 1) return 0;
     return static_cast<size_t>(moe::ffn_max_blocks(T, k, C));
 }
+
+extern "C" int moe_block_rows(int T) { return T < 0 ? 0 : moe::ffn_block_rows(T); }
 
 extern "C" size_t moe_block_list_len(int T, int k, int C) {
     if (T < 0 || k < 1 || C < 1) return 0;

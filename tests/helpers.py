@@ -56,10 +56,10 @@ def rel_fro(a, b):
     return float(np.linalg.norm(a - b) / den) if den > 0 else float(np.linalg.norm(a - b))
 
 
-def expected_blocks(slot_off, block_rows=32, heavy_rows=16):
+def expected_blocks(slot_off, block_rows, heavy_rows=16):
     """The FFN work list that follows from slot_off: every slot's rows cut into blocks of at
     most `block_rows` rows; slots with more than `heavy_rows` requests first, ascending slot
-    order within each class; [n_blocks,0,0,0] then [slot, first row, slot end, 0] per block
+    order within each class; [n_blocks,block_rows,0,0] then [slot, first row, slot end, 0] per block
     (flattened int32)."""
     out = []
     for heavy in (True, False):
@@ -69,4 +69,4 @@ def expected_blocks(slot_off, block_rows=32, heavy_rows=16):
                 continue
             for r in range(lo, hi, block_rows):
                 out.append([s, r, hi, 0])
-    return np.array([[len(out), 0, 0, 0]] + out, dtype=np.int32).reshape(-1)
+    return np.array([[len(out), block_rows, 0, 0]] + out, dtype=np.int32).reshape(-1)

@@ -78,9 +78,11 @@ def test_argument_validation_without_launch():
     assert L.moe_combine(None, None, None, 4, 2, 128, B.MOE_DTYPE_F32, None, None) == B.MOE_EINVAL
     assert L.moe_pack_weights_bf16(None, None, 2, 100, 64, None, None, None) == B.MOE_ESHAPE
     assert L.moe_workspace_init(None, 0, None) == B.MOE_EINVAL
-    # a slot gets at most one request per token: min(C*ceil(T/32), C + T*k/32) blocks
+    # a slot gets at most one request per token: min(C*ceil(T/R), C + T*k/R) blocks of R rows
+    assert L.moe_block_rows(128) == 32 and L.moe_block_rows(512) == B.MOE_FFN_BLOCK_ROWS == 64
     assert L.moe_max_blocks(128, 6, 17) == 17 + 128 * 6 // 32
     assert L.moe_max_blocks(16, 8, 36) == 36
+    assert L.moe_max_blocks(512, 8, 36) == 36 + 512 * 8 // 64
     assert L.moe_block_list_len(128, 6, 17) == 4 * (1 + 41)
     assert L.moe_workspace_status(None, None) == B.MOE_EINVAL
     ws = L.moe_workspace_bytes(128, 6, 17, 2048, 1408, B.MOE_DTYPE_BF16)

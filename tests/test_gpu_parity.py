@@ -134,7 +134,7 @@ def test_schedule_and_permute_parity(cfg):
         d_blk = torch.full((B.moe_block_list_len(cfg.T, cfg.k, cfg.C),), -9, dtype=torch.int32, device="cuda")
         B.moe_permute(pl, g, d_rid, cfg.T, cfg.k, d_cnt, d_off, d_perm, d_pos, d_blk)
         torch.cuda.synchronize()
-        blk = expected_blocks(off)
+        blk = expected_blocks(off, B.moe_block_rows(cfg.T))
         assert blk[0] <= B.moe_max_blocks(cfg.T, cfg.k, cfg.C)
         g_blk = d_blk.cpu().numpy()
         np.testing.assert_array_equal(g_blk[:len(blk)], blk)
@@ -274,13 +274,16 @@ def test_unactivated_slots_are_not_read_bf16():
     assert np.isfinite(Y).all() and rel_fro(Y, orc.Y) < TOL_BF16
 
 
+@pytest.mark.parametrize("T", [70, 400], ids=["blocks32", "blocks64"])
 @pytest.mark.parametrize("d_h,d_e", [(256, 192), (160, 96), (192, 160)], ids=["even-even", "odd-odd", "even-odd"])
-def test_ffn_block_boundaries(d_h, d_e):
+def test_ffn_block_boundaries(d_h, d_e, T):
     """The grouped FFN alone on a hand-made dispatch whose slots hold 0, 1, 8, 9, 16, 17, 24, 25,
-    32, 33 and 65 rows (every number of 8-row halves, one and several blocks per slot), for even and
-    odd numbers of K-steps in either stage, against the oracle's grouped FFN."""
-    counts = [8, 9, 0, 16, 17, 24, 1, 25, 32, 33, 0, 65]
-    C, k, T = len(counts), 4, 70
+    32, 33, ... 65 rows (every number of 8-row halves, one and several blocks per slot, for blocks of
+    32 and of 64 rows), for even and odd numbers of K-steps in either stage, against the oracle's
+    grouped FFN.  A list cut for another block size is refused."""
+    counts = [8, 9, 0, 16, 17, 24, 1, 25, 32, 33, 0, 65, 40, 41, 48, 49, 56, 57, 64]
+    C, k = len(counts), 10
+    assert B.moe_block_rows(T) == (32 if T == 70 else 64)
     cfg = W.MoEConfig("blocks", E=C, k=k, d_h=d_h, d_e=d_e, T=T, n_inst=1, C=C, zipf_s=0.0, seed=11)
     rng = np.random.default_rng(3)
     slot_off = np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
@@ -290,7 +293,7 @@ def test_ffn_block_boundaries(d_h, d_e):
     W13 = np.stack([W.expert_weights(cfg, e)[0] for e in range(C)])
     W2 = np.stack([W.expert_weights(cfg, e)[1] for e in range(C)])
     Yp_ref = ffn.grouped_ffn(X, W13, W2, slot_off, perm, k)
-    blk = expected_blocks(slot_off)
+    blk = expected_blocks(slot_off, B.moe_block_rows(T))
     assert blk[0] <= B.moe_max_blocks(T, k, C)
     d_blk = torch.zeros((B.moe_block_list_len(T, k, C),), dtype=torch.int32)
     d_blk[:len(blk)] = torch.from_numpy(blk)
@@ -311,6 +314,15 @@ def test_ffn_block_boundaries(d_h, d_e):
         assert (num <= 2.5 * TOL_BF16 * den + 1e-30).all(), (rep, int(np.argmax(num / den)))
         assert rel_fro(got[:n_local], Yp_ref) < TOL_BF16
         assert B.moe_workspace_status(ws) == 0
+    # the same list with the other block size in its header: nothing is computed, bit 1 of the status
+    d_blk[1] = 96 - B.moe_block_rows(T)
+    Yp.fill_(123.0)
+    B.moe_grouped_ffn(to_device_bf16(X), W13p, W2p, T, k, C, d_h, d_e, B.MOE_DTYPE_BF16,
+                      torch.from_numpy(slot_off).cuda(), torch.from_numpy(perm).cuda(), d_blk, Yp, ws)
+    torch.cuda.synchronize()
+    assert (Yp == 123.0).all() and B.moe_workspace_status(ws) == 2
+    B.moe_workspace_init(ws)
+    assert B.moe_workspace_status(ws) == 0
 
 
 def test_ffn_rejects_small_workspace():
