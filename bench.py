@@ -160,7 +160,7 @@ def main() -> None:
                     "p10_us": round(float(np.percentile(ffn_us, 10)), 2),
                     "p50_us": round(statistics.median(ffn_us), 2),
                     "p90_us": round(float(np.percentile(ffn_us, 90)), 2),
-                    "read_probe_GBps": round(read_probe_gbps(W13s), 1),
+                    "read_probe_same_bytes": dict(zip(("us", "GBps"), (round(v, 1) for v in read_probe(W13s, int(mean_bytes_ffn))))),
                     "algorithmic_bytes": int(mean_bytes_ffn)}
     else:
         roofline = None
@@ -262,22 +262,23 @@ def _time_us(fn, reps):
     return a.elapsed_time(b) * 1e3 / reps
 
 
-def read_probe_gbps(bufs) -> float:
-    """A plain streaming read (moe_read_probe) over the ring of weight copies: the practical
-    HBM read ceiling on this machine, in GB/s (median of one pass per copy)."""
+def read_probe(bufs, nbytes: int):
+    """A plain streaming read (moe_read_probe) of `nbytes` from each copy of the weight ring in
+    turn, one launch between two HIP events like the FFN launch it is compared with: the practical
+    ceiling for a launch that moves that many bytes.  Returns (median us, GB/s)."""
     import torch
     from paper_2512_13525_amd import binding as B
     sink = torch.zeros((64,), dtype=torch.int32, device="cuda")
-    ts = []
-    for rep in range(3):
+    n = min(nbytes, min(t.numel() * t.element_size() for t in bufs)) // 16 * 16
+    ev = []
+    for rep in range(8):                       # queued back to back, like the steps of the timed region
         for t in bufs:
-            n = t.numel() * t.element_size()
             a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             a.record(); B.moe_read_probe(t, n, sink); b.record()
-            torch.cuda.synchronize()
-            if rep:
-                ts.append(n / (a.elapsed_time(b) * 1e-3) / 1e9)
-    return statistics.median(ts)
+            ev.append((a, b))
+    torch.cuda.synchronize()
+    us = statistics.median(a.elapsed_time(b) * 1e3 for a, b in ev[len(bufs):])
+    return us, n / (us * 1e-6) / 1e9
 
 
 def sched_sweep(args) -> None:

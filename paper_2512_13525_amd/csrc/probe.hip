@@ -4,25 +4,27 @@
 
 namespace {
 
-// Every thread keeps four independent 16-byte loads in flight per iteration of a grid-stride loop
-// over 4 KiB-per-workgroup-per-load chunks; the xor of everything read is stored so that no load
-// can be dropped.
+// Every thread keeps kUnroll independent 16-byte loads in flight per iteration of a grid-stride
+// loop (consecutive threads read consecutive 16 bytes); the xor of everything read is stored
+// under a condition that practically never holds, so that no load can be dropped.
+constexpr int kUnroll = 8;
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
 __global__ __launch_bounds__(256)
-void read_probe_kernel(const uint4 *__restrict__ src, size_t n16, uint32_t *__restrict__ sink) {
+void read_probe_kernel(const u32x4 *__restrict__ src, size_t n16, uint32_t *__restrict__ sink) {
     const size_t stride = static_cast<size_t>(gridDim.x) * blockDim.x;
     size_t i = blockIdx.x * static_cast<size_t>(blockDim.x) + threadIdx.x;
-    uint4 acc = make_uint4(0u, 0u, 0u, 0u);
-    for (; i + 3 * stride < n16; i += 4 * stride) {
-        const uint4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
-        acc.x ^= a.x ^ b.x ^ c.x ^ d.x; acc.y ^= a.y ^ b.y ^ c.y ^ d.y;
-        acc.z ^= a.z ^ b.z ^ c.z ^ d.z; acc.w ^= a.w ^ b.w ^ c.w ^ d.w;
+    u32x4 acc = {0u, 0u, 0u, 0u};
+    for (; i + (kUnroll - 1) * stride < n16; i += kUnroll * stride) {
+        u32x4 v[kUnroll];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) v[u] = __builtin_nontemporal_load(&src[i + u * stride]);
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) acc ^= v[u];
     }
-    for (; i < n16; i += stride) {
-        const uint4 a = src[i];
-        acc.x ^= a.x; acc.y ^= a.y; acc.z ^= a.z; acc.w ^= a.w;
-    }
-    const uint32_t v = acc.x ^ acc.y ^ acc.z ^ acc.w;
-    if (v == 0x9e3779b9u) sink[blockIdx.x & 63] = v;           // practically never: keeps the loads alive
+    for (; i < n16; i += stride) acc ^= src[i];
+    const uint32_t x = acc.x ^ acc.y ^ acc.z ^ acc.w;
+    if (x == 0x9e3779b9u) sink[blockIdx.x & 63] = x;
 }
 
 }  // namespace
@@ -31,7 +33,7 @@ extern "C" int moe_read_probe(const void *src_dev, size_t bytes, void *sink_dev,
     if (!src_dev || !sink_dev) return MOE_EINVAL;
     if (!moe::aligned(src_dev, 16) || !moe::aligned(sink_dev, 4)) return MOE_EINVAL;
     if (bytes < 16) return MOE_OK;
-    hipLaunchKernelGGL(read_probe_kernel, dim3(256 * 8), dim3(256), 0, static_cast<hipStream_t>(stream),
-                       static_cast<const uint4 *>(src_dev), bytes / 16, static_cast<uint32_t *>(sink_dev));
+    hipLaunchKernelGGL(read_probe_kernel, dim3(512), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       static_cast<const u32x4 *>(src_dev), bytes / 16, static_cast<uint32_t *>(sink_dev));
     return moe::check_launch("moe_read_probe");
 }
