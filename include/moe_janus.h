@@ -127,6 +127,21 @@ int moe_route(const float *logits_dev, int T, int E, int k, const moe_route_cfg 
 int moe_schedule(const moe_placement_t *pl, const int32_t *topk_ids_dev, int T, int k,
                  int32_t *rid_dev, int32_t *act_rep_dev, int32_t *load_dev, void *stream);
 
+/* ------------------------------------------------------------------ baseline policies
+ * The two policies AEBS is compared with (Sec. 5, the a_max study): MOE_POLICY_HOME sends every
+ * request of expert e to e's first replica (lowest instance: no scheduling at all);
+ * MOE_POLICY_RANDOM sends request p to replica number draws[p] mod R(e) of e, replicas counted
+ * in ascending instance order (balances tokens, not activated experts; the caller supplies the
+ * draws, uint32 [T*k]; NULL for MOE_POLICY_HOME).
+ *   rid_dev  [T*k]    int32  replica id per request
+ *   load_dev [n_inst] int32  distinct replicas per instance that received a request; max = a_max
+ */
+#define MOE_POLICY_HOME   0
+#define MOE_POLICY_RANDOM 1
+int moe_schedule_baseline(const moe_placement_t *pl, const int32_t *topk_ids_dev, int T, int k,
+                          int policy, const uint32_t *draws_dev, int32_t *rid_dev, int32_t *load_dev,
+                          void *stream);
+
 /* ------------------------------------------------------------------ a4: dispatch (Step 4)
  * Keeps the requests whose replica lives on instance g_self and groups them by local slot
  * s = rid - g_self*C, ascending request id inside a slot (a stable grouping: the output is

@@ -114,13 +114,22 @@ def home_only(L: np.ndarray, pl: Placement) -> np.ndarray:
     return first[np.asarray(L)]
 
 
-def random_replica(L: np.ndarray, pl: Placement, rng: np.random.Generator) -> np.ndarray:
-    """Per-request random replica: each (token, choice) independently picks one replica of
-    its expert uniformly (balances tokens, not activated experts)."""
+def random_replica_from_draws(L: np.ndarray, pl: Placement, U: np.ndarray) -> np.ndarray:
+    """Per-request random replica (the token-balancing baselines of Sec. 5: each (token, choice)
+    independently picks one replica of its expert uniformly; balances tokens, not activated
+    experts).  The draws are inputs: request (i, j) takes replica number U[i, j] mod R(e) of its
+    expert e, replicas counted in ascending instance order."""
     L = np.asarray(L)
+    U = np.asarray(U, dtype=np.uint64)
     O = np.empty(L.shape, dtype=np.int32)
     for i in range(L.shape[0]):
         for j in range(L.shape[1]):
             r = pl.rids[int(L[i, j])]
-            O[i, j] = r[int(rng.integers(len(r)))]
+            O[i, j] = r[int(U[i, j] % np.uint64(len(r)))]
     return O
+
+
+def random_replica(L: np.ndarray, pl: Placement, rng: np.random.Generator) -> np.ndarray:
+    """random_replica_from_draws with 32-bit draws taken from `rng`."""
+    L = np.asarray(L)
+    return random_replica_from_draws(L, pl, rng.integers(0, 1 << 32, size=L.shape, dtype=np.uint64))

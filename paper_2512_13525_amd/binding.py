@@ -19,11 +19,12 @@ MOE_EINVAL, MOE_ESHAPE, MOE_EPLACEMENT, MOE_EHIP, MOE_ENOMEM, MOE_EWORKSPACE = -
 MOE_DTYPE_BF16, MOE_DTYPE_F32 = 0, 1
 MOE_ROUTE_SOFTMAX, MOE_ROUTE_SIGMOID_GROUP = 0, 1
 MOE_FFN_BLOCK_ROWS = 64
+MOE_POLICY_HOME, MOE_POLICY_RANDOM = 0, 1
 
 EXPORTS = [
     "moe_strerror", "moe_last_error",
     "moe_placement_create", "moe_placement_destroy", "moe_placement_replicas", "moe_placement_dims",
-    "moe_route", "moe_schedule", "moe_permute", "moe_block_rows", "moe_max_blocks", "moe_block_list_len",
+    "moe_route", "moe_schedule", "moe_schedule_baseline", "moe_permute", "moe_block_rows", "moe_max_blocks", "moe_block_list_len",
     "moe_route_schedule_permute", "moe_pack_weights_bf16",
     "moe_workspace_bytes", "moe_workspace_init", "moe_workspace_status", "moe_grouped_ffn", "moe_combine",
     "moe_read_probe",
@@ -70,6 +71,8 @@ def lib() -> ctypes.CDLL:
     L.moe_route.argtypes = [vp, ci, ci, ci, ctypes.POINTER(moe_route_cfg), vp, vp, vp]
     L.moe_schedule.restype = ci
     L.moe_schedule.argtypes = [vp, vp, ci, ci, vp, vp, vp, vp]
+    L.moe_schedule_baseline.restype = ci
+    L.moe_schedule_baseline.argtypes = [vp, vp, ci, ci, ci, vp, vp, vp, vp]
     L.moe_permute.restype = ci
     L.moe_permute.argtypes = [vp, ci, vp, ci, ci, vp, vp, vp, vp, vp, vp]
     L.moe_block_rows.restype = ci
@@ -162,6 +165,11 @@ def moe_route(logits, k: int, topk_ids, topk_w, mode: int = MOE_ROUTE_SOFTMAX, r
 def moe_schedule(pl: Placement, topk_ids, T: int, k: int, rid, act_rep, load, stream=None) -> None:
     _check(lib().moe_schedule(pl.handle, _ptr(topk_ids), T, k, _ptr(rid), _ptr(act_rep), _ptr(load),
                               _stream(stream)), "moe_schedule")
+
+
+def moe_schedule_baseline(pl: Placement, topk_ids, T: int, k: int, policy: int, draws, rid, load, stream=None) -> None:
+    _check(lib().moe_schedule_baseline(pl.handle, _ptr(topk_ids), T, k, policy, _ptr(draws), _ptr(rid), _ptr(load),
+                                       _stream(stream)), "moe_schedule_baseline")
 
 
 def moe_permute(pl: Placement, g_self: int, rid, T: int, k: int, slot_count, slot_off, perm, pos, blocks,

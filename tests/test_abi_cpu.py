@@ -65,6 +65,7 @@ def test_argument_validation_without_launch():
     g = B.moe_route_cfg(B.MOE_ROUTE_SIGMOID_GROUP, 1, 3, 2, 1.0)
     assert L.moe_route(None, 4, 8, 2, ctypes.byref(g), None, None, None) == B.MOE_ESHAPE       # 8 % 3
     assert L.moe_schedule(None, None, 4, 2, None, None, None, None) == B.MOE_EINVAL
+    assert L.moe_schedule_baseline(None, None, 4, 2, 0, None, None, None, None) == B.MOE_EINVAL
     assert L.moe_permute(None, 0, None, 4, 2, None, None, None, None, None, None) == B.MOE_EINVAL
     # FFN: shapes first, then pointers
     assert L.moe_grouped_ffn(None, None, None, 4, 2, 5, 100, 64, B.MOE_DTYPE_BF16, None, None, None, None, None, 0,

@@ -149,6 +149,28 @@ def test_schedule_and_permute_parity(cfg):
         np.testing.assert_array_equal(d_pos.cpu().numpy(), pos)
 
 
+@pytest.mark.parametrize("cfg", [W.tiny(), W.dsv2lite(), W.qwen3(256), W.dsv3(512), small("ragged", k=5, T=77),
+                                 W.stress(1000, 1.25, 0.8), W.stress(8192, 1.125, 1.5)],
+                         ids=lambda c: f"{c.name}-T{c.T}")
+def test_baseline_policies_parity(cfg):
+    """moe_schedule_baseline: the home-only and the random-replica policy, bit for bit."""
+    lay = W.build_placement(cfg)
+    opl = scheduling.make_placement(lay, cfg.E, cfg.n_inst, cfg.C)
+    pl = B.Placement(lay, cfg.E, cfg.n_inst, cfg.C)
+    ids, _, _ = oracle_route(cfg, W.router_logits(cfg))
+    U = np.random.default_rng(cfg.seed + 17).integers(0, 1 << 32, size=ids.shape, dtype=np.uint64)
+    d_draws = torch.from_numpy(U.astype(np.uint32).view(np.int32)).cuda()
+    for policy, O in ((B.MOE_POLICY_HOME, scheduling.home_only(ids, opl)),
+                      (B.MOE_POLICY_RANDOM, scheduling.random_replica_from_draws(ids, opl, U))):
+        d_rid = torch.full(ids.shape, -9, dtype=torch.int32, device="cuda")
+        d_load = torch.full((cfg.n_inst,), -9, dtype=torch.int32, device="cuda")
+        B.moe_schedule_baseline(pl, dev_i32(ids), cfg.T, cfg.k, policy,
+                                d_draws if policy == B.MOE_POLICY_RANDOM else None, d_rid, d_load)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(d_rid.cpu().numpy(), O)
+        np.testing.assert_array_equal(d_load.cpu().numpy(), scheduling.loads_of(O, opl))
+
+
 def test_schedule_empty_batch_and_layout_swap():
     cfg = W.tiny()
     lay = W.build_placement(cfg)

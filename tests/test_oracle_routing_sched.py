@@ -318,3 +318,29 @@ def test_expected_activated_closed_form_uniform():
 def test_a_max_bound_formula_values():
     assert bounds.a_max_bound(10.0, 27, 8) == math.floor(10 + math.sqrt(20 * math.log(8)) + 1)
     assert bounds.a_max_bound(26.5, 27, 16) == 28      # capped at C, then +1
+
+
+def test_random_replica_draws_pick_the_stated_replica():
+    """The token-balancing baseline with its draws as inputs: draw 0 is the first replica (the
+    home-only policy), draw R(e)-1 the last, every choice hosts the expert, and the loads are the
+    distinct replicas per instance."""
+    cfg = W.stress(64, 1.25, 0.8)
+    lay = W.build_placement(cfg)
+    pl = scheduling.make_placement(lay, cfg.E, cfg.n_inst, cfg.C)
+    rng = np.random.default_rng(11)
+    L = np.stack([rng.choice(cfg.E, size=cfg.k, replace=False) for _ in range(40)]).astype(np.int32)
+    zero = scheduling.random_replica_from_draws(L, pl, np.zeros(L.shape, dtype=np.uint32))
+    np.testing.assert_array_equal(zero, scheduling.home_only(L, pl))
+    lastd = np.array([[pl.R[e] - 1 for e in row] for row in L], dtype=np.uint32)
+    last = scheduling.random_replica_from_draws(L, pl, lastd)
+    assert all(last[i, j] == pl.rids[int(L[i, j])][-1] for i in range(L.shape[0]) for j in range(L.shape[1]))
+    U = rng.integers(0, 1 << 32, size=L.shape, dtype=np.uint64)
+    O = scheduling.random_replica_from_draws(L, pl, U)
+    lay64 = np.asarray(lay)
+    assert (lay64[O] == L).all()                                  # the chosen slot holds the requested expert
+    # wrap-around of the modulus: draw + R(e) picks the same replica
+    shifted = U + np.array([[pl.R[e] for e in row] for row in L], dtype=np.uint64)
+    np.testing.assert_array_equal(scheduling.random_replica_from_draws(L, pl, shifted), O)
+    load = scheduling.loads_of(O, pl)
+    assert load.sum() == len(set(O.reshape(-1).tolist()))
+    assert load.max() >= optimum.optimum_matching(sorted(set(L.reshape(-1).tolist())), pl)   # no policy beats the optimum
