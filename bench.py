@@ -54,11 +54,12 @@ def main() -> None:
     ap.add_argument("--ring-bytes", type=float, default=1.25e9, help="minimum total bytes of rotating weight copies")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-events", action="store_true", help="do not record per-kernel events in the timed region")
-    ap.add_argument("--mode", default="step", choices=["step", "sched", "act_sweep", "skew", "batch_sweep"],
+    ap.add_argument("--mode", default="step", choices=["step", "sched", "act_sweep", "skew", "batch_sweep", "amax"],
                     help="step: the headline line (default); sched: scheduler us and a_max vs optimum over the "
                          "stress sweep; act_sweep: layer us vs number of activated experts; skew: same "
                          "activated set with an even and a Zipf split of the requests; batch_sweep: layer "
-                         "us vs batch size with every slot activated")
+                         "us vs batch size with every slot activated; amax: Monte-Carlo a_max of AEBS and the "
+                         "baseline policies over sampled batches, against the exact optimum and Eq. 5")
     args = ap.parse_args()
     if args.gpus != 1:
         raise SystemExit("this build runs on ONE GPU: the other MoE instances exist only as replica placement "
@@ -79,6 +80,8 @@ def main() -> None:
         return act_sweep(args)
     if args.mode in ("skew", "batch_sweep"):
         return split_sweeps(args)
+    if args.mode == "amax":
+        return amax_study(args)
     cfg = make_cfg(args.workload, args.tokens)
     lay = W.build_placement(cfg)
     T, k, C, d_h, d_e = cfg.T, cfg.k, cfg.C, cfg.d_h, cfg.d_e
@@ -432,6 +435,65 @@ def split_sweeps(args) -> None:
                               "weight_GBps": round(C * 3 * d_h * d_e * 2 / (us * 1e-6) / 1e9, 1)}), flush=True)
         del W13s, W2s, step
         torch.cuda.empty_cache()
+
+
+def amax_study(args) -> None:
+    """Monte-Carlo table of a_max (the largest per-instance number of activated experts, which
+    Eq. 1c turns into the MoE-side latency) over sampled decode batches, for AEBS and for the two
+    baseline policies (first replica only; random replica per request), next to the exact optimum
+    on a subsample and the balls-into-bins bound of Eq. 5 (Appendix A).  E = 256, k = 8, Zipf 0.8,
+    replication 1.25; n_e instances and batch size B vary.  Logits are drawn on the GPU with the
+    recipe of the other workloads (N(0,1) + ln(E p_e))."""
+    import numpy as np
+    import torch
+    from oracle import bounds, optimum, scheduling
+    from paper_2512_13525_amd import binding as B
+    from paper_2512_13525_amd import workloads as W
+
+    E, k, s, r, n_batches, n_opt = 256, 8, 0.8, 1.25, 200, 16
+    gen = torch.Generator(device="cuda").manual_seed(7)
+    for n_inst in (8, 16, 32):
+        C = int(np.ceil(E * r / n_inst))
+        cfg0 = W.MoEConfig(f"amax_ne{n_inst}", E=E, k=k, d_h=64, d_e=64, T=1, n_inst=n_inst, C=C, zipf_s=s, seed=0)
+        lay = W.build_placement(cfg0)
+        pl = B.Placement(lay, E, n_inst, C)
+        opl = scheduling.make_placement(lay, E, n_inst, C)
+        bias = torch.from_numpy(np.log(E * W.expert_popularity(cfg0)).astype(np.float32)).cuda()
+        # p_e = probability that one token selects e, from a calibration sample of routed tokens
+        Tc = 1 << 15
+        ids = torch.empty((Tc, k), dtype=torch.int32, device="cuda")
+        wts = torch.empty((Tc, k), dtype=torch.float32, device="cuda")
+        B.moe_route(torch.randn((Tc, E), generator=gen, device="cuda") + bias, k, ids, wts)
+        p_e = np.bincount(ids.cpu().numpy().reshape(-1), minlength=E) / Tc
+        hosted = [[int(e) for e in lay[g * C:(g + 1) * C] if e >= 0] for g in range(n_inst)]
+        for T in (64, 128, 256, 512, 1024):
+            ids = torch.empty((T, k), dtype=torch.int32, device="cuda")
+            wts = torch.empty((T, k), dtype=torch.float32, device="cuda")
+            rid = torch.empty((T, k), dtype=torch.int32, device="cuda")
+            rep = torch.empty((E,), dtype=torch.int32, device="cuda")
+            loads = torch.zeros((3, n_batches, n_inst), dtype=torch.int32, device="cuda")
+            ids_keep = []
+            for b in range(n_batches):
+                logits = torch.randn((T, E), generator=gen, device="cuda") + bias
+                draws = torch.randint(0, 1 << 31, (T, k), generator=gen, device="cuda", dtype=torch.int32)
+                B.moe_route(logits, k, ids, wts)
+                B.moe_schedule(pl, ids, T, k, rid, rep, loads[0, b])
+                B.moe_schedule_baseline(pl, ids, T, k, B.MOE_POLICY_HOME, None, rid, loads[1, b])
+                B.moe_schedule_baseline(pl, ids, T, k, B.MOE_POLICY_RANDOM, draws, rid, loads[2, b])
+                if b < n_opt:
+                    ids_keep.append(ids.cpu().numpy().copy())
+            torch.cuda.synchronize()
+            amax = loads.max(dim=2).values.cpu().numpy()                       # [3, n_batches]
+            opt = [optimum.optimum_matching(sorted(set(i.reshape(-1).tolist())), opl) for i in ids_keep]
+            a_bar = max(bounds.expected_activated(p_e, h, T) for h in hosted)
+            print(json.dumps({"mode": "amax", "n_inst": n_inst, "C": C, "B": T, "batches": n_batches,
+                              "a_max_aebs": {"mean": round(float(amax[0].mean()), 2), "max": int(amax[0].max())},
+                              "a_max_home_only": {"mean": round(float(amax[1].mean()), 2), "max": int(amax[1].max())},
+                              "a_max_random": {"mean": round(float(amax[2].mean()), 2), "max": int(amax[2].max())},
+                              "a_max_optimum_mean_first16": round(float(np.mean(opt)), 2),
+                              "a_max_aebs_mean_first16": round(float(amax[0][:n_opt].mean()), 2),
+                              "eq4_expected_max": round(a_bar, 2), "eq5_bound": bounds.a_max_bound(a_bar, C, n_inst)}),
+                  flush=True)
 
 
 if __name__ == "__main__":
