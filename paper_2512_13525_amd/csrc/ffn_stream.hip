@@ -22,11 +22,13 @@
 // units that the tail of stage 1 leaves idle.  A stage-2 workgroup first puts its weight loads in
 // flight and then waits until the 16-channel tiles of its block of `act` rows are all written: a
 // counter per block in the workspace is bumped by each stage-1 workgroup once its stores are
-// acknowledged, and polled (bounded; an overrun raises the workspace's error word and the
-// workgroup carries on, so every wave reaches the end of the kernel).  `act` is written with
-// agent-scope stores and read with agent-scope loads, and the counters are agent-scope atomics,
-// because the 8 XCDs do not share an L2.  The last stage-2 workgroup of a block to get through
-// the wait clears the block's counters for the next call.
+// acknowledged; the workgroup that completes the count raises the block's ready flags, which the
+// stage-2 workgroups poll (bounded; an overrun raises the workspace's error word and the
+// workgroup carries on, so every wave reaches the end of the kernel).  The 8 XCDs do not share an
+// L2: `act` is written with agent-scope (write-through) stores, every 128-byte line of it has one
+// writing workgroup, and no workgroup reads a line before its block is ready, so plain loads see
+// the data; counters and flags are agent-scope atomics.  The last stage-2 workgroup of a block to
+// get through the wait clears the block's control lines for the next call.
 #include "common.h"
 
 namespace {
