@@ -147,7 +147,7 @@ __device__ __forceinline__ void wait_block_ready(const StreamArgs &a, int item, 
                 __hip_atomic_fetch_or(a.ctrl + 1, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 break;
             }
-            __builtin_amdgcn_s_sleep(32);
+            __builtin_amdgcn_s_sleep(8);
         }
         if (__hip_atomic_fetch_add(blk + 1, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == n_readers - 1) {
             __hip_atomic_store(blk, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
