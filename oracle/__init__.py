@@ -5,6 +5,7 @@ hot path computes, written from the paper.  It shares no code with the HIP
 library and is imported only by tests/, __graft_entry__.smoke() and the
 cpu_baseline leg of bench.py.  The product path never calls it.
 
+  gating.py      the router's linear layer (gate logits from the activations)  (Sec. 3.3)
   routing.py     gating selection: top-k ids and normalised weights        (Sec. 3.4, Step 0)
   scheduling.py  replica layout tables and Alg. 1 (AEBS), plus the two
                  comparison policies the evaluation describes              (Sec. 3.4, Alg. 1; Sec. 5)

@@ -127,6 +127,19 @@ def router_logits(cfg: MoEConfig, T: Optional[int] = None, sub: int = 0) -> np.n
     return np.ascontiguousarray(z, dtype=np.float32)
 
 
+def router_weights(cfg: MoEConfig) -> Tuple[np.ndarray, Optional[np.ndarray]]:
+    """Router (gate) matrix W_r [E,d_h] ~ N(0, 1/d_h), so that logits of N(0,1) activations are
+    ~N(0,1) like `router_logits`, and the per-expert bias ln(E*p_e) of the Zipf skew (None when
+    zipf_s == 0).  W_r is bf16-representable when cfg.dtype == 'bf16'; the bias stays float32."""
+    wr = _rng(cfg, 5).standard_normal((cfg.E, cfg.d_h), dtype=np.float32) * np.float32(cfg.d_h ** -0.5)
+    if cfg.dtype == "bf16":
+        wr = round_to_bf16(wr)
+    bias = None
+    if cfg.zipf_s != 0.0:
+        bias = np.log(cfg.E * expert_popularity(cfg)).astype(np.float32)
+    return np.ascontiguousarray(wr), bias
+
+
 def activations(cfg: MoEConfig, T: Optional[int] = None, sub: int = 0) -> np.ndarray:
     """N(0,1) activations, float32 [T,d_h]; bf16-representable when cfg.dtype == 'bf16'."""
     T = cfg.T if T is None else T
