@@ -183,6 +183,35 @@ int moe_route_schedule_permute(const moe_placement_t *pl, int g_self, const floa
                                int32_t *slot_count_dev, int32_t *slot_off_dev, int32_t *perm_dev,
                                int32_t *pos_dev, int32_t *blocks_dev, int32_t *sync_dev, void *stream);
 
+/* ------------------------------------------------------------------ the gate in the same launch
+ * Sec. 3.3 ("gating on the MoE side"): the MoE instance receives the complete activations and
+ * runs the gate itself.  These two entry points start from the activations instead of from
+ * logits: logits[i, e] = sum_c X[i, c] * W_r[e, c] (+ bias[e]), bf16 operands, fp32 products
+ * and sums (MFMA), then the selection of moe_route on those fp32 logits, in one launch;
+ * moe_gate_route_schedule_permute continues through Alg. 1 and the dispatch exactly like
+ * moe_route_schedule_permute.
+ *   X_dev      [T, d_h] bf16, row-major, 16-byte aligned
+ *   Wr_dev     [E, d_h] bf16, row-major (one row per logical expert), 16-byte aligned
+ *   bias_dev   [E] float, or NULL
+ *   logits_dev [T, E] float, OUTPUT (the selection reads it back inside the launch)
+ *   sync_dev   moe_gate_sync_len(T) int32, zero before the first call; every call leaves them
+ *              zero.  Calls that share sync_dev must not overlap in time.
+ * Needs d_h % 32 == 0 (MOE_ESHAPE otherwise).  The sum over c is taken in a fixed order
+ * (16 contiguous shares of the hidden dimension, added in ascending order), so results are
+ * reproducible; it is not the order of a sequential dot product, so a logit can differ from one
+ * in the last bits and a selection between logits closer than that can differ too.
+ */
+size_t moe_gate_sync_len(int T);
+int moe_gate_route(const void *X_dev, const void *Wr_dev, const float *bias_dev, int T, int E, int d_h, int k,
+                   const moe_route_cfg *cfg, float *logits_dev, int32_t *topk_ids_dev, float *topk_w_dev,
+                   int32_t *sync_dev, void *stream);
+int moe_gate_route_schedule_permute(const moe_placement_t *pl, int g_self, const void *X_dev, const void *Wr_dev,
+                                    const float *bias_dev, int T, int d_h, int k, const moe_route_cfg *cfg,
+                                    float *logits_dev, int32_t *topk_ids_dev, float *topk_w_dev,
+                                    int32_t *rid_dev, int32_t *act_rep_dev, int32_t *load_dev,
+                                    int32_t *slot_count_dev, int32_t *slot_off_dev, int32_t *perm_dev,
+                                    int32_t *pos_dev, int32_t *blocks_dev, int32_t *sync_dev, void *stream);
+
 /* ------------------------------------------------------------------ expert weights
  * Canonical layout of one instance's physical experts (what a checkpoint holds):
  *   W13 [C, 2*d_e, d_h]  rows 0..d_e-1 = gate projection, rows d_e..2*d_e-1 = up projection

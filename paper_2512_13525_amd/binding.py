@@ -25,7 +25,8 @@ EXPORTS = [
     "moe_strerror", "moe_last_error",
     "moe_placement_create", "moe_placement_destroy", "moe_placement_replicas", "moe_placement_dims",
     "moe_route", "moe_schedule", "moe_schedule_baseline", "moe_permute", "moe_block_rows", "moe_max_blocks", "moe_block_list_len",
-    "moe_route_schedule_permute", "moe_pack_weights_bf16",
+    "moe_route_schedule_permute", "moe_gate_sync_len", "moe_gate_route", "moe_gate_route_schedule_permute",
+    "moe_pack_weights_bf16",
     "moe_workspace_bytes", "moe_workspace_init", "moe_workspace_status", "moe_grouped_ffn", "moe_combine",
     "moe_read_probe",
 ]
@@ -83,6 +84,12 @@ def lib() -> ctypes.CDLL:
     L.moe_block_list_len.argtypes = [ci, ci, ci]
     L.moe_route_schedule_permute.restype = ci
     L.moe_route_schedule_permute.argtypes = [vp, ci, vp, ci, ci, ctypes.POINTER(moe_route_cfg)] + [vp] * 12
+    L.moe_gate_sync_len.restype = cs
+    L.moe_gate_sync_len.argtypes = [ci]
+    L.moe_gate_route.restype = ci
+    L.moe_gate_route.argtypes = [vp, vp, vp, ci, ci, ci, ci, ctypes.POINTER(moe_route_cfg)] + [vp] * 5
+    L.moe_gate_route_schedule_permute.restype = ci
+    L.moe_gate_route_schedule_permute.argtypes = [vp, ci, vp, vp, vp, ci, ci, ci, ctypes.POINTER(moe_route_cfg)] + [vp] * 13
     L.moe_pack_weights_bf16.restype = ci
     L.moe_pack_weights_bf16.argtypes = [vp, vp, ci, ci, ci, vp, vp, vp]
     L.moe_workspace_bytes.restype = cs
@@ -200,6 +207,33 @@ def moe_route_schedule_permute(pl: Placement, g_self: int, logits, k: int, topk_
                                             _ptr(topk_ids), _ptr(topk_w), _ptr(rid), _ptr(act_rep), _ptr(load),
                                             _ptr(slot_count), _ptr(slot_off), _ptr(perm), _ptr(pos), _ptr(blocks),
                                             _ptr(sync),                                             _stream(stream)), "moe_route_schedule_permute")
+
+
+def moe_gate_sync_len(T: int) -> int:
+    return int(lib().moe_gate_sync_len(T))
+
+
+def moe_gate_route(X, Wr, bias, k: int, logits, topk_ids, topk_w, sync, mode: int = MOE_ROUTE_SOFTMAX,
+                   renormalize: bool = True, n_group: int = 1, topk_group: int = 1, scale: float = 1.0,
+                   stream=None) -> None:
+    T, d_h = X.shape
+    E = Wr.shape[0]
+    cfg = moe_route_cfg(mode, int(renormalize), n_group, topk_group, scale)
+    _check(lib().moe_gate_route(_ptr(X), _ptr(Wr), _ptr(bias), T, E, d_h, k, ctypes.byref(cfg), _ptr(logits),
+                                _ptr(topk_ids), _ptr(topk_w), _ptr(sync), _stream(stream)), "moe_gate_route")
+
+
+def moe_gate_route_schedule_permute(pl: Placement, g_self: int, X, Wr, bias, k: int, logits, topk_ids, topk_w, rid,
+                                    act_rep, load, slot_count, slot_off, perm, pos, blocks, sync,
+                                    mode: int = MOE_ROUTE_SOFTMAX, renormalize: bool = True, n_group: int = 1,
+                                    topk_group: int = 1, scale: float = 1.0, stream=None) -> None:
+    T, d_h = X.shape
+    cfg = moe_route_cfg(mode, int(renormalize), n_group, topk_group, scale)
+    _check(lib().moe_gate_route_schedule_permute(pl.handle, g_self, _ptr(X), _ptr(Wr), _ptr(bias), T, d_h, k,
+                                                 ctypes.byref(cfg), _ptr(logits), _ptr(topk_ids), _ptr(topk_w),
+                                                 _ptr(rid), _ptr(act_rep), _ptr(load), _ptr(slot_count),
+                                                 _ptr(slot_off), _ptr(perm), _ptr(pos), _ptr(blocks), _ptr(sync),
+                                                 _stream(stream)), "moe_gate_route_schedule_permute")
 
 
 def moe_pack_weights_bf16(W13, W2, C: int, d_h: int, d_e: int, W13_packed, W2_packed, stream=None) -> None:

@@ -6,6 +6,15 @@
 // agent-scope stores; the workgroup that finishes last (an atomic ticket, nobody waits) then
 // runs Alg. 1 and the counting sort on its own, reading the ids with agent-scope loads because
 // they were written on other XCDs.
+//
+// The gated variants start one step earlier (Sec. 3.3: gating runs on the MoE side, from the
+// complete activations): the logits are the router's linear layer X * W_r^T (+ bias), computed
+// in the same launch.  A workgroup owns (16 tokens) x (16 experts) of the logits: its 16
+// wavefronts split the hidden dimension, each accumulates one 16x16 MFMA tile over its share,
+// and the partial tiles are summed in LDS in wavefront order.  The workgroup that completes a
+// token group (a ticket per group) routes its 16 tokens from the logits the others published.
+#include <type_traits>
+
 #include "dispatch_dev.h"
 
 namespace {
@@ -21,7 +30,65 @@ struct FrontArgs {
     int32_t *rid, *act_rep, *load, *slot_count, *slot_off, *perm, *pos, *blocks;
     int32_t *ticket;
     int block_rows;
+    // gated variants: logits = X * Wr^T (+ bias) are computed here and written to `logits_out`
+    const uint16_t *X, *Wr;              // bf16 [T,d_h], [E,d_h]
+    const float *bias;                   // [E] or null
+    float *logits_out;                   // [T,E]
+    int d_h, n_tiles;                    // n_tiles = ceil(E/16) expert tiles
+    int tail;                            // 0: stop after the gating selection
 };
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// Logits of token group tg (16 tokens) against expert tile j (16 experts).  MFMA 16x16x32: the
+// router rows are the A operand (lane l: expert l%16, 8 columns at (l/16)*8 of the K-step), the
+// token rows the B operand (same shape), and the D tile leaves lane l with experts (l/16)*4..+3
+// of token l%16.  Rows past T or E repeat the last valid row and are not stored.
+__device__ __forceinline__ void gate_tile(const FrontArgs &a, int tg, int j, f32x4 *part, int wave, int lane) {
+    const int KS = a.d_h / 32;
+    const int per = (KS + moe::kFrontWaves - 1) / moe::kFrontWaves;
+    const int k0 = wave * per;
+    const int k1 = k0 + per < KS ? k0 + per : KS;
+    int tok = tg * 16 + (lane & 15);
+    tok = tok < a.T ? tok : a.T - 1;
+    int e = j * 16 + (lane & 15);
+    e = e < a.E ? e : a.E - 1;
+    const char *xb = reinterpret_cast<const char *>(a.X) + (static_cast<size_t>(tok) * a.d_h + (lane >> 4) * 8) * 2;
+    const char *wb = reinterpret_cast<const char *>(a.Wr) + (static_cast<size_t>(e) * a.d_h + (lane >> 4) * 8) * 2;
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    int kk = k0;
+    for (; kk + 4 <= k1; kk += 4) {
+        bf16x8 av[4], bv[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            av[u] = *reinterpret_cast<const bf16x8 *>(wb + (kk + u) * 64);
+            bv[u] = *reinterpret_cast<const bf16x8 *>(xb + (kk + u) * 64);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[u], bv[u], acc, 0, 0, 0);
+    }
+    for (; kk < k1; ++kk) {
+        const bf16x8 av = *reinterpret_cast<const bf16x8 *>(wb + kk * 64);
+        const bf16x8 bv = *reinterpret_cast<const bf16x8 *>(xb + kk * 64);
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, bv, acc, 0, 0, 0);
+    }
+    part[wave * MOE_WAVE + lane] = acc;
+    __syncthreads();
+    if (threadIdx.x < MOE_WAVE) {
+        f32x4 s = part[lane];
+#pragma unroll
+        for (int w = 1; w < moe::kFrontWaves; ++w) s += part[w * MOE_WAVE + lane];
+        const int t = tg * 16 + (lane & 15);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int ee = j * 16 + (lane >> 4) * 4 + i;
+            if (t < a.T && ee < a.E)
+                __hip_atomic_store(a.logits_out + static_cast<size_t>(t) * a.E + ee, s[i] + (a.bias ? a.bias[ee] : 0.0f),
+                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+}
 
 // Decode-size tail (up to kRegPairs requests): Alg. 1 and the counting sort with every request id
 // held in registers.  Wavefront w owns requests [w*gpw*64, (w+1)*gpw*64), the mapping the sort needs,
@@ -194,7 +261,7 @@ __device__ __forceinline__ void front_tail_small(const FrontArgs &a, SmallShared
     }
 }
 
-template <int VPL>
+template <int VPL, bool GATE>
 __global__ __launch_bounds__(moe::kFrontThreads)
 void front_kernel(FrontArgs a) {
     // the phases run one after another, so their LDS overlays
@@ -204,26 +271,70 @@ void front_kernel(FrontArgs a) {
         moe::PermShared perm;
         SmallShared small;
     };
+    // gated variants: the partial tiles of the split-K sum, then the logits rows being routed
+    union GateShared {
+        f32x4 part[moe::kFrontWaves * MOE_WAVE];
+        float row[moe::kFrontWaves][VPL * MOE_WAVE];
+    };
     __shared__ Shared sh;
+    __shared__ std::conditional_t<GATE, GateShared, int> gs;
     __shared__ int s_last;
 
     const int wave = threadIdx.x / MOE_WAVE;
     const int lane = moe::lane_id();
-    const int t = blockIdx.x * moe::kFrontWaves + wave;
     const int n_pairs = a.T * a.k;
     const bool small = n_pairs <= kRegPairs && a.E * a.n_inst <= kSlotOfLds;
     TablePrefetch tp{};
-    if (small) tp = prefetch_tables(a);
-    if (t < a.T) {
-        moe::route_token<VPL, true>(a.logits + static_cast<size_t>(t) * a.E, a.E, a.k, a.cfg, sh.row[wave], lane,
-                                    a.ids + static_cast<size_t>(t) * a.k, a.w + static_cast<size_t>(t) * a.k);
+    int expected = static_cast<int>(gridDim.x);                       // arrivals that complete the selection
+    if constexpr (GATE) {
+        if (a.tail && small) tp = prefetch_tables(a);
+        expected = a.T > 0 ? (a.T + 15) / 16 : 1;
+        if (a.T > 0) {
+            const int tg = blockIdx.x / a.n_tiles, j = blockIdx.x % a.n_tiles;
+            gate_tile(a, tg, j, gs.part, wave, lane);
+            // the group's ticket must not overtake the logits
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __syncthreads();
+            if (threadIdx.x == 0) {
+                int32_t *grp = a.ticket + 1 + tg;
+                const int old = __hip_atomic_fetch_add(grp, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                s_last = old == a.n_tiles - 1;
+                if (s_last) __hip_atomic_store(grp, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+            __syncthreads();
+            if (!s_last) return;
+            const int t = tg * 16 + wave;
+            if (t < a.T) {
+                float *row = gs.row[wave];
+#pragma unroll
+                for (int i = 0; i < VPL; ++i) {
+                    const int e = lane + i * MOE_WAVE;
+                    row[e] = e < a.E ? __hip_atomic_load(a.logits_out + static_cast<size_t>(t) * a.E + e, __ATOMIC_RELAXED,
+                                                         __HIP_MEMORY_SCOPE_AGENT)
+                                     : 0.0f;
+                }
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                moe::route_token<VPL, true>(row, a.E, a.k, a.cfg, sh.row[wave], lane,
+                                            a.ids + static_cast<size_t>(t) * a.k, a.w + static_cast<size_t>(t) * a.k);
+            }
+        }
+        if (!a.tail) return;
+    } else {
+        if (small) tp = prefetch_tables(a);
+        const int t = blockIdx.x * moe::kFrontWaves + wave;
+        if (t < a.T) {
+            moe::route_token<VPL, true>(a.logits + static_cast<size_t>(t) * a.E, a.E, a.k, a.cfg, sh.row[wave], lane,
+                                        a.ids + static_cast<size_t>(t) * a.k, a.w + static_cast<size_t>(t) * a.k);
+        }
     }
     // a workgroup barrier does not wait for global stores: the ticket must not overtake the ids
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     if (threadIdx.x == 0) {
         const int old = __hip_atomic_fetch_add(a.ticket, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        s_last = old == static_cast<int>(gridDim.x) - 1;
+        s_last = old == expected - 1;
         if (s_last) __hip_atomic_store(a.ticket, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next call
     }
     __syncthreads();
@@ -242,11 +353,63 @@ void front_kernel(FrontArgs a) {
     moe::permute_block(sh.perm, a.rid, n_pairs, a.g_self, a.C, a.slot_count, a.slot_off, a.perm, a.pos, a.blocks, a.block_rows);
 }
 
-template <int VPL>
-int launch_front(const FrontArgs &a, hipStream_t st) {
-    const int blocks = a.T > 0 ? (a.T + moe::kFrontWaves - 1) / moe::kFrontWaves : 1;
-    hipLaunchKernelGGL(front_kernel<VPL>, dim3(blocks), dim3(moe::kFrontThreads), 0, st, a);
-    return moe::check_launch("moe_route_schedule_permute");
+template <int VPL, bool GATE>
+int launch_front(const FrontArgs &a, const char *what, hipStream_t st) {
+    int blocks = 1;
+    if (a.T > 0) blocks = GATE ? (a.T + 15) / 16 * a.n_tiles : (a.T + moe::kFrontWaves - 1) / moe::kFrontWaves;
+    hipLaunchKernelGGL((front_kernel<VPL, GATE>), dim3(blocks), dim3(moe::kFrontThreads), 0, st, a);
+    return moe::check_launch(what);
+}
+
+template <bool GATE>
+int launch_front_for(const FrontArgs &a, const char *what, hipStream_t st) {
+    const int vpl = (a.E + MOE_WAVE - 1) / MOE_WAVE;
+    if (vpl <= 1) return launch_front<1, GATE>(a, what, st);
+    if (vpl <= 2) return launch_front<2, GATE>(a, what, st);
+    if (vpl <= 4) return launch_front<4, GATE>(a, what, st);
+    if (vpl <= 8) return launch_front<8, GATE>(a, what, st);
+    return launch_front<16, GATE>(a, what, st);
+}
+
+int check_selection(int T, int E, int k, const moe_route_cfg *cfg) {
+    if (!cfg || T < 0 || E < 1 || k < 1 || k > E) return MOE_EINVAL;
+    if (E > MOE_MAX_EXPERTS || k > MOE_MAX_TOPK) return MOE_ESHAPE;
+    if (static_cast<long long>(T) * k > 0x7fffffffLL) return MOE_ESHAPE;
+    if (cfg->mode != MOE_ROUTE_SOFTMAX && cfg->mode != MOE_ROUTE_SIGMOID_GROUP) return MOE_EINVAL;
+    if (cfg->mode == MOE_ROUTE_SIGMOID_GROUP) {
+        if (cfg->n_group < 1 || cfg->topk_group < 1 || cfg->topk_group > cfg->n_group) return MOE_EINVAL;
+        if (cfg->n_group > 64 || E % cfg->n_group != 0 || E / cfg->n_group < 2) return MOE_ESHAPE;
+        if (k > cfg->topk_group * (E / cfg->n_group)) return MOE_EINVAL;
+    }
+    return MOE_OK;
+}
+
+// the gate's operands: bf16 rows of d_h elements read 16 bytes at a time
+int check_gate(const void *X, const void *Wr, const float *bias, const float *logits, int T, int E, int d_h) {
+    if (d_h < 32 || d_h % 32 != 0) return MOE_ESHAPE;
+    if (static_cast<long long>(T) * E > 0x7fffffffLL) return MOE_ESHAPE;
+    if (!Wr || !moe::aligned(Wr, 16) || !moe::aligned(bias, 4)) return MOE_EINVAL;
+    if (T > 0 && (!X || !logits || !moe::aligned(X, 16) || !moe::aligned(logits, 4))) return MOE_EINVAL;
+    return MOE_OK;
+}
+
+int fill_tail(FrontArgs &a, const moe_placement_t *pl, int g_self, int T, int32_t *rid_dev, int32_t *act_rep_dev,
+              int32_t *load_dev, int32_t *slot_count_dev, int32_t *slot_off_dev, int32_t *perm_dev, int32_t *pos_dev,
+              int32_t *blocks_dev) {
+    if (g_self < 0 || g_self >= pl->n_inst) return MOE_EINVAL;
+    if (!act_rep_dev || !load_dev || !slot_count_dev || !slot_off_dev || !blocks_dev) return MOE_EINVAL;
+    if (T > 0 && (!rid_dev || !perm_dev || !pos_dev)) return MOE_EINVAL;
+    const void *ptrs[] = {rid_dev, act_rep_dev, load_dev, slot_count_dev, slot_off_dev, perm_dev, pos_dev};
+    for (const void *p : ptrs)
+        if (!moe::aligned(p, 4)) return MOE_EINVAL;
+    if (!moe::aligned(blocks_dev, 16)) return MOE_EINVAL;
+    a.tb = moe::SchedTables{pl->host_mask_d, pl->slot_of_d, pl->single_rid_d, pl->multi_mask_d, pl->single_mask_d};
+    a.n_inst = pl->n_inst; a.C = pl->C; a.n_words = pl->n_words; a.g_self = g_self;
+    a.rid = rid_dev; a.act_rep = act_rep_dev; a.load = load_dev;
+    a.slot_count = slot_count_dev; a.slot_off = slot_off_dev; a.perm = perm_dev; a.pos = pos_dev; a.blocks = blocks_dev;
+    a.block_rows = moe::ffn_block_rows(T);
+    a.tail = 1;
+    return MOE_OK;
 }
 
 }  // namespace
@@ -256,39 +419,65 @@ extern "C" int moe_route_schedule_permute(const moe_placement_t *pl, int g_self,
                                           int32_t *rid_dev, int32_t *act_rep_dev, int32_t *load_dev,
                                           int32_t *slot_count_dev, int32_t *slot_off_dev, int32_t *perm_dev,
                                           int32_t *pos_dev, int32_t *blocks_dev, int32_t *sync_dev, void *stream) {
-    if (!pl || !cfg || T < 0 || k < 1) return MOE_EINVAL;
+    if (!pl) return MOE_EINVAL;
     const int E = pl->E;
-    if (k > E) return MOE_EINVAL;
-    if (k > MOE_MAX_TOPK) return MOE_ESHAPE;
-    if (static_cast<long long>(T) * k > 0x7fffffffLL) return MOE_ESHAPE;
-    if (g_self < 0 || g_self >= pl->n_inst) return MOE_EINVAL;
-    if (cfg->mode != MOE_ROUTE_SOFTMAX && cfg->mode != MOE_ROUTE_SIGMOID_GROUP) return MOE_EINVAL;
-    if (cfg->mode == MOE_ROUTE_SIGMOID_GROUP) {
-        if (cfg->n_group < 1 || cfg->topk_group < 1 || cfg->topk_group > cfg->n_group) return MOE_EINVAL;
-        if (cfg->n_group > 64 || E % cfg->n_group != 0 || E / cfg->n_group < 2) return MOE_ESHAPE;
-        if (k > cfg->topk_group * (E / cfg->n_group)) return MOE_EINVAL;
-    }
-    if (!act_rep_dev || !load_dev || !slot_count_dev || !slot_off_dev || !blocks_dev || !sync_dev) return MOE_EINVAL;
-    if (T > 0 && (!logits_dev || !topk_ids_dev || !topk_w_dev || !rid_dev || !perm_dev || !pos_dev)) return MOE_EINVAL;
-    const void *ptrs[] = {logits_dev, topk_ids_dev, topk_w_dev, rid_dev, act_rep_dev, load_dev,
-                          slot_count_dev, slot_off_dev, perm_dev, pos_dev, sync_dev};
-    for (const void *p : ptrs)
-        if (!moe::aligned(p, 4)) return MOE_EINVAL;
-    if (!moe::aligned(blocks_dev, 16)) return MOE_EINVAL;
-    FrontArgs a;
+    if (const int rc = check_selection(T, E, k, cfg)) return rc;
+    if (!sync_dev || !moe::aligned(sync_dev, 4)) return MOE_EINVAL;
+    if (T > 0 && (!logits_dev || !topk_ids_dev || !topk_w_dev)) return MOE_EINVAL;
+    if (!moe::aligned(logits_dev, 4) || !moe::aligned(topk_ids_dev, 4) || !moe::aligned(topk_w_dev, 4)) return MOE_EINVAL;
+    FrontArgs a{};
+    if (const int rc = fill_tail(a, pl, g_self, T, rid_dev, act_rep_dev, load_dev, slot_count_dev, slot_off_dev,
+                                 perm_dev, pos_dev, blocks_dev))
+        return rc;
     a.logits = logits_dev; a.T = T; a.E = E; a.k = k; a.cfg = *cfg;
     a.ids = topk_ids_dev; a.w = topk_w_dev;
-    a.tb = moe::SchedTables{pl->host_mask_d, pl->slot_of_d, pl->single_rid_d, pl->multi_mask_d, pl->single_mask_d};
-    a.n_inst = pl->n_inst; a.C = pl->C; a.n_words = pl->n_words; a.g_self = g_self;
-    a.rid = rid_dev; a.act_rep = act_rep_dev; a.load = load_dev;
-    a.slot_count = slot_count_dev; a.slot_off = slot_off_dev; a.perm = perm_dev; a.pos = pos_dev; a.blocks = blocks_dev;
     a.ticket = sync_dev;
-    a.block_rows = moe::ffn_block_rows(T);
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    const int vpl = (E + MOE_WAVE - 1) / MOE_WAVE;
-    if (vpl <= 1) return launch_front<1>(a, st);
-    if (vpl <= 2) return launch_front<2>(a, st);
-    if (vpl <= 4) return launch_front<4>(a, st);
-    if (vpl <= 8) return launch_front<8>(a, st);
-    return launch_front<16>(a, st);
+    return launch_front_for<false>(a, "moe_route_schedule_permute", static_cast<hipStream_t>(stream));
+}
+
+extern "C" size_t moe_gate_sync_len(int T) { return T > 0 ? 1 + (static_cast<size_t>(T) + 15) / 16 : 1; }
+
+extern "C" int moe_gate_route(const void *X_dev, const void *Wr_dev, const float *bias_dev, int T, int E, int d_h, int k,
+                              const moe_route_cfg *cfg, float *logits_dev, int32_t *topk_ids_dev, float *topk_w_dev,
+                              int32_t *sync_dev, void *stream) {
+    if (const int rc = check_selection(T, E, k, cfg)) return rc;
+    if (const int rc = check_gate(X_dev, Wr_dev, bias_dev, logits_dev, T, E, d_h)) return rc;
+    if (!sync_dev || !moe::aligned(sync_dev, 4)) return MOE_EINVAL;
+    if (T == 0) return MOE_OK;
+    if (!topk_ids_dev || !topk_w_dev || !moe::aligned(topk_ids_dev, 4) || !moe::aligned(topk_w_dev, 4)) return MOE_EINVAL;
+    FrontArgs a{};
+    a.T = T; a.E = E; a.k = k; a.cfg = *cfg;
+    a.ids = topk_ids_dev; a.w = topk_w_dev;
+    a.ticket = sync_dev;
+    a.X = static_cast<const uint16_t *>(X_dev); a.Wr = static_cast<const uint16_t *>(Wr_dev); a.bias = bias_dev;
+    a.logits_out = logits_dev; a.d_h = d_h; a.n_tiles = (E + 15) / 16;
+    a.n_inst = 1;
+    a.tail = 0;
+    return launch_front_for<true>(a, "moe_gate_route", static_cast<hipStream_t>(stream));
+}
+
+extern "C" int moe_gate_route_schedule_permute(const moe_placement_t *pl, int g_self, const void *X_dev,
+                                               const void *Wr_dev, const float *bias_dev, int T, int d_h, int k,
+                                               const moe_route_cfg *cfg, float *logits_dev, int32_t *topk_ids_dev,
+                                               float *topk_w_dev, int32_t *rid_dev, int32_t *act_rep_dev,
+                                               int32_t *load_dev, int32_t *slot_count_dev, int32_t *slot_off_dev,
+                                               int32_t *perm_dev, int32_t *pos_dev, int32_t *blocks_dev,
+                                               int32_t *sync_dev, void *stream) {
+    if (!pl) return MOE_EINVAL;
+    const int E = pl->E;
+    if (const int rc = check_selection(T, E, k, cfg)) return rc;
+    if (const int rc = check_gate(X_dev, Wr_dev, bias_dev, logits_dev, T, E, d_h)) return rc;
+    if (!sync_dev || !moe::aligned(sync_dev, 4)) return MOE_EINVAL;
+    if (T > 0 && (!topk_ids_dev || !topk_w_dev)) return MOE_EINVAL;
+    if (!moe::aligned(topk_ids_dev, 4) || !moe::aligned(topk_w_dev, 4)) return MOE_EINVAL;
+    FrontArgs a{};
+    if (const int rc = fill_tail(a, pl, g_self, T, rid_dev, act_rep_dev, load_dev, slot_count_dev, slot_off_dev,
+                                 perm_dev, pos_dev, blocks_dev))
+        return rc;
+    a.T = T; a.E = E; a.k = k; a.cfg = *cfg;
+    a.ids = topk_ids_dev; a.w = topk_w_dev;
+    a.ticket = sync_dev;
+    a.X = static_cast<const uint16_t *>(X_dev); a.Wr = static_cast<const uint16_t *>(Wr_dev); a.bias = bias_dev;
+    a.logits_out = logits_dev; a.d_h = d_h; a.n_tiles = (E + 15) / 16;
+    return launch_front_for<true>(a, "moe_gate_route_schedule_permute", static_cast<hipStream_t>(stream));
 }

@@ -44,6 +44,8 @@ class LayerStep:
         self.workspace = torch.empty((ws,), dtype=torch.uint8, device=device)
         B.moe_workspace_init(self.workspace)
         self.sync = torch.zeros((64,), **i32)
+        self.gate_sync = torch.zeros((B.moe_gate_sync_len(T),), **i32)
+        self.gate_logits = torch.empty((T, cfg.E), dtype=torch.float32, device=device)
         self.W13 = None
         self.W2 = None
 
@@ -87,6 +89,17 @@ class LayerStep:
                                      self.act_rep, self.load, self.slot_count, self.slot_off, self.perm, self.pos,
                                      self.blocks, self.sync, B.MOE_ROUTE_SIGMOID_GROUP if group else B.MOE_ROUTE_SOFTMAX, True,
                                      c.n_group if group else 1, c.topk_group if group else 1, 1.0, stream=stream)
+
+    def front_gate(self, X, Wr, bias=None, stream=None):
+        """gate (X * Wr^T + bias) + route + schedule + permute in one launch; returns the logits."""
+        c = self.cfg
+        group = c.route != "softmax"
+        B.moe_gate_route_schedule_permute(self.pl, self.g_self, X, Wr, bias, c.k, self.gate_logits, self.topk_ids,
+                                          self.topk_w, self.rid, self.act_rep, self.load, self.slot_count,
+                                          self.slot_off, self.perm, self.pos, self.blocks, self.gate_sync,
+                                          B.MOE_ROUTE_SIGMOID_GROUP if group else B.MOE_ROUTE_SOFTMAX, True,
+                                          c.n_group if group else 1, c.topk_group if group else 1, 1.0, stream=stream)
+        return self.gate_logits
 
     def ffn(self, X, stream=None, W13=None, W2=None):
         c = self.cfg

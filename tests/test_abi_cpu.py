@@ -66,6 +66,14 @@ def test_argument_validation_without_launch():
     assert L.moe_route(None, 4, 8, 2, ctypes.byref(g), None, None, None) == B.MOE_ESHAPE       # 8 % 3
     assert L.moe_schedule(None, None, 4, 2, None, None, None, None) == B.MOE_EINVAL
     assert L.moe_schedule_baseline(None, None, 4, 2, 0, None, None, None, None) == B.MOE_EINVAL
+    # gate: selection arguments, then the hidden size, then pointers; T == 0 launches nothing
+    assert L.moe_gate_sync_len(0) == 1 and L.moe_gate_sync_len(16) == 2 and L.moe_gate_sync_len(17) == 3
+    gate = lambda T, E, d_h, k: L.moe_gate_route(None, None, None, T, E, d_h, k, ctypes.byref(cfg), None, None, None,
+                                                 None, None)
+    assert gate(4, 8, 64, 9) == B.MOE_EINVAL
+    assert gate(4, 8, 48, 2) == B.MOE_ESHAPE
+    assert gate(4, 8, 64, 2) == B.MOE_EINVAL
+    assert L.moe_gate_route_schedule_permute(*([None, 0] + [None] * 3 + [4, 64, 2, ctypes.byref(cfg)] + [None] * 13)) == B.MOE_EINVAL
     assert L.moe_permute(None, 0, None, 4, 2, None, None, None, None, None, None) == B.MOE_EINVAL
     # FFN: shapes first, then pointers
     assert L.moe_grouped_ffn(None, None, None, 4, 2, 5, 100, 64, B.MOE_DTYPE_BF16, None, None, None, None, None, 0,

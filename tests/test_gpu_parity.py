@@ -354,3 +354,154 @@ def test_ffn_rejects_small_workspace():
         B.moe_grouped_ffn(step.Y, step.Y, step.Y, cfg.T, cfg.k, cfg.C, cfg.d_h, cfg.d_e, step.dtype,
                           step.slot_off, step.perm, step.blocks, step.Yp, step.workspace[:256])
     assert ei.value.code == B.MOE_EWORKSPACE
+
+
+# ----------------------------------------------------------------------------- gate + selection
+# The gate sums d_h fp32 products in an order of its own, so a logit differs from the oracle's
+# (fp64, rounded once) by up to ~sqrt(d_h) * 2^-24 * |terms| ~ 5e-6 at d_h = 7168; the test allows
+# GATE_ATOL.  A selection is compared bit for bit wherever the oracle's decision margin exceeds
+# GATE_MARGIN (both neighbours may move by GATE_ATOL each); closer calls must still be a valid
+# selection within that tolerance.
+GATE_ATOL = 2e-5
+GATE_MARGIN = 1e-4
+
+
+def as_bf16(cfg, **kw):
+    import dataclasses
+    return dataclasses.replace(cfg, dtype="bf16", **kw)
+
+
+def gate_oracle(cfg):
+    from oracle import gating
+    X = W.activations(cfg)
+    Wr, bias = W.router_weights(cfg)
+    z64 = gating.gate_logits(X, Wr, bias)
+    z32 = z64.astype(np.float32)
+    ids, w, info = oracle_route(cfg, z32)
+    if info is None:
+        sure = gating.selection_margin(z64, cfg.k) > GATE_MARGIN
+    else:
+        per = cfg.E // cfg.n_group
+        kept = np.zeros((cfg.T, cfg.n_group), dtype=bool)
+        np.put_along_axis(kept, info["kept_groups"], True, axis=1)
+        masked = np.where(np.repeat(kept, per, axis=1), z64, -1e30)
+        sure = (info["group_margin"] > GATE_MARGIN) & (gating.selection_margin(masked, cfg.k) > GATE_MARGIN)
+    return X, Wr, bias, z64, ids, w, sure
+
+
+def route_kwargs(cfg):
+    if cfg.route == "softmax":
+        return dict(mode=B.MOE_ROUTE_SOFTMAX)
+    return dict(mode=B.MOE_ROUTE_SIGMOID_GROUP, n_group=cfg.n_group, topk_group=cfg.topk_group)
+
+
+def check_selection(cfg, z64, ids, w, sure, g_ids, g_w):
+    np.testing.assert_array_equal(g_ids[sure], ids[sure])
+    np.testing.assert_allclose(g_w[sure], w[sure], rtol=2e-4)
+    kth = -np.sort(-z64, axis=1)[:, cfg.k - 1]
+    for i in np.nonzero(~sure)[0]:
+        assert len(set(g_ids[i].tolist())) == cfg.k
+        if cfg.route == "softmax":
+            assert (z64[i, g_ids[i]] >= kth[i] - GATE_MARGIN).all()
+        else:
+            assert len(set((g_ids[i] // (cfg.E // cfg.n_group)).tolist())) <= cfg.topk_group
+    np.testing.assert_allclose(g_w.sum(axis=1), 1.0, rtol=1e-5)
+
+
+GATE_CFGS = [as_bf16(W.tiny()), W.dsv2lite(), W.qwen3(256), W.dsv3(512), W.stress(1024, 1.25, 0.8),
+             small("odd", E=70, k=5, T=3), small("ragged", E=40, d_h=160, T=37), small("k1", k=1, T=1),
+             small("e1024", E=1024, k=32, T=9, d_h=96, zipf_s=0.0)]
+
+
+@pytest.mark.parametrize("cfg", GATE_CFGS, ids=lambda c: f"{c.name}-T{c.T}")
+def test_gate_route_parity(cfg):
+    X, Wr, bias, z64, ids, w, sure = gate_oracle(cfg)
+    assert sure.mean() > 0.6
+    d_X, d_Wr = to_device_bf16(X), to_device_bf16(Wr)
+    d_bias = None if bias is None else torch.from_numpy(bias).cuda()
+    sync = torch.zeros(B.moe_gate_sync_len(cfg.T), dtype=torch.int32, device="cuda")
+    for rep in range(2):                                   # the second call finds the tickets cleared
+        d_z = torch.full((cfg.T, cfg.E), float("nan"), dtype=torch.float32, device="cuda")
+        d_ids = torch.full((cfg.T, cfg.k), -7, dtype=torch.int32, device="cuda")
+        d_w = torch.zeros((cfg.T, cfg.k), dtype=torch.float32, device="cuda")
+        B.moe_gate_route(d_X, d_Wr, d_bias, cfg.k, d_z, d_ids, d_w, sync, **route_kwargs(cfg))
+        torch.cuda.synchronize()
+        np.testing.assert_allclose(d_z.cpu().numpy(), z64, rtol=0, atol=GATE_ATOL)
+        check_selection(cfg, z64, ids, w, sure, d_ids.cpu().numpy(), d_w.cpu().numpy())
+        assert int(sync.abs().sum().item()) == 0
+
+
+def all_sure_variant(cfg):
+    """First seed from cfg.seed on for which every token's selection is decided by more than the
+    margin (found with the oracle alone), so that every integer result downstream is unique."""
+    for seed in range(cfg.seed, cfg.seed + 200):
+        c = as_bf16(cfg, seed=seed)
+        out = gate_oracle(c)
+        if out[-1].all():
+            return c, out
+    raise AssertionError("no seed with clear margins")
+
+
+FRONT_GATE_CFGS = [as_bf16(W.tiny()), W.dsv2lite(64), W.qwen3(32), W.dsv3(16), small("ragged", E=40, d_h=160, k=5, T=77, n_inst=4, C=12),
+                   small("k1", k=1, T=1)]
+
+
+@pytest.mark.parametrize("cfg", FRONT_GATE_CFGS, ids=lambda c: f"{c.name}-T{c.T}")
+def test_gate_front_parity(cfg):
+    """X, W_r -> everything a0-a4 produce, in one launch, against the oracle chain."""
+    cfg, (X, Wr, bias, z64, ids, w, sure) = all_sure_variant(cfg)
+    lay = W.build_placement(cfg)
+    pl = scheduling.make_placement(lay, cfg.E, cfg.n_inst, cfg.C)
+    O, act_rep, load = scheduling.aebs(ids, pl)
+    g_self = int(np.argmax(load))
+    slot_count, slot_off, perm = dispatch.permute(O, g_self, cfg.C)
+    pos = np.full(cfg.T * cfg.k, -1, dtype=np.int32)
+    pos[perm] = np.arange(len(perm), dtype=np.int32)
+    s = LayerStep(cfg, lay, g_self)
+    d_X, d_Wr = to_device_bf16(X), to_device_bf16(Wr)
+    d_bias = None if bias is None else torch.from_numpy(bias).cuda()
+    for rep in range(2):
+        for t in (s.topk_ids, s.rid, s.act_rep, s.load, s.slot_count, s.slot_off, s.perm, s.pos, s.blocks):
+            t.fill_(-5)
+        d_z = s.front_gate(d_X, d_Wr, d_bias)
+        torch.cuda.synchronize()
+        np.testing.assert_allclose(d_z.cpu().numpy(), z64, rtol=0, atol=GATE_ATOL)
+        np.testing.assert_array_equal(s.topk_ids.cpu().numpy(), ids)
+        np.testing.assert_allclose(s.topk_w.cpu().numpy(), w, rtol=2e-4)
+        np.testing.assert_array_equal(s.rid.cpu().numpy().reshape(cfg.T, cfg.k), O)
+        np.testing.assert_array_equal(s.act_rep.cpu().numpy(), act_rep)
+        np.testing.assert_array_equal(s.load.cpu().numpy(), load)
+        np.testing.assert_array_equal(s.slot_count.cpu().numpy(), slot_count)
+        np.testing.assert_array_equal(s.slot_off.cpu().numpy(), slot_off)
+        np.testing.assert_array_equal(s.perm.cpu().numpy()[:len(perm)], perm)
+        np.testing.assert_array_equal(s.pos.cpu().numpy(), pos)
+        exp = expected_blocks(slot_off, B.moe_block_rows(cfg.T))
+        np.testing.assert_array_equal(s.blocks.cpu().numpy()[:len(exp)], exp)
+        assert int(s.gate_sync.abs().sum().item()) == 0
+
+
+@pytest.mark.parametrize("cfg", [W.dsv2lite(), W.qwen3(1024), W.dsv3(512), W.stress(8192, 1.25, 0.8)],
+                         ids=lambda c: f"{c.name}-T{c.T}")
+def test_gate_front_full_size_is_consistent(cfg):
+    """At full size some selections are closer than the gate's rounding, so the chain is checked
+    in two halves: logits and selection against the oracle (margin-aware), and Alg. 1 + dispatch
+    bit for bit against the separately verified entry points run on the ids the launch chose."""
+    X, Wr, bias, z64, ids, w, sure = gate_oracle(cfg)
+    lay = W.build_placement(cfg)
+    a = LayerStep(cfg, lay, cfg.n_inst - 1)
+    b = LayerStep(cfg, lay, cfg.n_inst - 1)
+    d_X, d_Wr = to_device_bf16(X), to_device_bf16(Wr)
+    d_bias = None if bias is None else torch.from_numpy(bias).cuda()
+    d_z = b.front_gate(d_X, d_Wr, d_bias)
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(d_z.cpu().numpy(), z64, rtol=0, atol=GATE_ATOL)
+    check_selection(cfg, z64, ids, w, sure, b.topk_ids.cpu().numpy(), b.topk_w.cpu().numpy())
+    a.topk_ids.copy_(b.topk_ids)
+    a.schedule(); a.permute()
+    torch.cuda.synchronize()
+    n_local = int(a.slot_off[-1].item())
+    for name in ("rid", "act_rep", "load", "slot_count", "slot_off", "pos"):
+        assert torch.equal(getattr(a, name), getattr(b, name)), name
+    assert torch.equal(a.perm[:n_local], b.perm[:n_local])
+    n_blk = 4 * (1 + int(a.blocks[0].item()))
+    assert torch.equal(a.blocks[:n_blk], b.blocks[:n_blk])
