@@ -54,12 +54,13 @@ def main() -> None:
     ap.add_argument("--ring-bytes", type=float, default=1.25e9, help="minimum total bytes of rotating weight copies")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-events", action="store_true", help="do not record per-kernel events in the timed region")
-    ap.add_argument("--mode", default="step", choices=["step", "sched", "act_sweep", "skew", "batch_sweep", "amax"],
+    ap.add_argument("--mode", default="step", choices=["step", "sched", "act_sweep", "skew", "batch_sweep", "amax", "gate"],
                     help="step: the headline line (default); sched: scheduler us and a_max vs optimum over the "
                          "stress sweep; act_sweep: layer us vs number of activated experts; skew: same "
                          "activated set with an even and a Zipf split of the requests; batch_sweep: layer "
                          "us vs batch size with every slot activated; amax: Monte-Carlo a_max of AEBS and the "
-                         "baseline policies over sampled batches, against the exact optimum and Eq. 5")
+                         "baseline policies over sampled batches, against the exact optimum and Eq. 5; gate: the front "
+                         "launch with and without the router's linear layer in it")
     args = ap.parse_args()
     if args.gpus != 1:
         raise SystemExit("this build runs on ONE GPU: the other MoE instances exist only as replica placement "
@@ -82,6 +83,8 @@ def main() -> None:
         return split_sweeps(args)
     if args.mode == "amax":
         return amax_study(args)
+    if args.mode == "gate":
+        return gate_front(args)
     cfg = make_cfg(args.workload, args.tokens)
     lay = W.build_placement(cfg)
     T, k, C, d_h, d_e = cfg.T, cfg.k, cfg.C, cfg.d_h, cfg.d_e
@@ -321,6 +324,45 @@ def sched_sweep(args) -> None:
                 print(json.dumps({"mode": "sched", "T": T, "replication": r, "zipf_s": s, "sched_us": round(us, 2),
                                   "route_us": round(route_us, 2), "activated": len(act), "a_max_aebs": a_max,
                                   "a_max_optimum": opt, "a_max_home_only": home}), flush=True)
+
+
+def gate_front(args) -> None:
+    """The front of the step with the router's linear layer inside the launch (Sec. 3.3: the gate
+    runs on the MoE side): us per launch of logits -> a0-a4 (moe_route_schedule_permute), of
+    X, W_r -> selection (moe_gate_route) and of X, W_r -> a0-a4 (moe_gate_route_schedule_permute),
+    one JSON line per workload.  Inputs rotate over 8 batches."""
+    import torch
+    from paper_2512_13525_amd import binding as B
+    from paper_2512_13525_amd import workloads as W
+    from paper_2512_13525_amd.layer import LayerStep, to_device_bf16
+
+    for name in ("dsv2lite", "qwen3", "dsv3"):
+        cfg = make_cfg(name, args.tokens)
+        lay = W.build_placement(cfg)
+        s = LayerStep(cfg, lay, 0)
+        Wr, bias = W.router_weights(cfg)
+        d_Wr = to_device_bf16(Wr)
+        d_bias = None if bias is None else torch.from_numpy(bias).cuda()
+        Xs = [to_device_bf16(W.activations(cfg, sub=i)) for i in range(8)]
+        zs = [torch.from_numpy(W.router_logits(cfg, sub=i)).cuda() for i in range(8)]
+        group = cfg.route != "softmax"
+        kw = dict(mode=B.MOE_ROUTE_SIGMOID_GROUP, n_group=cfg.n_group, topk_group=cfg.topk_group) if group else {}
+        it = [0]
+
+        def nxt(xs):
+            it[0] += 1
+            return xs[it[0] % len(xs)]
+
+        front = _time_us(lambda: s.front(nxt(zs)), 400)
+        gate_only = _time_us(lambda: B.moe_gate_route(nxt(Xs), d_Wr, d_bias, cfg.k, s.gate_logits, s.topk_ids,
+                                                      s.topk_w, s.gate_sync, **kw), 400)
+        gate_front_us = _time_us(lambda: s.front_gate(nxt(Xs), d_Wr, d_bias), 400)
+        flops = 2.0 * cfg.T * cfg.E * cfg.d_h
+        gate_bytes = (cfg.T + cfg.E) * cfg.d_h * 2 + cfg.T * cfg.E * 4
+        print(json.dumps({"mode": "gate", "workload": cfg.name, "T": cfg.T, "E": cfg.E, "d_h": cfg.d_h,
+                          "front_from_logits_us": round(front, 2), "gate_route_us": round(gate_only, 2),
+                          "front_from_activations_us": round(gate_front_us, 2),
+                          "gate_gflop": round(flops / 1e9, 3), "gate_operand_MB": round(gate_bytes / 1e6, 2)}), flush=True)
 
 
 def act_sweep(args) -> None:

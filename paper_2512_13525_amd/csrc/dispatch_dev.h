@@ -59,10 +59,11 @@ __device__ __forceinline__ float sigmoid_f32(float x) { return 1.0f / (1.0f + ex
 // comparison.  With one key per lane (E <= 64) the top-k are the keys that fewer than k other keys
 // exceed (rank counting with scalar lane broadcasts, no shuffles); with more keys per lane the k
 // selections are k maxima, each found with a 6-step cross-lane butterfly.
-// row_lds: VPL*64 floats private to this wavefront.  COHERENT: results are written with agent-scope
+// row_lds: VPL*64 floats private to this wavefront.  ROW_IN_LDS: `row` already is that LDS copy (the
+// caller passes the same address twice and has ordered its writes).  COHERENT: results are written with agent-scope
 // stores (read by another workgroup of the same launch).
-template <int VPL, bool COHERENT>
-__device__ __forceinline__ void route_token(const float *__restrict__ row, int E, int k, const moe_route_cfg &cfg,
+template <int VPL, bool COHERENT, bool ROW_IN_LDS = false>
+__device__ __forceinline__ void route_token(const float *row, int E, int k, const moe_route_cfg &cfg,
                                             float *row_lds, int lane, int32_t *ids_out, float *w_out) {
     float v[VPL];
     uint64_t key[VPL];
@@ -78,7 +79,8 @@ __device__ __forceinline__ void route_token(const float *__restrict__ row, int E
         // group score = sum of the two largest sigmoid scores of the group, in fp32
         const int per = E / cfg.n_group;
 #pragma unroll
-        for (int i = 0; i < VPL; ++i) row_lds[lane + i * MOE_WAVE] = v[i];
+        for (int i = 0; i < VPL; ++i)
+            if (!ROW_IN_LDS) row_lds[lane + i * MOE_WAVE] = v[i];
         // the row is private to this wave: a wavefront-scope fence orders its LDS writes
         // before the reads below (no block barrier: waves may be on different tokens)
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");

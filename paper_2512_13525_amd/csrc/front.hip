@@ -13,8 +13,6 @@
 // wavefronts split the hidden dimension, each accumulates one 16x16 MFMA tile over its share,
 // and the partial tiles are summed in LDS in wavefront order.  The workgroup that completes a
 // token group (a ticket per group) routes its 16 tokens from the logits the others published.
-#include <type_traits>
-
 #include "dispatch_dev.h"
 
 namespace {
@@ -38,6 +36,8 @@ struct FrontArgs {
     int tail;                            // 0: stop after the gating selection
 };
 
+constexpr int kGateUnroll = 4;
+constexpr int kGateDepth = 4;
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
@@ -45,7 +45,11 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 // router rows are the A operand (lane l: expert l%16, 8 columns at (l/16)*8 of the K-step), the
 // token rows the B operand (same shape), and the D tile leaves lane l with experts (l/16)*4..+3
 // of token l%16.  Rows past T or E repeat the last valid row and are not stored.
-__device__ __forceinline__ void gate_tile(const FrontArgs &a, int tg, int j, f32x4 *part, int wave, int lane) {
+//
+// This wavefront's share of the sum, operands read straight into the MFMA layout: every lane
+// requests its own 16 bytes of its own row, four requests per 64 bytes.  Used when the hidden
+// size is not a multiple of 64.
+__device__ __forceinline__ f32x4 gate_acc_steps(const FrontArgs &a, int tg, int j, int wave, int lane) {
     const int KS = a.d_h / 32;
     const int per = (KS + moe::kFrontWaves - 1) / moe::kFrontWaves;
     const int k0 = wave * per;
@@ -57,22 +61,103 @@ __device__ __forceinline__ void gate_tile(const FrontArgs &a, int tg, int j, f32
     const char *xb = reinterpret_cast<const char *>(a.X) + (static_cast<size_t>(tok) * a.d_h + (lane >> 4) * 8) * 2;
     const char *wb = reinterpret_cast<const char *>(a.Wr) + (static_cast<size_t>(e) * a.d_h + (lane >> 4) * 8) * 2;
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-    int kk = k0;
-    for (; kk + 4 <= k1; kk += 4) {
-        bf16x8 av[4], bv[4];
+    // kGateUnroll K-steps of both operands in flight; steps past the share load the last valid step
+    // again and multiply by zero, so the loop has no tail
+    const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
+    for (int kk = k0; kk < k1; kk += kGateUnroll) {
+        bf16x8 av[kGateUnroll], bv[kGateUnroll];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            av[u] = *reinterpret_cast<const bf16x8 *>(wb + (kk + u) * 64);
-            bv[u] = *reinterpret_cast<const bf16x8 *>(xb + (kk + u) * 64);
+        for (int u = 0; u < kGateUnroll; ++u) {
+            const int q = kk + u < k1 ? kk + u : k1 - 1;
+            av[u] = *reinterpret_cast<const bf16x8 *>(wb + q * 64);
+            bv[u] = *reinterpret_cast<const bf16x8 *>(xb + q * 64);
         }
 #pragma unroll
-        for (int u = 0; u < 4; ++u) acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[u], bv[u], acc, 0, 0, 0);
+        for (int u = 0; u < kGateUnroll; ++u)
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[u], kk + u < k1 ? bv[u] : zero, acc, 0, 0, 0);
     }
-    for (; kk < k1; ++kk) {
-        const bf16x8 av = *reinterpret_cast<const bf16x8 *>(wb + kk * 64);
-        const bf16x8 bv = *reinterpret_cast<const bf16x8 *>(xb + kk * 64);
-        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, bv, acc, 0, 0, 0);
+    return acc;
+}
+
+// The same share with whole-line reads (hidden size a multiple of 64): a super-step is 64 columns =
+// one 128-byte line of each of the 16 + 16 rows; a load instruction fetches 8 whole lines (lane l:
+// row l/8, 16-byte chunk l%8), a quarter of the requests of the direct form, and the MFMA layout
+// comes from a round trip through a wave-private 4 KiB LDS tile (chunks XOR-swizzled by row so
+// that the row-major writes and the column-wise reads both spread over the banks).  Wavefront w
+// takes super-steps w, w+16, ...; kGateDepth of them are in flight.
+__device__ __forceinline__ f32x4 gate_acc_lines(const FrontArgs &a, int tg, int j, char *stage, int wave, int lane) {
+    const int SS = a.d_h / 64;
+    const int n = (SS - wave + moe::kFrontWaves - 1) / moe::kFrontWaves;
+    char *st = stage + wave * 4096;                                  // [router rows | token rows][16 rows][128 bytes]
+    const char *wp[2], *xp[2];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        int e = j * 16 + h * 8 + (lane >> 3);
+        e = e < a.E ? e : a.E - 1;
+        int t = tg * 16 + h * 8 + (lane >> 3);
+        t = t < a.T ? t : a.T - 1;
+        wp[h] = reinterpret_cast<const char *>(a.Wr) + static_cast<size_t>(e) * a.d_h * 2 + (lane & 7) * 16;
+        xp[h] = reinterpret_cast<const char *>(a.X) + static_cast<size_t>(t) * a.d_h * 2 + (lane & 7) * 16;
     }
+    // LDS: row R of an operand at R*128, its 16-byte chunk c at ((c ^ (R & 7)) * 16)
+    const uint32_t wr_lds = ((lane >> 3) * 128) + (((lane & 7) ^ (lane >> 3)) * 16);
+    const uint32_t rd_row = (lane & 15) * 128, rd_sw = lane & 7, rd_g = lane >> 4;
+    bf16x8 ld[kGateDepth][4];
+#define MOE_GATE_LOAD(d, i)                                                                      \
+    do {                                                                                         \
+        const size_t off_ = static_cast<size_t>(wave + moe::kFrontWaves * (i)) * 128;            \
+        ld[d][0] = *reinterpret_cast<const bf16x8 *>(wp[0] + off_);                              \
+        ld[d][1] = *reinterpret_cast<const bf16x8 *>(wp[1] + off_);                              \
+        ld[d][2] = *reinterpret_cast<const bf16x8 *>(xp[0] + off_);                              \
+        ld[d][3] = *reinterpret_cast<const bf16x8 *>(xp[1] + off_);                              \
+    } while (0)
+#pragma unroll
+    for (int d = 0; d < kGateDepth; ++d)
+        if (d < n) MOE_GATE_LOAD(d, d);
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    for (int i = 0; i < n; i += kGateDepth) {
+#pragma unroll
+        for (int d = 0; d < kGateDepth; ++d) {
+            if (i + d < n) {                                         // wave-uniform
+#pragma unroll
+                for (int q = 0; q < 4; ++q) *reinterpret_cast<bf16x8 *>(st + q * 1024 + wr_lds) = ld[d][q];
+                asm volatile("" ::: "memory");
+                if (i + d + kGateDepth < n) MOE_GATE_LOAD(d, i + d + kGateDepth);
+#pragma unroll
+                for (int ss = 0; ss < 2; ++ss) {
+                    const uint32_t o = rd_row + (((4 * ss + rd_g) ^ rd_sw) * 16);
+                    const bf16x8 av = *reinterpret_cast<const bf16x8 *>(st + o);
+                    const bf16x8 bv = *reinterpret_cast<const bf16x8 *>(st + 2048 + o);
+                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, bv, acc, 0, 0, 0);
+                }
+                asm volatile("" ::: "memory");
+            }
+        }
+    }
+#undef MOE_GATE_LOAD
+    return acc;
+}
+
+// lds: 64 KiB.  The partial tiles of the 16 wavefronts are summed in wavefront order.
+__device__ __forceinline__ void gate_tile(const FrontArgs &a, int tg, int j, char *lds, int wave, int lane) {
+    // the bias of this lane's four experts, fetched up front so that the stores at the end follow
+    // one another without a load (and its wait for the previous store) in between
+    float bias[4] = {0.f, 0.f, 0.f, 0.f};
+    if (a.bias && threadIdx.x < MOE_WAVE) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int ee = j * 16 + (lane >> 4) * 4 + i;
+            bias[i] = a.bias[ee < a.E ? ee : a.E - 1];
+        }
+    }
+    f32x4 acc;
+    if (a.d_h % 64 == 0) {
+        acc = gate_acc_lines(a, tg, j, lds, wave, lane);
+        __syncthreads();                                             // the staging tiles give way to the partial tiles
+    } else {
+        acc = gate_acc_steps(a, tg, j, wave, lane);
+    }
+    f32x4 *part = reinterpret_cast<f32x4 *>(lds);
     part[wave * MOE_WAVE + lane] = acc;
     __syncthreads();
     if (threadIdx.x < MOE_WAVE) {
@@ -84,7 +169,7 @@ __device__ __forceinline__ void gate_tile(const FrontArgs &a, int tg, int j, f32
         for (int i = 0; i < 4; ++i) {
             const int ee = j * 16 + (lane >> 4) * 4 + i;
             if (t < a.T && ee < a.E)
-                __hip_atomic_store(a.logits_out + static_cast<size_t>(t) * a.E + ee, s[i] + (a.bias ? a.bias[ee] : 0.0f),
+                __hip_atomic_store(a.logits_out + static_cast<size_t>(t) * a.E + ee, s[i] + bias[i],
                                    __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     }
@@ -270,14 +355,9 @@ void front_kernel(FrontArgs a) {
         moe::SchedShared sched;
         moe::PermShared perm;
         SmallShared small;
-    };
-    // gated variants: the partial tiles of the split-K sum, then the logits rows being routed
-    union GateShared {
-        f32x4 part[moe::kFrontWaves * MOE_WAVE];
-        float row[moe::kFrontWaves][VPL * MOE_WAVE];
+        char gate[moe::kFrontWaves * 4096];                           // gated variants: staging tiles, then partial tiles
     };
     __shared__ Shared sh;
-    __shared__ std::conditional_t<GATE, GateShared, int> gs;
     __shared__ int s_last;
 
     const int wave = threadIdx.x / MOE_WAVE;
@@ -290,8 +370,13 @@ void front_kernel(FrontArgs a) {
         if (a.tail && small) tp = prefetch_tables(a);
         expected = a.T > 0 ? (a.T + 15) / 16 : 1;
         if (a.T > 0) {
-            const int tg = blockIdx.x / a.n_tiles, j = blockIdx.x % a.n_tiles;
-            gate_tile(a, tg, j, gs.part, wave, lane);
+            // workgroups go to the 8 XCDs round-robin: all expert tiles of a token group run on one XCD,
+            // so each L2 reads an eighth of the activations (and the whole router matrix)
+            const int r = blockIdx.x / 8;
+            const int tg = blockIdx.x % 8 + 8 * (r / a.n_tiles), j = r % a.n_tiles;
+            if (tg * 16 >= a.T) return;
+            gate_tile(a, tg, j, sh.gate, wave, lane);
+            __syncthreads();                                          // the partial tiles give way to the logits rows
             // the group's ticket must not overtake the logits
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             __syncthreads();
@@ -305,7 +390,7 @@ void front_kernel(FrontArgs a) {
             if (!s_last) return;
             const int t = tg * 16 + wave;
             if (t < a.T) {
-                float *row = gs.row[wave];
+                float *row = sh.row[wave];
 #pragma unroll
                 for (int i = 0; i < VPL; ++i) {
                     const int e = lane + i * MOE_WAVE;
@@ -316,8 +401,8 @@ void front_kernel(FrontArgs a) {
                 __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
                 __builtin_amdgcn_wave_barrier();
                 __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-                moe::route_token<VPL, true>(row, a.E, a.k, a.cfg, sh.row[wave], lane,
-                                            a.ids + static_cast<size_t>(t) * a.k, a.w + static_cast<size_t>(t) * a.k);
+                moe::route_token<VPL, true, true>(row, a.E, a.k, a.cfg, row, lane,
+                                                  a.ids + static_cast<size_t>(t) * a.k, a.w + static_cast<size_t>(t) * a.k);
             }
         }
         if (!a.tail) return;
@@ -356,7 +441,7 @@ void front_kernel(FrontArgs a) {
 template <int VPL, bool GATE>
 int launch_front(const FrontArgs &a, const char *what, hipStream_t st) {
     int blocks = 1;
-    if (a.T > 0) blocks = GATE ? (a.T + 15) / 16 * a.n_tiles : (a.T + moe::kFrontWaves - 1) / moe::kFrontWaves;
+    if (a.T > 0) blocks = GATE ? (a.T + 127) / 128 * 8 * a.n_tiles : (a.T + moe::kFrontWaves - 1) / moe::kFrontWaves;
     hipLaunchKernelGGL((front_kernel<VPL, GATE>), dim3(blocks), dim3(moe::kFrontThreads), 0, st, a);
     return moe::check_launch(what);
 }
