@@ -183,6 +183,33 @@ int moe_route_schedule_permute(const moe_placement_t *pl, int g_self, const floa
                                int32_t *slot_count_dev, int32_t *slot_off_dev, int32_t *perm_dev,
                                int32_t *pos_dev, int32_t *blocks_dev, int32_t *sync_dev, void *stream);
 
+/* ------------------------------------------------------------------ replica management (host)
+ * Appendix B ("Activation-Aware Replica Placement").  Host-only, sequential, no GPU work: they
+ * run when the layout is rebuilt, and their result goes to moe_placement_create.  All pointers
+ * are HOST pointers.
+ *
+ * moe_coactivation_counts: window statistics from a trace of batches.  ids_host
+ *   [n_batches][batch_pairs] int32 expert ids (the T*k selections of each batch);
+ *   c_host_out [E] double = number of batches that activate e; a_host_out [E*E] double,
+ *   symmetric, zero diagonal = number of batches that activate both.  MOE_EINVAL on an id
+ *   outside [0, E).
+ * moe_replica_counts: one replica per expert, then each of the n_inst*C - E spare slots goes to
+ *   the expert with the largest c(e)/R(e) that has fewer than n_inst replicas (lower id on
+ *   ties).  R_host_out [E] int32.  MOE_EPLACEMENT if n_inst*C < E.
+ * moe_place_replicas: Alg. 3.  Replicas in decreasing order of c(e)/R(e) (then expert id); each
+ *   goes to the instance with room that does not host its expert and adds the smallest
+ *   sum of a(e, e') over the experts already there (lowest instance on ties); if no such
+ *   instance exists, the cheapest swap (replica j of an instance g without e moves to an
+ *   instance h with room, e takes its slot) by change of summed co-activation load.
+ *   a_host [E*E] symmetric; slot_to_expert_host_out [n_inst*C] int32 in placement order, -1 =
+ *   empty.  MOE_EPLACEMENT if R(e) < 1, R(e) > n_inst, sum R > n_inst*C, or no swap exists.
+ */
+int moe_coactivation_counts(const int32_t *ids_host, int n_batches, int batch_pairs, int E,
+                            double *c_host_out, double *a_host_out);
+int moe_replica_counts(int E, int n_inst, int C, const double *c_host, int32_t *R_host_out);
+int moe_place_replicas(int E, int n_inst, int C, const int32_t *R_host, const double *c_host,
+                       const double *a_host, int32_t *slot_to_expert_host_out);
+
 /* ------------------------------------------------------------------ the gate in the same launch
  * Sec. 3.3 ("gating on the MoE side"): the MoE instance receives the complete activations and
  * runs the gate itself.  These two entry points start from the activations instead of from

@@ -26,6 +26,7 @@ EXPORTS = [
     "moe_placement_create", "moe_placement_destroy", "moe_placement_replicas", "moe_placement_dims",
     "moe_route", "moe_schedule", "moe_schedule_baseline", "moe_permute", "moe_block_rows", "moe_max_blocks", "moe_block_list_len",
     "moe_route_schedule_permute", "moe_gate_sync_len", "moe_gate_route", "moe_gate_route_schedule_permute",
+    "moe_coactivation_counts", "moe_replica_counts", "moe_place_replicas",
     "moe_pack_weights_bf16",
     "moe_workspace_bytes", "moe_workspace_init", "moe_workspace_status", "moe_grouped_ffn", "moe_combine",
     "moe_read_probe",
@@ -84,6 +85,12 @@ def lib() -> ctypes.CDLL:
     L.moe_block_list_len.argtypes = [ci, ci, ci]
     L.moe_route_schedule_permute.restype = ci
     L.moe_route_schedule_permute.argtypes = [vp, ci, vp, ci, ci, ctypes.POINTER(moe_route_cfg)] + [vp] * 12
+    L.moe_coactivation_counts.restype = ci
+    L.moe_coactivation_counts.argtypes = [vp, ci, ci, ci, vp, vp]
+    L.moe_replica_counts.restype = ci
+    L.moe_replica_counts.argtypes = [ci, ci, ci, vp, vp]
+    L.moe_place_replicas.restype = ci
+    L.moe_place_replicas.argtypes = [ci, ci, ci, vp, vp, vp, vp]
     L.moe_gate_sync_len.restype = cs
     L.moe_gate_sync_len.argtypes = [ci]
     L.moe_gate_route.restype = ci
@@ -207,6 +214,40 @@ def moe_route_schedule_permute(pl: Placement, g_self: int, logits, k: int, topk_
                                             _ptr(topk_ids), _ptr(topk_w), _ptr(rid), _ptr(act_rep), _ptr(load),
                                             _ptr(slot_count), _ptr(slot_off), _ptr(perm), _ptr(pos), _ptr(blocks),
                                             _ptr(sync),                                             _stream(stream)), "moe_route_schedule_permute")
+
+
+def moe_coactivation_counts(ids, E: int):
+    """ids: host int array [n_batches, ...] -> (c [E], a [E,E]) float64 host arrays."""
+    import numpy as np
+    ids = np.ascontiguousarray(ids, dtype=np.int32)
+    nb = ids.shape[0]
+    pairs = int(ids.size // nb) if nb else 0
+    c = np.empty(E, dtype=np.float64)
+    a = np.empty((E, E), dtype=np.float64)
+    _check(lib().moe_coactivation_counts(ids.ctypes.data, nb, pairs, E, c.ctypes.data, a.ctypes.data),
+           "moe_coactivation_counts")
+    return c, a
+
+
+def moe_replica_counts(c, n_inst: int, C: int):
+    import numpy as np
+    c = np.ascontiguousarray(c, dtype=np.float64)
+    R = np.empty(len(c), dtype=np.int32)
+    _check(lib().moe_replica_counts(len(c), n_inst, C, c.ctypes.data, R.ctypes.data), "moe_replica_counts")
+    return R
+
+
+def moe_place_replicas(n_inst: int, C: int, R, c, a):
+    import numpy as np
+    R = np.ascontiguousarray(R, dtype=np.int32)
+    c = np.ascontiguousarray(c, dtype=np.float64)
+    a = np.ascontiguousarray(a, dtype=np.float64)
+    E = len(R)
+    assert a.shape == (E, E) and c.shape == (E,)
+    lay = np.empty(n_inst * C, dtype=np.int32)
+    _check(lib().moe_place_replicas(E, n_inst, C, R.ctypes.data, c.ctypes.data, a.ctypes.data, lay.ctypes.data),
+           "moe_place_replicas")
+    return lay
 
 
 def moe_gate_sync_len(T: int) -> int:

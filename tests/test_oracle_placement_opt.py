@@ -1,0 +1,198 @@
+"""Pins for the oracle's replica management (Appendix B: replica counts, Eq. 6, Alg. 3) and the
+same checks on the library's host implementation, which must agree with the oracle bit for bit
+(integer results; both sides add the same fp64 terms in the same order).  CPU only."""
+import ctypes
+import itertools
+import json
+import os
+
+import numpy as np
+import pytest
+
+from oracle import placement_opt as PO
+from paper_2512_13525_amd import binding as B
+from paper_2512_13525_amd import workloads as W
+
+GOLD = json.load(open(os.path.join(os.path.dirname(__file__), "golden", "placement_alg3_tiny.json")))
+
+
+def sym(E, pairs):
+    a = np.zeros((E, E))
+    for i, j, v in pairs:
+        a[i, j] = a[j, i] = v
+    return a
+
+
+def both_places(n, C, R, c, a):
+    o = PO.place_replicas(n, C, np.asarray(R), np.asarray(c, dtype=np.float64), a)
+    l = B.moe_place_replicas(n, C, np.asarray(R, dtype=np.int32), np.asarray(c, dtype=np.float64), a)
+    np.testing.assert_array_equal(l, o)
+    return o
+
+
+def test_replica_counts_hand_example_and_properties():
+    g = GOLD["counts_example"]
+    assert PO.replica_counts(g["c"], g["n_inst"], g["C"]).tolist() == g["R"]
+    assert B.moe_replica_counts(np.array(g["c"], dtype=np.float64), g["n_inst"], g["C"]).tolist() == g["R"]
+    rng = np.random.default_rng(3)
+    for _ in range(50):
+        E, n = int(rng.integers(2, 12)), int(rng.integers(1, 5))
+        C = int(-(-E // n) + rng.integers(0, 4))
+        c = rng.random(E) * 10
+        R = PO.replica_counts(c, n, C)
+        np.testing.assert_array_equal(B.moe_replica_counts(c, n, C), R)
+        assert (R >= 1).all() and (R <= n).all()
+        assert R.sum() == min(n * C, n * E)
+        # equalised per-replica load: nobody who received an extra replica had, before the
+        # grant, a smaller load per replica than anyone who could still receive one ends with
+        final = max([c[e] / R[e] for e in range(E) if R[e] < n], default=0.0)
+        for e in range(E):
+            if R[e] > 1:
+                assert c[e] / (R[e] - 1) >= final - 1e-12
+    with pytest.raises(ValueError):
+        PO.replica_counts([1.0, 2.0, 3.0], 1, 2)
+
+
+@pytest.mark.parametrize("name", ["feasible_example", "swap_example"])
+def test_alg3_hand_examples(name):
+    g = GOLD[name]
+    E = len(g["R"])
+    a = sym(E, g["a_pairs"])
+    lay = both_places(g["n_inst"], g["C"], g["R"], g["c"], a)
+    assert lay.tolist() == g["slot_to_expert"]
+    if "I" in g:
+        P = lay.reshape(g["n_inst"], g["C"])
+        assert [PO.coactivation_load([int(e) for e in P[q] if e >= 0], a) for q in range(g["n_inst"])] == g["I"]
+
+
+def test_coactivation_load_is_the_pair_sum_of_eq6():
+    rng = np.random.default_rng(4)
+    a = rng.random((7, 7)); a = a + a.T; np.fill_diagonal(a, 0)
+    members = [5, 0, 3, 6]
+    want = sum(a[x, y] for x, y in itertools.combinations(members, 2))
+    assert abs(PO.coactivation_load(members, a) - want) < 1e-12
+    # equivalently half the sum of the sub-matrix
+    assert abs(PO.coactivation_load(members, a) - a[np.ix_(members, members)].sum() / 2) < 1e-12
+
+
+def test_coactivation_counts_against_set_arithmetic():
+    rng = np.random.default_rng(5)
+    E, nb, Bt, k = 9, 40, 3, 2
+    ids = np.stack([W.uniform_topk_ids(E, k, Bt, rng) for _ in range(nb)])
+    c, a = PO.coactivation_counts(ids, E)
+    c2, a2 = B.moe_coactivation_counts(ids, E)
+    np.testing.assert_array_equal(c, c2)
+    np.testing.assert_array_equal(a, a2)
+    sets = [set(b.reshape(-1).tolist()) for b in ids]
+    for x in range(E):
+        assert c[x] == sum(x in s for s in sets)
+        assert a[x, x] == 0
+        for y in range(E):
+            if x != y:
+                assert a[x, y] == a[y, x] == sum((x in s) and (y in s) for s in sets)
+    # indicator-matrix form: M^T M has c on the diagonal and a off it
+    M = np.array([[x in s for x in range(E)] for s in sets], dtype=np.float64)
+    G = M.T @ M
+    np.testing.assert_array_equal(np.diag(G), c)
+    np.testing.assert_array_equal(G - np.diag(np.diag(G)), a)
+
+
+def random_instance(rng):
+    n = int(rng.integers(2, 5))
+    E = int(rng.integers(n, 10))
+    C = int(-(-E // n) + rng.integers(0, 3))
+    c = np.round(rng.random(E) * 9 + 1, 3)
+    if rng.random() < 0.5:
+        R = PO.replica_counts(c, n, C)
+    else:
+        # replica counts unrelated to the loads, layout exactly full: late replicas of widely
+        # replicated experts then find every instance with room already hosting them
+        R = rng.integers(1, n + 1, size=E)
+        while R.sum() % n:
+            R[int(rng.integers(E))] = 1 + (R[int(rng.integers(E))] % n)
+        C = int(R.sum() // n)
+    a = np.round(rng.random((E, E)) * 5, 2)
+    a = np.triu(a, 1); a = a + a.T
+    return n, C, E, R, c, a
+
+
+def test_alg3_invariants_and_step_replay():
+    """Every replica is placed, capacities and the one-replica-per-instance rule hold, and every
+    non-swap step put its replica on an instance whose penalty no other feasible instance beat
+    (replayed from the final layout's placement order)."""
+    rng = np.random.default_rng(6)
+    swaps = 0
+    for _ in range(200):
+        n, C, E, R, c, a = random_instance(rng)
+        try:
+            lay = PO.place_replicas(n, C, R, c, a)
+        except ValueError:
+            # no swap exists: the library must say so too
+            out = np.zeros(n * C, dtype=np.int32)
+            Ri = np.asarray(R, dtype=np.int32)
+            assert B.lib().moe_place_replicas(E, n, C, Ri.ctypes.data, c.ctypes.data, a.ctypes.data,
+                                              out.ctypes.data) == B.MOE_EPLACEMENT
+            continue
+        lay = both_places(n, C, R, c, a).reshape(n, C)
+        for e in range(E):
+            assert (lay == e).sum() == R[e]
+            assert ((lay == e).sum(axis=1) <= 1).all()
+        assert (lay >= 0).sum() == R.sum()
+        # replay: the order of the oracle's replica list, with an independent state
+        order = sorted([(e, r) for e in range(E) for r in range(int(R[e]))], key=lambda t: (-(c[t[0]] / R[t[0]]), t[0], t[1]))
+        P = [[] for _ in range(n)]
+        clean = True
+        for e, _ in order:
+            feas = [q for q in range(n) if len(P[q]) < C and e not in P[q]]
+            if not feas:
+                clean = False
+                swaps += 1
+                break
+            pen = {q: sum(a[e, m] for m in P[q]) for q in feas}
+            best = min(feas, key=lambda q: (pen[q], q))
+            P[best].append(e)
+        if clean:
+            assert [x for q in range(n) for x in P[q] + [-1] * (C - len(P[q]))] == lay.reshape(-1).tolist()
+    assert swaps > 0                      # the swap branch was exercised by the random instances
+
+
+def test_alg3_against_the_exact_min_max_on_tiny_instances():
+    """Alg. 3 is a heuristic for the min-max problem of Appendix B: on instances small enough to
+    enumerate, its objective is never below the optimum and stays within a factor of it."""
+    rng = np.random.default_rng(7)
+    ratios = []
+    for _ in range(40):
+        n, E = 2, int(rng.integers(3, 6))
+        C = int(-(-E // n) + rng.integers(0, 2))
+        c = np.round(rng.random(E) * 9 + 1, 3)
+        R = PO.replica_counts(c, n, C)
+        a = np.round(rng.random((E, E)) * 5, 2); a = np.triu(a, 1); a = a + a.T
+        lay = both_places(n, C, R, c, a).reshape(n, C)
+        got = max(PO.coactivation_load([int(e) for e in lay[q] if e >= 0], a) for q in range(n))
+        best = None
+        choices = [list(itertools.combinations(range(n), int(R[e]))) for e in range(E)]
+        for pick in itertools.product(*choices):
+            P = [[] for _ in range(n)]
+            for e, hosts in enumerate(pick):
+                for q in hosts:
+                    P[q].append(e)
+            if max(len(p) for p in P) > C:
+                continue
+            v = max(PO.coactivation_load(p, a) for p in P)
+            best = v if best is None or v < best else best
+        assert best is not None and got >= best - 1e-9
+        ratios.append(got / best if best > 0 else 1.0)
+    assert np.mean(ratios) < 1.5
+
+
+def test_library_rejects_bad_arguments():
+    L = B.lib()
+    assert L.moe_replica_counts(0, 2, 2, None, None) == B.MOE_EINVAL
+    c = np.ones(5)
+    R = np.zeros(5, dtype=np.int32)
+    assert L.moe_replica_counts(5, 2, 2, c.ctypes.data, R.ctypes.data) == B.MOE_EPLACEMENT   # 4 slots, 5 experts
+    a = np.zeros((2, 2))
+    out = np.zeros(4, dtype=np.int32)
+    bad = np.array([3, 1], dtype=np.int32)                                                   # 3 replicas, 2 instances
+    assert L.moe_place_replicas(2, 2, 2, bad.ctypes.data, c.ctypes.data, a.ctypes.data, out.ctypes.data) == B.MOE_EPLACEMENT
+    assert L.moe_place_replicas(2, 2, 2, None, None, None, None) == B.MOE_EINVAL
