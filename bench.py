@@ -54,13 +54,14 @@ def main() -> None:
     ap.add_argument("--ring-bytes", type=float, default=1.25e9, help="minimum total bytes of rotating weight copies")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-events", action="store_true", help="do not record per-kernel events in the timed region")
-    ap.add_argument("--mode", default="step", choices=["step", "sched", "act_sweep", "skew", "batch_sweep", "amax", "gate"],
+    ap.add_argument("--mode", default="step", choices=["step", "sched", "act_sweep", "skew", "batch_sweep", "amax", "gate", "placement"],
                     help="step: the headline line (default); sched: scheduler us and a_max vs optimum over the "
                          "stress sweep; act_sweep: layer us vs number of activated experts; skew: same "
                          "activated set with an even and a Zipf split of the requests; batch_sweep: layer "
                          "us vs batch size with every slot activated; amax: Monte-Carlo a_max of AEBS and the "
                          "baseline policies over sampled batches, against the exact optimum and Eq. 5; gate: the front "
-                         "launch with and without the router's linear layer in it")
+                         "launch with and without the router's linear layer in it; placement: a_max of AEBS over the "
+                         "layout of Alg. 3 (Appendix B) against the contiguous layout on traces with topics")
     args = ap.parse_args()
     if args.gpus != 1:
         raise SystemExit("this build runs on ONE GPU: the other MoE instances exist only as replica placement "
@@ -85,6 +86,8 @@ def main() -> None:
         return amax_study(args)
     if args.mode == "gate":
         return gate_front(args)
+    if args.mode == "placement":
+        return placement_study(args)
     cfg = make_cfg(args.workload, args.tokens)
     lay = W.build_placement(cfg)
     T, k, C, d_h, d_e = cfg.T, cfg.k, cfg.C, cfg.d_h, cfg.d_e
@@ -536,6 +539,67 @@ def amax_study(args) -> None:
                               "a_max_aebs_mean_first16": round(float(amax[0][:n_opt].mean()), 2),
                               "eq4_expected_max": round(a_bar, 2), "eq5_bound": bounds.a_max_bound(a_bar, C, n_inst)}),
                   flush=True)
+
+
+def placement_study(args) -> None:
+    """Effect of the activation-aware layout (Appendix B: replica counts from window statistics,
+    Alg. 3 placement by co-activation) on what Alg. 1 achieves.  A synthetic trace with topics
+    (each batch prefers one cluster of experts) is routed on the GPU; the first half of the
+    batches is the statistics window (moe_coactivation_counts -> moe_replica_counts ->
+    moe_place_replicas, host), the second half is scheduled by moe_schedule over (i) the contiguous
+    layout of the other workloads and (ii) the Alg. 3 layout.  E = 256, k = 8, 16 instances x 20
+    slots, Zipf 0.8; one JSON line per (cluster shape, batch size)."""
+    import time
+    import numpy as np
+    import torch
+    from oracle import optimum, placement_opt, scheduling
+    from paper_2512_13525_amd import binding as B
+    from paper_2512_13525_amd import workloads as W
+
+    E, k, n_inst, C, n_topics, boost, n_batches, n_opt = 256, 8, 16, 20, 8, 2.0, 400, 16
+    cfg = W.MoEConfig("placement", E=E, k=k, d_h=64, d_e=64, T=1, n_inst=n_inst, C=C, zipf_s=0.8, seed=0)
+    gen = torch.Generator(device="cuda").manual_seed(11)
+    for contiguous in (True, False):
+        tb = torch.from_numpy(W.topic_bias(cfg, n_topics, boost, contiguous)).cuda()
+        for T in (16, 64, 256):
+            ids = torch.empty((n_batches, T, k), dtype=torch.int32, device="cuda")
+            wts = torch.empty((T, k), dtype=torch.float32, device="cuda")
+            topics = torch.randint(0, n_topics, (n_batches,), generator=gen, device="cuda")
+            for b in range(n_batches):
+                logits = torch.randn((T, E), generator=gen, device="cuda") + tb[topics[b]]
+                B.moe_route(logits, k, ids[b], wts)
+            torch.cuda.synchronize()
+            half = n_batches // 2
+            window = ids[:half].cpu().numpy()
+            t0 = time.perf_counter()
+            c, a = B.moe_coactivation_counts(window, E)
+            R = B.moe_replica_counts(c, n_inst, C)
+            t1 = time.perf_counter()
+            lay3 = B.moe_place_replicas(n_inst, C, R, c, a)
+            t2 = time.perf_counter()
+            layouts = {"contiguous": W.build_placement(cfg), "alg3": lay3}
+            out = {"mode": "placement", "clusters": "contiguous ids" if contiguous else "random subsets",
+                   "B": T, "window_batches": half, "eval_batches": n_batches - half,
+                   "stats_ms": round((t1 - t0) * 1e3, 2), "alg3_ms": round((t2 - t1) * 1e3, 2)}
+            rid = torch.empty((T, k), dtype=torch.int32, device="cuda")
+            rep = torch.empty((E,), dtype=torch.int32, device="cuda")
+            for name, lay in layouts.items():
+                pl = B.Placement(lay, E, n_inst, C)
+                loads = torch.zeros((n_batches - half, n_inst), dtype=torch.int32, device="cuda")
+                for b in range(half, n_batches):
+                    B.moe_schedule(pl, ids[b], T, k, rid, rep, loads[b - half])
+                torch.cuda.synchronize()
+                amax = loads.max(dim=1).values.cpu().numpy()
+                opl = scheduling.make_placement(lay, E, n_inst, C)
+                opt = [optimum.optimum_matching(sorted(set(ids[half + i].cpu().numpy().reshape(-1).tolist())), opl)
+                       for i in range(n_opt)]
+                P = np.asarray(lay).reshape(n_inst, C)
+                I = [placement_opt.coactivation_load([int(e) for e in P[g] if e >= 0], a) for g in range(n_inst)]
+                out[name] = {"a_max_aebs_mean": round(float(amax.mean()), 2), "a_max_aebs_max": int(amax.max()),
+                             "a_max_aebs_mean_first16": round(float(amax[:n_opt].mean()), 2),
+                             "a_max_optimum_mean_first16": round(float(np.mean(opt)), 2),
+                             "max_coactivation_load": round(max(I), 1)}
+            print(json.dumps(out), flush=True)
 
 
 if __name__ == "__main__":

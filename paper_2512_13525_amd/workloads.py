@@ -140,6 +140,22 @@ def router_weights(cfg: MoEConfig) -> Tuple[np.ndarray, Optional[np.ndarray]]:
     return np.ascontiguousarray(wr), bias
 
 
+def topic_bias(cfg: MoEConfig, n_topics: int, boost: float, contiguous: bool) -> np.ndarray:
+    """Per-topic logit bias [n_topics, E] of a synthetic trace with co-activation structure (a
+    stand-in for the request traces of Sec. 5: batches of one topic prefer one cluster of
+    experts).  Topic t boosts E/n_topics experts by `boost`: a contiguous id range, or a seeded
+    random subset.  Added to the Zipf bias of `router_logits`; float32."""
+    E = cfg.E
+    per = E // n_topics
+    order = np.arange(E) if contiguous else _rng(cfg, 6).permutation(E)
+    bias = np.zeros((n_topics, E), dtype=np.float32)
+    for t in range(n_topics):
+        bias[t, order[t * per:(t + 1) * per]] = boost
+    if cfg.zipf_s != 0.0:
+        bias += np.log(E * expert_popularity(cfg)).astype(np.float32)[None, :]
+    return bias
+
+
 def activations(cfg: MoEConfig, T: Optional[int] = None, sub: int = 0) -> np.ndarray:
     """N(0,1) activations, float32 [T,d_h]; bf16-representable when cfg.dtype == 'bf16'."""
     T = cfg.T if T is None else T

@@ -505,3 +505,35 @@ def test_gate_front_full_size_is_consistent(cfg):
     assert torch.equal(a.perm[:n_local], b.perm[:n_local])
     n_blk = 4 * (1 + int(a.blocks[0].item()))
     assert torch.equal(a.blocks[:n_blk], b.blocks[:n_blk])
+
+
+def test_schedule_over_the_alg3_layout():
+    """The layout that Appendix B's rules build from a window of routed batches is a valid
+    layout for the library, and Alg. 1 over it matches the oracle bit for bit."""
+    from oracle import placement_opt, routing
+    cfg = W.MoEConfig("alg3", E=64, k=6, d_h=64, d_e=64, T=48, n_inst=4, C=20, zipf_s=1.0, seed=3)
+    tb = W.topic_bias(cfg, 4, 2.0, True)
+    rng = np.random.default_rng(9)
+    window = []
+    for b in range(40):
+        z = rng.standard_normal((cfg.T, cfg.E)).astype(np.float32) + tb[b % 4]
+        window.append(routing.route_softmax(z, cfg.k)[0])
+    window = np.stack(window)
+    c, a = placement_opt.coactivation_counts(window, cfg.E)
+    R = placement_opt.replica_counts(c, cfg.n_inst, cfg.C)
+    lay = placement_opt.place_replicas(cfg.n_inst, cfg.C, R, c, a)
+    np.testing.assert_array_equal(B.moe_place_replicas(cfg.n_inst, cfg.C, R, c, a), lay)
+    opl = scheduling.make_placement(lay, cfg.E, cfg.n_inst, cfg.C)
+    pl = B.Placement(lay, cfg.E, cfg.n_inst, cfg.C)
+    rid = torch.empty((cfg.T, cfg.k), dtype=torch.int32, device="cuda")
+    rep = torch.empty((cfg.E,), dtype=torch.int32, device="cuda")
+    load = torch.empty((cfg.n_inst,), dtype=torch.int32, device="cuda")
+    for b in range(40, 48):
+        z = rng.standard_normal((cfg.T, cfg.E)).astype(np.float32) + tb[b % 4]
+        ids = routing.route_softmax(z, cfg.k)[0]
+        O, act_rep, ld = scheduling.aebs(ids, opl)
+        B.moe_schedule(pl, dev_i32(ids), cfg.T, cfg.k, rid, rep, load)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(rid.cpu().numpy(), O)
+        np.testing.assert_array_equal(rep.cpu().numpy(), act_rep)
+        np.testing.assert_array_equal(load.cpu().numpy(), ld)
