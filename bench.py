@@ -54,14 +54,15 @@ def main() -> None:
     ap.add_argument("--ring-bytes", type=float, default=1.25e9, help="minimum total bytes of rotating weight copies")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-events", action="store_true", help="do not record per-kernel events in the timed region")
-    ap.add_argument("--mode", default="step", choices=["step", "sched", "act_sweep", "skew", "batch_sweep", "amax", "gate", "placement"],
+    ap.add_argument("--mode", default="step", choices=["step", "sched", "act_sweep", "skew", "batch_sweep", "amax", "gate", "placement", "scaling"],
                     help="step: the headline line (default); sched: scheduler us and a_max vs optimum over the "
                          "stress sweep; act_sweep: layer us vs number of activated experts; skew: same "
                          "activated set with an even and a Zipf split of the requests; batch_sweep: layer "
                          "us vs batch size with every slot activated; amax: Monte-Carlo a_max of AEBS and the "
                          "baseline policies over sampled batches, against the exact optimum and Eq. 5; gate: the front "
                          "launch with and without the router's linear layer in it; placement: a_max of AEBS over the "
-                         "layout of Alg. 3 (Appendix B) against the contiguous layout on traces with topics")
+                         "layout of Alg. 3 (Appendix B) against the contiguous layout on traces with topics; scaling: "
+                         "Alg. 2 fed with the measured MoE-side coefficients and a_max table")
     args = ap.parse_args()
     if args.gpus != 1:
         raise SystemExit("this build runs on ONE GPU: the other MoE instances exist only as replica placement "
@@ -88,6 +89,8 @@ def main() -> None:
         return gate_front(args)
     if args.mode == "placement":
         return placement_study(args)
+    if args.mode == "scaling":
+        return scaling_study(args)
     cfg = make_cfg(args.workload, args.tokens)
     lay = W.build_placement(cfg)
     T, k, C, d_h, d_e = cfg.T, cfg.k, cfg.C, cfg.d_h, cfg.d_e
@@ -539,6 +542,81 @@ def amax_study(args) -> None:
                               "a_max_aebs_mean_first16": round(float(amax[0][:n_opt].mean()), 2),
                               "eq4_expected_max": round(a_bar, 2), "eq5_bound": bounds.a_max_bound(a_bar, C, n_inst)}),
                   flush=True)
+
+
+def scaling_study(args) -> None:
+    """Alg. 2 (Sec. 3.5) on this machine's measurements: the MoE-side coefficients of Eq. 1c
+    (beta, c_e) are fitted from layer times of the default workload's shape at 6 activation counts,
+    a_max(n_e, B) is the Monte-Carlo mean of Alg. 1 on the GPU over 100 sampled batches per cell;
+    the attention-side and communication coefficients have no counterpart in this build and are
+    stated stand-ins.  Times in microseconds, demand in requests per microsecond."""
+    import numpy as np
+    import torch
+    from paper_2512_13525_amd import binding as B
+    from paper_2512_13525_amd import workloads as W
+    from paper_2512_13525_amd.layer import LayerStep, to_device_bf16
+
+    base = make_cfg("dsv2lite", 64)
+    E, k, C, d_h, d_e, T = base.E, base.k, base.C, base.d_h, base.d_e, base.T
+    # ---- beta, c_e: permute + FFN + combine against the number of activated experts
+    step = LayerStep(base, W.build_placement(base), 0)
+    gen = torch.Generator(device="cuda").manual_seed(1)
+    n_ring = max(4, int(-(-args.ring_bytes // (C * 3 * d_h * d_e * 2))))
+    W13s = [(torch.randn((C, 2 * d_e, d_h), generator=gen, device="cuda") * 0.02).to(torch.bfloat16) for _ in range(n_ring)]
+    W2s = [(torch.randn((C, d_h, d_e), generator=gen, device="cuda") * 0.02).to(torch.bfloat16) for _ in range(n_ring)]
+    X = to_device_bf16(W.activations(base))
+    step.topk_w.fill_(1.0 / k)
+    pts = []
+    for a in (2, 5, 8, 11, 14, 17):
+        step.rid.copy_(torch.from_numpy((np.arange(T * k, dtype=np.int32) % a).reshape(T, k)))
+        i = [0]
+
+        def layer():
+            j = i[0] % n_ring
+            i[0] += 1
+            step.permute(); step.ffn(X, W13=W13s[j], W2=W2s[j]); step.combine()
+
+        pts.append((a, _time_us(layer, 100)))
+    beta, c_e = (float(v) for v in np.polyfit([p[0] for p in pts], [p[1] for p in pts], 1))
+    del W13s, W2s
+    # ---- a_max table over (n_e, B)
+    ne_values, B_values, n_batches = [4, 8, 16], [16, 64, 256, 1024], 100
+    table = np.zeros((len(ne_values), len(B_values)))
+    for r, n_inst in enumerate(ne_values):
+        cfg = W.MoEConfig(f"scale_ne{n_inst}", E=E, k=k, d_h=64, d_e=64, T=1, n_inst=n_inst, C=C, zipf_s=base.zipf_s, seed=0)
+        pl = B.Placement(W.build_placement(cfg), E, n_inst, C)
+        bias = torch.from_numpy(np.log(E * W.expert_popularity(cfg)).astype(np.float32)).cuda()
+        for c, Bt in enumerate(B_values):
+            ids = torch.empty((Bt, k), dtype=torch.int32, device="cuda")
+            wts = torch.empty((Bt, k), dtype=torch.float32, device="cuda")
+            rid = torch.empty((Bt, k), dtype=torch.int32, device="cuda")
+            rep = torch.empty((E,), dtype=torch.int32, device="cuda")
+            loads = torch.zeros((n_batches, n_inst), dtype=torch.int32, device="cuda")
+            for b in range(n_batches):
+                B.moe_route(torch.randn((Bt, E), generator=gen, device="cuda") + bias, k, ids, wts)
+                B.moe_schedule(pl, ids, Bt, k, rid, rep, loads[b])
+            torch.cuda.synchronize()
+            table[r, c] = float(loads.max(dim=1).values.float().mean().item())
+    print(json.dumps({"mode": "scaling_inputs", "beta_us_per_expert": round(beta, 3), "c_e_us": round(c_e, 3),
+                      "fit_points": [[a, round(t, 2)] for a, t in pts], "ne_values": ne_values, "B_values": B_values,
+                      "a_max_table": np.round(table, 2).tolist()}), flush=True)
+
+    class M:                                   # stand-ins for what this build does not have (attention, network)
+        L = 26
+        c_a, alpha, c_kv = 30.0, 0.5, 4e-4
+        comm0, comm1 = 20.0, 0.02
+        S_ctx = 2048.0
+        mem_budget, mem_fixed, mem_per_token = 288e9, 40e9, 70e3
+    M.beta, M.c_e = beta, c_e
+    for slo_ms in (4.0, 6.0):
+        for lam in (0.002, 0.01, 0.03, 0.06, 0.1, 0.2):
+            r = B.moe_scaling_solve(M, table, ne_values, B_values, lam, slo_ms * 1e3, 16, -(-E // C), 1024.0)
+            out = {"mode": "scaling", "slo_ms": slo_ms, "lambda_req_per_us": lam}
+            if r is None:
+                out["feasible"] = False
+            else:
+                out.update({"feasible": True, "n_a": r[0], "n_e": r[1], "B_star": round(r[2], 1), "tpot_ms": round(r[3] / 1e3, 3)})
+            print(json.dumps(out), flush=True)
 
 
 def placement_study(args) -> None:

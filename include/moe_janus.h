@@ -210,6 +210,32 @@ int moe_replica_counts(int E, int n_inst, int C, const double *c_host, int32_t *
 int moe_place_replicas(int E, int n_inst, int C, const int32_t *R_host, const double *c_host,
                        const double *a_host, int32_t *slot_to_expert_host_out);
 
+/* ------------------------------------------------------------------ resource scaling (host)
+ * Sec. 3.5 ("Fine-Grained Scaling under SLOs"), Alg. 2.  Host-only.  For every (n_a, n_e) in
+ * {1..n_max} x {ne_min..n_max} whose n_e is on the table's grid: the steady-state batch B* of
+ * Eq. 2 (B = lambda * TPOT(B); B* = 1 if the load is too light, candidate dropped if B_max cannot
+ * sustain it, else 60 bisections of the residual on [1, B_max]), TPOT by Eq. 1a-1c, the SLO and the
+ * attention-side memory check; the feasible candidate with the fewest GPUs wins (first in
+ * enumeration order on ties).  All L layers share the coefficients; times in one unit of the
+ * caller's choice (lambda in requests per that unit).
+ *   TPOT = L * ( max(c_a, alpha*b + c_kv*b*S_ctx) + beta*a_max(n_e, B) + c_e + comm0 + comm1*B ),  b = B/n_a
+ *   memory: mem_fixed + mem_per_token * b * S_ctx <= mem_budget
+ *   amax_table_host [n_ne][n_B]: a_max on the grid ne_values_host x B_values_host (ascending B);
+ *   linear interpolation in B, clamped at the ends.
+ * Outputs (host): n_a, n_e, B*, TPOT of the choice; n_a = n_e = 0 if nothing is feasible (still MOE_OK).
+ */
+typedef struct {
+    int L;
+    double c_a, alpha, c_kv;       /* attention side, Eq. 1b */
+    double beta, c_e;              /* MoE side, Eq. 1c */
+    double comm0, comm1;           /* communication per layer: comm0 + comm1 * B */
+    double S_ctx;
+    double mem_budget, mem_fixed, mem_per_token;
+} moe_scaling_model;
+int moe_scaling_solve(const moe_scaling_model *m, const double *amax_table_host, const int *ne_values_host, int n_ne,
+                      const double *B_values_host, int n_B, double lambda, double slo, int n_max, int ne_min,
+                      double B_max, int *n_a_out, int *n_e_out, double *B_star_out, double *tpot_out);
+
 /* ------------------------------------------------------------------ the gate in the same launch
  * Sec. 3.3 ("gating on the MoE side"): the MoE instance receives the complete activations and
  * runs the gate itself.  These two entry points start from the activations instead of from

@@ -13,6 +13,8 @@ cpu_baseline leg of bench.py.  The product path never calls it.
   dispatch.py    this instance's share of Step 4 (permute) and the
                  weighted top-k combine                                     (Sec. 3.3, Sec. 3.4)
   ffn.py         grouped SwiGLU expert FFN and the dense per-token layer   (Sec. 2.2 roofline paragraph)
+  placement_opt.py  window statistics, replica counts, Alg. 3 placement   (Appendix B)
+  scaling.py     latency model, steady-state batch, Alg. 2                  (Sec. 3.5)
   bounds.py      balls-into-bins expectation and a_max bound               (Appendix A, Eq. 4-5)
 
 Floating point is fp64 unless a decision must be taken in the kernel's fp32

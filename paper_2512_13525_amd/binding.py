@@ -26,11 +26,16 @@ EXPORTS = [
     "moe_placement_create", "moe_placement_destroy", "moe_placement_replicas", "moe_placement_dims",
     "moe_route", "moe_schedule", "moe_schedule_baseline", "moe_permute", "moe_block_rows", "moe_max_blocks", "moe_block_list_len",
     "moe_route_schedule_permute", "moe_gate_sync_len", "moe_gate_route", "moe_gate_route_schedule_permute",
-    "moe_coactivation_counts", "moe_replica_counts", "moe_place_replicas",
+    "moe_coactivation_counts", "moe_replica_counts", "moe_place_replicas", "moe_scaling_solve",
     "moe_pack_weights_bf16",
     "moe_workspace_bytes", "moe_workspace_init", "moe_workspace_status", "moe_grouped_ffn", "moe_combine",
     "moe_read_probe",
 ]
+
+
+class moe_scaling_model(ctypes.Structure):
+    _fields_ = [("L", ctypes.c_int)] + [(n, ctypes.c_double) for n in (
+        "c_a", "alpha", "c_kv", "beta", "c_e", "comm0", "comm1", "S_ctx", "mem_budget", "mem_fixed", "mem_per_token")]
 
 
 class MoeError(RuntimeError):
@@ -91,6 +96,9 @@ def lib() -> ctypes.CDLL:
     L.moe_replica_counts.argtypes = [ci, ci, ci, vp, vp]
     L.moe_place_replicas.restype = ci
     L.moe_place_replicas.argtypes = [ci, ci, ci, vp, vp, vp, vp]
+    cd = ctypes.c_double
+    L.moe_scaling_solve.restype = ci
+    L.moe_scaling_solve.argtypes = [vp, vp, vp, ci, vp, ci, cd, cd, ci, ci, cd, vp, vp, vp, vp]
     L.moe_gate_sync_len.restype = cs
     L.moe_gate_sync_len.argtypes = [ci]
     L.moe_gate_route.restype = ci
@@ -248,6 +256,25 @@ def moe_place_replicas(n_inst: int, C: int, R, c, a):
     _check(lib().moe_place_replicas(E, n_inst, C, R.ctypes.data, c.ctypes.data, a.ctypes.data, lay.ctypes.data),
            "moe_place_replicas")
     return lay
+
+
+def moe_scaling_solve(model, table, ne_values, B_values, lam: float, slo: float, n_max: int, ne_min: int,
+                      B_max: float):
+    """model: any object with the fields of moe_scaling_model.  Returns (n_a, n_e, B*, TPOT) or None."""
+    import numpy as np
+    m = moe_scaling_model(*[getattr(model, n) for n, _ in moe_scaling_model._fields_])
+    table = np.ascontiguousarray(table, dtype=np.float64)
+    ne = np.ascontiguousarray(ne_values, dtype=np.int32)
+    Bs = np.ascontiguousarray(B_values, dtype=np.float64)
+    assert table.shape == (len(ne), len(Bs))
+    n_a, n_e = ctypes.c_int(0), ctypes.c_int(0)
+    b_star, t = ctypes.c_double(0.0), ctypes.c_double(0.0)
+    _check(lib().moe_scaling_solve(ctypes.byref(m), table.ctypes.data, ne.ctypes.data, len(ne), Bs.ctypes.data, len(Bs),
+                                   lam, slo, n_max, ne_min, B_max, ctypes.byref(n_a), ctypes.byref(n_e),
+                                   ctypes.byref(b_star), ctypes.byref(t)), "moe_scaling_solve")
+    if n_a.value == 0:
+        return None
+    return n_a.value, n_e.value, b_star.value, t.value
 
 
 def moe_gate_sync_len(T: int) -> int:
