@@ -54,7 +54,7 @@ def main() -> None:
     ap.add_argument("--ring-bytes", type=float, default=1.25e9, help="minimum total bytes of rotating weight copies")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-events", action="store_true", help="do not record per-kernel events in the timed region")
-    ap.add_argument("--mode", default="step", choices=["step", "sched", "act_sweep", "skew", "batch_sweep", "amax", "gate", "placement", "scaling"],
+    ap.add_argument("--mode", default="step", choices=["step", "sched", "act_sweep", "skew", "batch_sweep", "amax", "gate", "placement", "scaling", "shared"],
                     help="step: the headline line (default); sched: scheduler us and a_max vs optimum over the "
                          "stress sweep; act_sweep: layer us vs number of activated experts; skew: same "
                          "activated set with an even and a Zipf split of the requests; batch_sweep: layer "
@@ -62,7 +62,8 @@ def main() -> None:
                          "baseline policies over sampled batches, against the exact optimum and Eq. 5; gate: the front "
                          "launch with and without the router's linear layer in it; placement: a_max of AEBS over the "
                          "layout of Alg. 3 (Appendix B) against the contiguous layout on traces with topics; scaling: "
-                         "Alg. 2 fed with the measured MoE-side coefficients and a_max table")
+                         "Alg. 2 fed with the measured MoE-side coefficients and a_max table; shared: the step with a "
+                         "shared expert run on the instance")
     args = ap.parse_args()
     if args.gpus != 1:
         raise SystemExit("this build runs on ONE GPU: the other MoE instances exist only as replica placement "
@@ -91,6 +92,8 @@ def main() -> None:
         return placement_study(args)
     if args.mode == "scaling":
         return scaling_study(args)
+    if args.mode == "shared":
+        return shared_step(args)
     cfg = make_cfg(args.workload, args.tokens)
     lay = W.build_placement(cfg)
     T, k, C, d_h, d_e = cfg.T, cfg.k, cfg.C, cfg.d_h, cfg.d_e
@@ -542,6 +545,58 @@ def amax_study(args) -> None:
                               "a_max_aebs_mean_first16": round(float(amax[0][:n_opt].mean()), 2),
                               "eq4_expected_max": round(a_bar, 2), "eq5_bound": bounds.a_max_bound(a_bar, C, n_inst)}),
                   flush=True)
+
+
+def shared_step(args) -> None:
+    """The layer step with the shared-expert option (the paper keeps the shared expert on the
+    attention side, Sec. 4; this runs it on the instance as one more slot that all T tokens visit):
+    us per step without and with it, and of the shared FFN launch alone."""
+    import torch
+    from paper_2512_13525_amd import binding as B
+    from paper_2512_13525_amd import workloads as W
+    from paper_2512_13525_amd.layer import LayerStep, to_device_bf16
+
+    for name, d_s in (("dsv2lite", 2816), ("dsv3", 2048)):
+        cfg = make_cfg(name, args.tokens)
+        lay = W.build_placement(cfg)
+        T, C, d_h, d_e = cfg.T, cfg.C, cfg.d_h, cfg.d_e
+        n_ring = max(4, int(-(-args.ring_bytes // (C * 3 * d_h * d_e * 2))))
+        gen = torch.Generator(device="cuda").manual_seed(cfg.seed)
+        W13s = [(torch.randn((C, 2 * d_e, d_h), generator=gen, device="cuda") * 0.02).to(torch.bfloat16) for _ in range(n_ring)]
+        W2s = [(torch.randn((C, d_h, d_e), generator=gen, device="cuda") * 0.02).to(torch.bfloat16) for _ in range(n_ring)]
+        logits = [torch.from_numpy(W.router_logits(cfg, sub=i)).cuda() for i in range(n_ring)]
+        Xs = [to_device_bf16(W.activations(cfg, sub=i)) for i in range(n_ring)]
+        s = LayerStep(cfg, lay, 0)
+        s.route(logits[0]); s.schedule()
+        torch.cuda.synchronize()
+        s = LayerStep(cfg, lay, int(torch.argmax(s.load).item()))
+        ws13, ws2 = W.shared_expert_weights(cfg, d_s)
+        s.enable_shared(to_device_bf16(ws13), to_device_bf16(ws2))
+        i = [0]
+
+        def nxt():
+            i[0] += 1
+            return i[0] % n_ring
+
+        def plain():
+            j = nxt()
+            s.step_fused(logits[j], Xs[j], W13=W13s[j], W2=W2s[j])
+
+        def shared():
+            j = nxt()
+            s.step_fused_shared(logits[j], Xs[j], W13=W13s[j], W2=W2s[j])
+
+        def shared_ffn():
+            j = nxt()
+            B.moe_grouped_ffn(Xs[j], s.s_W13, s.s_W2, T, 1, 1, d_h, d_s, s.dtype, s.s_slot_off, s.s_perm, s.s_blocks,
+                              s.s_Yp, s.s_workspace)
+
+        print(json.dumps({"mode": "shared", "workload": cfg.name, "T": T, "shared_width": d_s,
+                          "shared_weight_MB": round(3 * d_h * d_s * 2 / 1e6, 1),
+                          "step_us": round(_time_us(plain, 200), 2), "step_with_shared_us": round(_time_us(shared, 200), 2),
+                          "shared_ffn_us": round(_time_us(shared_ffn, 200), 2)}), flush=True)
+        del W13s, W2s
+        torch.cuda.empty_cache()
 
 
 def scaling_study(args) -> None:

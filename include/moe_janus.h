@@ -340,6 +340,20 @@ int moe_read_probe(const void *src_dev, size_t bytes, void *sink_dev, void *stre
 int moe_combine(const float *Yp_dev, const int32_t *pos_dev, const float *topk_w_dev,
                 int T, int k, int d_h, int dtype, void *Y_dev, void *stream);
 
+/* ------------------------------------------------------------------ shared expert (option)
+ * Some model families add an expert that every token visits with weight 1.  The paper runs it on
+ * the attention side, overlapped with the transfer (Sec. 4), so it is not part of the MoE-instance
+ * step; these two calls let an instance run it anyway with the same FFN kernel:
+ * moe_shared_dispatch writes the dispatch of one slot that holds all T tokens in order
+ * (slot_off_dev [2] = {0, T}; perm_dev [T] = identity; blocks_dev [moe_block_list_len(T, 1, 1)],
+ * 16-byte aligned), to be passed to moe_grouped_ffn with k = 1, C = 1 and the shared expert's
+ * weights; moe_combine_shared is moe_combine plus Ys_dev [T, d_h] f32 (that FFN's output rows)
+ * added to each token's routed sum, in fp32, after it.
+ */
+int moe_shared_dispatch(int T, int32_t *slot_off_dev, int32_t *perm_dev, int32_t *blocks_dev, void *stream);
+int moe_combine_shared(const float *Yp_dev, const int32_t *pos_dev, const float *topk_w_dev, const float *Ys_dev,
+                       int T, int k, int d_h, int dtype, void *Y_dev, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

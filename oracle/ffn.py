@@ -61,3 +61,9 @@ def dense_layer(X: np.ndarray, ids: np.ndarray, w: np.ndarray, weights_of) -> np
                 y += a * w2[:, c].astype(np.float64)
             Y[i] += float(w[i, j]) * y
     return Y
+
+
+def add_shared_expert(Y_routed: np.ndarray, X: np.ndarray, w13_shared: np.ndarray, w2_shared: np.ndarray) -> np.ndarray:
+    """Layer output with a shared expert (an expert every token visits with weight 1; Sec. 4
+    notes that the paper itself runs it on the attention side): Y[i] = Y_routed[i] + FFN_shared(x_i)."""
+    return np.asarray(Y_routed, dtype=np.float64) + expert_ffn(np.asarray(X), w13_shared, w2_shared)

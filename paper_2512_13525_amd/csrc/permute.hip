@@ -16,11 +16,28 @@ void permute_kernel(const int32_t *__restrict__ rid, int n_pairs, int g_self, in
     moe::permute_block(sh, rid, n_pairs, g_self, C, slot_count, slot_off, perm, pos, blocks, block_rows);
 }
 
+// The dispatch of a shared expert: one slot that every token visits once (identity permutation),
+// cut into the same blocks of rows as any other slot.
+__global__ __launch_bounds__(256)
+void shared_dispatch_kernel(int T, int block_rows, int32_t *__restrict__ slot_off, int32_t *__restrict__ perm,
+                            int32_t *__restrict__ blocks) {
+    const int tid = blockIdx.x * blockDim.x + threadIdx.x, n = gridDim.x * blockDim.x;
+    const int n_blocks = (T + block_rows - 1) / block_rows;
+    if (tid == 0) {
+        slot_off[0] = 0;
+        slot_off[1] = T;
+        reinterpret_cast<int4 *>(blocks)[0] = make_int4(n_blocks, block_rows, 0, 0);
+    }
+    for (int i = tid; i < T; i += n) perm[i] = i;
+    for (int b = tid; b < n_blocks; b += n) reinterpret_cast<int4 *>(blocks)[1 + b] = make_int4(0, b * block_rows, T, 0);
+}
+
 // One workgroup per (token, 1024-column chunk); each thread owns 4 consecutive columns.
+// Ys (optional): rows of a shared expert's output, added with weight 1 after the routed sum.
 template <bool OUT_BF16>
 __global__ __launch_bounds__(256)
 void combine_kernel(const float *__restrict__ Yp, const int32_t *__restrict__ pos,
-                    const float *__restrict__ w, int k, int d_h, void *__restrict__ Y) {
+                    const float *__restrict__ w, const float *__restrict__ Ys, int k, int d_h, void *__restrict__ Y) {
     const int i = blockIdx.x;
     const int col = (blockIdx.y * 256 + threadIdx.x) * 4;
     if (col >= d_h) return;
@@ -31,6 +48,10 @@ void combine_kernel(const float *__restrict__ Yp, const int32_t *__restrict__ po
         const float wj = w[i * k + j];
         const float4 y = *reinterpret_cast<const float4 *>(Yp + static_cast<size_t>(r) * d_h + col);
         acc.x += wj * y.x; acc.y += wj * y.y; acc.z += wj * y.z; acc.w += wj * y.w;
+    }
+    if (Ys) {
+        const float4 y = *reinterpret_cast<const float4 *>(Ys + static_cast<size_t>(i) * d_h + col);
+        acc.x += y.x; acc.y += y.y; acc.z += y.z; acc.w += y.w;
     }
     if (OUT_BF16) {
         ushort4 o;
@@ -74,21 +95,44 @@ extern "C" size_t moe_block_list_len(int T, int k, int C) {
     return 4 * (1 + static_cast<size_t>(moe::ffn_max_blocks(T, k, C)));
 }
 
-extern "C" int moe_combine(const float *Yp_dev, const int32_t *pos_dev, const float *topk_w_dev,
-                           int T, int k, int d_h, int dtype, void *Y_dev, void *stream) {
+namespace {
+
+int combine(const float *Yp_dev, const int32_t *pos_dev, const float *topk_w_dev, const float *Ys_dev, bool shared,
+            int T, int k, int d_h, int dtype, void *Y_dev, void *stream, const char *what) {
     if (T < 0 || k < 1 || d_h < 1) return MOE_EINVAL;
     if (dtype != MOE_DTYPE_BF16 && dtype != MOE_DTYPE_F32) return MOE_EINVAL;
     if (d_h % 4 != 0 || k > MOE_MAX_TOPK) return MOE_ESHAPE;
     if (T == 0) return MOE_OK;
-    if (!Yp_dev || !pos_dev || !topk_w_dev || !Y_dev) return MOE_EINVAL;
+    if (!Yp_dev || !pos_dev || !topk_w_dev || !Y_dev || (shared && !Ys_dev)) return MOE_EINVAL;
     if (!moe::aligned(Yp_dev, 16) || !moe::aligned(pos_dev, 4) || !moe::aligned(topk_w_dev, 4) ||
-        !moe::aligned(Y_dev, dtype == MOE_DTYPE_BF16 ? 8 : 16))
+        !moe::aligned(Ys_dev, 16) || !moe::aligned(Y_dev, dtype == MOE_DTYPE_BF16 ? 8 : 16))
         return MOE_EINVAL;
     const dim3 grid(T, (d_h + 1023) / 1024);
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (dtype == MOE_DTYPE_BF16)
-        hipLaunchKernelGGL(combine_kernel<true>, grid, dim3(256), 0, st, Yp_dev, pos_dev, topk_w_dev, k, d_h, Y_dev);
+        hipLaunchKernelGGL(combine_kernel<true>, grid, dim3(256), 0, st, Yp_dev, pos_dev, topk_w_dev, Ys_dev, k, d_h, Y_dev);
     else
-        hipLaunchKernelGGL(combine_kernel<false>, grid, dim3(256), 0, st, Yp_dev, pos_dev, topk_w_dev, k, d_h, Y_dev);
-    return moe::check_launch("moe_combine");
+        hipLaunchKernelGGL(combine_kernel<false>, grid, dim3(256), 0, st, Yp_dev, pos_dev, topk_w_dev, Ys_dev, k, d_h, Y_dev);
+    return moe::check_launch(what);
+}
+
+}  // namespace
+
+extern "C" int moe_combine(const float *Yp_dev, const int32_t *pos_dev, const float *topk_w_dev,
+                           int T, int k, int d_h, int dtype, void *Y_dev, void *stream) {
+    return combine(Yp_dev, pos_dev, topk_w_dev, nullptr, false, T, k, d_h, dtype, Y_dev, stream, "moe_combine");
+}
+
+extern "C" int moe_combine_shared(const float *Yp_dev, const int32_t *pos_dev, const float *topk_w_dev,
+                                  const float *Ys_dev, int T, int k, int d_h, int dtype, void *Y_dev, void *stream) {
+    return combine(Yp_dev, pos_dev, topk_w_dev, Ys_dev, true, T, k, d_h, dtype, Y_dev, stream, "moe_combine_shared");
+}
+
+extern "C" int moe_shared_dispatch(int T, int32_t *slot_off_dev, int32_t *perm_dev, int32_t *blocks_dev, void *stream) {
+    if (T < 0 || !slot_off_dev || !blocks_dev || (T > 0 && !perm_dev)) return MOE_EINVAL;
+    if (!moe::aligned(slot_off_dev, 4) || !moe::aligned(perm_dev, 4) || !moe::aligned(blocks_dev, 16)) return MOE_EINVAL;
+    const int grid = T > 256 ? (T + 255) / 256 < 64 ? (T + 255) / 256 : 64 : 1;
+    hipLaunchKernelGGL(shared_dispatch_kernel, dim3(grid), dim3(256), 0, static_cast<hipStream_t>(stream), T,
+                       moe::ffn_block_rows(T), slot_off_dev, perm_dev, blocks_dev);
+    return moe::check_launch("moe_shared_dispatch");
 }

@@ -126,3 +126,36 @@ class LayerStep:
         self.ffn(X, stream, W13, W2)
         self.combine(stream)
         return self.Y
+
+    # -- shared expert (option) ----------------------------------------------------------
+    def enable_shared(self, W13_shared: torch.Tensor, W2_shared: torch.Tensor):
+        """Canonical [2*d_s, d_h] / [d_h, d_s] device tensors of a shared expert: one more slot
+        that every token visits, run by the same FFN kernel through a dispatch of its own."""
+        c = self.cfg
+        d_s = W2_shared.shape[1]
+        i32 = dict(dtype=torch.int32, device=self.dev)
+        self.d_s = d_s
+        self.s_slot_off = torch.empty((2,), **i32)
+        self.s_perm = torch.empty((max(c.T, 1),), **i32)
+        self.s_blocks = torch.empty((B.moe_block_list_len(c.T, 1, 1),), **i32)
+        self.s_Yp = torch.empty((c.T, c.d_h), dtype=torch.float32, device=self.dev)
+        ws = B.moe_workspace_bytes(c.T, 1, 1, c.d_h, d_s, self.dtype)
+        self.s_workspace = torch.empty((ws,), dtype=torch.uint8, device=self.dev)
+        B.moe_workspace_init(self.s_workspace)
+        w13, w2 = W13_shared.reshape(1, 2 * d_s, c.d_h), W2_shared.reshape(1, c.d_h, d_s)
+        if self.dtype == B.MOE_DTYPE_BF16:
+            self.s_W13, self.s_W2 = torch.empty_like(w13), torch.empty_like(w2)
+            B.moe_pack_weights_bf16(w13, w2, 1, c.d_h, d_s, self.s_W13, self.s_W2)
+        else:
+            self.s_W13, self.s_W2 = w13.contiguous(), w2.contiguous()
+        B.moe_shared_dispatch(c.T, self.s_slot_off, self.s_perm, self.s_blocks)
+
+    def step_fused_shared(self, logits, X, stream=None, W13=None, W2=None):
+        """front, routed FFN, shared-expert FFN, combine of both (four launches)."""
+        c = self.cfg
+        self.front(logits, stream)
+        self.ffn(X, stream, W13, W2)
+        B.moe_grouped_ffn(X, self.s_W13, self.s_W2, c.T, 1, 1, c.d_h, self.d_s, self.dtype, self.s_slot_off,
+                          self.s_perm, self.s_blocks, self.s_Yp, self.s_workspace, stream=stream)
+        B.moe_combine_shared(self.Yp, self.pos, self.topk_w, self.s_Yp, c.T, c.k, c.d_h, self.dtype, self.Y, stream=stream)
+        return self.Y

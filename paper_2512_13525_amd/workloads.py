@@ -175,6 +175,17 @@ def expert_weights(cfg: MoEConfig, e: int) -> Tuple[np.ndarray, np.ndarray]:
     return w13, w2
 
 
+def shared_expert_weights(cfg: MoEConfig, d_e_shared: int) -> Tuple[np.ndarray, np.ndarray]:
+    """Weights of a shared expert of width d_e_shared, N(0, 0.02) like the routed experts:
+    W13 [2*d_e_shared, d_h], W2 [d_h, d_e_shared]."""
+    g = _rng(cfg, 7)
+    w13 = g.standard_normal((2 * d_e_shared, cfg.d_h), dtype=np.float32) * np.float32(0.02)
+    w2 = g.standard_normal((cfg.d_h, d_e_shared), dtype=np.float32) * np.float32(0.02)
+    if cfg.dtype == "bf16":
+        w13, w2 = round_to_bf16(w13), round_to_bf16(w2)
+    return w13, w2
+
+
 def instance_weights(cfg: MoEConfig, slot_to_expert: np.ndarray, g: int,
                      cache: Optional[Dict[int, Tuple[np.ndarray, np.ndarray]]] = None
                      ) -> Tuple[np.ndarray, np.ndarray]:

@@ -537,3 +537,36 @@ def test_schedule_over_the_alg3_layout():
         np.testing.assert_array_equal(rid.cpu().numpy(), O)
         np.testing.assert_array_equal(rep.cpu().numpy(), act_rep)
         np.testing.assert_array_equal(load.cpu().numpy(), ld)
+
+
+@pytest.mark.parametrize("cfg,d_s", [(W.dsv2lite(), 2816), (small("ragged", k=5, T=77), 160), (W.tiny(), 512),
+                                     (small("k1", k=1, T=1), 96), (W.qwen3(1024), 768)],
+                         ids=lambda v: f"{v.name}-T{v.T}" if hasattr(v, "name") else str(v))
+def test_layer_with_shared_expert(cfg, d_s):
+    """Routed layer plus a shared expert over all tokens (several blocks of rows on one slot),
+    against the oracle; the dispatch of the shared slot is checked bit for bit."""
+    o = OracleRun(cfg)
+    ws13, ws2 = W.shared_expert_weights(cfg, d_s)
+    want = ffn.add_shared_expert(o.Y, o.X, ws13, ws2)
+    s = LayerStep(cfg, o.lay, o.g_self)
+    upload_weights(s, cfg, o.W13, o.W2)
+    if cfg.dtype == "bf16":
+        s.enable_shared(to_device_bf16(ws13), to_device_bf16(ws2))
+    else:
+        s.enable_shared(torch.from_numpy(ws13).cuda(), torch.from_numpy(ws2).cuda())
+    torch.cuda.synchronize()
+    assert s.s_slot_off.cpu().tolist() == [0, cfg.T]
+    np.testing.assert_array_equal(s.s_perm.cpu().numpy()[:cfg.T], np.arange(cfg.T))
+    exp = expected_blocks(np.array([0, cfg.T]), B.moe_block_rows(cfg.T))
+    np.testing.assert_array_equal(s.s_blocks.cpu().numpy()[:len(exp)], exp)
+    X = upload_x(cfg, o.X)
+    logits = torch.from_numpy(o.logits).cuda()
+    for rep in range(2):
+        s.Y.zero_()
+        s.step_fused_shared(logits, X)
+        torch.cuda.synchronize()
+        got = s.Y.float().cpu().numpy()
+        tol = TOL_BF16 if cfg.dtype == "bf16" else TOL_F32
+        assert rel_fro(got, want) < tol
+        assert rel_fro(s.s_Yp.cpu().numpy(), ffn.expert_ffn(o.X, ws13, ws2)) < tol
+        assert B.moe_workspace_status(s.workspace) == 0 and B.moe_workspace_status(s.s_workspace) == 0

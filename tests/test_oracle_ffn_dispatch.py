@@ -152,3 +152,25 @@ def test_bf16_rounding_helper():
     y = rng.standard_normal(100000).astype(np.float32) * 3
     np.testing.assert_array_equal(W.round_to_bf16(y), torch.from_numpy(y).to(torch.bfloat16).to(torch.float32).numpy())
     np.testing.assert_array_equal(W.bf16_bits_to_f32(W.bf16_bits(W.round_to_bf16(y))), W.round_to_bf16(y))
+
+
+def test_shared_expert_is_one_more_choice_with_weight_one():
+    """Adding a shared expert equals the dense per-token loop run with one extra choice per token
+    (the shared expert, weight 1); with all routed weights zero it is a plain MLP."""
+    import torch
+    cfg = W.MoEConfig("sh", E=6, k=2, d_h=16, d_e=8, T=5, n_inst=2, C=4, zipf_s=0.5, dtype="f32", seed=2)
+    X = W.activations(cfg)
+    z = W.router_logits(cfg)
+    from oracle import routing
+    ids, w = routing.route_softmax(z, cfg.k)
+    ws13, ws2 = W.shared_expert_weights(cfg, 12)
+    weights_of = lambda e: (ws13, ws2) if e == cfg.E else W.expert_weights(cfg, e)
+    routed = ffn.dense_layer(X, ids, w, weights_of)
+    want = ffn.dense_layer(X, np.concatenate([ids, np.full((cfg.T, 1), cfg.E, dtype=ids.dtype)], axis=1),
+                           np.concatenate([w, np.ones((cfg.T, 1))], axis=1), weights_of)
+    np.testing.assert_allclose(ffn.add_shared_expert(routed, X, ws13, ws2), want, rtol=1e-12, atol=1e-15)
+    x = torch.from_numpy(X.astype(np.float64))
+    h = x @ torch.from_numpy(ws13[:12].astype(np.float64)).T
+    u = x @ torch.from_numpy(ws13[12:].astype(np.float64)).T
+    mlp = (torch.nn.functional.silu(h) * u) @ torch.from_numpy(ws2.astype(np.float64)).T
+    np.testing.assert_allclose(ffn.add_shared_expert(np.zeros_like(routed), X, ws13, ws2), mlp.numpy(), rtol=1e-10, atol=1e-14)
