@@ -54,7 +54,7 @@ def main() -> None:
     ap.add_argument("--ring-bytes", type=float, default=1.25e9, help="minimum total bytes of rotating weight copies")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-events", action="store_true", help="do not record per-kernel events in the timed region")
-    ap.add_argument("--mode", default="step", choices=["step", "sched", "act_sweep", "skew", "batch_sweep", "amax", "gate", "placement", "scaling", "shared"],
+    ap.add_argument("--mode", default="step", choices=["step", "sched", "act_sweep", "skew", "batch_sweep", "amax", "gate", "placement", "scaling", "shared", "graph"],
                     help="step: the headline line (default); sched: scheduler us and a_max vs optimum over the "
                          "stress sweep; act_sweep: layer us vs number of activated experts; skew: same "
                          "activated set with an even and a Zipf split of the requests; batch_sweep: layer "
@@ -63,7 +63,8 @@ def main() -> None:
                          "launch with and without the router's linear layer in it; placement: a_max of AEBS over the "
                          "layout of Alg. 3 (Appendix B) against the contiguous layout on traces with topics; scaling: "
                          "Alg. 2 fed with the measured MoE-side coefficients and a_max table; shared: the step with a "
-                         "shared expert run on the instance")
+                         "shared expert run on the instance; graph: the step queued eagerly against the same steps "
+                         "replayed from a captured HIP graph")
     args = ap.parse_args()
     if args.gpus != 1:
         raise SystemExit("this build runs on ONE GPU: the other MoE instances exist only as replica placement "
@@ -94,6 +95,8 @@ def main() -> None:
         return scaling_study(args)
     if args.mode == "shared":
         return shared_step(args)
+    if args.mode == "graph":
+        return graph_step(args)
     cfg = make_cfg(args.workload, args.tokens)
     lay = W.build_placement(cfg)
     T, k, C, d_h, d_e = cfg.T, cfg.k, cfg.C, cfg.d_h, cfg.d_e
@@ -144,17 +147,20 @@ def main() -> None:
         run_step(i)
     torch.cuda.synchronize()
 
-    # ---- timed region: exactly K steps; one event pair per step around the FFN launch(es)
-    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    # ---- timed region: exactly K steps; an event pair around the FFN launch of every 4th step (an
+    # event record costs the stream about 3 us, which is time of the step, so not every step pays it)
+    every = 1 if args.no_events else 4
+    timed = [i for i in range(args.steps) if i % every == 0 and not args.no_events]
+    ev = {i: (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for i in timed}
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
         j = i % n_ring
         step.front(logits[j])
-        if not args.no_events:
+        if i in ev:
             ev[i][0].record()
         step.ffn(Xs[j], W13=W13s[j], W2=W2s[j])
-        if not args.no_events:
+        if i in ev:
             ev[i][1].record()
         step.combine()
     torch.cuda.synchronize()
@@ -164,14 +170,21 @@ def main() -> None:
     value = mean_bytes_step / (ms_per_step * 1e-3) / 1e9
 
     if not args.no_events:
-        ffn_us = [a.elapsed_time(b) * 1e3 for a, b in ev]
+        ffn_us = [ev[i][0].elapsed_time(ev[i][1]) * 1e3 for i in timed]
         ffn_avg_us = statistics.mean(ffn_us)
-        mean_bytes_ffn = statistics.mean(bytes_ffn(i % n_ring) for i in range(args.steps))
+        mean_bytes_ffn = statistics.mean(bytes_ffn(i % n_ring) for i in timed)
         achieved = mean_bytes_ffn / (ffn_avg_us * 1e-6) / 1e9
+        # what an event pair reads with nothing between its two records, queued like the pairs above
+        # (the part of avg_us that is not the kernel; rocprofv3's kernel durations do not contain it)
+        cal = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(50)]
+        for a, b in cal:
+            step.front(logits[0]); a.record(); b.record(); step.combine()
+        torch.cuda.synchronize()
+        empty_pair_us = statistics.median(a.elapsed_time(b) * 1e3 for a, b in cal)
         roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": MEASURED_TRAFFIC.get((args.workload, T)),
                     "traffic_unit": "bytes per launch",
-                    "kernel": "moe_grouped_ffn", "avg_us": round(ffn_avg_us, 2),
+                    "kernel": "moe_grouped_ffn", "avg_us": round(ffn_avg_us, 2), "launches_timed": len(timed), "empty_event_pair_us": round(empty_pair_us, 2),
                     "p10_us": round(float(np.percentile(ffn_us, 10)), 2),
                     "p50_us": round(statistics.median(ffn_us), 2),
                     "p90_us": round(float(np.percentile(ffn_us, 90)), 2),
@@ -545,6 +558,49 @@ def amax_study(args) -> None:
                               "a_max_aebs_mean_first16": round(float(amax[0][:n_opt].mean()), 2),
                               "eq4_expected_max": round(a_bar, 2), "eq5_bound": bounds.a_max_bound(a_bar, C, n_inst)}),
                   flush=True)
+
+
+def graph_step(args) -> None:
+    """Every compute entry point is asynchronous, allocates nothing and reads nothing back, so
+    a run of layer steps can be captured in a HIP graph: us per step for the ring of batches
+    queued eagerly (three launches per step from Python) and for the same ring replayed from one
+    captured graph."""
+    import torch
+    from paper_2512_13525_amd import workloads as W
+    from paper_2512_13525_amd.layer import LayerStep, to_device_bf16
+
+    for name in ("dsv2lite", "qwen3", "dsv3"):
+        cfg = make_cfg(name, args.tokens)
+        lay = W.build_placement(cfg)
+        C, d_h, d_e = cfg.C, cfg.d_h, cfg.d_e
+        n_ring = max(4, int(-(-args.ring_bytes // (C * 3 * d_h * d_e * 2))))
+        gen = torch.Generator(device="cuda").manual_seed(cfg.seed)
+        W13s = [(torch.randn((C, 2 * d_e, d_h), generator=gen, device="cuda") * 0.02).to(torch.bfloat16) for _ in range(n_ring)]
+        W2s = [(torch.randn((C, d_h, d_e), generator=gen, device="cuda") * 0.02).to(torch.bfloat16) for _ in range(n_ring)]
+        logits = [torch.from_numpy(W.router_logits(cfg, sub=i)).cuda() for i in range(n_ring)]
+        Xs = [to_device_bf16(W.activations(cfg, sub=i)) for i in range(n_ring)]
+        s = LayerStep(cfg, lay, 0)
+        s.route(logits[0]); s.schedule()
+        torch.cuda.synchronize()
+        s = LayerStep(cfg, lay, int(torch.argmax(s.load).item()))
+
+        def ring():
+            for j in range(n_ring):
+                s.step_fused(logits[j], Xs[j], W13=W13s[j], W2=W2s[j])
+
+        ring()
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            ring()
+        torch.cuda.synchronize()
+        reps = max(1, 400 // n_ring)
+        eager = _time_us(ring, reps) / n_ring
+        graph = _time_us(g.replay, reps) / n_ring
+        print(json.dumps({"mode": "graph", "workload": cfg.name, "T": cfg.T, "steps_per_graph": n_ring,
+                          "eager_step_us": round(eager, 2), "graph_step_us": round(graph, 2)}), flush=True)
+        del g, W13s, W2s
+        torch.cuda.empty_cache()
 
 
 def shared_step(args) -> None:

@@ -155,8 +155,9 @@ int moe_schedule_baseline(const moe_placement_t *pl, const int32_t *topk_ids_dev
  *                  R = moe_block_rows(T) rows (32 for small batches, MOE_FFN_BLOCK_ROWS otherwise);
  *                  slots with more than 16 requests come first (their work takes longest),
  *                  ascending slot order otherwise.  Four int32 per entry: entry 0 = {number of
- *                  blocks B, R, 0, 0}; entry 1+j = {slot, first row of the block,
- *                  slot_off[slot+1], 0}.  Entries past B are left untouched.
+ *                  blocks B, R, number of 128-row blocks that the slots with more than 64 requests
+ *                  make, 0}; entry 1+j = {slot, first row of the block, slot_off[slot+1], 0}.
+ *                  Entries past B are left untouched.
  * n_local and B stay on the device; nothing is read back.  The grouped FFN cannot size its
  * launch by them, so it sizes it for moe_max_blocks() and lets the surplus leave at once.
  */
@@ -321,6 +322,14 @@ int moe_grouped_ffn(const void *X_dev, const void *W13_dev, const void *W2_dev,
                     int T, int k, int C, int d_h, int d_e, int dtype,
                     const int32_t *slot_off_dev, const int32_t *perm_dev, const int32_t *blocks_dev,
                     float *Yp_dev, void *workspace_dev, size_t workspace_bytes, void *stream);
+
+/* Tuning knob of the bf16 path (process-wide, not thread-safe against concurrent FFN calls).  For
+ * batches whose list has blocks of 64 rows, slots with more than 64 requests are computed by two
+ * extra launches of a tiled GEMM (blocks of 128 rows) instead of the streaming launch, but only
+ * when the batch has enough such blocks to fill the chip: (number of 128-row blocks) x (d_e / 64
+ * workgroups per block) >= min_workgroups, default 512.  0 restores the default; results do not
+ * depend on the setting beyond rounding order. */
+void moe_ffn_set_wide_min_workgroups(int min_workgroups);
 
 /* ------------------------------------------------------------------ measurement helper
  * Streams `bytes` (rounded down to 16) from src_dev with plain coalesced 128-bit loads and

@@ -29,7 +29,7 @@ EXPORTS = [
     "moe_coactivation_counts", "moe_replica_counts", "moe_place_replicas", "moe_scaling_solve",
     "moe_pack_weights_bf16",
     "moe_workspace_bytes", "moe_workspace_init", "moe_workspace_status", "moe_grouped_ffn", "moe_combine",
-    "moe_shared_dispatch", "moe_combine_shared",
+    "moe_shared_dispatch", "moe_combine_shared", "moe_ffn_set_wide_min_workgroups",
     "moe_read_probe",
 ]
 
@@ -120,6 +120,8 @@ def lib() -> ctypes.CDLL:
     L.moe_read_probe.argtypes = [vp, cs, vp, vp]
     L.moe_combine.restype = ci
     L.moe_combine.argtypes = [vp, vp, vp, ci, ci, ci, ci, vp, vp]
+    L.moe_ffn_set_wide_min_workgroups.restype = None
+    L.moe_ffn_set_wide_min_workgroups.argtypes = [ci]
     L.moe_shared_dispatch.restype = ci
     L.moe_shared_dispatch.argtypes = [ci, vp, vp, vp, vp]
     L.moe_combine_shared.restype = ci
@@ -353,3 +355,7 @@ def moe_shared_dispatch(T: int, slot_off, perm, blocks, stream=None) -> None:
 def moe_combine_shared(Yp, pos, topk_w, Ys, T: int, k: int, d_h: int, dtype: int, Y, stream=None) -> None:
     _check(lib().moe_combine_shared(_ptr(Yp), _ptr(pos), _ptr(topk_w), _ptr(Ys), T, k, d_h, dtype, _ptr(Y),
                                     _stream(stream)), "moe_combine_shared")
+
+
+def moe_ffn_set_wide_min_workgroups(n: int) -> None:
+    lib().moe_ffn_set_wide_min_workgroups(n)

@@ -58,8 +58,29 @@ inline long long ffn_max_blocks(int T, int k, int C) {
 // control region of the workspace, `act` holds ffn_max_blocks(T, k, C) blocks of ffn_block_rows(T) x d_e
 // bf16.  Returns MOE_OK or MOE_ESHAPE (too many blocks).
 int launch_ffn_stream(const void *X, const void *W13p, const void *W2p, int T, int k, int C, int d_h, int d_e,
-                      const int32_t *blocks, const int32_t *perm, int *ctrl, uint16_t *act, float *Yp,
-                      hipStream_t st);
+                      const int32_t *blocks, const int32_t *slot_off, const int32_t *perm, int *ctrl, uint16_t *act,
+                      float *Yp, hipStream_t st);
+
+// Slots with more than 64 requests (only when the list has blocks of 64 rows): blocks of 128 rows as
+// tiled GEMMs (ffn_wide.hip); the streaming launch skips those slots.  `act_rows` holds T*k rows of
+// d_e bf16.
+inline bool ffn_has_wide(int T) { return ffn_block_rows(T) == 64; }
+// The tiled-GEMM launches pay off only when they can fill the chip (a workgroup runs the whole K
+// dimension of its tile): they take a batch's slots with more than 64 requests when the list counts
+// enough 128-row blocks for kWideMinWorkgroups stage-1 workgroups, otherwise the streaming launch
+// keeps them.  Every kernel takes the decision from the list's header in the same way.
+constexpr int kWideMinWorkgroups = 512;
+int ffn_wide_min_workgroups();           // kWideMinWorkgroups unless moe_ffn_set_wide_min_workgroups changed it
+__device__ __forceinline__ bool ffn_wide_on(int4 head, int wide_tiles1, int min_workgroups) {
+    return head.y == 64 && head.z > 0 && head.z * wide_tiles1 >= min_workgroups;
+}
+inline size_t ffn_stream_act_bytes(int T, int k, int C, int d_e) {
+    const size_t b = static_cast<size_t>(ffn_max_blocks(T, k, C)) * ffn_block_rows(T) * d_e * 2;
+    return (b + 255) / 256 * 256;
+}
+int launch_ffn_wide(const void *X, const void *W13p, const void *W2p, int T, int k, int C, int d_h, int d_e,
+                    const int32_t *blocks, const int32_t *slot_off, const int32_t *perm, uint16_t *act_rows,
+                    float *Yp, hipStream_t st);
 
 inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 

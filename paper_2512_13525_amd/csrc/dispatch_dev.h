@@ -350,6 +350,7 @@ struct PermShared {
     int total[MOE_MAX_SLOTS];
     int off[MOE_MAX_SLOTS + 1];
     int blk_base[MOE_MAX_SLOTS + 1];         // exclusive scan of the slots' block counts
+    int n_wide;                              // 128-row blocks of the slots with more than 64 requests
 };
 
 // Exclusive scan over slots of the request totals (sh.total -> sh.off, slot_off), and the place of
@@ -359,11 +360,12 @@ struct PermShared {
 constexpr int kHeavyRows = 16;
 __device__ __forceinline__ void scan_slots(PermShared &sh, int C, int block_rows, int32_t *__restrict__ slot_off,
                                            int lane) {
-    int carry = 0, hcarry = 0, lcarry = 0;
+    int carry = 0, hcarry = 0, lcarry = 0, wide = 0;
     for (int s0 = 0; s0 < C; s0 += MOE_WAVE) {
         const int s = s0 + lane;
         const int v = s < C ? sh.total[s] : 0;
         const int nb = (v + block_rows - 1) / block_rows;
+        wide += v > 64 ? (v + 127) / 128 : 0;
         const int hb = v > kHeavyRows ? nb : 0, lb = nb - hb;
         int incl = v, hincl = hb, lincl = lb;
 #pragma unroll
@@ -385,21 +387,24 @@ __device__ __forceinline__ void scan_slots(PermShared &sh, int C, int block_rows
     }
     for (int s = lane; s < C; s += MOE_WAVE)
         if (sh.blk_base[s] < 0) sh.blk_base[s] = hcarry + (-sh.blk_base[s] - 1);
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) wide += __shfl_xor(wide, d, MOE_WAVE);
     if (lane == 0) {
         sh.off[C] = carry;
         slot_off[C] = carry;
         sh.blk_base[C] = hcarry + lcarry;
+        sh.n_wide = wide;
     }
 }
 
 // Work list of the grouped FFN (a5): the local request rows cut into blocks of at most
 // block_rows rows of one slot, in the order scan_slots fixed.  Entry 0 = {number of blocks,
-// block_rows, 0, 0}; entry 1+j = {slot, first row, end of the slot's rows, 0}.  All threads, after
+// block_rows, number of 128-row blocks of the slots with more than 64 requests, 0}; entry 1+j = {slot, first row, end of the slot's rows, 0}.  All threads, after
 // scan_slots and a barrier; one thread per slot writes that slot's entries.
 __device__ __forceinline__ void list_blocks(const PermShared &sh, int C, int block_rows,
                                             int32_t *__restrict__ blocks) {
     int4 *out = reinterpret_cast<int4 *>(blocks);
-    if (threadIdx.x == 0) out[0] = make_int4(sh.blk_base[C], block_rows, 0, 0);
+    if (threadIdx.x == 0) out[0] = make_int4(sh.blk_base[C], block_rows, sh.n_wide, 0);
     for (int s = threadIdx.x; s < C; s += blockDim.x) {
         const int lo = sh.off[s], hi = sh.off[s + 1];
         int j = sh.blk_base[s];

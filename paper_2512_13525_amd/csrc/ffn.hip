@@ -130,13 +130,25 @@ void down_f32_kernel(const float *__restrict__ act, const float *__restrict__ W2
 
 }  // namespace
 
+namespace {
+int g_wide_min_workgroups = moe::kWideMinWorkgroups;
+}
+namespace moe {
+int ffn_wide_min_workgroups() { return g_wide_min_workgroups; }
+}  // namespace moe
+
+extern "C" void moe_ffn_set_wide_min_workgroups(int min_workgroups) {
+    g_wide_min_workgroups = min_workgroups > 0 ? min_workgroups : moe::kWideMinWorkgroups;
+}
+
 extern "C" size_t moe_workspace_bytes(int T, int k, int C, int d_h, int d_e, int dtype) {
     (void)d_h;
     if (T < 0 || k < 1 || C < 1 || d_e < 1) return 0;
     // fp32: one row per request; bf16: whole blocks of rows (at most C partly filled ones)
+    // (+ one row per request for the slots that take the tiled-GEMM path)
     const size_t bytes = dtype == MOE_DTYPE_F32
         ? static_cast<size_t>(T) * k * d_e * 4
-        : static_cast<size_t>(moe::ffn_max_blocks(T, k, C)) * moe::ffn_block_rows(T) * d_e * 2;
+        : moe::ffn_stream_act_bytes(T, k, C, d_e) + (moe::ffn_has_wide(T) ? static_cast<size_t>(T) * k * d_e * 2 : 0);
     return kCtrlBytes + (bytes + 255) / 256 * 256 + 256;
 }
 
@@ -196,7 +208,13 @@ extern "C" int moe_grouped_ffn(const void *X_dev, const void *W13_dev, const voi
     if (dtype == MOE_DTYPE_BF16) {
         // the kernels address token rows with 32-bit byte offsets
         if (static_cast<long long>(T) * d_h * 2 > 0xffffffffLL) return MOE_ESHAPE;
-        const int rc = moe::launch_ffn_stream(X_dev, W13_dev, W2_dev, T, k, C, d_h, d_e, blocks_dev, perm_dev,
+        if (moe::ffn_has_wide(T)) {
+            uint16_t *act_rows = reinterpret_cast<uint16_t *>(ws + kCtrlBytes + moe::ffn_stream_act_bytes(T, k, C, d_e));
+            const int rcw = moe::launch_ffn_wide(X_dev, W13_dev, W2_dev, T, k, C, d_h, d_e, blocks_dev, slot_off_dev,
+                                                 perm_dev, act_rows, Yp_dev, st);
+            if (rcw != MOE_OK) return rcw;
+        }
+        const int rc = moe::launch_ffn_stream(X_dev, W13_dev, W2_dev, T, k, C, d_h, d_e, blocks_dev, slot_off_dev, perm_dev,
                                               reinterpret_cast<int *>(ws), reinterpret_cast<uint16_t *>(ws + kCtrlBytes),
                                               Yp_dev, st);
         if (rc != MOE_OK) return rc;

@@ -67,12 +67,14 @@ struct StageArgs {
 struct StreamArgs {
     StageArgs s[2];
     const int32_t *blocks;               // work list written by the dispatch step
+    const int32_t *slot_off;
     const int32_t *perm;
     uint16_t *act;                       // stage-1 output
     float *Yp;                           // stage-2 output
     int *ctrl;
     int k, C;
     int spin_limit;
+    int wide_tiles1, wide_min;           // stage-1 workgroup tiles of the tiled-GEMM launches and their on/off threshold
 };
 
 __device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
@@ -396,6 +398,9 @@ __device__ __forceinline__ void run_item(const StreamArgs &a, const StageArgs &g
     const int n_blocks = list[0].x;
     const int4 ent = list[1 + item];
     if (item >= n_blocks) return;                                // past the last block: nothing else is read
+    // lists with blocks of 64 rows: slots with more than 64 requests belong to the tiled-GEMM launches
+    // when those are on for this batch
+    if (TT == 4 && moe::ffn_wide_on(list[0], a.wide_tiles1, a.wide_min) && ent.z - a.slot_off[ent.x] > 64) return;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / MOE_WAVE), lane = threadIdx.x % MOE_WAVE;
     const int slot = ent.x, row0 = ent.y, hi = ent.z;
     const char *w = g.Wp + (static_cast<size_t>(slot) * g.tiles + tile) * g.KS * 2048;
@@ -499,14 +504,15 @@ void launch_lines(const StreamArgs &a, int block_rows, unsigned blocks, hipStrea
 namespace moe {
 
 int launch_ffn_stream(const void *X, const void *W13p, const void *W2p, int T, int k, int C, int d_h, int d_e,
-                      const int32_t *blocks, const int32_t *perm, int *ctrl, uint16_t *act, float *Yp,
-                      hipStream_t st) {
+                      const int32_t *blocks, const int32_t *slot_off, const int32_t *perm, int *ctrl, uint16_t *act,
+                      float *Yp, hipStream_t st) {
     const int block_rows = ffn_block_rows(T);
     const long long items = ffn_max_blocks(T, k, C);
     if (items > kMaxItems) return MOE_ESHAPE;
     StreamArgs a;
-    a.blocks = blocks; a.perm = perm; a.act = act; a.Yp = Yp; a.ctrl = ctrl; a.k = k; a.C = C;
+    a.blocks = blocks; a.slot_off = slot_off; a.perm = perm; a.act = act; a.Yp = Yp; a.ctrl = ctrl; a.k = k; a.C = C;
     a.spin_limit = 1 << 20;
+    a.wide_tiles1 = (d_e / 16 + 3) / 4; a.wide_min = ffn_wide_min_workgroups();
     a.s[0].B = static_cast<const uint16_t *>(X);
     a.s[0].Wp = static_cast<const char *>(W13p);
     a.s[0].tiles = d_e / 16; a.s[0].KS = d_h / 32; a.s[0].b_stride = d_h; a.s[0].out_stride = 0;

@@ -304,6 +304,10 @@ def test_ffn_block_boundaries(d_h, d_e, T):
     32 and of 64 rows), for even and odd numbers of K-steps in either stage, against the oracle's
     grouped FFN.  A list cut for another block size is refused."""
     counts = [8, 9, 0, 16, 17, 24, 1, 25, 32, 33, 0, 65, 40, 41, 48, 49, 56, 57, 64]
+    if T == 400:
+        # lists with blocks of 64 rows: slots with more than 64 requests take the tiled-GEMM path in
+        # blocks of 128 rows (one partly filled, exactly one, one + 1 row, two full + 44)
+        counts += [66, 128, 129, 300]
     C, k = len(counts), 10
     assert B.moe_block_rows(T) == (32 if T == 70 else 64)
     cfg = W.MoEConfig("blocks", E=C, k=k, d_h=d_h, d_e=d_e, T=T, n_inst=1, C=C, zipf_s=0.0, seed=11)
@@ -325,10 +329,15 @@ def test_ffn_block_boundaries(d_h, d_e, T):
     ws = torch.empty((B.moe_workspace_bytes(T, k, C, d_h, d_e, B.MOE_DTYPE_BF16),), dtype=torch.uint8, device="cuda")
     B.moe_workspace_init(ws)
     Yp = torch.full((T * k, d_h), 123.0, dtype=torch.float32, device="cuda")
-    for rep in range(2):
+    for rep in range(3):
+        # rep 1: the tiled-GEMM launches take the slots with more than 64 requests even though this
+        # small batch would not fill the chip with them (only lists with blocks of 64 rows have any)
+        B.moe_ffn_set_wide_min_workgroups(1 if rep == 1 else 0)
+        Yp.fill_(123.0)
         B.moe_grouped_ffn(to_device_bf16(X), W13p, W2p, T, k, C, d_h, d_e, B.MOE_DTYPE_BF16,
                           torch.from_numpy(slot_off).cuda(), torch.from_numpy(perm).cuda(), d_blk, Yp, ws)
         torch.cuda.synchronize()
+        B.moe_ffn_set_wide_min_workgroups(0)
         got = Yp.cpu().numpy()
         assert (got[n_local:] == 123.0).all()
         num = np.linalg.norm(got[:n_local] - Yp_ref, axis=1)
@@ -570,3 +579,33 @@ def test_layer_with_shared_expert(cfg, d_s):
         assert rel_fro(got, want) < tol
         assert rel_fro(s.s_Yp.cpu().numpy(), ffn.expert_ffn(o.X, ws13, ws2)) < tol
         assert B.moe_workspace_status(s.workspace) == 0 and B.moe_workspace_status(s.s_workspace) == 0
+
+
+def test_steps_replayed_from_a_hip_graph_match_eager():
+    """The entry points neither allocate nor synchronise, so a layer step can be captured; every
+    replay must reproduce the eager result bit for bit, with eager work in between."""
+    cfg = W.dsv2lite()
+    o = OracleRun(cfg)
+    s = LayerStep(cfg, o.lay, o.g_self)
+    upload_weights(s, cfg, o.W13, o.W2)
+    X = upload_x(cfg, o.X)
+    logits = torch.from_numpy(o.logits).cuda()
+    other_logits = torch.from_numpy(W.router_logits(cfg, sub=3)).cuda()
+    other_X = upload_x(cfg, W.activations(cfg, sub=3))
+    s.step_fused(logits, X)
+    torch.cuda.synchronize()
+    assert rel_fro(s.Y.float().cpu().numpy(), o.Y) < TOL_BF16
+    keep = {n: getattr(s, n).clone() for n in ("Y", "topk_ids", "rid", "load", "slot_off", "pos")}
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        s.step_fused(logits, X)
+    torch.cuda.synchronize()
+    for rep in range(4):
+        s.step_fused(other_logits, other_X)                  # eager work on the same buffers in between
+        torch.cuda.synchronize()
+        assert not torch.equal(s.topk_ids, keep["topk_ids"])
+        g.replay()
+        torch.cuda.synchronize()
+        for n, t in keep.items():
+            assert torch.equal(getattr(s, n), t), (n, rep)
+        assert B.moe_workspace_status(s.workspace) == 0
