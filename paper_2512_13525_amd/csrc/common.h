@@ -70,6 +70,8 @@ inline bool ffn_has_wide(int T) { return ffn_block_rows(T) == 64; }
 // enough 128-row blocks for kWideMinWorkgroups stage-1 workgroups, otherwise the streaming launch
 // keeps them.  Every kernel takes the decision from the list's header in the same way.
 constexpr int kWideMinWorkgroups = 512;
+constexpr int kWideWaves = 4;            // wavefronts (= packed weight tiles) of a tiled-GEMM workgroup
+inline int ffn_wide_tiles1(int d_e) { return (d_e / 16 + kWideWaves - 1) / kWideWaves; }
 int ffn_wide_min_workgroups();           // kWideMinWorkgroups unless moe_ffn_set_wide_min_workgroups changed it
 __device__ __forceinline__ bool ffn_wide_on(int4 head, int wide_tiles1, int min_workgroups) {
     return head.y == 64 && head.z > 0 && head.z * wide_tiles1 >= min_workgroups;

@@ -193,9 +193,11 @@ __device__ __forceinline__ void stream_item_lines(const StreamArgs &a, const Sta
             boff[h] = ((lane & 7) >> 1) * (TT * 512) + (h * 8 + (lane >> 3)) * 32 + (lane & 1) * 16;
         }
     }
-    // LDS: row R of a tile at R*128, its 16-byte chunk c at ((c ^ (R & 7)) * 16)
-    const uint32_t wr_lds = ((lane >> 3) * 128) + (((lane & 7) ^ (lane >> 3)) * 16);
-    const uint32_t rd_row = (lane & 15) * 128, rd_sw = lane & 7, rd_g = lane >> 4;
+    // LDS: row R of a tile at R*128, its 16-byte chunk c at ((c ^ ((R >> 1) & 7)) * 16): the 16 rows a
+    // fragment read touches fall into 16 different bank groups.  wr_lds[p]: rows of an even / odd half.
+    const uint32_t wr_lds[2] = {static_cast<uint32_t>(((lane >> 3) * 128) + (((lane & 7) ^ (lane >> 4)) * 16)),
+                                static_cast<uint32_t>(((lane >> 3) * 128) + (((lane & 7) ^ (4 + (lane >> 4))) * 16))};
+    const uint32_t rd_row = (lane & 15) * 128, rd_sw = (lane >> 1) & 7, rd_g = lane >> 4;
     const char *bbase = STAGE1 ? reinterpret_cast<const char *>(g.B)
                                : reinterpret_cast<const char *>(g.B) + static_cast<size_t>(item) * a.s[0].tiles * (TT * 512);
     constexpr int kBStep = STAGE1 ? 128 : 4 * TT * 512;                  // bytes a super-step advances the token operand
@@ -243,7 +245,7 @@ __device__ __forceinline__ void stream_item_lines(const StreamArgs &a, const Sta
 #define MOE_STAGE_B()                                                                            \
     do {                                                                                         \
         _Pragma("unroll") for (int h = 0; h < NH; ++h)                                           \
-            *reinterpret_cast<bf16x8 *>(stg + (h / 2) * 2048 + (h % 2) * 1024 + wr_lds) = br[h]; \
+            *reinterpret_cast<bf16x8 *>(stg + (h / 2) * 2048 + (h % 2) * 1024 + wr_lds[h % 2]) = br[h]; \
         asm volatile("" ::: "memory");                                                           \
     } while (0)
 #define MOE_MMA_STEP(d)                                                                          \
@@ -512,7 +514,7 @@ int launch_ffn_stream(const void *X, const void *W13p, const void *W2p, int T, i
     StreamArgs a;
     a.blocks = blocks; a.slot_off = slot_off; a.perm = perm; a.act = act; a.Yp = Yp; a.ctrl = ctrl; a.k = k; a.C = C;
     a.spin_limit = 1 << 20;
-    a.wide_tiles1 = (d_e / 16 + 3) / 4; a.wide_min = ffn_wide_min_workgroups();
+    a.wide_tiles1 = ffn_wide_tiles1(d_e); a.wide_min = ffn_wide_min_workgroups();
     a.s[0].B = static_cast<const uint16_t *>(X);
     a.s[0].Wp = static_cast<const char *>(W13p);
     a.s[0].tiles = d_e / 16; a.s[0].KS = d_h / 32; a.s[0].b_stride = d_h; a.s[0].out_stride = 0;

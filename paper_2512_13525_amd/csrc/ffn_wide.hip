@@ -27,7 +27,9 @@ namespace {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kThreads = 256;
+constexpr int kWaves = moe::kWideWaves;
+constexpr int kThreads = kWaves * MOE_WAVE;
+constexpr int kLoadsB = 128 * 8 / kThreads;     // 16-byte pieces of the 128 x 128-byte token tile per thread
 constexpr int kRows = 128;               // request rows of a wide block
 constexpr int kRowTiles = kRows / 16;
 
@@ -52,7 +54,7 @@ template <bool STAGE1, bool UPPER>
 __device__ __forceinline__ void wide_block(const WideArgs &a, char (*lds)[kRows * 128], int tile, int slot, int row0, int m);
 
 template <bool STAGE1>
-__global__ __launch_bounds__(kThreads, 2)
+__global__ __launch_bounds__(kThreads, 8 / kWaves)
 void ffn_wide_kernel(WideArgs a) {
     __shared__ __attribute__((aligned(16))) char lds[2][kRows * 128];
     const int tile = blockIdx.x % a.tiles_pad, item = blockIdx.x / a.tiles_pad;
@@ -74,16 +76,16 @@ template <bool STAGE1, bool UPPER>
 __device__ __forceinline__ void wide_block(const WideArgs &a, char (*lds)[kRows * 128], int tile, int slot, int row0, int m) {
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid / MOE_WAVE), lane = tid % MOE_WAVE;
-    int pt = tile * 4 + wave;
+    int pt = tile * kWaves + wave;
     const bool pt_ok = pt < a.ptiles;
     pt = pt_ok ? pt : a.ptiles - 1;
     const char *w = a.Wp + (static_cast<size_t>(slot) * a.ptiles + pt) * a.KS * 2048 + lane * 16;
 
-    // token rows this thread fetches: rows q*32 + tid/8 (q = 0..3), 16-byte chunk tid%8 of the line
-    const char *bp[4];
+    // token rows this thread fetches: rows q*(kThreads/8) + tid/8, 16-byte chunk tid%8 of the line
+    const char *bp[kLoadsB];
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        int r = q * 32 + (tid >> 3);
+    for (int q = 0; q < kLoadsB; ++q) {
+        int r = q * (kThreads / 8) + (tid >> 3);
         r = row0 + (r < m ? r : m - 1);
         const size_t src = STAGE1 ? static_cast<size_t>(a.perm[r] / a.k) : static_cast<size_t>(r);
         bp[q] = a.B + src * a.b_row_bytes + (tid & 7) * 16;
@@ -101,7 +103,7 @@ __device__ __forceinline__ void wide_block(const WideArgs &a, char (*lds)[kRows 
     // and LDS buffer i % 2); loads past the last K-tile fetch the last one again, so the steady-state
     // loop has no branch around a load and the compiler counts outstanding loads exactly.
     constexpr int kRing = 4;
-    bf16x8 breg[kRing][4];
+    bf16x8 breg[kRing][kLoadsB];
     bf16x8 areg[kRing][2][2];                                        // [set][K-step of the tile][fragment]
     const int last = NT - 1;
 
@@ -122,14 +124,14 @@ __device__ __forceinline__ void wide_block(const WideArgs &a, char (*lds)[kRows 
     do {                                                                                         \
         const int j_ = (j) < last ? (j) : last;                                                  \
         const size_t off_ = static_cast<size_t>(j_) * 128 - ((2 * j_ + 1 >= a.KS && (tid & 7) >= 4) ? 64 : 0); \
-        _Pragma("unroll") for (int q = 0; q < 4; ++q)                                            \
+        _Pragma("unroll") for (int q = 0; q < kLoadsB; ++q)                                      \
             breg[set][q] = *reinterpret_cast<const bf16x8 *>(bp[q] + off_);                      \
         asm volatile("" ::: "memory");                                                           \
     } while (0)
 #define MOE_WIDE_STAGE(set)                                                                      \
     do {                                                                                         \
-        _Pragma("unroll") for (int q = 0; q < 4; ++q)                                            \
-            *reinterpret_cast<bf16x8 *>(lds[(set) & 1] + q * 4096 + wr_lds) = breg[set][q];      \
+        _Pragma("unroll") for (int q = 0; q < kLoadsB; ++q)                                      \
+            *reinterpret_cast<bf16x8 *>(lds[(set) & 1] + q * (kThreads * 16) + wr_lds) = breg[set][q];       \
         asm volatile("" ::: "memory");                                                           \
     } while (0)
 #define MOE_WIDE_MMA_HALF(set, ss, h)                                                            \
@@ -225,13 +227,13 @@ int launch_ffn_wide(const void *X, const void *W13p, const void *W2p, int T, int
     // stage 1
     a.B = static_cast<const char *>(X); a.Wp = static_cast<const char *>(W13p);
     a.ptiles = d_e / 16; a.KS = d_h / 32; a.b_row_bytes = static_cast<uint32_t>(d_h) * 2; a.out_stride = d_e;
-    a.tiles = (a.ptiles + 3) / 4; a.tiles_pad = (a.tiles + 7) / 8 * 8; a.tiles1 = a.tiles; a.wide_min = ffn_wide_min_workgroups();
+    a.tiles = (a.ptiles + kWaves - 1) / kWaves; a.tiles_pad = (a.tiles + 7) / 8 * 8; a.tiles1 = a.tiles; a.wide_min = ffn_wide_min_workgroups();
     if (items * a.tiles_pad > 0x7fffffffLL) return MOE_ESHAPE;
     hipLaunchKernelGGL(ffn_wide_kernel<true>, dim3(static_cast<unsigned>(items * a.tiles_pad)), dim3(kThreads), 0, st, a);
     // stage 2
     a.B = reinterpret_cast<const char *>(act_rows); a.Wp = static_cast<const char *>(W2p);
     a.ptiles = d_h / 32; a.KS = d_e / 32; a.b_row_bytes = static_cast<uint32_t>(d_e) * 2; a.out_stride = d_h;
-    a.tiles = (a.ptiles + 3) / 4; a.tiles_pad = (a.tiles + 7) / 8 * 8;
+    a.tiles = (a.ptiles + kWaves - 1) / kWaves; a.tiles_pad = (a.tiles + 7) / 8 * 8;
     if (items * a.tiles_pad > 0x7fffffffLL) return MOE_ESHAPE;
     hipLaunchKernelGGL(ffn_wide_kernel<false>, dim3(static_cast<unsigned>(items * a.tiles_pad)), dim3(kThreads), 0, st, a);
     return MOE_OK;
