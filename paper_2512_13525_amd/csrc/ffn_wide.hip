@@ -14,7 +14,12 @@
 // between wavefronts.  The token rows (the B operand, shared by the 4 wavefronts) go through LDS:
 // per K-tile of 64 columns the workgroup reads one 128-byte line of each row with whole-line
 // loads (8 rows per instruction) into a double-buffered, XOR-swizzled 16 KiB tile, from which
-// every wavefront reads the MFMA layout.  One barrier per K-tile.
+// every wavefront reads the MFMA layout.  One barrier per K-tile; four K-tiles of both operands
+// are in flight in registers.
+//
+// A workgroup runs the whole K dimension of its tile, so these launches pay off only when a
+// batch has enough wide blocks to fill the chip; the list header counts them and this kernel and
+// the streaming kernel take the same decision from it (moe::ffn_wide_on).
 //
 // Work comes from the same block list as the streaming launch (blocks of 64 rows): the entry
 // whose first row is a multiple of 128 rows into a slot with more than 64 requests leads a wide
