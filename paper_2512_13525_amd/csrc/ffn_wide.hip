@@ -152,24 +152,25 @@ __device__ __forceinline__ void wide_block(const WideArgs &a, char (*lds)[kRows 
     } while (0)
     // rows past the block's last repeat that row (their results are not stored); the upper four row
     // tiles are skipped when the block has at most 64 rows
-#define MOE_WIDE_MMA(set, i)                                                                     \
+#define MOE_WIDE_MMA(set, full)                                                                  \
     do {                                                                                         \
         MOE_WIDE_MMA_HALF(set, 0, 0);                                                            \
         if constexpr (UPPER) MOE_WIDE_MMA_HALF(set, 0, 1);                                       \
-        if (2 * (i) + 1 < a.KS) {                                                                \
+        if (full) {                                                                              \
             MOE_WIDE_MMA_HALF(set, 1, 0);                                                        \
             if constexpr (UPPER) MOE_WIDE_MMA_HALF(set, 1, 1);                                   \
         }                                                                                        \
         asm volatile("" ::: "memory");                                                           \
     } while (0)
     // The LDS buffer written here was last read in the multiply of K-tile i-2, which every wavefront
-    // finished before the barrier of K-tile i-1.
-#define MOE_WIDE_STEP(set, i)                                                                    \
+    // finished before the barrier of K-tile i-1.  full: both K-steps of the tile exist (a literal, so
+    // the multiply of a full tile is one straight run of LDS reads and MFMAs).
+#define MOE_WIDE_STEP(set, i, full)                                                              \
     do {                                                                                         \
         MOE_WIDE_STAGE(set);                                                                     \
         MOE_WIDE_LOAD_B(set, (i) + kRing);                                                       \
         __syncthreads();                                                                         \
-        MOE_WIDE_MMA(set, i);                                                                    \
+        MOE_WIDE_MMA(set, full);                                                                 \
         MOE_WIDE_LOAD_A(set, (i) + kRing);                                                       \
     } while (0)
 
@@ -177,17 +178,26 @@ __device__ __forceinline__ void wide_block(const WideArgs &a, char (*lds)[kRows 
     MOE_WIDE_LOAD_A(1, 1); MOE_WIDE_LOAD_B(1, 1);
     MOE_WIDE_LOAD_A(2, 2); MOE_WIDE_LOAD_B(2, 2);
     MOE_WIDE_LOAD_A(3, 3); MOE_WIDE_LOAD_B(3, 3);
+    const int n_full = a.KS >> 1;                                    // K-tiles with both K-steps
     int i = 0;
-    for (; i + kRing <= NT; i += kRing) {
-        MOE_WIDE_STEP(0, i);
-        MOE_WIDE_STEP(1, i + 1);
-        MOE_WIDE_STEP(2, i + 2);
-        MOE_WIDE_STEP(3, i + 3);
+    for (; i + kRing <= n_full; i += kRing) {
+        MOE_WIDE_STEP(0, i, true);
+        MOE_WIDE_STEP(1, i + 1, true);
+        MOE_WIDE_STEP(2, i + 2, true);
+        MOE_WIDE_STEP(3, i + 3, true);
     }
-    const int rem = NT - i;                                          // 0 .. 3 K-tiles left
-    if (rem > 0) MOE_WIDE_STEP(0, i);
-    if (rem > 1) MOE_WIDE_STEP(1, i + 1);
-    if (rem > 2) MOE_WIDE_STEP(2, i + 2);
+    const int rem = n_full - i;                                      // 0 .. 3 full K-tiles left
+    if (rem > 0) MOE_WIDE_STEP(0, i, true);
+    if (rem > 1) MOE_WIDE_STEP(1, i + 1, true);
+    if (rem > 2) MOE_WIDE_STEP(2, i + 2, true);
+    if (a.KS & 1) {                                                  // the half tile of an odd number of K-steps
+        switch (rem) {
+            case 0: MOE_WIDE_STEP(0, n_full, false); break;
+            case 1: MOE_WIDE_STEP(1, n_full, false); break;
+            case 2: MOE_WIDE_STEP(2, n_full, false); break;
+            default: MOE_WIDE_STEP(3, n_full, false); break;
+        }
+    }
 #undef MOE_WIDE_LOAD_A
 #undef MOE_WIDE_LOAD_B
 #undef MOE_WIDE_STAGE
