@@ -451,7 +451,10 @@ def split_sweeps(args) -> None:
     from paper_2512_13525_amd import workloads as W
     from paper_2512_13525_amd.layer import LayerStep, to_device_bf16
 
-    Ts = [args.tokens or 64] if args.mode == "skew" else [16, 32, 64, 128, 256, 512, 1024, 2048, 4096]
+    if args.mode == "skew":
+        Ts = [args.tokens or 64]
+    else:
+        Ts = [args.tokens] if args.tokens else [16, 32, 64, 128, 256, 512, 1024, 2048, 4096]
     for T in Ts:
         cfg = make_cfg(args.workload, T)
         lay = W.build_placement(cfg)
