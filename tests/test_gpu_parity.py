@@ -609,3 +609,70 @@ def test_steps_replayed_from_a_hip_graph_match_eager():
         for n, t in keep.items():
             assert torch.equal(getattr(s, n), t), (n, rep)
         assert B.moe_workspace_status(s.workspace) == 0
+
+
+@pytest.mark.parametrize("cfg", [W.qwen3(1024), W.stress(2048, 1.25, 0.8)], ids=lambda c: f"{c.name}-T{c.T}")
+def test_layer_parity_with_tiled_gemm_forced_on(cfg):
+    """The full-size layers whose hottest slots hold more than 64 requests, with those slots taken
+    by the tiled-GEMM launches (forced on: these batches have too few such blocks for the rule)."""
+    orc = OracleRun(cfg, only_activated=True)
+    assert (orc.slot_count > 64).any()
+    step = LayerStep(cfg, orc.lay, orc.g_self)
+    upload_weights(step, cfg, orc.W13, orc.W2)
+    step.Yp.fill_(123.0)
+    n_local = len(orc.perm)
+    try:
+        B.moe_ffn_set_wide_min_workgroups(1)
+        Y = step.step_fused(torch.from_numpy(orc.logits).cuda(), upload_x(cfg, orc.X))
+        torch.cuda.synchronize()
+    finally:
+        B.moe_ffn_set_wide_min_workgroups(0)
+    Yp = step.Yp.cpu().numpy()
+    assert (Yp[n_local:] == 123.0).all() and np.isfinite(Yp[:n_local]).all()
+    num = np.linalg.norm(Yp[:n_local] - orc.Yp, axis=1)
+    den = np.linalg.norm(orc.Yp, axis=1)
+    assert (num <= 2.5 * TOL_BF16 * den + 1e-30).all()
+    assert rel_fro(Yp[:n_local], orc.Yp) < TOL_BF16
+    assert rel_fro(Y.float().cpu().numpy(), orc.Y) < TOL_BF16
+    assert B.moe_workspace_status(step.workspace) == 0
+    # and the streaming launch alone gives the same rows within the same bar
+    Y2 = step.step_fused(torch.from_numpy(orc.logits).cuda(), upload_x(cfg, orc.X))
+    torch.cuda.synchronize()
+    assert rel_fro(step.Yp.cpu().numpy()[:n_local], orc.Yp) < TOL_BF16
+    assert rel_fro(Y2.float().cpu().numpy(), orc.Y) < TOL_BF16
+
+
+def test_tiled_gemm_taken_by_the_rule_on_a_token_heavy_batch():
+    """Every slot of the instance holds 181 requests (config 2's shape, T = 512): 34 blocks of 128
+    rows x 22 workgroups reach the threshold, so the default rule hands all slots to the
+    tiled-GEMM launches.  Dispatch through moe_permute, rows against the oracle's grouped FFN."""
+    cfg = W.dsv2lite(512)
+    T, k, C = cfg.T, cfg.k, cfg.C
+    lay = W.build_placement(cfg)
+    g_self = 1
+    rid = (g_self * C + np.arange(T * k, dtype=np.int32) % C).reshape(T, k)
+    slot_count, slot_off, perm = dispatch.permute(rid, g_self, C)
+    assert slot_count.min() > 64 and int(sum((c + 127) // 128 for c in slot_count)) * (cfg.d_e // 64) >= 512
+    X = W.activations(cfg)
+    W13, W2 = W.instance_weights(cfg, lay, g_self)
+    Yp_ref = ffn.grouped_ffn(X, W13, W2, slot_off, perm, k)
+    s = LayerStep(cfg, lay, g_self)
+    upload_weights(s, cfg, W13, W2)
+    s.rid.copy_(torch.from_numpy(rid))
+    s.Yp.fill_(123.0)
+    for rep in range(2):
+        s.permute()
+        s.ffn(upload_x(cfg, X))
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(s.slot_off.cpu().numpy(), slot_off)
+        blk = s.blocks.cpu().numpy()
+        exp = expected_blocks(slot_off, 64)
+        np.testing.assert_array_equal(blk[:len(exp)], exp)
+        got = s.Yp.cpu().numpy()
+        n_local = int(slot_off[-1])
+        assert n_local == T * k
+        num = np.linalg.norm(got - Yp_ref, axis=1)
+        den = np.linalg.norm(Yp_ref, axis=1)
+        assert (num <= 2.5 * TOL_BF16 * den + 1e-30).all()
+        assert rel_fro(got, Yp_ref) < TOL_BF16
+        assert B.moe_workspace_status(s.workspace) == 0
