@@ -37,6 +37,7 @@ constexpr int kThreads = kWaves * MOE_WAVE;
 constexpr int kLoadsB = 128 * 8 / kThreads;     // 16-byte pieces of the 128 x 128-byte token tile per thread
 constexpr int kRows = 128;               // request rows of a wide block
 constexpr int kRowTiles = kRows / 16;
+constexpr int kRing = 2;                 // K-tiles of both operands in flight (register sets)
 
 struct WideArgs {
     const char *B;                       // token operand: X (stage 1, rows through perm) or the intermediate (stage 2)
@@ -59,7 +60,7 @@ template <bool STAGE1, bool UPPER>
 __device__ __forceinline__ void wide_block(const WideArgs &a, char (*lds)[kRows * 128], int tile, int slot, int row0, int m);
 
 template <bool STAGE1>
-__global__ __launch_bounds__(kThreads, 8 / kWaves)
+__global__ __launch_bounds__(kThreads, kRing == 2 ? 3 : 2)
 void ffn_wide_kernel(WideArgs a) {
     __shared__ __attribute__((aligned(16))) char lds[2][kRows * 128];
     const int tile = blockIdx.x % a.tiles_pad, item = blockIdx.x / a.tiles_pad;
@@ -107,7 +108,6 @@ __device__ __forceinline__ void wide_block(const WideArgs &a, char (*lds)[kRows 
     // Four K-tiles of both operands are in flight in a ring of register sets (K-tile i uses set i % 4
     // and LDS buffer i % 2); loads past the last K-tile fetch the last one again, so the steady-state
     // loop has no branch around a load and the compiler counts outstanding loads exactly.
-    constexpr int kRing = 4;
     bf16x8 breg[kRing][kLoadsB];
     bf16x8 areg[kRing][2][2];                                        // [set][K-step of the tile][fragment]
     const int last = NT - 1;
@@ -174,28 +174,44 @@ __device__ __forceinline__ void wide_block(const WideArgs &a, char (*lds)[kRows 
         MOE_WIDE_LOAD_A(set, (i) + kRing);                                                       \
     } while (0)
 
-    MOE_WIDE_LOAD_A(0, 0); MOE_WIDE_LOAD_B(0, 0);
-    MOE_WIDE_LOAD_A(1, 1); MOE_WIDE_LOAD_B(1, 1);
-    MOE_WIDE_LOAD_A(2, 2); MOE_WIDE_LOAD_B(2, 2);
-    MOE_WIDE_LOAD_A(3, 3); MOE_WIDE_LOAD_B(3, 3);
     const int n_full = a.KS >> 1;                                    // K-tiles with both K-steps
     int i = 0;
-    for (; i + kRing <= n_full; i += kRing) {
-        MOE_WIDE_STEP(0, i, true);
-        MOE_WIDE_STEP(1, i + 1, true);
-        MOE_WIDE_STEP(2, i + 2, true);
-        MOE_WIDE_STEP(3, i + 3, true);
-    }
-    const int rem = n_full - i;                                      // 0 .. 3 full K-tiles left
-    if (rem > 0) MOE_WIDE_STEP(0, i, true);
-    if (rem > 1) MOE_WIDE_STEP(1, i + 1, true);
-    if (rem > 2) MOE_WIDE_STEP(2, i + 2, true);
-    if (a.KS & 1) {                                                  // the half tile of an odd number of K-steps
-        switch (rem) {
-            case 0: MOE_WIDE_STEP(0, n_full, false); break;
-            case 1: MOE_WIDE_STEP(1, n_full, false); break;
-            case 2: MOE_WIDE_STEP(2, n_full, false); break;
-            default: MOE_WIDE_STEP(3, n_full, false); break;
+    if constexpr (kRing == 4) {
+        MOE_WIDE_LOAD_A(0, 0); MOE_WIDE_LOAD_B(0, 0);
+        MOE_WIDE_LOAD_A(1, 1); MOE_WIDE_LOAD_B(1, 1);
+        MOE_WIDE_LOAD_A(2, 2); MOE_WIDE_LOAD_B(2, 2);
+        MOE_WIDE_LOAD_A(3, 3); MOE_WIDE_LOAD_B(3, 3);
+        for (; i + 4 <= n_full; i += 4) {
+            MOE_WIDE_STEP(0, i, true);
+            MOE_WIDE_STEP(1, i + 1, true);
+            MOE_WIDE_STEP(2, i + 2, true);
+            MOE_WIDE_STEP(3, i + 3, true);
+        }
+        const int rem = n_full - i;                                  // 0 .. 3 full K-tiles left
+        if (rem > 0) MOE_WIDE_STEP(0, i, true);
+        if (rem > 1) MOE_WIDE_STEP(1, i + 1, true);
+        if (rem > 2) MOE_WIDE_STEP(2, i + 2, true);
+        if (a.KS & 1) {                                              // the half tile of an odd number of K-steps
+            switch (rem) {
+                case 0: MOE_WIDE_STEP(0, n_full, false); break;
+                case 1: MOE_WIDE_STEP(1, n_full, false); break;
+                case 2: MOE_WIDE_STEP(2, n_full, false); break;
+                default: MOE_WIDE_STEP(3, n_full, false); break;
+            }
+        }
+    } else {
+        static_assert(kRing == 2 || kRing == 4, "the K loop is written out for rings of 2 and 4");
+        MOE_WIDE_LOAD_A(0, 0); MOE_WIDE_LOAD_B(0, 0);
+        MOE_WIDE_LOAD_A(1, 1); MOE_WIDE_LOAD_B(1, 1);
+        for (; i + 2 <= n_full; i += 2) {
+            MOE_WIDE_STEP(0, i, true);
+            MOE_WIDE_STEP(1, i + 1, true);
+        }
+        const int rem = n_full - i;                                  // 0 .. 1
+        if (rem > 0) MOE_WIDE_STEP(0, i, true);
+        if (a.KS & 1) {
+            if (rem == 0) MOE_WIDE_STEP(0, n_full, false);
+            else MOE_WIDE_STEP(1, n_full, false);
         }
     }
 #undef MOE_WIDE_LOAD_A
