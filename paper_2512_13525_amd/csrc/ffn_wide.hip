@@ -14,8 +14,8 @@
 // between wavefronts.  The token rows (the B operand, shared by the 4 wavefronts) go through LDS:
 // per K-tile of 64 columns the workgroup reads one 128-byte line of each row with whole-line
 // loads (8 rows per instruction) into a double-buffered, XOR-swizzled 16 KiB tile, from which
-// every wavefront reads the MFMA layout.  One barrier per K-tile; four K-tiles of both operands
-// are in flight in registers.
+// every wavefront reads the MFMA layout.  One barrier per K-tile; two K-tiles of both operands
+// are in flight in registers (three workgroups fit a CU).
 //
 // A workgroup runs the whole K dimension of its tile, so these launches pay off only when a
 // batch has enough wide blocks to fill the chip; the list header counts them and this kernel and
@@ -105,8 +105,8 @@ __device__ __forceinline__ void wide_block(const WideArgs &a, char (*lds)[kRows 
     f32x4 acc[kRowTiles][2];
 #pragma unroll
     for (int rt = 0; rt < kRowTiles; ++rt) { acc[rt][0] = f32x4{0.f, 0.f, 0.f, 0.f}; acc[rt][1] = acc[rt][0]; }
-    // Four K-tiles of both operands are in flight in a ring of register sets (K-tile i uses set i % 4
-    // and LDS buffer i % 2); loads past the last K-tile fetch the last one again, so the steady-state
+    // kRing K-tiles of both operands are in flight in a ring of register sets (K-tile i uses set
+    // i % kRing and LDS buffer i % 2); loads past the last K-tile fetch the last one again, so the steady-state
     // loop has no branch around a load and the compiler counts outstanding loads exactly.
     bf16x8 breg[kRing][kLoadsB];
     bf16x8 areg[kRing][2][2];                                        // [set][K-step of the tile][fragment]
