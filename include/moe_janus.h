@@ -324,7 +324,7 @@ int moe_grouped_ffn(const void *X_dev, const void *W13_dev, const void *W2_dev,
                     float *Yp_dev, void *workspace_dev, size_t workspace_bytes, void *stream);
 
 /* Tuning knob of the bf16 path (process-wide, not thread-safe against concurrent FFN calls).  For
- * batches whose list has blocks of 64 rows, slots with more than 64 requests are computed by two
+ * batches of at least 1024 tokens, slots with more than 64 requests are computed by two
  * extra launches of a tiled GEMM (blocks of 128 rows) instead of the streaming launch, but only
  * when the batch has enough such blocks to fill the chip: (number of 128-row blocks) x (d_e / 64
  * workgroups per block) >= min_workgroups, default 512.  0 restores the default; results do not

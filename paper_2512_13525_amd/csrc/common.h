@@ -61,10 +61,12 @@ int launch_ffn_stream(const void *X, const void *W13p, const void *W2p, int T, i
                       const int32_t *blocks, const int32_t *slot_off, const int32_t *perm, int *ctrl, uint16_t *act,
                       float *Yp, hipStream_t st);
 
-// Slots with more than 64 requests (only when the list has blocks of 64 rows): blocks of 128 rows as
-// tiled GEMMs (ffn_wide.hip); the streaming launch skips those slots.  `act_rows` holds T*k rows of
-// d_e bf16.
-inline bool ffn_has_wide(int T) { return ffn_block_rows(T) == 64; }
+// Slots with more than 64 requests of batches of at least kWideMinTokens tokens: blocks of 128 rows
+// as tiled GEMMs (ffn_wide.hip); the streaming launch skips those slots.  Smaller batches never
+// have enough such blocks under top-k routing, and would pay two launches that find nothing.
+// `act_rows` holds T*k rows of d_e bf16.
+constexpr int kWideMinTokens = 1024;
+inline bool ffn_has_wide(int T) { return T >= kWideMinTokens; }
 // The tiled-GEMM launches pay off only when they can fill the chip (a workgroup runs the whole K
 // dimension of its tile): they take a batch's slots with more than 64 requests when the list counts
 // enough 128-row blocks for kWideMinWorkgroups stage-1 workgroups, otherwise the streaming launch

@@ -514,7 +514,8 @@ int launch_ffn_stream(const void *X, const void *W13p, const void *W2p, int T, i
     StreamArgs a;
     a.blocks = blocks; a.slot_off = slot_off; a.perm = perm; a.act = act; a.Yp = Yp; a.ctrl = ctrl; a.k = k; a.C = C;
     a.spin_limit = 1 << 20;
-    a.wide_tiles1 = ffn_wide_tiles1(d_e); a.wide_min = ffn_wide_min_workgroups();
+    a.wide_tiles1 = ffn_wide_tiles1(d_e);
+    a.wide_min = ffn_has_wide(T) ? ffn_wide_min_workgroups() : 0x7fffffff;
     a.s[0].B = static_cast<const uint16_t *>(X);
     a.s[0].Wp = static_cast<const char *>(W13p);
     a.s[0].tiles = d_e / 16; a.s[0].KS = d_h / 32; a.s[0].b_stride = d_h; a.s[0].out_stride = 0;

@@ -296,7 +296,7 @@ def test_unactivated_slots_are_not_read_bf16():
     assert np.isfinite(Y).all() and rel_fro(Y, orc.Y) < TOL_BF16
 
 
-@pytest.mark.parametrize("T", [70, 400], ids=["blocks32", "blocks64"])
+@pytest.mark.parametrize("T", [70, 400, 1030], ids=["blocks32", "blocks64", "blocks64+gemm"])
 @pytest.mark.parametrize("d_h,d_e", [(256, 192), (160, 96), (192, 160)], ids=["even-even", "odd-odd", "even-odd"])
 def test_ffn_block_boundaries(d_h, d_e, T):
     """The grouped FFN alone on a hand-made dispatch whose slots hold 0, 1, 8, 9, 16, 17, 24, 25,
@@ -304,9 +304,10 @@ def test_ffn_block_boundaries(d_h, d_e, T):
     32 and of 64 rows), for even and odd numbers of K-steps in either stage, against the oracle's
     grouped FFN.  A list cut for another block size is refused."""
     counts = [8, 9, 0, 16, 17, 24, 1, 25, 32, 33, 0, 65, 40, 41, 48, 49, 56, 57, 64]
-    if T == 400:
-        # lists with blocks of 64 rows: slots with more than 64 requests take the tiled-GEMM path in
-        # blocks of 128 rows (one partly filled, exactly one, one + 1 row, two full + 44)
+    if T >= 400:
+        # slots with more than 64 requests: several blocks of 64 rows in the streaming launch; in
+        # batches of at least 1024 tokens the tiled-GEMM launches can take them in blocks of 128
+        # rows (one partly filled, exactly one, one + 1 row, two full + 44)
         counts += [66, 128, 129, 300]
     C, k = len(counts), 10
     assert B.moe_block_rows(T) == (32 if T == 70 else 64)
@@ -331,7 +332,7 @@ def test_ffn_block_boundaries(d_h, d_e, T):
     Yp = torch.full((T * k, d_h), 123.0, dtype=torch.float32, device="cuda")
     for rep in range(3):
         # rep 1: the tiled-GEMM launches take the slots with more than 64 requests even though this
-        # small batch would not fill the chip with them (only lists with blocks of 64 rows have any)
+        # batch would not fill the chip with them (they exist for batches of at least 1024 tokens)
         B.moe_ffn_set_wide_min_workgroups(1 if rep == 1 else 0)
         Yp.fill_(123.0)
         B.moe_grouped_ffn(to_device_bf16(X), W13p, W2p, T, k, C, d_h, d_e, B.MOE_DTYPE_BF16,
@@ -643,10 +644,10 @@ def test_layer_parity_with_tiled_gemm_forced_on(cfg):
 
 
 def test_tiled_gemm_taken_by_the_rule_on_a_token_heavy_batch():
-    """Every slot of the instance holds 181 requests (config 2's shape, T = 512): 34 blocks of 128
-    rows x 22 workgroups reach the threshold, so the default rule hands all slots to the
+    """Every slot of the instance holds 361 or 362 requests (config 2's shape, T = 1024): 51 blocks of
+    128 rows x 22 workgroups reach the threshold, so the default rule hands all slots to the
     tiled-GEMM launches.  Dispatch through moe_permute, rows against the oracle's grouped FFN."""
-    cfg = W.dsv2lite(512)
+    cfg = W.dsv2lite(1024)
     T, k, C = cfg.T, cfg.k, cfg.C
     lay = W.build_placement(cfg)
     g_self = 1
