@@ -41,6 +41,9 @@ inline int check_launch(const char *where) {
 // Control region at the start of the FFN workspace: error word + hand-off counters (ffn_stream.hip)
 constexpr size_t kFfnCtrlBytes = 4u << 20;
 
+// Blocks of the work list that get workgroups of their own in the streaming launch (longer lists wrap around)
+constexpr unsigned kFfnLaneBlocks = 128;
+
 // Request rows per block of the FFN work list: small batches take blocks of 32 rows (more, shorter
 // workgroups), larger ones blocks of 64 (hot slots then re-read their expert half as often).
 inline int ffn_block_rows(int T) { return T < 384 ? 32 : MOE_FFN_BLOCK_ROWS; }

@@ -442,9 +442,9 @@ __device__ __forceinline__ void run_item(const StreamArgs &a, const StageArgs &g
     }
 }
 
-// 1-D grid sized for the worst case.  With B = the batch's number of blocks, ids below B*tiles_pad(1)
-// are the stage-1 workgroups (id = block * tiles_pad + tile), the next B*tiles_pad(2) ids the
-// stage-2 workgroups, and the rest leave at once.  Workgroups are dispatched in id order, so a
+// 1-D grid sized for the worst case (at most kFfnLaneBlocks blocks).  With B = min(the batch's number of
+// blocks, kFfnLaneBlocks), ids below B*tiles_pad(1) are the stage-1 workgroups (id = block * tiles_pad +
+// tile), the next B*tiles_pad(2) ids the stage-2 workgroups, and the rest leave at once.  Workgroups are dispatched in id order, so a
 // stage-2 workgroup is started after every stage-1 workgroup, and go to the XCDs round-robin, so
 // the blocks of one tile of a slot (ids tiles_pad apart, a multiple of 8) run on the same XCD at
 // about the same time: the tile's weights come from HBM once and are shared through that XCD's
@@ -458,6 +458,7 @@ void ffn_stream_kernel(StreamArgs a) {
     // its per-wavefront staging tiles during the K loop
     __shared__ __attribute__((aligned(16))) char lds[kWaves * 2 * TT * MOE_WAVE * 16];
     static_assert(kWaves * TT * 2048 <= sizeof(lds), "staging tiles must fit in the reduction buffer");
+    __shared__ unsigned long long s_visit;
 #ifdef MOE_STREAM_TRACE
     const long long t_start = wall_clock64();
 #endif
@@ -471,10 +472,45 @@ void ffn_stream_kernel(StreamArgs a) {
                 __hip_atomic_fetch_or(a.ctrl + 1, 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             return;
         }
+        // Up to kFfnLaneBlocks blocks have workgroups of their own; a longer list wraps around (the
+        // workgroup of block b also takes blocks b + kFfnLaneBlocks, ..., at most 64 of them), which
+        // keeps the worst-case grid of large batches small.  A stage-1 workgroup never waits, and all of them are started
+        // before any stage-2 workgroup, so every flag a stage-2 workgroup waits for is raised.
         const unsigned n_blocks = static_cast<unsigned>(head.x);
-        const unsigned n1 = n_blocks * a.s[0].tiles_pad;
-        if (blockIdx.x < n1) run_item<true, LINES1, false, TT>(a, a.s[0], lds, blockIdx.x);
-        else if (blockIdx.x - n1 < n_blocks * a.s[1].tiles_pad) run_item<false, LINES2, true, TT>(a, a.s[1], lds, blockIdx.x - n1);
+        const unsigned lanes = n_blocks < moe::kFfnLaneBlocks ? n_blocks : moe::kFfnLaneBlocks;
+        const unsigned n1 = lanes * a.s[0].tiles_pad, n2 = lanes * a.s[1].tiles_pad;
+        if (n_blocks <= lanes) {
+            if (blockIdx.x < n1) run_item<true, LINES1, false, TT>(a, a.s[0], lds, blockIdx.x);
+            else if (blockIdx.x - n1 < n2) run_item<false, LINES2, true, TT>(a, a.s[1], lds, blockIdx.x - n1);
+        } else if (blockIdx.x < n1 + n2) {
+            // a long list: the first wavefront looks at all the blocks of this workgroup at once (lane l:
+            // block + l*lanes) and the workgroup then visits only those that are its own to compute
+            const bool s1 = blockIdx.x < n1;
+            const unsigned id0 = s1 ? blockIdx.x : blockIdx.x - n1;
+            const unsigned tp = s1 ? a.s[0].tiles_pad : a.s[1].tiles_pad;
+            if (id0 % tp >= static_cast<unsigned>(s1 ? a.s[0].tiles : a.s[1].tiles)) return;
+            if (threadIdx.x < MOE_WAVE) {
+                const unsigned b = id0 / tp + threadIdx.x * lanes;
+                bool mine = false;
+                if (b < n_blocks) {
+                    const int4 e = reinterpret_cast<const int4 *>(a.blocks)[1 + b];
+                    mine = !(TT == 4 && moe::ffn_wide_on(head, a.wide_tiles1, a.wide_min) && e.z - a.slot_off[e.x] > 64);
+                }
+                const unsigned long long m = __ballot(mine);
+                if (threadIdx.x == 0) s_visit = m;
+            }
+            __syncthreads();
+            unsigned long long visit = s_visit;
+            bool first = true;
+            while (visit) {
+                const unsigned l = static_cast<unsigned>(__builtin_ctzll(visit));
+                visit &= visit - 1;
+                if (!first) __syncthreads();                         // the LDS buffer is reused
+                first = false;
+                if (s1) run_item<true, LINES1, false, TT>(a, a.s[0], lds, id0 + l * n1);
+                else run_item<false, LINES2, true, TT>(a, a.s[1], lds, id0 + l * n2);
+            }
+        }
     }
 #ifdef MOE_STREAM_TRACE
     if (threadIdx.x == 0 && blockIdx.x < (1u << 15)) {
@@ -523,7 +559,8 @@ int launch_ffn_stream(const void *X, const void *W13p, const void *W2p, int T, i
     a.s[1].Wp = static_cast<const char *>(W2p);
     a.s[1].tiles = d_h / 32; a.s[1].KS = d_e / 32; a.s[1].b_stride = 0; a.s[1].out_stride = d_h;
     for (int i = 0; i < 2; ++i) a.s[i].tiles_pad = (a.s[i].tiles + 7) / 8 * 8;
-    const long long n1 = items * a.s[0].tiles_pad, n2 = items * a.s[1].tiles_pad;
+    const long long lanes = items < kFfnLaneBlocks ? items : kFfnLaneBlocks;
+    const long long n1 = lanes * a.s[0].tiles_pad, n2 = lanes * a.s[1].tiles_pad;
     if (n1 + n2 > 0x7fffffffLL) return MOE_ESHAPE;
     launch_lines(a, block_rows, static_cast<unsigned>(n1 + n2), st);
     return MOE_OK;

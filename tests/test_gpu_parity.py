@@ -677,3 +677,41 @@ def test_tiled_gemm_taken_by_the_rule_on_a_token_heavy_batch():
         assert (num <= 2.5 * TOL_BF16 * den + 1e-30).all()
         assert rel_fro(got, Yp_ref) < TOL_BF16
         assert B.moe_workspace_status(s.workspace) == 0
+
+
+def test_ffn_long_block_list_wraps_around():
+    """More blocks than get workgroups of their own (128): the workgroups of the first 128 blocks
+    also take blocks 128 further on, in both stages, and a second call finds the counters cleared."""
+    T, k, C, d_h, d_e = 400, 32, 150, 64, 96
+    counts = [(65, 65, 64, 130, 17, 66)[s % 6] for s in range(C)]
+    cfg = W.MoEConfig("wrap", E=C, k=k, d_h=d_h, d_e=d_e, T=T, n_inst=1, C=C, zipf_s=0.0, seed=13)
+    rng = np.random.default_rng(4)
+    slot_off = np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
+    n_local = int(slot_off[-1])
+    assert n_local <= T * k
+    perm = rng.permutation(T * k)[:n_local].astype(np.int32)
+    X = W.activations(cfg)
+    W13 = np.stack([W.expert_weights(cfg, e)[0] for e in range(C)])
+    W2 = np.stack([W.expert_weights(cfg, e)[1] for e in range(C)])
+    Yp_ref = ffn.grouped_ffn(X, W13, W2, slot_off, perm, k)
+    blk = expected_blocks(slot_off, 64)
+    assert 128 * 2 < blk[0] <= B.moe_max_blocks(T, k, C)
+    d_blk = torch.zeros((B.moe_block_list_len(T, k, C),), dtype=torch.int32)
+    d_blk[:len(blk)] = torch.from_numpy(blk)
+    d_blk = d_blk.cuda()
+    W13p, W2p = torch.empty_like(to_device_bf16(W13)), torch.empty_like(to_device_bf16(W2))
+    B.moe_pack_weights_bf16(to_device_bf16(W13), to_device_bf16(W2), C, d_h, d_e, W13p, W2p)
+    ws = torch.empty((B.moe_workspace_bytes(T, k, C, d_h, d_e, B.MOE_DTYPE_BF16),), dtype=torch.uint8, device="cuda")
+    B.moe_workspace_init(ws)
+    Yp = torch.full((T * k, d_h), 123.0, dtype=torch.float32, device="cuda")
+    for rep in range(2):
+        Yp.fill_(123.0)
+        B.moe_grouped_ffn(to_device_bf16(X), W13p, W2p, T, k, C, d_h, d_e, B.MOE_DTYPE_BF16,
+                          torch.from_numpy(slot_off).cuda(), torch.from_numpy(perm).cuda(), d_blk, Yp, ws)
+        torch.cuda.synchronize()
+        got = Yp.cpu().numpy()
+        assert (got[n_local:] == 123.0).all()
+        num = np.linalg.norm(got[:n_local] - Yp_ref, axis=1)
+        den = np.linalg.norm(Yp_ref, axis=1)
+        assert (num <= 2.5 * TOL_BF16 * den + 1e-30).all(), (rep, int(np.argmax(num / den)))
+        assert B.moe_workspace_status(ws) == 0
