@@ -148,20 +148,24 @@ def main() -> None:
     torch.cuda.synchronize()
 
     # ---- timed region: exactly K steps; an event pair around the FFN launch of every 4th step (an
-    # event record costs the stream about 3 us, which is time of the step, so not every step pays it)
+    # event record costs the stream a few us, which is time of the step, so not every step pays it).
+    # The events are created without the system-scope fence of default events: with it a pair read
+    # 5 us with nothing in between and the FFN launch 43.2 us; without it 3.8 us and 41.4 us, against
+    # 40.5 us for the kernel alone in the rocprofv3 trace.
     every = 1 if args.no_events else 4
     timed = [i for i in range(args.steps) if i % every == 0 and not args.no_events]
-    ev = {i: (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for i in timed}
+    te = TimingEvents()
+    ev = {i: (te.new(), te.new()) for i in timed}
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
         j = i % n_ring
         step.front(logits[j])
         if i in ev:
-            ev[i][0].record()
+            te.record(ev[i][0])
         step.ffn(Xs[j], W13=W13s[j], W2=W2s[j])
         if i in ev:
-            ev[i][1].record()
+            te.record(ev[i][1])
         step.combine()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
@@ -170,17 +174,18 @@ def main() -> None:
     value = mean_bytes_step / (ms_per_step * 1e-3) / 1e9
 
     if not args.no_events:
-        ffn_us = [ev[i][0].elapsed_time(ev[i][1]) * 1e3 for i in timed]
+        ffn_us = [te.us(ev[i][0], ev[i][1]) for i in timed]
         ffn_avg_us = statistics.mean(ffn_us)
         mean_bytes_ffn = statistics.mean(bytes_ffn(i % n_ring) for i in timed)
         achieved = mean_bytes_ffn / (ffn_avg_us * 1e-6) / 1e9
         # what an event pair reads with nothing between its two records, queued like the pairs above
         # (the part of avg_us that is not the kernel; rocprofv3's kernel durations do not contain it)
-        cal = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(50)]
+        cal = [(te.new(), te.new()) for _ in range(50)]
         for a, b in cal:
-            step.front(logits[0]); a.record(); b.record(); step.combine()
+            step.front(logits[0]); te.record(a); te.record(b); step.combine()
         torch.cuda.synchronize()
-        empty_pair_us = statistics.median(a.elapsed_time(b) * 1e3 for a, b in cal)
+        empty_pair_us = statistics.median(te.us(a, b) for a, b in cal)
+        te.close()
         roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": MEASURED_TRAFFIC.get((args.workload, T)),
                     "traffic_unit": "bytes per launch",
@@ -197,29 +202,31 @@ def main() -> None:
     stages = ["route", "schedule", "permute", "ffn", "combine"]
     acc = {s: [] for s in stages}
     n_inst_steps = min(args.steps, 100)
-    marks = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in range(n_inst_steps)]
+    te2 = TimingEvents()
+    marks = [[te2.new() for _ in range(6)] for _ in range(n_inst_steps)]
     torch.cuda.synchronize()
     for i in range(n_inst_steps):
         j = i % n_ring
         m = marks[i]
-        m[0].record(); step.route(logits[j])
-        m[1].record(); step.schedule()
-        m[2].record(); step.permute()
-        m[3].record(); step.ffn(Xs[j], W13=W13s[j], W2=W2s[j])
-        m[4].record(); step.combine()
-        m[5].record()
+        te2.record(m[0]); step.route(logits[j])
+        te2.record(m[1]); step.schedule()
+        te2.record(m[2]); step.permute()
+        te2.record(m[3]); step.ffn(Xs[j], W13=W13s[j], W2=W2s[j])
+        te2.record(m[4]); step.combine()
+        te2.record(m[5])
     torch.cuda.synchronize()
     for m in marks:
         for si, s in enumerate(stages):
-            acc[s].append(m[si].elapsed_time(m[si + 1]) * 1e3)
+            acc[s].append(te2.us(m[si], m[si + 1]))
     stage_us = {s: round(statistics.median(v), 2) for s, v in acc.items()}
     # the fused front launch (what the timed region uses instead of route + schedule + permute)
-    fm = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_inst_steps)]
+    fm = [(te2.new(), te2.new()) for _ in range(n_inst_steps)]
     for i in range(n_inst_steps):
-        fm[i][0].record(); step.front(logits[i % n_ring]); fm[i][1].record()
+        te2.record(fm[i][0]); step.front(logits[i % n_ring]); te2.record(fm[i][1])
         step.ffn(Xs[i % n_ring], W13=W13s[i % n_ring], W2=W2s[i % n_ring]); step.combine()
     torch.cuda.synchronize()
-    stage_us["front_fused"] = round(statistics.median(a.elapsed_time(b) * 1e3 for a, b in fm), 2)
+    stage_us["front_fused"] = round(statistics.median(te2.us(a, b) for a, b in fm), 2)
+    te2.close()
 
     out = {
         "metric": "moe_layer_step_algorithmic_GBps", "value": round(value, 1), "unit": "GB/s",
@@ -275,6 +282,58 @@ def main() -> None:
     print(json.dumps(out), flush=True)
 
 
+class TimingEvents:
+    """HIP events for timing only: created with hipEventDisableSystemFence, so that recording one does
+    not put a system-scope fence (a cache write-back) between the kernels it separates, which the
+    default events of torch.cuda.Event do."""
+
+    def __init__(self):
+        import ctypes
+        import torch
+        lib = None
+        for name in ("libamdhip64.so.7", "libamdhip64.so",
+                     os.path.join(os.path.dirname(torch.__file__), "lib", "libamdhip64.so")):
+            try:
+                lib = ctypes.CDLL(name)
+                break
+            except OSError:
+                continue
+        if lib is None:
+            raise RuntimeError("libamdhip64 not found")
+        self.ct, self.lib = ctypes, lib
+        lib.hipEventCreateWithFlags.argtypes = [ctypes.POINTER(ctypes.c_void_p), ctypes.c_uint]
+        lib.hipEventRecord.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
+        lib.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+        lib.hipEventDestroy.argtypes = [ctypes.c_void_p]
+        self.made = []
+
+    def new(self):
+        ev = self.ct.c_void_p()
+        rc = self.lib.hipEventCreateWithFlags(self.ct.byref(ev), 0x20000000)     # hipEventDisableSystemFence
+        if rc != 0:
+            raise RuntimeError(f"hipEventCreateWithFlags: {rc}")
+        self.made.append(ev)
+        return ev
+
+    def record(self, ev):
+        import torch
+        rc = self.lib.hipEventRecord(ev, self.ct.c_void_p(torch.cuda.current_stream().cuda_stream or None))
+        if rc != 0:
+            raise RuntimeError(f"hipEventRecord: {rc}")
+
+    def us(self, a, b):
+        ms = self.ct.c_float(0.0)
+        rc = self.lib.hipEventElapsedTime(self.ct.byref(ms), a, b)
+        if rc != 0:
+            raise RuntimeError(f"hipEventElapsedTime: {rc}")
+        return ms.value * 1e3
+
+    def close(self):
+        for ev in self.made:
+            self.lib.hipEventDestroy(ev)
+        self.made = []
+
+
 def _time_us(fn, reps):
     """Mean microseconds per call of fn over `reps` back-to-back launches (HIP events)."""
     import torch
@@ -298,14 +357,16 @@ def read_probe(bufs, nbytes: int):
     from paper_2512_13525_amd import binding as B
     sink = torch.zeros((64,), dtype=torch.int32, device="cuda")
     n = min(nbytes, min(t.numel() * t.element_size() for t in bufs)) // 16 * 16
+    te = TimingEvents()
     ev = []
     for rep in range(8):                       # queued back to back, like the steps of the timed region
         for t in bufs:
-            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            a.record(); B.moe_read_probe(t, n, sink); b.record()
+            a, b = te.new(), te.new()
+            te.record(a); B.moe_read_probe(t, n, sink); te.record(b)
             ev.append((a, b))
     torch.cuda.synchronize()
-    us = statistics.median(a.elapsed_time(b) * 1e3 for a, b in ev[len(bufs):])
+    us = statistics.median(te.us(a, b) for a, b in ev[len(bufs):])
+    te.close()
     return us, n / (us * 1e-6) / 1e9
 
 
