@@ -349,6 +349,22 @@ def _time_us(fn, reps):
     return a.elapsed_time(b) * 1e3 / reps
 
 
+def _time_us_graph(fn, per_graph=50, reps=8):
+    """Mean microseconds per call of fn on the GPU's own timeline: per_graph back-to-back calls are
+    captured in a HIP graph and the graph is replayed, so that the Python and launch-call overhead
+    of the host (about 6 us per call through the ctypes binding) does not bound small kernels."""
+    import torch
+    for _ in range(3):
+        fn()
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        for _ in range(per_graph):
+            fn()
+    torch.cuda.synchronize()
+    return _time_us(g.replay, reps) / per_graph
+
+
 def read_probe(bufs, nbytes: int):
     """A plain streaming read (moe_read_probe) of `nbytes` from each copy of the weight ring in
     turn, one launch between two HIP events like the FFN launch it is compared with: the practical
@@ -396,8 +412,8 @@ def sched_sweep(args) -> None:
                 rep = torch.empty((cfg.E,), dtype=torch.int32, device="cuda")
                 load = torch.empty((cfg.n_inst,), dtype=torch.int32, device="cuda")
                 B.moe_route(d_logits, cfg.k, ids, w)
-                us = _time_us(lambda: B.moe_schedule(pl, ids, T, cfg.k, rid, rep, load), 200)
-                route_us = _time_us(lambda: B.moe_route(d_logits, cfg.k, ids, w), 200)
+                us = _time_us_graph(lambda: B.moe_schedule(pl, ids, T, cfg.k, rid, rep, load))
+                route_us = _time_us_graph(lambda: B.moe_route(d_logits, cfg.k, ids, w))
                 a_max = int(load.max().item())
                 o_ids, _, _ = oracle_route(cfg, logits)
                 opl = scheduling.make_placement(lay, cfg.E, cfg.n_inst, cfg.C)
