@@ -148,8 +148,12 @@ def _ptr(t) -> Optional[int]:
 def _stream(stream) -> Optional[int]:
     """hipStream_t of a torch stream (None = torch's current stream)."""
     import torch
-    s = torch.cuda.current_stream() if stream is None else stream
-    return s.cuda_stream or None
+    if stream is None:
+        raw = getattr(torch._C, "_cuda_getCurrentRawStream", None)
+        if raw is not None:                   # the fast path: no Stream object is built
+            return raw(torch.cuda.current_device()) or None
+        stream = torch.cuda.current_stream()
+    return stream.cuda_stream or None
 
 
 class Placement:
