@@ -352,7 +352,7 @@ def _time_us(fn, reps):
 def _time_us_graph(fn, per_graph=50, reps=8):
     """Mean microseconds per call of fn on the GPU's own timeline: per_graph back-to-back calls are
     captured in a HIP graph and the graph is replayed, so that the Python and launch-call overhead
-    of the host (about 6 us per call through the ctypes binding) does not bound small kernels."""
+    of the host (about 4 us per call through the ctypes binding) does not bound small kernels."""
     import torch
     for _ in range(3):
         fn()
