@@ -715,3 +715,42 @@ def test_ffn_long_block_list_wraps_around():
         den = np.linalg.norm(Yp_ref, axis=1)
         assert (num <= 2.5 * TOL_BF16 * den + 1e-30).all(), (rep, int(np.argmax(num / den)))
         assert B.moe_workspace_status(ws) == 0
+
+
+def random_cfg(seed):
+    """A small layer with randomly drawn shape parameters (seeded): odd token counts, expert counts
+    that are not powers of two, both parities of the K-step counts, with and without spare slots."""
+    r = np.random.default_rng(1000 + seed)
+    n_inst = int(r.integers(1, 6))
+    per = int(r.integers(1, 9))
+    E = n_inst * per
+    C = per + int(r.integers(0, 4))
+    k = int(r.integers(1, min(E, 8) + 1))
+    return W.MoEConfig(f"rand{seed}", E=E, k=k, d_h=32 * int(r.integers(1, 9)), d_e=32 * int(r.integers(1, 7)),
+                       T=int(r.integers(1, 200)), n_inst=n_inst, C=C, zipf_s=float(r.choice([0.0, 0.8, 1.5])), seed=seed)
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_layer_parity_random_shapes(seed):
+    cfg = random_cfg(seed)
+    orc = OracleRun(cfg)
+    for g_self in sorted({orc.g_self, 0, cfg.n_inst - 1}):
+        o = orc if g_self == orc.g_self else OracleRun(cfg, g_self=g_self)
+        step = LayerStep(cfg, o.lay, g_self)
+        upload_weights(step, cfg, o.W13, o.W2)
+        Y = step.step_fused(torch.from_numpy(o.logits).cuda(), upload_x(cfg, o.X))
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(step.topk_ids.cpu().numpy(), o.ids)
+        np.testing.assert_array_equal(step.rid.cpu().numpy(), o.O)
+        np.testing.assert_array_equal(step.act_rep.cpu().numpy(), o.act_rep)
+        np.testing.assert_array_equal(step.load.cpu().numpy(), o.load)
+        np.testing.assert_array_equal(step.slot_off.cpu().numpy(), o.slot_off)
+        n_local = len(o.perm)
+        np.testing.assert_array_equal(step.perm.cpu().numpy()[:n_local], o.perm)
+        np.testing.assert_array_equal(step.pos.cpu().numpy(), o.pos)
+        if n_local:
+            assert rel_fro(step.Yp.cpu().numpy()[:n_local], o.Yp) < TOL_BF16
+            assert rel_fro(Y.float().cpu().numpy(), o.Y) < TOL_BF16
+        else:
+            assert not Y.float().cpu().numpy().any()
+        assert B.moe_workspace_status(step.workspace) == 0
