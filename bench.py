@@ -54,7 +54,7 @@ def main() -> None:
     ap.add_argument("--ring-bytes", type=float, default=1.25e9, help="minimum total bytes of rotating weight copies")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-events", action="store_true", help="do not record per-kernel events in the timed region")
-    ap.add_argument("--mode", default="step", choices=["step", "sched", "act_sweep", "skew", "batch_sweep", "amax", "gate", "placement", "scaling", "shared", "graph"],
+    ap.add_argument("--mode", default="step", choices=["step", "sched", "act_sweep", "skew", "batch_sweep", "amax", "gate", "placement", "scaling", "shared", "graph", "configs"],
                     help="step: the headline line (default); sched: scheduler us and a_max vs optimum over the "
                          "stress sweep; act_sweep: layer us vs number of activated experts; skew: same "
                          "activated set with an even and a Zipf split of the requests; batch_sweep: layer "
@@ -64,7 +64,8 @@ def main() -> None:
                          "layout of Alg. 3 (Appendix B) against the contiguous layout on traces with topics; scaling: "
                          "Alg. 2 fed with the measured MoE-side coefficients and a_max table; shared: the step with a "
                          "shared expert run on the instance; graph: the step queued eagerly against the same steps "
-                         "replayed from a captured HIP graph")
+                         "replayed from a captured HIP graph; configs: one line per workload configuration and "
+                         "token count of the workload list")
     args = ap.parse_args()
     if args.gpus != 1:
         raise SystemExit("this build runs on ONE GPU: the other MoE instances exist only as replica placement "
@@ -97,6 +98,8 @@ def main() -> None:
         return shared_step(args)
     if args.mode == "graph":
         return graph_step(args)
+    if args.mode == "configs":
+        return all_configs(args)
     cfg = make_cfg(args.workload, args.tokens)
     lay = W.build_placement(cfg)
     T, k, C, d_h, d_e = cfg.T, cfg.k, cfg.C, cfg.d_h, cfg.d_e
@@ -638,6 +641,73 @@ def amax_study(args) -> None:
                               "a_max_aebs_mean_first16": round(float(amax[0][:n_opt].mean()), 2),
                               "eq4_expected_max": round(a_bar, 2), "eq5_bound": bounds.a_max_bound(a_bar, C, n_inst)}),
                   flush=True)
+
+
+def all_configs(args) -> None:
+    """One line per configuration and token count of the workload list: the step (front + FFN +
+    combine, queued back to back over a ring of batches and weight copies) on the instance with the
+    largest load of batch 0, the FFN launch alone, the activated experts and requests of that
+    instance, and the FFN's algorithmic GB/s and fraction of the 8 TB/s peak."""
+    import numpy as np
+    import torch
+    from paper_2512_13525_amd import workloads as W
+    from paper_2512_13525_amd.layer import LayerStep, to_device_bf16
+
+    cfgs = [W.tiny(), W.dsv2lite(128), W.qwen3(32), W.qwen3(256), W.qwen3(1024), W.dsv3(512)]
+    cfgs += [W.stress(T, 1.25, 0.8) for T in (64, 512, 2048, 8192)]
+    for cfg in cfgs:
+        lay = W.build_placement(cfg)
+        T, k, C, d_h, d_e = cfg.T, cfg.k, cfg.C, cfg.d_h, cfg.d_e
+        bf16 = cfg.dtype == "bf16"
+        esz = 2 if bf16 else 4
+        n_ring = max(2, min(8, int(-(-args.ring_bytes // (C * 3 * d_h * d_e * esz)))))
+        gen = torch.Generator(device="cuda").manual_seed(cfg.seed)
+        tdt = torch.bfloat16 if bf16 else torch.float32
+        W13s = [(torch.randn((C, 2 * d_e, d_h), generator=gen, device="cuda") * 0.02).to(tdt) for _ in range(n_ring)]
+        W2s = [(torch.randn((C, d_h, d_e), generator=gen, device="cuda") * 0.02).to(tdt) for _ in range(n_ring)]
+        logits = [torch.from_numpy(W.router_logits(cfg, sub=i)).cuda() for i in range(n_ring)]
+        Xs = [to_device_bf16(W.activations(cfg, sub=i)) if bf16 else torch.from_numpy(W.activations(cfg, sub=i)).cuda()
+              for i in range(n_ring)]
+        s = LayerStep(cfg, lay, 0)
+        s.route(logits[0]); s.schedule()
+        torch.cuda.synchronize()
+        s = LayerStep(cfg, lay, int(torch.argmax(s.load).item()))
+        a_g, n_local = [], []
+        for j in range(n_ring):
+            s.step_fused(logits[j], Xs[j], W13=W13s[j], W2=W2s[j])
+            torch.cuda.synchronize()
+            cnt = s.slot_count.cpu().numpy()
+            a_g.append(int((cnt > 0).sum())); n_local.append(int(cnt.sum()))
+        i = [0]
+
+        def nxt():
+            i[0] += 1
+            return i[0] % n_ring
+
+        def step():
+            j = nxt()
+            s.step_fused(logits[j], Xs[j], W13=W13s[j], W2=W2s[j])
+
+        def ffn():
+            j = nxt()
+            s.ffn(Xs[j], W13=W13s[j], W2=W2s[j])
+
+        def front():
+            s.front(logits[nxt()])
+
+        reps = 200 if T <= 1024 else 50
+        step_us, front_us = _time_us(step, reps), _time_us_graph(front, 20, 4)
+        ffn_us = _time_us(ffn, reps)          # the dispatch of the last step stays in place: the batch of copy j
+        bytes_ffn = float(np.mean([a * 3 * d_h * d_e * esz + min(T, n) * d_h * esz + n * d_h * 4 for a, n in zip(a_g, n_local)]))
+        gbps = bytes_ffn / (ffn_us * 1e-6) / 1e9
+        print(json.dumps({"mode": "configs", "workload": cfg.name, "T": T, "dtype": cfg.dtype, "E": cfg.E, "k": k,
+                          "d_h": d_h, "d_e": d_e, "n_inst": cfg.n_inst, "C": C,
+                          "activated_a_g_mean": round(float(np.mean(a_g)), 2), "n_local_mean": round(float(np.mean(n_local)), 1),
+                          "step_us": round(step_us, 2), "front_us": round(front_us, 2), "ffn_us": round(ffn_us, 2),
+                          "ffn_algorithmic_MB": round(bytes_ffn / 1e6, 1), "ffn_GBps": round(gbps, 1),
+                          "ffn_frac_of_8TBps": round(gbps / HBM_PEAK_GBPS, 3)}), flush=True)
+        del W13s, W2s, s
+        torch.cuda.empty_cache()
 
 
 def graph_step(args) -> None:
