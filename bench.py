@@ -52,6 +52,8 @@ def main() -> None:
     ap.add_argument("--workload", default="dsv2lite", choices=["dsv2lite", "qwen3", "dsv3", "stress"])
     ap.add_argument("--tokens", type=int, default=None)
     ap.add_argument("--ring-bytes", type=float, default=1.25e9, help="minimum total bytes of rotating weight copies")
+    ap.add_argument("--rows-per-slot", type=int, default=0,
+                    help="act_sweep: requests on every activated slot (0 = spread all T*k requests over them)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-events", action="store_true", help="do not record per-kernel events in the timed region")
     ap.add_argument("--mode", default="step", choices=["step", "sched", "act_sweep", "skew", "batch_sweep", "amax", "gate", "placement", "scaling", "shared", "graph", "configs"],
@@ -488,9 +490,15 @@ def act_sweep(args) -> None:
     X = to_device_bf16(W.activations(cfg))
     step.topk_w.fill_(1.0 / k)
     pts = []
-    for a in range(1, C + 1):
-        # every request goes to one of the first `a` local slots of instance 0, round-robin
-        rid = (np.arange(T * k, dtype=np.int32) % a).reshape(T, k)
+    a_hi = min(C, T * k // args.rows_per_slot) if args.rows_per_slot else C
+    for a in range(1, a_hi + 1):
+        # every request goes to one of the first `a` local slots of instance 0, round-robin; with
+        # --rows-per-slot only a*rows requests do and the others are not local
+        rid = np.arange(T * k, dtype=np.int32) % a
+        if args.rows_per_slot:
+            assert args.rows_per_slot <= T and a * args.rows_per_slot <= T * k
+            rid = np.where(np.arange(T * k) < a * args.rows_per_slot, rid, C * 1000).astype(np.int32)
+        rid = rid.reshape(T, k)
         step.rid.copy_(torch.from_numpy(rid))
         i = [0]
 
@@ -510,7 +518,8 @@ def act_sweep(args) -> None:
         ffn_us = _time_us(ffn_only, 100)
         gbps = a * 3 * d_h * d_e * 2 / (ffn_us * 1e-6) / 1e9
         pts.append((a, us))
-        print(json.dumps({"mode": "act_sweep", "workload": cfg.name, "T": T, "activated": a, "layer_us": round(us, 2),
+        print(json.dumps({"mode": "act_sweep", "workload": cfg.name, "T": T, "activated": a,
+                          "rows_per_slot": args.rows_per_slot or round(T * k / a, 1), "layer_us": round(us, 2),
                           "ffn_us": round(ffn_us, 2), "ffn_weight_GBps": round(gbps, 1),
                           "pct_hbm_peak": round(100 * gbps / HBM_PEAK_GBPS, 1)}), flush=True)
     xs = np.array([p[0] for p in pts], dtype=np.float64)
@@ -807,7 +816,8 @@ def shared_step(args) -> None:
 
 def scaling_study(args) -> None:
     """Alg. 2 (Sec. 3.5) on this machine's measurements: the MoE-side coefficients of Eq. 1c
-    (beta, c_e) are fitted from layer times of the default workload's shape at 6 activation counts,
+    (beta, c_e) are fitted from layer times of the default workload's shape at 6 activation counts
+    (16 requests on every activated slot),
     a_max(n_e, B) is the Monte-Carlo mean of Alg. 1 on the GPU over 100 sampled batches per cell;
     the attention-side and communication coefficients have no counterpart in this build and are
     stated stand-ins.  Times in microseconds, demand in requests per microsecond."""
@@ -829,7 +839,9 @@ def scaling_study(args) -> None:
     step.topk_w.fill_(1.0 / k)
     pts = []
     for a in (2, 5, 8, 11, 14, 17):
-        step.rid.copy_(torch.from_numpy((np.arange(T * k, dtype=np.int32) % a).reshape(T, k)))
+        # 16 requests on every activated slot, the other requests of the batch on other instances
+        rid = np.where(np.arange(T * k) < a * 16, np.arange(T * k) % a, C * 1000).astype(np.int32)
+        step.rid.copy_(torch.from_numpy(rid.reshape(T, k)))
         i = [0]
 
         def layer():
