@@ -233,6 +233,15 @@ def main() -> None:
     stage_us["front_fused"] = round(statistics.median(te2.us(a, b) for a, b in fm), 2)
     te2.close()
 
+    # ---- one step at a time: submit, wait, host wall clock (launch and completion latency included)
+    single = []
+    for i in range(min(args.steps, 50)):
+        torch.cuda.synchronize()
+        c0 = time.perf_counter()
+        run_step(i)
+        torch.cuda.synchronize()
+        single.append((time.perf_counter() - c0) * 1e6)
+
     out = {
         "metric": "moe_layer_step_algorithmic_GBps", "value": round(value, 1), "unit": "GB/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
@@ -248,6 +257,9 @@ def main() -> None:
         "n_local_mean": round(statistics.mean(n_local), 1),
         "stage_us_median": stage_us,
         "launches_per_step": 3,
+        "single_step_latency_us": {"p50": round(statistics.median(single), 1),
+                                   "p10": round(float(np.percentile(single, 10)), 1),
+                                   "p90": round(float(np.percentile(single, 90)), 1)},
         "sched_us": stage_us["schedule"],
         "layer_us_permute_ffn_combine": round(stage_us["permute"] + stage_us["ffn"] + stage_us["combine"], 2),
         "roofline": roofline,
