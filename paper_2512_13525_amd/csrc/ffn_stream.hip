@@ -14,8 +14,11 @@
 // The 4 wavefronts of a workgroup split the K dimension of the tile round-robin in super-steps
 // of 64 columns and meet in LDS once, at the end (fixed summation order: results are
 // reproducible).  Per super-step a wavefront reads 4 KiB of weights (packed MFMA A-operand
-// images, fully coalesced 128-bit loads, two super-steps ahead) and one 128-byte line of each
-// token row (the B operand, from L2, one super-step ahead).
+// images, fully coalesced 128-bit loads, two super-steps ahead) and the token rows (the B operand,
+// from L2).  In stage 1 those are gathered rows of X: one 128-byte line of each row, one super-step
+// ahead, turned into the MFMA layout through a wave-private LDS tile.  Stage 1 writes `act` as
+// B-operand images, so stage 2 reads its token fragments like the weights, straight into
+// registers and as far ahead.
 //
 // Both stages run in ONE launch: the stage-2 workgroups have the higher ids, so the hardware
 // starts them only after every stage-1 workgroup has been started, and they fill the compute
@@ -113,10 +116,14 @@ __device__ __forceinline__ void reduce_store(const StreamArgs &a, const StageArg
                                    static_cast<uint64_t>(moe::f32_to_bf16(silu_mul(gt[1], up[1]))) << 16 |
                                    static_cast<uint64_t>(moe::f32_to_bf16(silu_mul(gt[2], up[2]))) << 32 |
                                    static_cast<uint64_t>(moe::f32_to_bf16(silu_mul(gt[3], up[3]))) << 48;
-                // act block of this item: [tile][TT*16 rows][16 channels], one writer per 128-byte line
+                // act block of this item: [K-step of stage 2][token tile][64 lanes][16 B], the register image of
+                // the MFMA B operand (lane: row % 16, channels (lane / 16) * 8 .. + 7 of the K-step's 32); this
+                // tile is half a K-step, and every 128-byte line of the image has one writing workgroup
+                const int fl = (l & 15) + 16 * ((tile & 1) * 2 + (l >> 5));
                 uint64_t *dst = reinterpret_cast<uint64_t *>(
-                    reinterpret_cast<char *>(a.act) + (static_cast<size_t>(item_id) * g.tiles + tile) * (TT * 512) +
-                    (brow + t * 16 + (l & 15)) * 32 + (l >> 4) * 8);
+                    reinterpret_cast<char *>(a.act) +
+                    ((static_cast<size_t>(item_id) * (g.tiles >> 1) + (tile >> 1)) * TT + (brow >> 4) + t) * 1024 +
+                    fl * 16 + ((l >> 4) & 1) * 8);
                 __hip_atomic_store(dst, o, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
         }
@@ -162,16 +169,15 @@ __device__ __forceinline__ void wait_block_ready(const StreamArgs &a, int item, 
     lds_barrier();
 }
 
-// One item with an even number of K-steps.  A super-step is two K-steps = 64 columns = one
-// 128-byte line of every token row (in stage 2: the 32-byte pieces of 4 consecutive stage-1 tiles).
+// One stage-1 item with an even number of K-steps.  A super-step is two K-steps = 64 columns = one
+// 128-byte line of every token row.
 // A token load instruction fetches whole lines (lane l: row l/8, 16-byte chunk l%8), so no line
 // is requested twice and none by halves; the MFMA layout (lane l: row l%16, 16-byte chunk 4*step + l/16) is produced by a
 // round trip through a wave-private 2 KiB LDS tile per 16 rows (chunks XOR-swizzled by row so
 // that both the row-major writes and the column-wise reads spread over the banks).  NH = number
 // of 8-row halves that hold requests (rows past the end repeat the last row; halves past it are
 // not loaded and leave unspecified values in token columns whose results are never stored).
-// WAIT: the token rows are `act` rows that other workgroups of this launch produce.
-template <bool STAGE1, int NH, bool WAIT, int TT>
+template <int NH, int TT>
 __device__ __forceinline__ void stream_item_lines(const StreamArgs &a, const StageArgs &g, char *lds,
                                                   const char *w, int item, int tile, int row0, int row_end,
                                                   int wave, int lane) {
@@ -184,23 +190,17 @@ __device__ __forceinline__ void stream_item_lines(const StreamArgs &a, const Sta
     uint32_t boff[NH];
 #pragma unroll
     for (int h = 0; h < NH; ++h) {
-        if (STAGE1) {
-            int r = row0 + h * 8 + (lane >> 3);
-            r = r < row_end ? r : row_end - 1;
-            boff[h] = static_cast<uint32_t>(a.perm[r] / a.k) * static_cast<uint32_t>(g.b_stride) * 2 + (lane & 7) * 16;
-        } else {
-            // act block: [tile][TT*16 rows][16 channels]; chunk c of a super-step = tile c/2, half c%2
-            boff[h] = ((lane & 7) >> 1) * (TT * 512) + (h * 8 + (lane >> 3)) * 32 + (lane & 1) * 16;
-        }
+        int r = row0 + h * 8 + (lane >> 3);
+        r = r < row_end ? r : row_end - 1;
+        boff[h] = static_cast<uint32_t>(a.perm[r] / a.k) * static_cast<uint32_t>(g.b_stride) * 2 + (lane & 7) * 16;
     }
     // LDS: row R of a tile at R*128, its 16-byte chunk c at ((c ^ ((R >> 1) & 7)) * 16): the 16 rows a
     // fragment read touches fall into 16 different bank groups.  wr_lds[p]: rows of an even / odd half.
     const uint32_t wr_lds[2] = {static_cast<uint32_t>(((lane >> 3) * 128) + (((lane & 7) ^ (lane >> 4)) * 16)),
                                 static_cast<uint32_t>(((lane >> 3) * 128) + (((lane & 7) ^ (4 + (lane >> 4))) * 16))};
     const uint32_t rd_row = (lane & 15) * 128, rd_sw = (lane >> 1) & 7, rd_g = lane >> 4;
-    const char *bbase = STAGE1 ? reinterpret_cast<const char *>(g.B)
-                               : reinterpret_cast<const char *>(g.B) + static_cast<size_t>(item) * a.s[0].tiles * (TT * 512);
-    constexpr int kBStep = STAGE1 ? 128 : 4 * TT * 512;                  // bytes a super-step advances the token operand
+    const char *bbase = reinterpret_cast<const char *>(g.B);
+    constexpr int kBStep = 128;                                  // bytes a super-step advances a token row
     const int n = (g.KS / 2 - wave + kWaves - 1) / kWaves;      // super-steps wave, wave+4, ... of this wavefront
     f32x4 acc[2][NT];
 #pragma unroll
@@ -259,20 +259,10 @@ __device__ __forceinline__ void stream_item_lines(const StreamArgs &a, const Sta
             }                                                                                    \
         asm volatile("" ::: "memory");                                                           \
     } while (0)
-    if (WAIT) {
-        // weights first: they do not depend on stage 1
-        if (n > 0) {
-#pragma unroll
-            for (int d = 0; d < D; ++d) MOE_LOAD_A(d, d);
-        }
-        wait_block_ready(a, item, tile, g.tiles);
-    }
     if (n > 0) {
         MOE_LOAD_B(0);
-        if (!WAIT) {
 #pragma unroll
-            for (int d = 0; d < D; ++d) MOE_LOAD_A(d, d);
-        }
+        for (int d = 0; d < D; ++d) MOE_LOAD_A(d, d);
         int i = 0;
         for (; i + 2 * D <= n; i += D) {
 #pragma unroll
@@ -304,13 +294,13 @@ __device__ __forceinline__ void stream_item_lines(const StreamArgs &a, const Sta
 #undef MOE_STAGE_B
 #undef MOE_MMA_STEP
     __syncthreads();                                             // the staging tiles are reused for the reduction
-    reduce_store<STAGE1, NT, TT>(a, g, red, acc, item, 0, tile, row0, row_end, wave, lane);
+    reduce_store<true, NT, TT>(a, g, red, acc, item, 0, tile, row0, row_end, wave, lane);
 }
 
-// One item with an odd number of K-steps (shapes that are multiples of 32 but not of 64): single
+// One stage-1 item with an odd number of K-steps (shapes that are multiples of 32 but not of 64): single
 // K-steps, token rows read 64 bytes at a time straight into the MFMA layout (lane l: row l%16,
 // 16 bytes at (l/16)*16), four steps of weights and tokens in flight.
-template <bool STAGE1, int NT, bool WAIT, int TT>
+template <int NT, int TT>
 __device__ __forceinline__ void stream_item_steps(const StreamArgs &a, const StageArgs &g, char *lds,
                                                   const char *w, int item, int brow, int tile, int row0, int row_end,
                                                   int wave, int lane) {
@@ -320,18 +310,12 @@ __device__ __forceinline__ void stream_item_steps(const StreamArgs &a, const Sta
     uint32_t boff[NT];
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
-        if (STAGE1) {
-            int r = row0 + t * 16 + (lane & 15);
-            r = r < row_end ? r : row_end - 1;
-            boff[t] = (static_cast<uint32_t>(a.perm[r] / a.k) * static_cast<uint32_t>(g.b_stride) + (lane >> 4) * 8) * 2;
-        } else {
-            // act block: [tile][TT*16 rows][16 channels]; a K-step = 2 tiles, chunk l/16 = tile (l/16)/2, half (l/16)%2
-            boff[t] = (lane >> 5) * (TT * 512) + (brow + t * 16 + (lane & 15)) * 32 + ((lane >> 4) & 1) * 16;
-        }
+        int r = row0 + t * 16 + (lane & 15);
+        r = r < row_end ? r : row_end - 1;
+        boff[t] = (static_cast<uint32_t>(a.perm[r] / a.k) * static_cast<uint32_t>(g.b_stride) + (lane >> 4) * 8) * 2;
     }
-    const char *bbase = STAGE1 ? reinterpret_cast<const char *>(g.B)
-                               : reinterpret_cast<const char *>(g.B) + static_cast<size_t>(item) * a.s[0].tiles * (TT * 512);
-    constexpr int kBStep = STAGE1 ? 64 : 2 * TT * 512;                   // bytes a K-step advances the token operand
+    const char *bbase = reinterpret_cast<const char *>(g.B);
+    constexpr int kBStep = 64;                                   // bytes a K-step advances a token row
     const int n = (g.KS - wave + kWaves - 1) / kWaves;          // K-steps wave, wave+4, ... of this wavefront
     f32x4 acc[2][NT];
 #pragma unroll
@@ -339,7 +323,6 @@ __device__ __forceinline__ void stream_item_steps(const StreamArgs &a, const Sta
 #pragma unroll
         for (int t = 0; t < NT; ++t) acc[h][t] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    if (WAIT && brow == 0) wait_block_ready(a, item, tile, g.tiles);
     if (n > 0) {
         bf16x8 wr[D][2], br[D][NT];
         const int last = n - 1;
@@ -387,10 +370,100 @@ __device__ __forceinline__ void stream_item_steps(const StreamArgs &a, const Sta
 #undef MOE_LOAD_STEP
 #undef MOE_MMA_STEP
     }
-    reduce_store<STAGE1, NT, TT>(a, g, red, acc, item, brow, tile, row0, row_end, wave, lane);
+    reduce_store<true, NT, TT>(a, g, red, acc, item, brow, tile, row0, row_end, wave, lane);
 }
 
-template <bool STAGE1, bool LINES, bool WAIT, int TT>
+// Stage 2 of one item.  Stage 1 leaves the block's rows of `act` as MFMA B-operand images, so a
+// token fragment is one coalesced 1 KiB load straight into registers, like a weight fragment, with
+// no LDS on the way.  A step is U K-steps (U = 2, 4 KiB of contiguous weights, when the number of
+// K-steps is even and the token tiles leave room in the registers); the steps go round-robin over
+// the wavefronts, 4 / U or 3 of them in flight for both operands, the weights issued before the
+// wait for the block (they do not depend on stage 1).
+template <int NT, int TT, int U>
+__device__ __forceinline__ void stream_item_down(const StreamArgs &a, const StageArgs &g, char *lds,
+                                                 const char *w, int item, int tile, int row0, int row_end,
+                                                 int wave, int lane) {
+    constexpr int D = U == 2 ? 2 : NT > 2 ? 3 : 4;               // steps in flight that fit the registers
+    f32x4 (*red)[2][TT][MOE_WAVE] = reinterpret_cast<f32x4 (*)[2][TT][MOE_WAVE]>(lds);
+    const uint32_t aoff = lane * 16;
+    const char *bbase = reinterpret_cast<const char *>(g.B) + static_cast<size_t>(item) * g.KS * (TT * 1024) + aoff;
+    const int n = (g.KS / U - wave + kWaves - 1) / kWaves;      // steps wave, wave+4, ... of this wavefront
+    f32x4 acc[2][NT];
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+        for (int t = 0; t < NT; ++t) acc[h][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+    bf16x8 wr[D][U][2], br[D][U][NT];
+    const int last = n > 0 ? n - 1 : 0;
+    const int rot = n > 0 ? static_cast<int>(static_cast<unsigned>(tile) % static_cast<unsigned>(n)) : 0;
+#define MOE_STEP_INDEX(step)                                                                     \
+        const int q_ = (step);                                                                   \
+        int r_ = (q_ < last ? q_ : last) + rot;                                                  \
+        r_ = r_ >= n ? r_ - n : r_;                                                              \
+        const int s_ = wave + kWaves * r_;
+#define MOE_LOAD_W(d, step)                                                                      \
+    do {                                                                                         \
+        MOE_STEP_INDEX(step)                                                                     \
+        const char *ws_ = w + static_cast<size_t>(s_) * (U * 2048) + aoff;                       \
+        _Pragma("unroll") for (int u = 0; u < U; ++u) {                                          \
+            wr[d][u][0] = *reinterpret_cast<const bf16x8 *>(ws_ + u * 2048);                     \
+            wr[d][u][1] = *reinterpret_cast<const bf16x8 *>(ws_ + u * 2048 + 1024);              \
+        }                                                                                        \
+        asm volatile("" ::: "memory");                                                           \
+    } while (0)
+#define MOE_LOAD_T(d, step)                                                                      \
+    do {                                                                                         \
+        MOE_STEP_INDEX(step)                                                                     \
+        const char *bs_ = bbase + static_cast<size_t>(s_) * (U * TT * 1024);                     \
+        _Pragma("unroll") for (int u = 0; u < U; ++u)                                            \
+            _Pragma("unroll") for (int t = 0; t < NT; ++t)                                       \
+                br[d][u][t] = *reinterpret_cast<const bf16x8 *>(bs_ + (u * TT + t) * 1024);      \
+        asm volatile("" ::: "memory");                                                           \
+    } while (0)
+#define MOE_MMA_STEP(d)                                                                          \
+    do {                                                                                         \
+        _Pragma("unroll") for (int u = 0; u < U; ++u)                                            \
+            _Pragma("unroll") for (int t = 0; t < NT; ++t) {                                     \
+                acc[0][t] = mfma16(wr[d][u][0], br[d][u][t], acc[0][t]);                         \
+                acc[1][t] = mfma16(wr[d][u][1], br[d][u][t], acc[1][t]);                         \
+            }                                                                                    \
+    } while (0)
+    if (n > 0) {
+#pragma unroll
+        for (int d = 0; d < D; ++d) MOE_LOAD_W(d, d);
+    }
+    wait_block_ready(a, item, tile, g.tiles);
+    if (n > 0) {
+#pragma unroll
+        for (int d = 0; d < D; ++d) MOE_LOAD_T(d, d);
+        int i = 0;
+        for (; i + 2 * D <= n; i += D) {
+#pragma unroll
+            for (int d = 0; d < D; ++d) {
+                MOE_MMA_STEP(d);
+                MOE_LOAD_W(d, i + d + D);
+                MOE_LOAD_T(d, i + d + D);
+            }
+        }
+        const int rem = n - i;                                   // 1 .. 2*D-1 steps left
+#pragma unroll
+        for (int d = 0; d < D; ++d) {
+            if (d < rem) MOE_MMA_STEP(d);
+            if (d < D - 1) { MOE_LOAD_W(d, i + d + D); MOE_LOAD_T(d, i + d + D); }
+        }
+#pragma unroll
+        for (int d = 0; d < D - 1; ++d)
+            if (D + d < rem) MOE_MMA_STEP(d);
+    }
+#undef MOE_STEP_INDEX
+#undef MOE_LOAD_W
+#undef MOE_LOAD_T
+#undef MOE_MMA_STEP
+    reduce_store<false, NT, TT>(a, g, red, acc, item, 0, tile, row0, row_end, wave, lane);
+}
+
+// LINES: this stage has an even number of K-steps
+template <bool STAGE1, bool LINES, int TT>
 __device__ __forceinline__ void run_item(const StreamArgs &a, const StageArgs &g, char *lds, unsigned id) {
     const int tile = id % g.tiles_pad, item = id / g.tiles_pad;
     if (tile >= g.tiles) return;
@@ -407,9 +480,18 @@ __device__ __forceinline__ void run_item(const StreamArgs &a, const StageArgs &g
     const int slot = ent.x, row0 = ent.y, hi = ent.z;
     const char *w = g.Wp + (static_cast<size_t>(slot) * g.tiles + tile) * g.KS * 2048;
     const int m = hi - row0;
-    if (LINES) {
+    if constexpr (!STAGE1) {
+        const int tiles16 = ((m < TT * 16 ? m : TT * 16) + 15) >> 4;     // 16-row token tiles that hold requests
+#define MOE_CASE(NT, U) case NT: stream_item_down<NT, TT, U>(a, g, lds, w, item, tile, row0, hi, wave, lane); break;
+        if constexpr (TT == 2) {
+            switch (tiles16) { MOE_CASE(1, LINES ? 2 : 1) MOE_CASE(2, LINES ? 2 : 1) }
+        } else {
+            switch (tiles16) { MOE_CASE(1, LINES ? 2 : 1) MOE_CASE(2, LINES ? 2 : 1) MOE_CASE(3, 1) MOE_CASE(4, 1) }
+        }
+#undef MOE_CASE
+    } else if (LINES) {
         const int halves = ((m < TT * 16 ? m : TT * 16) + 7) >> 3;     // 8-row halves that hold requests
-#define MOE_CASE(NH) case NH: stream_item_lines<STAGE1, NH, WAIT, TT>(a, g, lds, w, item, tile, row0, hi, wave, lane); break;
+#define MOE_CASE(NH) case NH: stream_item_lines<NH, TT>(a, g, lds, w, item, tile, row0, hi, wave, lane); break;
         if constexpr (TT == 2) {
             switch (halves) { MOE_CASE(1) MOE_CASE(2) MOE_CASE(3) MOE_CASE(4) }
         } else {
@@ -421,8 +503,8 @@ __device__ __forceinline__ void run_item(const StreamArgs &a, const StageArgs &g
         const int end = m < TT * 16 ? hi : row0 + TT * 16;
         for (int brow = 0; row0 + brow < end; brow += 32) {
             if (brow) __syncthreads();                           // the reduction buffer is reused
-            if (end - (row0 + brow) <= 16) stream_item_steps<STAGE1, 1, WAIT, TT>(a, g, lds, w, item, brow, tile, row0 + brow, end, wave, lane);
-            else stream_item_steps<STAGE1, 2, WAIT, TT>(a, g, lds, w, item, brow, tile, row0 + brow, end, wave, lane);
+            if (end - (row0 + brow) <= 16) stream_item_steps<1, TT>(a, g, lds, w, item, brow, tile, row0 + brow, end, wave, lane);
+            else stream_item_steps<2, TT>(a, g, lds, w, item, brow, tile, row0 + brow, end, wave, lane);
         }
     }
     if (STAGE1) {
@@ -480,8 +562,8 @@ void ffn_stream_kernel(StreamArgs a) {
         const unsigned lanes = n_blocks < moe::kFfnLaneBlocks ? n_blocks : moe::kFfnLaneBlocks;
         const unsigned n1 = lanes * a.s[0].tiles_pad, n2 = lanes * a.s[1].tiles_pad;
         if (n_blocks <= lanes) {
-            if (blockIdx.x < n1) run_item<true, LINES1, false, TT>(a, a.s[0], lds, blockIdx.x);
-            else if (blockIdx.x - n1 < n2) run_item<false, LINES2, true, TT>(a, a.s[1], lds, blockIdx.x - n1);
+            if (blockIdx.x < n1) run_item<true, LINES1, TT>(a, a.s[0], lds, blockIdx.x);
+            else if (blockIdx.x - n1 < n2) run_item<false, LINES2, TT>(a, a.s[1], lds, blockIdx.x - n1);
         } else if (blockIdx.x < n1 + n2) {
             // a long list: the first wavefront looks at all the blocks of this workgroup at once (lane l:
             // block + l*lanes) and the workgroup then visits only those that are its own to compute
@@ -507,8 +589,8 @@ void ffn_stream_kernel(StreamArgs a) {
                 visit &= visit - 1;
                 if (!first) __syncthreads();                         // the LDS buffer is reused
                 first = false;
-                if (s1) run_item<true, LINES1, false, TT>(a, a.s[0], lds, id0 + l * n1);
-                else run_item<false, LINES2, true, TT>(a, a.s[1], lds, id0 + l * n2);
+                if (s1) run_item<true, LINES1, TT>(a, a.s[0], lds, id0 + l * n1);
+                else run_item<false, LINES2, TT>(a, a.s[1], lds, id0 + l * n2);
             }
         }
     }
