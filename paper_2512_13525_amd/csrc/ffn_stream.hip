@@ -208,13 +208,16 @@ __device__ __forceinline__ void stream_item_lines(const StreamArgs &a, const Sta
 #pragma unroll
         for (int t = 0; t < NT; ++t) acc[h][t] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    // Weights run D super-steps ahead (ring wr); the token rows, which come from L2, only one:
-    // the loads of super-step q+1 are issued in iteration q *before* the weights of q+D, so that
-    // waiting for them (loads return in order) leaves those weights in flight.  The steady-state
+    // Weights run D super-steps ahead (ring wr); the token rows DB super-steps: the loads of
+    // super-step q+DB are issued in iteration q *before* the weights of q+D.  Loads return in order,
+    // so waiting for the token rows of the next super-step also waits for every older weight load:
+    // with DB = 1 only the newest super-step of weights stays in flight across that wait, with
+    // DB = 2 (where the registers allow it: blocks of up to 16 rows, 32 in the 64-row kernel) two do.  The steady-state
     // loop has no branch, so the compiler counts outstanding loads exactly.  Loads past the last
     // super-step fetch the last one again (a cache hit): every load is unconditional.
+    constexpr int DB = (NH <= 4) ? D : 1;                        // D: the two rings share their positions
     bf16x8 wr[D][2][2];
-    bf16x8 br[NH];
+    bf16x8 br[DB][NH];
     const int last = n > 0 ? n - 1 : 0;
     // Workgroups start their K loop at different places (and wrap around) so that they do not
     // march through equally aligned tiles in lockstep.
@@ -234,18 +237,18 @@ __device__ __forceinline__ void stream_item_lines(const StreamArgs &a, const Sta
         }                                                                                        \
         asm volatile("" ::: "memory");                                                           \
     } while (0)
-#define MOE_LOAD_B(step)                                                                         \
+#define MOE_LOAD_B(d, step)                                                                      \
     do {                                                                                         \
         MOE_STEP_INDEX(step)                                                                     \
         const char *bs_ = bbase + static_cast<size_t>(s_) * kBStep;                              \
         _Pragma("unroll") for (int h = 0; h < NH; ++h)                                           \
-            br[h] = *reinterpret_cast<const bf16x8 *>(bs_ + boff[h]);                            \
+            br[(d) % DB][h] = *reinterpret_cast<const bf16x8 *>(bs_ + boff[h]);                  \
         asm volatile("" ::: "memory");                                                           \
     } while (0)
-#define MOE_STAGE_B()                                                                            \
+#define MOE_STAGE_B(d)                                                                           \
     do {                                                                                         \
         _Pragma("unroll") for (int h = 0; h < NH; ++h)                                           \
-            *reinterpret_cast<bf16x8 *>(stg + (h / 2) * 2048 + (h % 2) * 1024 + wr_lds[h % 2]) = br[h]; \
+            *reinterpret_cast<bf16x8 *>(stg + (h / 2) * 2048 + (h % 2) * 1024 + wr_lds[h % 2]) = br[(d) % DB][h]; \
         asm volatile("" ::: "memory");                                                           \
     } while (0)
 #define MOE_MMA_STEP(d)                                                                          \
@@ -260,15 +263,18 @@ __device__ __forceinline__ void stream_item_lines(const StreamArgs &a, const Sta
         asm volatile("" ::: "memory");                                                           \
     } while (0)
     if (n > 0) {
-        MOE_LOAD_B(0);
+        // issue order of the first loads: tokens of a super-step before its weights
 #pragma unroll
-        for (int d = 0; d < D; ++d) MOE_LOAD_A(d, d);
+        for (int d = 0; d < D; ++d) {
+            if (d < DB) MOE_LOAD_B(d, d);
+            MOE_LOAD_A(d, d);
+        }
         int i = 0;
         for (; i + 2 * D <= n; i += D) {
 #pragma unroll
             for (int d = 0; d < D; ++d) {
-                MOE_STAGE_B();
-                MOE_LOAD_B(i + d + 1);
+                MOE_STAGE_B(d);
+                MOE_LOAD_B(d + DB, i + d + DB);
                 MOE_MMA_STEP(d);
                 MOE_LOAD_A(d, i + d + D);
             }
@@ -276,15 +282,14 @@ __device__ __forceinline__ void stream_item_lines(const StreamArgs &a, const Sta
         const int rem = n - i;                                   // 1 .. 2*D-1 super-steps left
 #pragma unroll
         for (int d = 0; d < D; ++d) {
-            MOE_STAGE_B();
-            MOE_LOAD_B(i + d + 1);
+            MOE_STAGE_B(d);
+            MOE_LOAD_B(d + DB, i + d + DB);
             if (d < rem) MOE_MMA_STEP(d);
             if (d < D - 1) MOE_LOAD_A(d, i + d + D);
         }
 #pragma unroll
         for (int d = 0; d < D - 1; ++d) {
-            MOE_STAGE_B();
-            if (d < D - 2) MOE_LOAD_B(i + D + d + 1);
+            MOE_STAGE_B(D + d);
             if (D + d < rem) MOE_MMA_STEP(d);
         }
     }
