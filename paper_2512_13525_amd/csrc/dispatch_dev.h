@@ -23,19 +23,58 @@ __device__ __forceinline__ uint64_t readfirstlane_u64(uint64_t v) {
 }
 
 // ------------------------------------------------------------------ a0: one token per wavefront
-__device__ __forceinline__ uint64_t wave_max_u64(uint64_t v) {
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) {
-        uint64_t o = __shfl_xor(v, off, MOE_WAVE);
-        v = o > v ? o : v;
-    }
-    return v;
+// Largest key of the wavefront, in every lane.  Data-parallel-primitive moves instead of LDS-crossbar
+// shuffles (the k selection rounds of a token are a chain of these): two exchanges inside quads, two
+// rotations inside rows of 16 lanes, then the row results travel to the last lane through the two
+// row broadcasts, and a scalar lane read hands the result to everybody.  Lanes a move does not
+// write read 0, the smallest key.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ uint64_t dpp_max_step(uint64_t v) {
+    const uint32_t lo = __builtin_amdgcn_update_dpp(0, static_cast<int>(v & 0xffffffffu), CTRL, ROW_MASK, 0xf, false);
+    const uint32_t hi = __builtin_amdgcn_update_dpp(0, static_cast<int>(v >> 32), CTRL, ROW_MASK, 0xf, false);
+    const uint64_t o = (static_cast<uint64_t>(hi) << 32) | lo;
+    return o > v ? o : v;
 }
 
+__device__ __forceinline__ uint64_t wave_max_u64(uint64_t v) {
+    v = dpp_max_step<0xB1, 0xf>(v);                      // quad_perm [1,0,3,2]
+    v = dpp_max_step<0x4E, 0xf>(v);                      // quad_perm [2,3,0,1]
+    v = dpp_max_step<0x124, 0xf>(v);                     // row_ror:4
+    v = dpp_max_step<0x128, 0xf>(v);                     // row_ror:8   -> every lane: its row's largest
+    v = dpp_max_step<0x142, 0xa>(v);                     // row_bcast:15 into rows 1 and 3
+    v = dpp_max_step<0x143, 0xc>(v);                     // row_bcast:31 into rows 2 and 3 -> lane 63: the largest
+    return readlane_u64(v, MOE_WAVE - 1);
+}
+
+// Inclusive prefix sum over the 64 lanes with the same moves: three shifts of the input and two of
+// the partial sums inside rows of 16 lanes (lanes without a source add 0), then the row totals
+// through the row broadcasts.
+__device__ __forceinline__ int wave_incl_scan_i32(int v) {
+    int s = v;
+    s += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, true);    // row_shr:1
+    s += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, true);    // row_shr:2
+    s += __builtin_amdgcn_update_dpp(0, v, 0x113, 0xf, 0xf, true);    // row_shr:3
+    s += __builtin_amdgcn_update_dpp(0, s, 0x114, 0xf, 0xe, true);    // row_shr:4, lanes 4..15 of a row
+    s += __builtin_amdgcn_update_dpp(0, s, 0x118, 0xf, 0xc, true);    // row_shr:8, lanes 8..15 of a row
+    s += __builtin_amdgcn_update_dpp(0, s, 0x142, 0xa, 0xf, false);   // row_bcast:15 into rows 1 and 3
+    s += __builtin_amdgcn_update_dpp(0, s, 0x143, 0xc, 0xf, false);   // row_bcast:31 into rows 2 and 3
+    return s;
+}
+
+// Sum over the wavefront, in every lane (fixed order: reproducible).
 __device__ __forceinline__ float wave_sum_f32(float v) {
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, MOE_WAVE);
-    return v;
+#define MOE_DPP_ADD(ctrl, rows)                                                                   \
+    v += __uint_as_float(static_cast<uint32_t>(                                                   \
+        __builtin_amdgcn_update_dpp(0, static_cast<int>(__float_as_uint(v)), ctrl, rows, 0xf, false)))
+    MOE_DPP_ADD(0xB1, 0xf);                              // quad_perm [1,0,3,2]
+    MOE_DPP_ADD(0x4E, 0xf);                              // quad_perm [2,3,0,1]
+    MOE_DPP_ADD(0x124, 0xf);                             // row_ror:4
+    MOE_DPP_ADD(0x128, 0xf);                             // row_ror:8  -> every lane: its row's sum
+    MOE_DPP_ADD(0x142, 0xa);                             // row_bcast:15 into rows 1 and 3
+    MOE_DPP_ADD(0x143, 0xc);                             // row_bcast:31 into rows 2 and 3 -> lane 63: the sum
+#undef MOE_DPP_ADD
+    return __uint_as_float(static_cast<uint32_t>(
+        __builtin_amdgcn_readlane(static_cast<int>(__float_as_uint(v)), MOE_WAVE - 1)));
 }
 
 __device__ __forceinline__ uint32_t orderable(float f) {
@@ -367,28 +406,20 @@ __device__ __forceinline__ void scan_slots(PermShared &sh, int C, int block_rows
         const int nb = (v + block_rows - 1) / block_rows;
         wide += v > 64 ? (v + 127) / 128 : 0;
         const int hb = v > kHeavyRows ? nb : 0, lb = nb - hb;
-        int incl = v, hincl = hb, lincl = lb;
-#pragma unroll
-        for (int d = 1; d < MOE_WAVE; d <<= 1) {
-            const int o = __shfl_up(incl, d, MOE_WAVE);
-            const int ho = __shfl_up(hincl, d, MOE_WAVE);
-            const int lo = __shfl_up(lincl, d, MOE_WAVE);
-            if (lane >= d) { incl += o; hincl += ho; lincl += lo; }
-        }
+        const int incl = wave_incl_scan_i32(v), hincl = wave_incl_scan_i32(hb), lincl = wave_incl_scan_i32(lb);
         if (s < C) {
             sh.off[s] = carry + incl - v;
             slot_off[s] = carry + incl - v;
             // light slots are placed relative to the end of the heavy class, added below
             sh.blk_base[s] = hb ? hcarry + hincl - hb : -(lcarry + lincl - lb) - 1;
         }
-        carry += __shfl(incl, MOE_WAVE - 1, MOE_WAVE);
-        hcarry += __shfl(hincl, MOE_WAVE - 1, MOE_WAVE);
-        lcarry += __shfl(lincl, MOE_WAVE - 1, MOE_WAVE);
+        carry += __builtin_amdgcn_readlane(incl, MOE_WAVE - 1);
+        hcarry += __builtin_amdgcn_readlane(hincl, MOE_WAVE - 1);
+        lcarry += __builtin_amdgcn_readlane(lincl, MOE_WAVE - 1);
     }
     for (int s = lane; s < C; s += MOE_WAVE)
         if (sh.blk_base[s] < 0) sh.blk_base[s] = hcarry + (-sh.blk_base[s] - 1);
-#pragma unroll
-    for (int d = 32; d >= 1; d >>= 1) wide += __shfl_xor(wide, d, MOE_WAVE);
+    wide = __builtin_amdgcn_readlane(wave_incl_scan_i32(wide), MOE_WAVE - 1);
     if (lane == 0) {
         sh.off[C] = carry;
         slot_off[C] = carry;
