@@ -331,6 +331,36 @@ __device__ __forceinline__ void front_tail_small(const FrontArgs &a, SmallShared
     MOE_FSTAMP(8);
 
     // ---- pass B
+    if (C <= MOE_WAVE) {
+        // the wavefront's running base of slot s lives in lane s: the loop over a group's slots reads
+        // and bumps it with scalar-indexed lane accesses, no LDS round trip per slot
+        int base_reg = lane < C ? sh.perm.cnt[wave][lane] + sh.perm.off[lane] : 0;
+#pragma unroll
+        for (int g = 0; g < kGpwMax; ++g) {
+            if (g < gpw) {                                            // wave-uniform
+                const int p = (wave * gpw + g) * MOE_WAVE + lane;
+                const int s = sl[g];
+                const bool local = s >= 0;
+                int row = -1;
+                uint64_t todo = __ballot(local);
+                while (todo) {
+                    const int lead = __builtin_ctzll(todo);
+                    const int s0 = __builtin_amdgcn_readlane(s, lead);
+                    const uint64_t same = __ballot(local && s == s0);
+                    const int b = __builtin_amdgcn_readlane(base_reg, s0);
+                    if (local && s == s0) row = b + __popcll(same & moe::lanemask_lt());
+                    if (lane == s0) base_reg += __popcll(same);
+                    todo &= ~same;
+                }
+                if (p < n_pairs) {
+                    a.pos[p] = row;
+                    if (local) a.perm[row] = p;
+                }
+            }
+        }
+        MOE_FSTAMP(9);
+        return;
+    }
     volatile int *base = &sh.perm.cnt[wave][0];
 #pragma unroll
     for (int g = 0; g < kGpwMax; ++g) {

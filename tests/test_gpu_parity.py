@@ -94,7 +94,9 @@ def test_route_ties_lower_id():
 
 
 SCHED_CFGS = ([W.tiny(), W.dsv2lite(), W.qwen3(32), W.qwen3(256), W.qwen3(1024), W.dsv3(512), small(),
-               small("k1", k=1, T=1), small("ragged", k=5, T=77)] +
+               small("k1", k=1, T=1), small("ragged", k=5, T=77),
+               # more than 64 slots per instance: the slot scan takes two rounds of 64 lanes
+               small("many_slots", E=150, n_inst=2, C=80, k=4, T=200)] +
               [W.stress(T, r, s) for (T, r, s) in [(64, 1.0, 0.0), (64, 1.125, 0.8), (64, 1.25, 1.5),
                                                    (1000, 1.25, 0.8), (8192, 1.125, 1.5), (8192, 1.25, 0.0)]])
 
@@ -239,7 +241,8 @@ def test_layer_parity(cfg):
 
 
 @pytest.mark.parametrize("cfg", [W.tiny(), W.dsv2lite(), W.qwen3(1024), W.dsv3(512), small("ragged", k=5, T=77),
-                                 W.stress(8192, 1.25, 0.8), small("k1", k=1, T=1)], ids=lambda c: f"{c.name}-T{c.T}")
+                                 W.stress(8192, 1.25, 0.8), small("k1", k=1, T=1),
+                                 small("many_slots", E=150, n_inst=2, C=80, k=4, T=200)], ids=lambda c: f"{c.name}-T{c.T}")
 def test_fused_front_equals_separate_calls(cfg):
     """moe_route_schedule_permute gives the bits of the three separate calls, call after call."""
     lay = W.build_placement(cfg)
