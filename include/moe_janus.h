@@ -156,7 +156,7 @@ int moe_schedule_baseline(const moe_placement_t *pl, const int32_t *topk_ids_dev
  *                  slots with more than 16 requests come first (their work takes longest),
  *                  ascending slot order otherwise.  Four int32 per entry: entry 0 = {number of
  *                  blocks B, R, number of 128-row blocks that the slots with more than 64 requests
- *                  make, 0}; entry 1+j = {slot, first row of the block, slot_off[slot+1], 0}.
+ *                  make, 0}; entry 1+j = {slot, first row of the block, slot_off[slot+1], slot_off[slot]}.
  *                  Entries past B are left untouched.
  * n_local and B stay on the device; nothing is read back.  The grouped FFN cannot size its
  * launch by them, so it sizes it for moe_max_blocks() and lets the surplus leave at once.

@@ -430,7 +430,7 @@ __device__ __forceinline__ void scan_slots(PermShared &sh, int C, int block_rows
 
 // Work list of the grouped FFN (a5): the local request rows cut into blocks of at most
 // block_rows rows of one slot, in the order scan_slots fixed.  Entry 0 = {number of blocks,
-// block_rows, number of 128-row blocks of the slots with more than 64 requests, 0}; entry 1+j = {slot, first row, end of the slot's rows, 0}.  All threads, after
+// block_rows, number of 128-row blocks of the slots with more than 64 requests, 0}; entry 1+j = {slot, first row, end of the slot's rows, first of the slot's rows}.  All threads, after
 // scan_slots and a barrier; one thread per slot writes that slot's entries.
 __device__ __forceinline__ void list_blocks(const PermShared &sh, int C, int block_rows,
                                             int32_t *__restrict__ blocks) {
@@ -439,7 +439,7 @@ __device__ __forceinline__ void list_blocks(const PermShared &sh, int C, int blo
     for (int s = threadIdx.x; s < C; s += blockDim.x) {
         const int lo = sh.off[s], hi = sh.off[s + 1];
         int j = sh.blk_base[s];
-        for (int r = lo; r < hi; r += block_rows) out[1 + j++] = make_int4(s, r, hi, 0);
+        for (int r = lo; r < hi; r += block_rows) out[1 + j++] = make_int4(s, r, hi, lo);
     }
 }
 

@@ -84,6 +84,18 @@ __device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
     return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
 }
 
+// The weights of a slot with a single block are read exactly once: they are loaded with the
+// streaming hint (STREAM), so that on their way through an L2 they do not push out the token rows,
+// which every tile of a block reads again (7 MB of rows against a 4 MB L2 at d_h = 7168, T = 512:
+// 237 -> 227 us for that launch).  The blocks of a slot with several share their tiles through L2
+// and keep the plain loads (with the hint on those too, all-slot batches of 128 to 512 tokens
+// were 20 % slower).
+template <bool STREAM>
+__device__ __forceinline__ bf16x8 load_weights(const char *p) {
+    if constexpr (STREAM) return __builtin_nontemporal_load(reinterpret_cast<const bf16x8 *>(p));
+    else return *reinterpret_cast<const bf16x8 *>(p);
+}
+
 __device__ __forceinline__ float silu_mul(float g, float u) { return g / (1.0f + __expf(-g)) * u; }
 
 // Workgroup barrier for LDS exchange only: waits for this wavefront's LDS traffic, not for its
@@ -177,7 +189,7 @@ __device__ __forceinline__ void wait_block_ready(const StreamArgs &a, int item, 
 // that both the row-major writes and the column-wise reads spread over the banks).  NH = number
 // of 8-row halves that hold requests (rows past the end repeat the last row; halves past it are
 // not loaded and leave unspecified values in token columns whose results are never stored).
-template <int NH, int TT>
+template <int NH, int TT, bool STREAM>
 __device__ __forceinline__ void stream_item_lines(const StreamArgs &a, const StageArgs &g, char *lds,
                                                   const char *w, int item, int tile, int row0, int row_end,
                                                   int wave, int lane) {
@@ -232,8 +244,8 @@ __device__ __forceinline__ void stream_item_lines(const StreamArgs &a, const Sta
         MOE_STEP_INDEX(step)                                                                     \
         const char *ws_ = w + static_cast<size_t>(s_) * 4096;                                    \
         _Pragma("unroll") for (int ss = 0; ss < 2; ++ss) {                                       \
-            wr[d][ss][0] = *reinterpret_cast<const bf16x8 *>(ws_ + ss * 2048 + aoff);            \
-            wr[d][ss][1] = *reinterpret_cast<const bf16x8 *>(ws_ + ss * 2048 + 1024 + aoff);     \
+            wr[d][ss][0] = load_weights<STREAM>(ws_ + ss * 2048 + aoff);                        \
+            wr[d][ss][1] = load_weights<STREAM>(ws_ + ss * 2048 + 1024 + aoff);                 \
         }                                                                                        \
         asm volatile("" ::: "memory");                                                           \
     } while (0)
@@ -340,8 +352,8 @@ __device__ __forceinline__ void stream_item_steps(const StreamArgs &a, const Sta
             const int s_ = wave + kWaves * r_;                                                   \
             const char *ws_ = w + static_cast<size_t>(s_) * 2048;                                \
             const char *bs_ = bbase + static_cast<size_t>(s_) * kBStep;                            \
-            wr[d][0] = *reinterpret_cast<const bf16x8 *>(ws_ + aoff);                            \
-            wr[d][1] = *reinterpret_cast<const bf16x8 *>(ws_ + 1024 + aoff);                     \
+            wr[d][0] = load_weights<false>(ws_ + aoff);                                          \
+            wr[d][1] = load_weights<false>(ws_ + 1024 + aoff);                                   \
             _Pragma("unroll") for (int t = 0; t < NT; ++t)                                       \
                 br[d][t] = *reinterpret_cast<const bf16x8 *>(bs_ + boff[t]);                     \
             asm volatile("" ::: "memory");                                                       \
@@ -384,7 +396,7 @@ __device__ __forceinline__ void stream_item_steps(const StreamArgs &a, const Sta
 // K-steps is even and the token tiles leave room in the registers); the steps go round-robin over
 // the wavefronts, 4 / U or 3 of them in flight for both operands, the weights issued before the
 // wait for the block (they do not depend on stage 1).
-template <int NT, int TT, int U>
+template <int NT, int TT, int U, bool STREAM>
 __device__ __forceinline__ void stream_item_down(const StreamArgs &a, const StageArgs &g, char *lds,
                                                  const char *w, int item, int tile, int row0, int row_end,
                                                  int wave, int lane) {
@@ -411,8 +423,8 @@ __device__ __forceinline__ void stream_item_down(const StreamArgs &a, const Stag
         MOE_STEP_INDEX(step)                                                                     \
         const char *ws_ = w + static_cast<size_t>(s_) * (U * 2048) + aoff;                       \
         _Pragma("unroll") for (int u = 0; u < U; ++u) {                                          \
-            wr[d][u][0] = *reinterpret_cast<const bf16x8 *>(ws_ + u * 2048);                     \
-            wr[d][u][1] = *reinterpret_cast<const bf16x8 *>(ws_ + u * 2048 + 1024);              \
+            wr[d][u][0] = load_weights<STREAM>(ws_ + u * 2048);                                 \
+            wr[d][u][1] = load_weights<STREAM>(ws_ + u * 2048 + 1024);                          \
         }                                                                                        \
         asm volatile("" ::: "memory");                                                           \
     } while (0)
@@ -472,7 +484,7 @@ template <bool STAGE1, bool LINES, int TT>
 __device__ __forceinline__ void run_item(const StreamArgs &a, const StageArgs &g, char *lds, unsigned id) {
     const int tile = id % g.tiles_pad, item = id / g.tiles_pad;
     if (tile >= g.tiles) return;
-    // work list entry: {slot, first row, end of the slot's rows}; entry 0 holds the number of blocks
+    // work list entry: {slot, first row, end of the slot's rows, first of the slot's rows}; entry 0 holds the number of blocks
     // (both are wave-uniform scalar loads issued together; an entry past the end is never used)
     const int4 *list = reinterpret_cast<const int4 *>(a.blocks);
     const int n_blocks = list[0].x;
@@ -480,14 +492,19 @@ __device__ __forceinline__ void run_item(const StreamArgs &a, const StageArgs &g
     if (item >= n_blocks) return;                                // past the last block: nothing else is read
     // lists with blocks of 64 rows: slots with more than 64 requests belong to the tiled-GEMM launches
     // when those are on for this batch
-    if (TT == 4 && moe::ffn_wide_on(list[0], a.wide_tiles1, a.wide_min) && ent.z - a.slot_off[ent.x] > 64) return;
+    if (TT == 4 && moe::ffn_wide_on(list[0], a.wide_tiles1, a.wide_min) && ent.z - ent.w > 64) return;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / MOE_WAVE), lane = threadIdx.x % MOE_WAVE;
     const int slot = ent.x, row0 = ent.y, hi = ent.z;
     const char *w = g.Wp + (static_cast<size_t>(slot) * g.tiles + tile) * g.KS * 2048;
     const int m = hi - row0;
+    const bool single = m <= TT * 16 && row0 == ent.w;                  // the slot's only block
     if constexpr (!STAGE1) {
         const int tiles16 = ((m < TT * 16 ? m : TT * 16) + 15) >> 4;     // 16-row token tiles that hold requests
-#define MOE_CASE(NT, U) case NT: stream_item_down<NT, TT, U>(a, g, lds, w, item, tile, row0, hi, wave, lane); break;
+#define MOE_CASE(NT, U)                                                                              \
+    case NT:                                                                                         \
+        if (single) stream_item_down<NT, TT, U, true>(a, g, lds, w, item, tile, row0, hi, wave, lane);  \
+        else stream_item_down<NT, TT, U, false>(a, g, lds, w, item, tile, row0, hi, wave, lane);        \
+        break;
         if constexpr (TT == 2) {
             switch (tiles16) { MOE_CASE(1, LINES ? 2 : 1) MOE_CASE(2, LINES ? 2 : 1) }
         } else {
@@ -496,7 +513,11 @@ __device__ __forceinline__ void run_item(const StreamArgs &a, const StageArgs &g
 #undef MOE_CASE
     } else if (LINES) {
         const int halves = ((m < TT * 16 ? m : TT * 16) + 7) >> 3;     // 8-row halves that hold requests
-#define MOE_CASE(NH) case NH: stream_item_lines<NH, TT>(a, g, lds, w, item, tile, row0, hi, wave, lane); break;
+#define MOE_CASE(NH)                                                                                 \
+    case NH:                                                                                         \
+        if (single) stream_item_lines<NH, TT, true>(a, g, lds, w, item, tile, row0, hi, wave, lane);    \
+        else stream_item_lines<NH, TT, false>(a, g, lds, w, item, tile, row0, hi, wave, lane);          \
+        break;
         if constexpr (TT == 2) {
             switch (halves) { MOE_CASE(1) MOE_CASE(2) MOE_CASE(3) MOE_CASE(4) }
         } else {
@@ -581,7 +602,7 @@ void ffn_stream_kernel(StreamArgs a) {
                 bool mine = false;
                 if (b < n_blocks) {
                     const int4 e = reinterpret_cast<const int4 *>(a.blocks)[1 + b];
-                    mine = !(TT == 4 && moe::ffn_wide_on(head, a.wide_tiles1, a.wide_min) && e.z - a.slot_off[e.x] > 64);
+                    mine = !(TT == 4 && moe::ffn_wide_on(head, a.wide_tiles1, a.wide_min) && e.z - e.w > 64);
                 }
                 const unsigned long long m = __ballot(mine);
                 if (threadIdx.x == 0) s_visit = m;

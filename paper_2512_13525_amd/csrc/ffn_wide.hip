@@ -70,7 +70,7 @@ void ffn_wide_kernel(WideArgs a) {
     if (item >= head.x || !moe::ffn_wide_on(head, a.tiles1, a.wide_min)) return;
     const int4 ent = list[1 + item];
     const int slot = ent.x, row0 = ent.y, hi = ent.z;
-    const int lo = a.slot_off[slot];
+    const int lo = ent.w;                                            // first of the slot's rows
     // the leader of a wide block: more than 64 requests on the slot, first row a multiple of 128 into it
     if (hi - lo <= 64 || ((row0 - lo) & (kRows - 1)) != 0) return;
     const int m = hi - row0 < kRows ? hi - row0 : kRows;             // rows of this block
