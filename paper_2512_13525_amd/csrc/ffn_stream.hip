@@ -225,8 +225,9 @@ __device__ __forceinline__ void stream_item_lines(const StreamArgs &a, const Sta
     // so waiting for the token rows of the next super-step also waits for every older weight load:
     // with DB = 1 only the newest super-step of weights stays in flight across that wait, with
     // DB = 2 (where the registers allow it: blocks of up to 16 rows, 32 in the 64-row kernel) two do.  The steady-state
-    // loop has no branch, so the compiler counts outstanding loads exactly.  Loads past the last
-    // super-step fetch the last one again (a cache hit): every load is unconditional.
+    // loop has no branch, so the compiler counts outstanding loads exactly.  Token loads past the last
+    // super-step fetch the last one again (a cache hit) and stay unconditional; weight loads, which
+    // may bypass the cache, are only issued for super-steps that exist.
     constexpr int DB = (NH <= 4) ? D : 1;                        // D: the two rings share their positions
     bf16x8 wr[D][2][2];
     bf16x8 br[DB][NH];
@@ -279,7 +280,7 @@ __device__ __forceinline__ void stream_item_lines(const StreamArgs &a, const Sta
 #pragma unroll
         for (int d = 0; d < D; ++d) {
             if (d < DB) MOE_LOAD_B(d, d);
-            MOE_LOAD_A(d, d);
+            if (d < n) MOE_LOAD_A(d, d);
         }
         int i = 0;
         for (; i + 2 * D <= n; i += D) {
@@ -297,7 +298,7 @@ __device__ __forceinline__ void stream_item_lines(const StreamArgs &a, const Sta
             MOE_STAGE_B(d);
             MOE_LOAD_B(d + DB, i + d + DB);
             if (d < rem) MOE_MMA_STEP(d);
-            if (d < D - 1) MOE_LOAD_A(d, i + d + D);
+            if (d < D - 1 && d + D < rem) MOE_LOAD_A(d, i + d + D);      // only super-steps that exist (wave-uniform)
         }
 #pragma unroll
         for (int d = 0; d < D - 1; ++d) {
@@ -379,7 +380,7 @@ __device__ __forceinline__ void stream_item_steps(const StreamArgs &a, const Sta
 #pragma unroll
         for (int d = 0; d < D; ++d) {
             if (d < rem) MOE_MMA_STEP(d);
-            if (d < D - 1) MOE_LOAD_STEP(d, i + d + D);
+            if (d < D - 1 && d + D < rem) MOE_LOAD_STEP(d, i + d + D);
         }
 #pragma unroll
         for (int d = 0; d < D - 1; ++d)
@@ -445,14 +446,14 @@ __device__ __forceinline__ void stream_item_down(const StreamArgs &a, const Stag
                 acc[1][t] = mfma16(wr[d][u][1], br[d][u][t], acc[1][t]);                         \
             }                                                                                    \
     } while (0)
-    if (n > 0) {
 #pragma unroll
-        for (int d = 0; d < D; ++d) MOE_LOAD_W(d, d);
-    }
+    for (int d = 0; d < D; ++d)
+        if (d < n) MOE_LOAD_W(d, d);
     wait_block_ready(a, item, tile, g.tiles);
     if (n > 0) {
 #pragma unroll
-        for (int d = 0; d < D; ++d) MOE_LOAD_T(d, d);
+        for (int d = 0; d < D; ++d)
+            if (d < n) MOE_LOAD_T(d, d);
         int i = 0;
         for (; i + 2 * D <= n; i += D) {
 #pragma unroll
@@ -466,7 +467,7 @@ __device__ __forceinline__ void stream_item_down(const StreamArgs &a, const Stag
 #pragma unroll
         for (int d = 0; d < D; ++d) {
             if (d < rem) MOE_MMA_STEP(d);
-            if (d < D - 1) { MOE_LOAD_W(d, i + d + D); MOE_LOAD_T(d, i + d + D); }
+            if (d < D - 1 && d + D < rem) { MOE_LOAD_W(d, i + d + D); MOE_LOAD_T(d, i + d + D); }
         }
 #pragma unroll
         for (int d = 0; d < D - 1; ++d)
