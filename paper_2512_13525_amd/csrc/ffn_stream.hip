@@ -225,9 +225,8 @@ __device__ __forceinline__ void stream_item_lines(const StreamArgs &a, const Sta
     // so waiting for the token rows of the next super-step also waits for every older weight load:
     // with DB = 1 only the newest super-step of weights stays in flight across that wait, with
     // DB = 2 (where the registers allow it: blocks of up to 16 rows, 32 in the 64-row kernel) two do.  The steady-state
-    // loop has no branch, so the compiler counts outstanding loads exactly.  Token loads past the last
-    // super-step fetch the last one again (a cache hit) and stay unconditional; weight loads, which
-    // may bypass the cache, are only issued for super-steps that exist.
+    // loop has no branch, so the compiler counts outstanding loads exactly; before and after it
+    // loads are only issued for super-steps that exist.
     constexpr int DB = (NH <= 4) ? D : 1;                        // D: the two rings share their positions
     bf16x8 wr[D][2][2];
     bf16x8 br[DB][NH];
@@ -279,7 +278,7 @@ __device__ __forceinline__ void stream_item_lines(const StreamArgs &a, const Sta
         // issue order of the first loads: tokens of a super-step before its weights
 #pragma unroll
         for (int d = 0; d < D; ++d) {
-            if (d < DB) MOE_LOAD_B(d, d);
+            if (d < DB && d < n) MOE_LOAD_B(d, d);
             if (d < n) MOE_LOAD_A(d, d);
         }
         int i = 0;
@@ -293,17 +292,21 @@ __device__ __forceinline__ void stream_item_lines(const StreamArgs &a, const Sta
             }
         }
         const int rem = n - i;                                   // 1 .. 2*D-1 super-steps left
+        // the last 1 .. 2*D-1 super-steps: only those that exist are loaded, staged and multiplied
+        // (wave-uniform conditions)
 #pragma unroll
         for (int d = 0; d < D; ++d) {
-            MOE_STAGE_B(d);
-            MOE_LOAD_B(d + DB, i + d + DB);
+            if (d < rem) MOE_STAGE_B(d);
+            if (d + DB < rem) MOE_LOAD_B(d + DB, i + d + DB);
             if (d < rem) MOE_MMA_STEP(d);
-            if (d < D - 1 && d + D < rem) MOE_LOAD_A(d, i + d + D);      // only super-steps that exist (wave-uniform)
+            if (d < D - 1 && d + D < rem) MOE_LOAD_A(d, i + d + D);
         }
 #pragma unroll
         for (int d = 0; d < D - 1; ++d) {
-            MOE_STAGE_B(D + d);
-            if (D + d < rem) MOE_MMA_STEP(d);
+            if (D + d < rem) {
+                MOE_STAGE_B(D + d);
+                MOE_MMA_STEP(d);
+            }
         }
     }
 #undef MOE_STEP_INDEX
@@ -367,7 +370,8 @@ __device__ __forceinline__ void stream_item_steps(const StreamArgs &a, const Sta
             }                                                                                    \
         } while (0)
 #pragma unroll
-        for (int d = 0; d < D; ++d) MOE_LOAD_STEP(d, d);
+        for (int d = 0; d < D; ++d)
+            if (d < n) MOE_LOAD_STEP(d, d);
         int i = 0;
         for (; i + 2 * D <= n; i += D) {
 #pragma unroll
