@@ -27,7 +27,7 @@ sys.path.insert(0, ROOT)
 # HBM bytes per FFN launch from rocprofv3 FETCH_SIZE / WRITE_SIZE runs of this command, scaled by a plain
 # copy (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0); see profiles/ffn_stream_kernel_dsv2lite_T128_hbm_traffic.txt.
 # Workloads without such a run report null.
-MEASURED_TRAFFIC = {("dsv2lite", 128): 219824474, ("qwen3", 256): 126070205, ("dsv3", 512): 1540221579}
+MEASURED_TRAFFIC = {("dsv2lite", 128): 215778857, ("qwen3", 256): 124760462, ("dsv3", 512): 1420672878}
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
 
 
