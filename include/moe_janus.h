@@ -294,7 +294,9 @@ int moe_pack_weights_bf16(const void *W13_dev, const void *W2_dev, int C, int d_
  *   Yp_dev [T*k, d_h] float32, capacity T*k rows, rows >= n_local are left untouched
  *   blocks_dev       the work list moe_permute wrote for a batch of the same T (bf16 path; a
  *                    list cut for another block size is refused: bit 1 of the status word;
- *                    the f32 path does not read it and accepts NULL)
+ *                    the f32 path does not read it and accepts NULL).  The bf16 kernels take
+ *                    every row range from this list (it repeats what slot_off_dev says); the
+ *                    f32 kernels read slot_off_dev.
  *   workspace_dev    at least moe_workspace_bytes() bytes, 256-byte aligned; holds a control
  *                    region of hand-off flags and the intermediate a (bf16 or f32) between
  *                    the two GEMM stages.  The control region must have been cleared with

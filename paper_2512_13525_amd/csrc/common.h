@@ -61,7 +61,7 @@ inline long long ffn_max_blocks(int T, int k, int C) {
 // control region of the workspace, `act` holds ffn_max_blocks(T, k, C) blocks of ffn_block_rows(T) x d_e
 // bf16.  Returns MOE_OK or MOE_ESHAPE (too many blocks).
 int launch_ffn_stream(const void *X, const void *W13p, const void *W2p, int T, int k, int C, int d_h, int d_e,
-                      const int32_t *blocks, const int32_t *slot_off, const int32_t *perm, int *ctrl, uint16_t *act,
+                      const int32_t *blocks, const int32_t *perm, int *ctrl, uint16_t *act,
                       float *Yp, hipStream_t st);
 
 // Slots with more than 64 requests of batches of at least kWideMinTokens tokens: blocks of 128 rows
@@ -86,7 +86,7 @@ inline size_t ffn_stream_act_bytes(int T, int k, int C, int d_e) {
     return (b + 255) / 256 * 256;
 }
 int launch_ffn_wide(const void *X, const void *W13p, const void *W2p, int T, int k, int C, int d_h, int d_e,
-                    const int32_t *blocks, const int32_t *slot_off, const int32_t *perm, uint16_t *act_rows,
+                    const int32_t *blocks, const int32_t *perm, uint16_t *act_rows,
                     float *Yp, hipStream_t st);
 
 inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }

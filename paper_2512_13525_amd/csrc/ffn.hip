@@ -210,11 +210,11 @@ extern "C" int moe_grouped_ffn(const void *X_dev, const void *W13_dev, const voi
         if (static_cast<long long>(T) * d_h * 2 > 0xffffffffLL) return MOE_ESHAPE;
         if (moe::ffn_has_wide(T)) {
             uint16_t *act_rows = reinterpret_cast<uint16_t *>(ws + kCtrlBytes + moe::ffn_stream_act_bytes(T, k, C, d_e));
-            const int rcw = moe::launch_ffn_wide(X_dev, W13_dev, W2_dev, T, k, C, d_h, d_e, blocks_dev, slot_off_dev,
+            const int rcw = moe::launch_ffn_wide(X_dev, W13_dev, W2_dev, T, k, C, d_h, d_e, blocks_dev,
                                                  perm_dev, act_rows, Yp_dev, st);
             if (rcw != MOE_OK) return rcw;
         }
-        const int rc = moe::launch_ffn_stream(X_dev, W13_dev, W2_dev, T, k, C, d_h, d_e, blocks_dev, slot_off_dev, perm_dev,
+        const int rc = moe::launch_ffn_stream(X_dev, W13_dev, W2_dev, T, k, C, d_h, d_e, blocks_dev, perm_dev,
                                               reinterpret_cast<int *>(ws), reinterpret_cast<uint16_t *>(ws + kCtrlBytes),
                                               Yp_dev, st);
         if (rc != MOE_OK) return rc;

@@ -70,7 +70,6 @@ struct StageArgs {
 struct StreamArgs {
     StageArgs s[2];
     const int32_t *blocks;               // work list written by the dispatch step
-    const int32_t *slot_off;
     const int32_t *perm;
     uint16_t *act;                       // stage-1 output
     float *Yp;                           // stage-2 output
@@ -655,13 +654,13 @@ void launch_lines(const StreamArgs &a, int block_rows, unsigned blocks, hipStrea
 namespace moe {
 
 int launch_ffn_stream(const void *X, const void *W13p, const void *W2p, int T, int k, int C, int d_h, int d_e,
-                      const int32_t *blocks, const int32_t *slot_off, const int32_t *perm, int *ctrl, uint16_t *act,
+                      const int32_t *blocks, const int32_t *perm, int *ctrl, uint16_t *act,
                       float *Yp, hipStream_t st) {
     const int block_rows = ffn_block_rows(T);
     const long long items = ffn_max_blocks(T, k, C);
     if (items > kMaxItems) return MOE_ESHAPE;
     StreamArgs a;
-    a.blocks = blocks; a.slot_off = slot_off; a.perm = perm; a.act = act; a.Yp = Yp; a.ctrl = ctrl; a.k = k; a.C = C;
+    a.blocks = blocks; a.perm = perm; a.act = act; a.Yp = Yp; a.ctrl = ctrl; a.k = k; a.C = C;
     a.spin_limit = 1 << 20;
     a.wide_tiles1 = ffn_wide_tiles1(d_e);
     a.wide_min = ffn_has_wide(T) ? ffn_wide_min_workgroups() : 0x7fffffff;

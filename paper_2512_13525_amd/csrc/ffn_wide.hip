@@ -42,7 +42,7 @@ constexpr int kRing = 2;                 // K-tiles of both operands in flight (
 struct WideArgs {
     const char *B;                       // token operand: X (stage 1, rows through perm) or the intermediate (stage 2)
     const char *Wp;                      // packed weights: [C][ptiles][KS][2][64] fragments of 16 bytes
-    const int32_t *blocks, *slot_off, *perm;
+    const int32_t *blocks, *perm;
     uint16_t *act;                       // stage-1 output [request row][out_stride]
     float *Yp;                           // stage-2 output [request row][out_stride]
     int ptiles, tiles, tiles_pad, KS;    // tiles = workgroup tiles of 4 packed tiles
@@ -250,11 +250,11 @@ namespace moe {
 // Both stages for every wide block of the list (two launches sized for the largest possible number
 // of blocks; workgroups that find no wide block leave after three scalar loads).
 int launch_ffn_wide(const void *X, const void *W13p, const void *W2p, int T, int k, int C, int d_h, int d_e,
-                    const int32_t *blocks, const int32_t *slot_off, const int32_t *perm, uint16_t *act_rows,
+                    const int32_t *blocks, const int32_t *perm, uint16_t *act_rows,
                     float *Yp, hipStream_t st) {
     const long long items = ffn_max_blocks(T, k, C);
     WideArgs a;
-    a.blocks = blocks; a.slot_off = slot_off; a.perm = perm; a.act = act_rows; a.Yp = Yp; a.k = k;
+    a.blocks = blocks; a.perm = perm; a.act = act_rows; a.Yp = Yp; a.k = k;
     // stage 1
     a.B = static_cast<const char *>(X); a.Wp = static_cast<const char *>(W13p);
     a.ptiles = d_e / 16; a.KS = d_h / 32; a.b_row_bytes = static_cast<uint32_t>(d_h) * 2; a.out_stride = d_e;
