@@ -55,8 +55,15 @@ constexpr int kCtrlBlockInts = (1 + kCtrlCopies) * kCtrlLineInts;
 constexpr int kMaxItems = static_cast<int>(moe::kFfnCtrlBytes / 4) / kCtrlBlockInts - 1;
 
 #ifdef MOE_STREAM_TRACE
-// timeline of every workgroup (debug builds only): [linear id][start, stage, end, xcc/cu]
-__device__ long long g_trace[1 << 15][4];
+// timeline of every workgroup (debug builds only): [linear id][start, stage, end, xcc/cu, first operands
+// staged, K loop done, stores acknowledged, 0]
+__device__ long long g_trace[1 << 15][8];
+__device__ __forceinline__ void trace_stamp(int i) {
+    if (threadIdx.x == 0 && blockIdx.x < (1u << 15)) g_trace[blockIdx.x][i] = wall_clock64();
+}
+#define MOE_TSTAMP(i) trace_stamp(i)
+#else
+#define MOE_TSTAMP(i) do { } while (0)
 #endif
 
 struct StageArgs {
@@ -281,6 +288,7 @@ __device__ __forceinline__ void stream_item_lines(const StreamArgs &a, const Sta
             if (d < n) MOE_LOAD_A(d, d);
         }
         int i = 0;
+        MOE_TSTAMP(4);
         for (; i + 2 * D <= n; i += D) {
 #pragma unroll
             for (int d = 0; d < D; ++d) {
@@ -313,6 +321,7 @@ __device__ __forceinline__ void stream_item_lines(const StreamArgs &a, const Sta
 #undef MOE_LOAD_B
 #undef MOE_STAGE_B
 #undef MOE_MMA_STEP
+    MOE_TSTAMP(5);
     __syncthreads();                                             // the staging tiles are reused for the reduction
     reduce_store<true, NT, TT>(a, g, red, acc, item, 0, tile, row0, row_end, wave, lane);
 }
@@ -453,6 +462,7 @@ __device__ __forceinline__ void stream_item_down(const StreamArgs &a, const Stag
     for (int d = 0; d < D; ++d)
         if (d < n) MOE_LOAD_W(d, d);
     wait_block_ready(a, item, tile, g.tiles);
+    MOE_TSTAMP(4);
     if (n > 0) {
 #pragma unroll
         for (int d = 0; d < D; ++d)
@@ -480,6 +490,7 @@ __device__ __forceinline__ void stream_item_down(const StreamArgs &a, const Stag
 #undef MOE_LOAD_W
 #undef MOE_LOAD_T
 #undef MOE_MMA_STEP
+    MOE_TSTAMP(5);
     reduce_store<false, NT, TT>(a, g, red, acc, item, 0, tile, row0, row_end, wave, lane);
 }
 
@@ -542,6 +553,7 @@ __device__ __forceinline__ void run_item(const StreamArgs &a, const StageArgs &g
         // one thread bumps the block's counter and, if it completes the count, raises the ready flags
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
+        MOE_TSTAMP(6);
         if (threadIdx.x == 0) {
             int *blk = a.ctrl + (item + 1) * kCtrlBlockInts;
             if (__hip_atomic_fetch_add(blk, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == g.tiles - 1) {
