@@ -7,10 +7,13 @@ synchronisation, as three launches (fused front, fused FFN, combine).  Consecuti
 from a ring (>= 1 GiB of weights in total), so expert weights come from HBM and not from
 the 256 MB memory-side cache.
 
-Prints ONE JSON line.  `value` = algorithmic bytes of a step (activated experts' weights +
-activation traffic) / step time, in GB/s; the `roofline` object prices the dominant kernel
-(the grouped FFN) alone, with its duration taken from HIP events recorded in the timed
-region on the launching stream; `cpu_baseline` times the CPU oracle on the same workload.
+Prints ONE JSON line for the largest configuration of the workload list (DeepSeek-V3-shaped,
+T = 512).  `value` = algorithmic bytes of a step (activated experts' weights + activation
+traffic) / step time, in GB/s; the `roofline` object prices the dominant kernel (the grouped FFN)
+alone, with its duration taken from HIP events recorded in the timed region on the launching
+stream; `cpu_baseline` times the CPU oracle on the same workload; `other_decode_configs` carries
+the same measurement for the other decode configurations (DeepSeek-V2-Lite-shaped T = 128,
+Qwen3-30B-A3B-shaped T = 32 and 256).
 """
 from __future__ import annotations
 
@@ -24,11 +27,13 @@ import time
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
-# HBM bytes per FFN launch from rocprofv3 FETCH_SIZE / WRITE_SIZE runs of this command, scaled by a plain
-# copy (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0); see profiles/ffn_stream_kernel_dsv2lite_T128_hbm_traffic.txt.
-# Workloads without such a run report null.
-MEASURED_TRAFFIC = {("dsv2lite", 128): 215778857, ("qwen3", 256): 124760462, ("dsv3", 512): 1420672878}
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
+TRAFFIC_JSON = os.path.join(ROOT, "profiles", "ffn_kernel_hbm_traffic.json")
+
+# The headline line is quoted on the largest single-GPU configuration of the workload list; the other
+# decode configurations are measured in the same run and carried as extra rows of the same JSON line.
+HEADLINE = ("dsv3", 512)
+OTHER_ROWS = [("dsv2lite", 128), ("qwen3", 32), ("qwen3", 256)]
 
 
 def make_cfg(name: str, T):
@@ -44,19 +49,38 @@ def make_cfg(name: str, T):
     raise SystemExit(f"unknown workload {name}")
 
 
+def measured_traffic(workload: str, T: int):
+    """HBM bytes per FFN launch from the committed summary of the rocprofv3 FETCH_SIZE / WRITE_SIZE runs
+    (written by `bench.py --mode pmc_summary`), or None when no run of this workload is on record."""
+    try:
+        with open(TRAFFIC_JSON) as f:
+            rec = json.load(f).get(f"{workload}-T{T}")
+    except (OSError, ValueError):
+        return None, None
+    if not rec:
+        return None, None
+    return rec.get("hbm_bytes_per_launch"), {"file": os.path.relpath(TRAFFIC_JSON, ROOT), "kernel": rec.get("kernel"),
+                                             "source_commit": rec.get("commit")}
+
+
 def main() -> None:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="dsv2lite", choices=["dsv2lite", "qwen3", "dsv3", "stress"])
+    ap.add_argument("--workload", default=None, choices=["dsv2lite", "qwen3", "dsv3", "stress"],
+                    help="step mode: measure only this workload (default: the headline dsv3 T=512 plus the other "
+                         "decode configurations as extra rows)")
     ap.add_argument("--tokens", type=int, default=None)
     ap.add_argument("--ring-bytes", type=float, default=1.25e9, help="minimum total bytes of rotating weight copies")
     ap.add_argument("--rows-per-slot", type=int, default=0,
                     help="act_sweep: requests on every activated slot (0 = spread all T*k requests over them)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-events", action="store_true", help="do not record per-kernel events in the timed region")
-    ap.add_argument("--mode", default="step", choices=["step", "sched", "act_sweep", "skew", "batch_sweep", "amax", "gate", "placement", "scaling", "shared", "graph", "configs"],
+    ap.add_argument("--no-other-rows", action="store_true", help="step mode: only the headline workload")
+    ap.add_argument("--batches", type=int, default=2000, help="amax: sampled batches per (n_e, B)")
+    ap.add_argument("--pmc-dir", default=None, help="pmc_summary: folder with the rocprofv3 counter CSVs")
+    ap.add_argument("--mode", default="step", choices=["step", "sched", "act_sweep", "skew", "batch_sweep", "amax", "gate", "placement", "scaling", "shared", "graph", "configs", "probe_sweep", "calib_copy", "pmc_summary"],
                     help="step: the headline line (default); sched: scheduler us and a_max vs optimum over the "
                          "stress sweep; act_sweep: layer us vs number of activated experts; skew: same "
                          "activated set with an even and a Zipf split of the requests; batch_sweep: layer "
@@ -67,42 +91,60 @@ def main() -> None:
                          "Alg. 2 fed with the measured MoE-side coefficients and a_max table; shared: the step with a "
                          "shared expert run on the instance; graph: the step queued eagerly against the same steps "
                          "replayed from a captured HIP graph; configs: one line per workload configuration and "
-                         "token count of the workload list")
+                         "token count of the workload list; probe_sweep: the plain read probe over launch shapes; "
+                         "calib_copy: a device-to-device copy of known size (counter calibration); pmc_summary: "
+                         "turn rocprofv3 FETCH_SIZE / WRITE_SIZE CSVs into profiles/ffn_kernel_hbm_traffic.json (no GPU)")
     args = ap.parse_args()
     if args.gpus != 1:
         raise SystemExit("this build runs on ONE GPU: the other MoE instances exist only as replica placement "
                          "seen by the scheduler; run with --gpus 1")
+    if args.mode == "pmc_summary":
+        return pmc_summary(args)
 
+    import numpy as np
+    import torch
+    from paper_2512_13525_amd import binding as B
+
+    B.lib()                                   # fail loudly if the HIP library is missing
+    assert torch.cuda.is_available(), "bench.py needs an MI355X"
+    torch.cuda.set_device(0)
+    modes = {"sched": sched_sweep, "act_sweep": act_sweep, "skew": split_sweeps, "batch_sweep": split_sweeps,
+             "amax": amax_study, "gate": gate_front, "placement": placement_study, "scaling": scaling_study,
+             "shared": shared_step, "graph": graph_step, "configs": all_configs, "probe_sweep": probe_sweep,
+             "calib_copy": calib_copy}
+    if args.mode in modes:
+        return modes[args.mode](args)
+
+    if args.workload:
+        name, T = args.workload, make_cfg(args.workload, args.tokens).T
+        others = []
+    else:
+        name, T = HEADLINE
+        others = [] if args.no_other_rows else OTHER_ROWS
+    out = step_bench(args, name, T, args.steps, args.warmup, full=True)
+    rows = []
+    for oname, oT in others:
+        r = step_bench(args, oname, oT, min(args.steps, 100), min(args.warmup, 10), full=False)
+        rows.append({"workload": r["config"]["workload"], "step_us": r["step_us"], "value_GBps": r["value"],
+                     "pct_hbm_peak_whole_step": r["pct_hbm_peak_whole_step"],
+                     "activated_experts_a_g": r["activated_experts_a_g"], "n_local_mean": r["n_local_mean"],
+                     "steps": r["steps"], "roofline": r["roofline"]})
+    if rows:
+        out["other_decode_configs"] = rows
+    print(json.dumps(out), flush=True)
+
+
+def step_bench(args, name: str, T: int, steps: int, warmup: int, full: bool) -> dict:
+    """The layer step of one workload: K timed steps (front, FFN, combine queued on one stream over a ring of
+    batches and weight copies), the FFN launch timed by HIP events inside that region, and with `full`
+    the per-stage times, the single-step latency, the read probe and the CPU baseline."""
     import numpy as np
     import torch
     from paper_2512_13525_amd import binding as B
     from paper_2512_13525_amd import workloads as W
     from paper_2512_13525_amd.layer import LayerStep, to_device_bf16
 
-    B.lib()                                   # fail loudly if the HIP library is missing
-    assert torch.cuda.is_available(), "bench.py needs an MI355X"
-    torch.cuda.set_device(0)
-    if args.mode == "sched":
-        return sched_sweep(args)
-    if args.mode == "act_sweep":
-        return act_sweep(args)
-    if args.mode in ("skew", "batch_sweep"):
-        return split_sweeps(args)
-    if args.mode == "amax":
-        return amax_study(args)
-    if args.mode == "gate":
-        return gate_front(args)
-    if args.mode == "placement":
-        return placement_study(args)
-    if args.mode == "scaling":
-        return scaling_study(args)
-    if args.mode == "shared":
-        return shared_step(args)
-    if args.mode == "graph":
-        return graph_step(args)
-    if args.mode == "configs":
-        return all_configs(args)
-    cfg = make_cfg(args.workload, args.tokens)
+    cfg = make_cfg(name, T)
     lay = W.build_placement(cfg)
     T, k, C, d_h, d_e = cfg.T, cfg.k, cfg.C, cfg.d_h, cfg.d_e
 
@@ -115,9 +157,14 @@ def main() -> None:
     W13s, W2s = [], []
     for i in range(n_ring):
         # packed layout is a fixed permutation of the canonical one: seeded N(0, 0.02) values
-        # drawn straight into it are the same workload
-        W13s.append((torch.randn((C, 2 * d_e, d_h), generator=gen, device="cuda") * 0.02).to(torch.bfloat16))
-        W2s.append((torch.randn((C, d_h, d_e), generator=gen, device="cuda") * 0.02).to(torch.bfloat16))
+        # drawn straight into it are the same workload (one slot at a time: the fp32 draw of a whole
+        # instance would take several GB at the largest shape)
+        w13 = torch.empty((C, 2 * d_e, d_h), dtype=torch.bfloat16, device="cuda")
+        w2 = torch.empty((C, d_h, d_e), dtype=torch.bfloat16, device="cuda")
+        for s_ in range(C):
+            w13[s_] = (torch.randn((2 * d_e, d_h), generator=gen, device="cuda") * 0.02).to(torch.bfloat16)
+            w2[s_] = (torch.randn((d_h, d_e), generator=gen, device="cuda") * 0.02).to(torch.bfloat16)
+        W13s.append(w13); W2s.append(w2)
 
     # ---- choose the straggler instance of batch 0 (set-up, not timed)
     step = LayerStep(cfg, lay, 0)
@@ -125,6 +172,11 @@ def main() -> None:
     torch.cuda.synchronize()
     g_self = int(torch.argmax(step.load).item())
     step = LayerStep(cfg, lay, g_self)
+
+    def check_status(where):
+        st = B.moe_workspace_status(step.workspace)
+        if st != 0:
+            raise SystemExit(f"bench.py: FFN workspace status {st} after {where}: results of that section are invalid")
 
     def run_step(i):
         # three launches: front (route + Alg. 1 + dispatch), grouped FFN, combine
@@ -148,22 +200,23 @@ def main() -> None:
         # + combine (read Yp, write Y) + routing/schedule index traffic
         return (bytes_ffn(j) + n_local[j] * d_h * 4 + T * d_h * 2 + T * cfg.E * 4 + 6 * T * k * 4)
 
-    for i in range(args.warmup):
+    for i in range(warmup):
         run_step(i)
     torch.cuda.synchronize()
 
-    # ---- timed region: exactly K steps; an event pair around the FFN launch of every 4th step (an
-    # event record costs the stream a few us, which is time of the step, so not every step pays it).
-    # The events are created without the system-scope fence of default events: with it a pair read
-    # 5 us with nothing in between and the FFN launch 43.2 us; without it 3.8 us and 41.4 us, against
-    # 40.5 us for the kernel alone in the rocprofv3 trace.
-    every = 1 if args.no_events else 4
-    timed = [i for i in range(args.steps) if i % every == 0 and not args.no_events]
+    # ---- timed region: exactly K steps, with an event pair around the FFN launch.  An event record costs
+    # the stream a few us, which is time of the step: every step carries a pair when the step is long
+    # (more than 0.5 GB per launch) or the run is short (<= 50 steps), every 4th step otherwise.  The
+    # events are created without the system-scope fence of default events (a cache write-back between
+    # the kernels they separate).
+    mean_b = statistics.mean(bytes_ffn(j) for j in range(n_ring))
+    every = 1 if (steps <= 50 or mean_b > 5e8) else 4
+    timed = [] if args.no_events else [i for i in range(steps) if i % every == 0]
     te = TimingEvents()
     ev = {i: (te.new(), te.new()) for i in timed}
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for i in range(args.steps):
+    for i in range(steps):
         j = i % n_ring
         step.front(logits[j])
         if i in ev:
@@ -174,13 +227,16 @@ def main() -> None:
         step.combine()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
-    mean_bytes_step = statistics.mean(bytes_step(i % n_ring) for i in range(args.steps))
+    check_status("the timed region")
+    ms_per_step = (t1 - t0) * 1e3 / steps
+    mean_bytes_step = statistics.mean(bytes_step(i % n_ring) for i in range(steps))
     value = mean_bytes_step / (ms_per_step * 1e-3) / 1e9
 
-    if not args.no_events:
+    roofline = None
+    if timed:
         ffn_us = [te.us(ev[i][0], ev[i][1]) for i in timed]
         ffn_avg_us = statistics.mean(ffn_us)
+        ffn_p50_us = statistics.median(ffn_us)
         mean_bytes_ffn = statistics.mean(bytes_ffn(i % n_ring) for i in timed)
         achieved = mean_bytes_ffn / (ffn_avg_us * 1e-6) / 1e9
         # what an event pair reads with nothing between its two records, queued like the pairs above
@@ -190,23 +246,47 @@ def main() -> None:
             step.front(logits[0]); te.record(a); te.record(b); step.combine()
         torch.cuda.synchronize()
         empty_pair_us = statistics.median(te.us(a, b) for a, b in cal)
-        te.close()
+        traffic, traffic_src = measured_traffic(name, T)
         roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                    "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": MEASURED_TRAFFIC.get((args.workload, T)),
-                    "traffic_unit": "bytes per launch",
-                    "kernel": "moe_grouped_ffn", "avg_us": round(ffn_avg_us, 2), "launches_timed": len(timed), "empty_event_pair_us": round(empty_pair_us, 2),
+                    "frac": round(achieved / HBM_PEAK_GBPS, 4),
+                    "frac_p50": round(mean_bytes_ffn / (ffn_p50_us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4),
+                    "traffic": traffic, "traffic_unit": "bytes per launch", "traffic_from": traffic_src,
+                    "kernel": "moe_grouped_ffn", "avg_us": round(ffn_avg_us, 2), "launches_timed": len(timed),
+                    "empty_event_pair_us": round(empty_pair_us, 2),
                     "p10_us": round(float(np.percentile(ffn_us, 10)), 2),
-                    "p50_us": round(statistics.median(ffn_us), 2),
+                    "p50_us": round(ffn_p50_us, 2),
                     "p90_us": round(float(np.percentile(ffn_us, 90)), 2),
-                    "read_probe_same_bytes": dict(zip(("us", "GBps"), (round(v, 1) for v in read_probe(W13s, int(mean_bytes_ffn))))),
                     "algorithmic_bytes": int(mean_bytes_ffn)}
-    else:
-        roofline = None
+        if full:
+            best = read_probe_best(W13s, int(mean_bytes_ffn))
+            roofline["read_probe_same_bytes"] = best
+    te.close()
+
+    out = {
+        "metric": "moe_layer_step_algorithmic_GBps", "value": round(value, 1), "unit": "GB/s",
+        "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{cfg.name} MoE layer: E={cfg.E} k={k} d_h={d_h} d_e={d_e} T={T}, "
+                               f"{cfg.n_inst} instances x C={C} slots, Zipf s={cfg.zipf_s}, instance g_self={g_self} "
+                               f"(straggler of batch 0)",
+                   "ring_copies": n_ring, "ring_bytes": n_ring * per_copy},
+        "step_us": round(ms_per_step * 1e3, 2),
+        "pct_hbm_peak_whole_step": round(100 * value / HBM_PEAK_GBPS, 2),
+        "activated_experts_a_g": {"mean": round(statistics.mean(a_g), 2), "min": min(a_g), "max": max(a_g)},
+        "a_max_over_instances": {"mean": round(statistics.mean(a_max), 2), "max": max(a_max)},
+        "n_local_mean": round(statistics.mean(n_local), 1),
+        "launches_per_step": 3,
+        "roofline": roofline,
+    }
+    if not full:
+        del W13s, W2s, step
+        torch.cuda.empty_cache()
+        return out
 
     # ---- per-stage times (separate instrumented pass; events between all stages)
     stages = ["route", "schedule", "permute", "ffn", "combine"]
     acc = {s: [] for s in stages}
-    n_inst_steps = min(args.steps, 100)
+    n_inst_steps = min(steps, 100)
     te2 = TimingEvents()
     marks = [[te2.new() for _ in range(6)] for _ in range(n_inst_steps)]
     torch.cuda.synchronize()
@@ -235,35 +315,22 @@ def main() -> None:
 
     # ---- one step at a time: submit, wait, host wall clock (launch and completion latency included)
     single = []
-    for i in range(min(args.steps, 50)):
+    for i in range(min(steps, 50)):
         torch.cuda.synchronize()
         c0 = time.perf_counter()
         run_step(i)
         torch.cuda.synchronize()
         single.append((time.perf_counter() - c0) * 1e6)
+    check_status("the instrumented passes")
 
-    out = {
-        "metric": "moe_layer_step_algorithmic_GBps", "value": round(value, 1), "unit": "GB/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"{cfg.name} MoE layer: E={cfg.E} k={k} d_h={d_h} d_e={d_e} T={T}, "
-                               f"{cfg.n_inst} instances x C={C} slots, Zipf s={cfg.zipf_s}, instance g_self={g_self} "
-                               f"(straggler of batch 0)",
-                   "ring_copies": n_ring, "ring_bytes": n_ring * per_copy},
-        "step_us": round(ms_per_step * 1e3, 2),
-        "pct_hbm_peak_whole_step": round(100 * value / HBM_PEAK_GBPS, 2),
-        "activated_experts_a_g": {"mean": round(statistics.mean(a_g), 2), "min": min(a_g), "max": max(a_g)},
-        "a_max_over_instances": {"mean": round(statistics.mean(a_max), 2), "max": max(a_max)},
-        "n_local_mean": round(statistics.mean(n_local), 1),
+    out.update({
         "stage_us_median": stage_us,
-        "launches_per_step": 3,
         "single_step_latency_us": {"p50": round(statistics.median(single), 1),
                                    "p10": round(float(np.percentile(single, 10)), 1),
                                    "p90": round(float(np.percentile(single, 90)), 1)},
         "sched_us": stage_us["schedule"],
         "layer_us_permute_ffn_combine": round(stage_us["permute"] + stage_us["ffn"] + stage_us["combine"], 2),
-        "roofline": roofline,
-    }
+    })
 
     # ---- CPU baseline: the oracle, as it stands, on this machine's host cores
     if not args.no_cpu_baseline:
@@ -274,9 +341,17 @@ def main() -> None:
             cores = len(os.sched_getaffinity(0))
         except AttributeError:
             cores = os.cpu_count() or 1
-        W13h, W2h = W.instance_weights(cfg, lay, g_self)           # untimed: input generation
+        # untimed: input generation (only the slots batch 0 activates on this instance: the oracle
+        # reads no other)
         lg, Xh = W.router_logits(cfg, sub=0), W.activations(cfg, sub=0)
         opl = scheduling.make_placement(lay, cfg.E, cfg.n_inst, cfg.C)
+        ids0, _, _ = oracle_route(cfg, lg)
+        O0, _, _ = scheduling.aebs(ids0, opl)
+        cnt0, _, _ = dispatch.permute(O0, g_self, C)
+        W13h = np.zeros((C, 2 * d_e, d_h), dtype=np.float32)
+        W2h = np.zeros((C, d_h, d_e), dtype=np.float32)
+        for s_ in np.nonzero(cnt0 > 0)[0]:
+            W13h[s_], W2h[s_] = W.expert_weights(cfg, int(lay[g_self * C + s_]))
         reps, spent, sched_us = 0, 0.0, []
         while spent < 10.0 and reps < 20:
             c0 = time.perf_counter()
@@ -296,7 +371,9 @@ def main() -> None:
                                          f"NumPy fp64 oracle; {cpu_s * 1e3:.1f} ms per step, of which Alg. 1 "
                                          f"{statistics.median(sched_us):.0f} us",
                                "ms_per_step": round(cpu_s * 1e3, 2)}
-    print(json.dumps(out), flush=True)
+    del W13s, W2s, step
+    torch.cuda.empty_cache()
+    return out
 
 
 class TimingEvents:
@@ -382,25 +459,122 @@ def _time_us_graph(fn, per_graph=50, reps=8):
     return _time_us(g.replay, reps) / per_graph
 
 
-def read_probe(bufs, nbytes: int):
-    """A plain streaming read (moe_read_probe) of `nbytes` from each copy of the weight ring in
-    turn, one launch between two HIP events like the FFN launch it is compared with: the practical
-    ceiling for a launch that moves that many bytes.  Returns (median us, GB/s)."""
+PROBE_SHAPES = [(wg, u) for wg in (256, 512, 1024, 2048, 4096, 8192) for u in (2, 4, 8, 16)]
+
+
+def read_probe_sweep(bufs, nbytes: int):
+    """A plain streaming read (moe_read_probe, libmoe_bench) of `nbytes` from each copy of the weight
+    ring in turn, one launch between two HIP events like the FFN launch it is compared with, for every
+    launch shape of PROBE_SHAPES (workgroups of 256 threads x independent 16-byte loads in flight per
+    thread).  Returns a list of (workgroups, loads, median us, GB/s)."""
     import torch
     from paper_2512_13525_amd import binding as B
     sink = torch.zeros((64,), dtype=torch.int32, device="cuda")
     n = min(nbytes, min(t.numel() * t.element_size() for t in bufs)) // 16 * 16
     te = TimingEvents()
-    ev = []
-    for rep in range(8):                       # queued back to back, like the steps of the timed region
-        for t in bufs:
-            a, b = te.new(), te.new()
-            te.record(a); B.moe_read_probe(t, n, sink); te.record(b)
-            ev.append((a, b))
-    torch.cuda.synchronize()
-    us = statistics.median(te.us(a, b) for a, b in ev[len(bufs):])
+    res = []
+    for wg, u in PROBE_SHAPES:
+        ev = []
+        for rep in range(4):                       # queued back to back, like the steps of the timed region
+            for t in bufs:
+                a, b = te.new(), te.new()
+                te.record(a); B.moe_read_probe(t, n, sink, wg, u); te.record(b)
+                ev.append((a, b))
+        torch.cuda.synchronize()
+        us = statistics.median(te.us(a, b) for a, b in ev[len(bufs):])
+        res.append((wg, u, us, n / (us * 1e-6) / 1e9))
     te.close()
-    return us, n / (us * 1e-6) / 1e9
+    return res
+
+
+def read_probe_best(bufs, nbytes: int) -> dict:
+    """The best point of the read probe's launch-shape sweep for a launch of `nbytes`."""
+    wg, u, us, gbps = max(read_probe_sweep(bufs, nbytes), key=lambda r: r[3])
+    return {"us": round(us, 1), "GBps": round(gbps, 1), "workgroups": wg, "loads_in_flight": u,
+            "shapes_tried": len(PROBE_SHAPES)}
+
+
+def probe_sweep(args) -> None:
+    """The read probe over its launch shapes, for launches of the three decode workloads' byte counts."""
+    import torch
+    bufs = [torch.randint(0, 255, (int(1.6e9),), dtype=torch.uint8, device="cuda") for _ in range(4)]
+    for label, nbytes in (("qwen3 T=32", 77e6), ("qwen3 T=256", 115e6), ("dsv2lite T=128", 206e6), ("dsv3 T=512", 1290e6)):
+        for wg, u, us, gbps in read_probe_sweep(bufs, int(nbytes)):
+            print(json.dumps({"mode": "probe_sweep", "bytes_like": label, "MB": round(nbytes / 1e6, 1), "workgroups": wg,
+                              "loads_in_flight": u, "us": round(us, 2), "GBps": round(gbps, 1),
+                              "frac_of_8TBps": round(gbps / HBM_PEAK_GBPS, 3)}), flush=True)
+
+
+def calib_copy(args) -> None:
+    """Counter calibration: plain device-to-device copies of known size, so that what rocprofv3's
+    FETCH_SIZE / WRITE_SIZE read for them can scale the same counters read for the FFN kernel."""
+    import torch
+    mib, reps = 512, 4
+    n = mib << 20
+    # distinct source buffers so that every copy reads from HBM, not from the memory-side cache
+    srcs = [torch.full((n,), i + 1, dtype=torch.uint8, device="cuda") for i in range(reps)]
+    dst = torch.empty(n, dtype=torch.uint8, device="cuda")
+    torch.cuda.synchronize()
+    for t in srcs:
+        dst.copy_(t)
+    torch.cuda.synchronize()
+    print(json.dumps({"mode": "calib_copy", "copies": reps, "bytes_read_per_copy": n, "bytes_written_per_copy": n}), flush=True)
+
+
+def pmc_summary(args) -> None:
+    """No GPU: reads the rocprofv3 counter CSVs of four runs under --pmc-dir
+    (`<wl>_fetch/`, `<wl>_write/`: `bench.py --workload <wl> --no-other-rows --steps 20 --warmup 2 --no-cpu-baseline` under
+    `--pmc FETCH_SIZE` / `--pmc WRITE_SIZE`; `copy_fetch/`, `copy_write/`: `bench.py --mode calib_copy` under the same
+    counters), scales the FFN kernel's counters by the copy's, and records the HBM bytes per launch in
+    profiles/ffn_kernel_hbm_traffic.json, which the step mode quotes as `roofline.traffic`."""
+    import collections
+    import csv
+    import glob
+    import subprocess
+
+    def read(sub, counter):
+        vals = collections.defaultdict(list)
+        for f in glob.glob(os.path.join(args.pmc_dir, sub, "**", "*counter_collection.csv"), recursive=True):
+            for r in csv.DictReader(open(f)):
+                if r["Counter_Name"] == counter:
+                    vals[r["Kernel_Name"]].append(float(r["Counter_Value"]))
+        return vals
+
+    def mean_of(vals, pattern):
+        hits = [v for kname, vs in vals.items() if pattern in kname for v in vs]
+        return (statistics.mean(hits), len(hits)) if hits else (None, 0)
+
+    copy_bytes_kib = 512 * 1024
+    cf, _ = mean_of(read("copy_fetch", "FETCH_SIZE"), "copyBuffer")
+    cw, _ = mean_of(read("copy_write", "WRITE_SIZE"), "copyBuffer")
+    if not cf or not cw:
+        raise SystemExit("pmc_summary: the calibration copy's counters are missing")
+    f_fac, w_fac = copy_bytes_kib / cf, copy_bytes_kib / cw
+    try:
+        commit = subprocess.run(["git", "-C", ROOT, "rev-parse", "--short", "HEAD"], stdout=subprocess.PIPE, text=True).stdout.strip()
+    except OSError:
+        commit = None
+    try:
+        table = json.load(open(TRAFFIC_JSON))
+    except (OSError, ValueError):
+        table = {}
+    table["_calibration"] = {"FETCH_SIZE_factor": round(f_fac, 4), "WRITE_SIZE_factor": round(w_fac, 4),
+                             "copy_KiB": copy_bytes_kib, "FETCH_SIZE_read_KiB": round(cf, 1), "WRITE_SIZE_read_KiB": round(cw, 1)}
+    for wl, T in [HEADLINE] + OTHER_ROWS:
+        tag = f"{wl}_T{T}"
+        fetch, nf = mean_of(read(f"{tag}_fetch", "FETCH_SIZE"), "ffn_stream_kernel")
+        write, nw = mean_of(read(f"{tag}_write", "WRITE_SIZE"), "ffn_stream_kernel")
+        if fetch is None or write is None:
+            continue
+        rd, wr = fetch * f_fac * 1024, write * w_fac * 1024
+        table[f"{wl}-T{T}"] = {"hbm_bytes_per_launch": int(rd + wr), "read_bytes": int(rd), "written_bytes": int(wr),
+                               "dispatches": min(nf, nw), "kernel": "ffn_stream_kernel", "commit": commit,
+                               "command": f"rocprofv3 --pmc FETCH_SIZE|WRITE_SIZE -- python3 bench.py --workload {wl} "
+                                          f"--tokens {T} --no-other-rows --steps 20 --warmup 2 --no-cpu-baseline"}
+        print(json.dumps({"mode": "pmc_summary", "workload": wl, "T": T, **table[f"{wl}-T{T}"]}), flush=True)
+    with open(TRAFFIC_JSON, "w") as f:
+        json.dump(table, f, indent=1, sort_keys=True)
+        f.write("\n")
 
 
 def sched_sweep(args) -> None:
@@ -605,22 +779,59 @@ def split_sweeps(args) -> None:
         torch.cuda.empty_cache()
 
 
+def sample_loads(pl, bias, E, k, T, n_batches, gen, policies=("aebs",), keep_ids=0):
+    """Monte-Carlo sample for one cell of the a_max table: n_batches batches of T tokens drawn on the GPU
+    (logits N(0,1) + bias), routed in one launch and scheduled in ONE launch per policy
+    (moe_schedule_batched: one workgroup per batch).  Returns ({policy: loads [n_batches, n_inst]},
+    the first keep_ids batches' expert ids on the host, us of the AEBS launch per batch)."""
+    import torch
+    from paper_2512_13525_amd import binding as B
+    n_inst = pl.n_inst
+    ids = torch.empty((n_batches, T, k), dtype=torch.int32, device="cuda")
+    wts = torch.empty((n_batches * T, k), dtype=torch.float32, device="cuda")
+    chunk = max(1, (1 << 28) // (T * E))                    # batches per draw: at most 1 GiB of fp32 logits
+    for b0 in range(0, n_batches, chunk):
+        nb = min(chunk, n_batches - b0)
+        logits = torch.randn((nb * T, E), generator=gen, device="cuda") + bias
+        B.moe_route(logits, k, ids[b0:b0 + nb].view(nb * T, k), wts[:nb * T])
+    out = {}
+    us = None
+    for pol in policies:
+        loads = torch.zeros((n_batches, n_inst), dtype=torch.int32, device="cuda")
+        if pol == "aebs":
+            fn = lambda: B.moe_schedule_batched(pl, ids, n_batches, T, k, None, None, loads)
+            fn()
+            us = _time_us(fn, 5) / n_batches
+        elif pol == "home":
+            B.moe_schedule_baseline_batched(pl, ids, n_batches, T, k, B.MOE_POLICY_HOME, None, None, loads)
+        else:
+            draws = torch.randint(0, 1 << 31, (n_batches, T, k), generator=gen, device="cuda", dtype=torch.int32)
+            B.moe_schedule_baseline_batched(pl, ids, n_batches, T, k, B.MOE_POLICY_RANDOM, draws, None, loads)
+        out[pol] = loads
+    torch.cuda.synchronize()
+    return out, (ids[:keep_ids].cpu().numpy() if keep_ids else None), us
+
+
 def amax_study(args) -> None:
     """Monte-Carlo table of a_max (the largest per-instance number of activated experts, which
     Eq. 1c turns into the MoE-side latency) over sampled decode batches, for AEBS and for the two
     baseline policies (first replica only; random replica per request), next to the exact optimum
     on a subsample and the balls-into-bins bound of Eq. 5 (Appendix A).  E = 256, k = 8, Zipf 0.8,
-    replication 1.25; n_e instances and batch size B vary.  Logits are drawn on the GPU with the
-    recipe of the other workloads (N(0,1) + ln(E p_e))."""
+    replication 1.25; n_e instances and batch size B vary; --batches sampled batches per cell
+    (default 2000), all scheduled by one launch per policy.  Logits are drawn on the GPU with the
+    recipe of the other workloads (N(0,1) + ln(E p_e)).  The last line is the table a_max(n_e, B) in the
+    form moe_scaling_solve reads."""
     import numpy as np
     import torch
     from oracle import bounds, optimum, scheduling
     from paper_2512_13525_amd import binding as B
     from paper_2512_13525_amd import workloads as W
 
-    E, k, s, r, n_batches, n_opt = 256, 8, 0.8, 1.25, 200, 16
+    E, k, s, r, n_batches, n_opt = 256, 8, 0.8, 1.25, args.batches, 16
     gen = torch.Generator(device="cuda").manual_seed(7)
-    for n_inst in (8, 16, 32):
+    ne_values, B_values = [8, 16, 32], [64, 128, 256, 512, 1024]
+    table = np.zeros((len(ne_values), len(B_values)))
+    for ri, n_inst in enumerate(ne_values):
         C = int(np.ceil(E * r / n_inst))
         cfg0 = W.MoEConfig(f"amax_ne{n_inst}", E=E, k=k, d_h=64, d_e=64, T=1, n_inst=n_inst, C=C, zipf_s=s, seed=0)
         lay = W.build_placement(cfg0)
@@ -634,34 +845,29 @@ def amax_study(args) -> None:
         B.moe_route(torch.randn((Tc, E), generator=gen, device="cuda") + bias, k, ids, wts)
         p_e = np.bincount(ids.cpu().numpy().reshape(-1), minlength=E) / Tc
         hosted = [[int(e) for e in lay[g * C:(g + 1) * C] if e >= 0] for g in range(n_inst)]
-        for T in (64, 128, 256, 512, 1024):
-            ids = torch.empty((T, k), dtype=torch.int32, device="cuda")
-            wts = torch.empty((T, k), dtype=torch.float32, device="cuda")
+        for ci, T in enumerate(B_values):
+            loads, ids_keep, us_batch = sample_loads(pl, bias, E, k, T, n_batches, gen, ("aebs", "home", "random"), n_opt)
+            amax = {p: v.max(dim=1).values.cpu().numpy() for p, v in loads.items()}
+            # one launch per batch, for comparison (the single-batch entry point, graph-replayed)
+            one = torch.from_numpy(ids_keep[0]).cuda()
             rid = torch.empty((T, k), dtype=torch.int32, device="cuda")
             rep = torch.empty((E,), dtype=torch.int32, device="cuda")
-            loads = torch.zeros((3, n_batches, n_inst), dtype=torch.int32, device="cuda")
-            ids_keep = []
-            for b in range(n_batches):
-                logits = torch.randn((T, E), generator=gen, device="cuda") + bias
-                draws = torch.randint(0, 1 << 31, (T, k), generator=gen, device="cuda", dtype=torch.int32)
-                B.moe_route(logits, k, ids, wts)
-                B.moe_schedule(pl, ids, T, k, rid, rep, loads[0, b])
-                B.moe_schedule_baseline(pl, ids, T, k, B.MOE_POLICY_HOME, None, rid, loads[1, b])
-                B.moe_schedule_baseline(pl, ids, T, k, B.MOE_POLICY_RANDOM, draws, rid, loads[2, b])
-                if b < n_opt:
-                    ids_keep.append(ids.cpu().numpy().copy())
-            torch.cuda.synchronize()
-            amax = loads.max(dim=2).values.cpu().numpy()                       # [3, n_batches]
+            ld = torch.empty((n_inst,), dtype=torch.int32, device="cuda")
+            us_single = _time_us_graph(lambda: B.moe_schedule(pl, one, T, k, rid, rep, ld), 20, 4)
             opt = [optimum.optimum_matching(sorted(set(i.reshape(-1).tolist())), opl) for i in ids_keep]
             a_bar = max(bounds.expected_activated(p_e, h, T) for h in hosted)
+            table[ri, ci] = float(amax["aebs"].mean())
             print(json.dumps({"mode": "amax", "n_inst": n_inst, "C": C, "B": T, "batches": n_batches,
-                              "a_max_aebs": {"mean": round(float(amax[0].mean()), 2), "max": int(amax[0].max())},
-                              "a_max_home_only": {"mean": round(float(amax[1].mean()), 2), "max": int(amax[1].max())},
-                              "a_max_random": {"mean": round(float(amax[2].mean()), 2), "max": int(amax[2].max())},
+                              "a_max_aebs": {"mean": round(float(amax["aebs"].mean()), 3), "max": int(amax["aebs"].max())},
+                              "a_max_home_only": {"mean": round(float(amax["home"].mean()), 3), "max": int(amax["home"].max())},
+                              "a_max_random": {"mean": round(float(amax["random"].mean()), 3), "max": int(amax["random"].max())},
                               "a_max_optimum_mean_first16": round(float(np.mean(opt)), 2),
-                              "a_max_aebs_mean_first16": round(float(amax[0][:n_opt].mean()), 2),
-                              "eq4_expected_max": round(a_bar, 2), "eq5_bound": bounds.a_max_bound(a_bar, C, n_inst)}),
-                  flush=True)
+                              "a_max_aebs_mean_first16": round(float(amax["aebs"][:n_opt].mean()), 2),
+                              "eq4_expected_max": round(a_bar, 2), "eq5_bound": bounds.a_max_bound(a_bar, C, n_inst),
+                              "sched_us_per_batch_batched_launch": round(us_batch, 3),
+                              "sched_us_single_launch": round(us_single, 2)}), flush=True)
+    print(json.dumps({"mode": "amax_table", "policy": "aebs", "batches_per_cell": n_batches, "ne_values": ne_values,
+                      "B_values": B_values, "a_max_table": np.round(table, 3).tolist()}), flush=True)
 
 
 def all_configs(args) -> None:
@@ -830,7 +1036,8 @@ def scaling_study(args) -> None:
     """Alg. 2 (Sec. 3.5) on this machine's measurements: the MoE-side coefficients of Eq. 1c
     (beta, c_e) are fitted from layer times of the default workload's shape at 6 activation counts
     (16 requests on every activated slot),
-    a_max(n_e, B) is the Monte-Carlo mean of Alg. 1 on the GPU over 100 sampled batches per cell;
+    a_max(n_e, B) is the Monte-Carlo mean of Alg. 1 on the GPU over --batches sampled batches per cell
+    (default 2000, one batched launch per cell);
     the attention-side and communication coefficients have no counterpart in this build and are
     stated stand-ins.  Times in microseconds, demand in requests per microsecond."""
     import numpy as np
@@ -864,24 +1071,16 @@ def scaling_study(args) -> None:
         pts.append((a, _time_us(layer, 100)))
     beta, c_e = (float(v) for v in np.polyfit([p[0] for p in pts], [p[1] for p in pts], 1))
     del W13s, W2s
-    # ---- a_max table over (n_e, B)
-    ne_values, B_values, n_batches = [4, 8, 16], [16, 64, 256, 1024], 100
+    # ---- a_max table over (n_e, B): Monte-Carlo mean of Alg. 1, one batched launch per cell
+    ne_values, B_values, n_batches = [4, 8, 16], [16, 64, 256, 1024], args.batches
     table = np.zeros((len(ne_values), len(B_values)))
     for r, n_inst in enumerate(ne_values):
         cfg = W.MoEConfig(f"scale_ne{n_inst}", E=E, k=k, d_h=64, d_e=64, T=1, n_inst=n_inst, C=C, zipf_s=base.zipf_s, seed=0)
         pl = B.Placement(W.build_placement(cfg), E, n_inst, C)
         bias = torch.from_numpy(np.log(E * W.expert_popularity(cfg)).astype(np.float32)).cuda()
         for c, Bt in enumerate(B_values):
-            ids = torch.empty((Bt, k), dtype=torch.int32, device="cuda")
-            wts = torch.empty((Bt, k), dtype=torch.float32, device="cuda")
-            rid = torch.empty((Bt, k), dtype=torch.int32, device="cuda")
-            rep = torch.empty((E,), dtype=torch.int32, device="cuda")
-            loads = torch.zeros((n_batches, n_inst), dtype=torch.int32, device="cuda")
-            for b in range(n_batches):
-                B.moe_route(torch.randn((Bt, E), generator=gen, device="cuda") + bias, k, ids, wts)
-                B.moe_schedule(pl, ids, Bt, k, rid, rep, loads[b])
-            torch.cuda.synchronize()
-            table[r, c] = float(loads.max(dim=1).values.float().mean().item())
+            loads, _, _ = sample_loads(pl, bias, E, k, Bt, n_batches, gen)
+            table[r, c] = float(loads["aebs"].max(dim=1).values.float().mean().item())
     print(json.dumps({"mode": "scaling_inputs", "beta_us_per_expert": round(beta, 3), "c_e_us": round(c_e, 3),
                       "fit_points": [[a, round(t, 2)] for a, t in pts], "ne_values": ne_values, "B_values": B_values,
                       "a_max_table": np.round(table, 2).tolist()}), flush=True)

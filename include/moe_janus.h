@@ -142,6 +142,23 @@ int moe_schedule_baseline(const moe_placement_t *pl, const int32_t *topk_ids_dev
                           int policy, const uint32_t *draws_dev, int32_t *rid_dev, int32_t *load_dev,
                           void *stream);
 
+/* ------------------------------------------------------------------ batched scheduling
+ * Sec. 3.5: the scaling model reads a table a_max(n_e, B) estimated by Monte-Carlo sampling:
+ * batches of B tokens are drawn, scheduled, and the largest per-instance count is averaged.
+ * These two calls schedule n_batches independent batches of T tokens each in ONE launch (one
+ * workgroup per batch, the same code as moe_schedule / moe_schedule_baseline, same results bit
+ * for bit per batch):
+ *   topk_ids_dev [n_batches, T, k] -> load_dev [n_batches, n_inst]   (max over instances = a_max of the batch)
+ *   rid_dev [n_batches, T, k] and act_rep_dev [n_batches, E] are optional (NULL = not written);
+ *   draws_dev [n_batches, T, k] for MOE_POLICY_RANDOM.
+ * n_batches == 0 is a no-op.
+ */
+int moe_schedule_batched(const moe_placement_t *pl, const int32_t *topk_ids_dev, int n_batches, int T, int k,
+                         int32_t *rid_dev, int32_t *act_rep_dev, int32_t *load_dev, void *stream);
+int moe_schedule_baseline_batched(const moe_placement_t *pl, const int32_t *topk_ids_dev, int n_batches, int T, int k,
+                                  int policy, const uint32_t *draws_dev, int32_t *rid_dev, int32_t *load_dev,
+                                  void *stream);
+
 /* ------------------------------------------------------------------ a4: dispatch (Step 4)
  * Keeps the requests whose replica lives on instance g_self and groups them by local slot
  * s = rid - g_self*C, ascending request id inside a slot (a stable grouping: the output is
@@ -160,13 +177,16 @@ int moe_schedule_baseline(const moe_placement_t *pl, const int32_t *topk_ids_dev
  *                  Entries past B are left untouched.
  * n_local and B stay on the device; nothing is read back.  The grouped FFN cannot size its
  * launch by them, so it sizes it for moe_max_blocks() and lets the surplus leave at once.
+ * rid_dev may hold any values: entries outside [g_self*C, (g_self+1)*C) are simply not local, and
+ * a token may name one slot several times (the list never exceeds moe_max_blocks()).
  */
 int moe_permute(const moe_placement_t *pl, int g_self, const int32_t *rid_dev, int T, int k,
                 int32_t *slot_count_dev, int32_t *slot_off_dev, int32_t *perm_dev,
                 int32_t *pos_dev, int32_t *blocks_dev, void *stream);
 
-/* Largest number of blocks a batch of T tokens can produce on an instance with C slots (a slot
- * receives at most one request per token), and the int32 length of blocks_dev. */
+/* Largest number of blocks a batch of T tokens can produce on an instance with C slots, whatever
+ * the request ids are (C + T*k / R: one partly filled block per slot plus the full ones), and
+ * the int32 length of blocks_dev. */
 int moe_block_rows(int T);
 size_t moe_max_blocks(int T, int k, int C);
 size_t moe_block_list_len(int T, int k, int C);
@@ -305,9 +325,16 @@ int moe_pack_weights_bf16(const void *W13_dev, const void *W2_dev, int C, int d_
  *                    workspace must not overlap in time.
  * bf16 inputs are multiplied on the matrix cores with fp32 accumulation; `a` is rounded
  * to bf16 once.  The bf16 path is one launch in which the workgroups of the second stage
- * wait for flags raised by the first; the wait is bounded, and an overrun (which means the
- * control region was not cleared, or the GPU was shared with work that starved the kernel)
- * is reported by moe_workspace_status() instead of hanging.
+ * wait for flags raised by the first.  The wait is bounded: a workgroup whose wait runs out
+ * (which means the control region was not cleared, or the GPU was shared with work that starved
+ * the kernel) sets bit 0 of the status word, writes quiet NaNs into its rows of Yp instead of
+ * results (moe_combine propagates them) and leaves the block's control lines untouched.  After a
+ * non-zero status the workspace must be cleared with moe_workspace_init() before its next use.
+ * The second-stage workgroups have the higher ids of the launch and rely on the hardware starting
+ * workgroups in id order (every first-stage workgroup is started before any second-stage one gets a
+ * place); the flags are raised as long as the first-stage workgroups keep running, so only a GPU
+ * whose compute units are held by other work for longer than the spin limit (about a second) can
+ * overrun.
  * Limits: d_h % 32 == 0, d_e % 32 == 0 (bf16); d_h % 4 == 0, d_e % 4 == 0 (f32; T*k <= 65535);
  * moe_max_blocks(T, k, C) <= 4095 (bf16).
  */
@@ -325,22 +352,23 @@ int moe_grouped_ffn(const void *X_dev, const void *W13_dev, const void *W2_dev,
                     const int32_t *slot_off_dev, const int32_t *perm_dev, const int32_t *blocks_dev,
                     float *Yp_dev, void *workspace_dev, size_t workspace_bytes, void *stream);
 
-/* Tuning knob of the bf16 path (process-wide, not thread-safe against concurrent FFN calls).  For
- * batches of at least 1024 tokens, slots with more than 64 requests are computed by two
- * extra launches of a tiled GEMM (blocks of 128 rows) instead of the streaming launch, but only
- * when the batch has enough such blocks to fill the chip: (number of 128-row blocks) x (d_e / 64
- * workgroups per block) >= min_workgroups, default 512.  0 restores the default; results do not
- * depend on the setting beyond rounding order. */
-void moe_ffn_set_wide_min_workgroups(int min_workgroups);
-
-/* ------------------------------------------------------------------ measurement helper
- * Streams `bytes` (rounded down to 16) from src_dev with plain coalesced 128-bit loads and
- * discards them: the practical read-bandwidth ceiling that the weight stream of
- * moe_grouped_ffn (Sec. 2.2: the layer is bound by reading the activated experts' weights) is
- * reported against.  sink_dev: 256 bytes of device memory (written practically never).
- * src_dev 16-byte aligned.  Not a step of the layer.
+/* Per-workspace options of the bf16 path: a word in the workspace's header, written by a one-thread
+ * kernel on `stream` (so the call is ordered with the FFN calls on that stream and can be captured),
+ * read by every later moe_grouped_ffn on this workspace, reset to the default by
+ * moe_workspace_init.  value 0 = default; value < 0 is MOE_EINVAL.
+ *   MOE_WS_OPT_SPIN_LIMIT            polls a second-stage workgroup spends on its block's flag
+ *                                    before it gives up (default 2^20).  For tests of the overrun path.
+ *   MOE_WS_OPT_WIDE_MIN_WORKGROUPS   for batches of at least 1024 tokens, slots with more than 64
+ *                                    requests are computed by two extra launches of a tiled GEMM
+ *                                    (blocks of 128 rows) instead of the streaming launch, but only
+ *                                    when the batch has enough such blocks to fill the chip: (number
+ *                                    of 128-row blocks) x (d_e / 64 workgroups per block) >= this
+ *                                    value, default 512.  Results do not depend on it beyond
+ *                                    rounding order.
  */
-int moe_read_probe(const void *src_dev, size_t bytes, void *sink_dev, void *stream);
+#define MOE_WS_OPT_SPIN_LIMIT            0
+#define MOE_WS_OPT_WIDE_MIN_WORKGROUPS   1
+int moe_workspace_set_option(void *workspace_dev, size_t workspace_bytes, int option, int value, void *stream);
 
 /* ------------------------------------------------------------------ a6: combine
  * Y[i,:] = sum over j with pos[i*k+j] >= 0, in ascending j, of topk_w[i,j] * Yp[pos[i*k+j],:]

@@ -13,6 +13,7 @@ import numpy as np
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libmoe_janus.so")
+BENCH_LIB_PATH = os.path.join(_PKG, "libmoe_bench.so")
 
 MOE_OK = 0
 MOE_EINVAL, MOE_ESHAPE, MOE_EPLACEMENT, MOE_EHIP, MOE_ENOMEM, MOE_EWORKSPACE = -1, -2, -3, -4, -5, -6
@@ -24,14 +25,15 @@ MOE_POLICY_HOME, MOE_POLICY_RANDOM = 0, 1
 EXPORTS = [
     "moe_strerror", "moe_last_error",
     "moe_placement_create", "moe_placement_destroy", "moe_placement_replicas", "moe_placement_dims",
-    "moe_route", "moe_schedule", "moe_schedule_baseline", "moe_permute", "moe_block_rows", "moe_max_blocks", "moe_block_list_len",
+    "moe_route", "moe_schedule", "moe_schedule_baseline", "moe_schedule_batched", "moe_schedule_baseline_batched", "moe_permute", "moe_block_rows", "moe_max_blocks", "moe_block_list_len",
     "moe_route_schedule_permute", "moe_gate_sync_len", "moe_gate_route", "moe_gate_route_schedule_permute",
     "moe_coactivation_counts", "moe_replica_counts", "moe_place_replicas", "moe_scaling_solve",
     "moe_pack_weights_bf16",
     "moe_workspace_bytes", "moe_workspace_init", "moe_workspace_status", "moe_grouped_ffn", "moe_combine",
-    "moe_shared_dispatch", "moe_combine_shared", "moe_ffn_set_wide_min_workgroups",
-    "moe_read_probe",
+    "moe_shared_dispatch", "moe_combine_shared", "moe_workspace_set_option",
 ]
+BENCH_EXPORTS = ["moe_read_probe"]
+MOE_WS_OPT_SPIN_LIMIT, MOE_WS_OPT_WIDE_MIN_WORKGROUPS = 0, 1
 
 
 class moe_scaling_model(ctypes.Structure):
@@ -81,6 +83,10 @@ def lib() -> ctypes.CDLL:
     L.moe_schedule.argtypes = [vp, vp, ci, ci, vp, vp, vp, vp]
     L.moe_schedule_baseline.restype = ci
     L.moe_schedule_baseline.argtypes = [vp, vp, ci, ci, ci, vp, vp, vp, vp]
+    L.moe_schedule_batched.restype = ci
+    L.moe_schedule_batched.argtypes = [vp, vp, ci, ci, ci, vp, vp, vp, vp]
+    L.moe_schedule_baseline_batched.restype = ci
+    L.moe_schedule_baseline_batched.argtypes = [vp, vp, ci, ci, ci, ci, vp, vp, vp, vp]
     L.moe_permute.restype = ci
     L.moe_permute.argtypes = [vp, ci, vp, ci, ci, vp, vp, vp, vp, vp, vp]
     L.moe_block_rows.restype = ci
@@ -116,12 +122,10 @@ def lib() -> ctypes.CDLL:
     L.moe_workspace_status.argtypes = [vp, ctypes.POINTER(ci)]
     L.moe_grouped_ffn.restype = ci
     L.moe_grouped_ffn.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, ci, vp, vp, vp, vp, vp, cs, vp]
-    L.moe_read_probe.restype = ci
-    L.moe_read_probe.argtypes = [vp, cs, vp, vp]
     L.moe_combine.restype = ci
     L.moe_combine.argtypes = [vp, vp, vp, ci, ci, ci, ci, vp, vp]
-    L.moe_ffn_set_wide_min_workgroups.restype = None
-    L.moe_ffn_set_wide_min_workgroups.argtypes = [ci]
+    L.moe_workspace_set_option.restype = ci
+    L.moe_workspace_set_option.argtypes = [vp, cs, ci, ci, vp]
     L.moe_shared_dispatch.restype = ci
     L.moe_shared_dispatch.argtypes = [ci, vp, vp, vp, vp]
     L.moe_combine_shared.restype = ci
@@ -203,6 +207,17 @@ def moe_schedule(pl: Placement, topk_ids, T: int, k: int, rid, act_rep, load, st
 def moe_schedule_baseline(pl: Placement, topk_ids, T: int, k: int, policy: int, draws, rid, load, stream=None) -> None:
     _check(lib().moe_schedule_baseline(pl.handle, _ptr(topk_ids), T, k, policy, _ptr(draws), _ptr(rid), _ptr(load),
                                        _stream(stream)), "moe_schedule_baseline")
+
+
+def moe_schedule_batched(pl: Placement, topk_ids, n_batches: int, T: int, k: int, rid, act_rep, load, stream=None) -> None:
+    _check(lib().moe_schedule_batched(pl.handle, _ptr(topk_ids), n_batches, T, k, _ptr(rid), _ptr(act_rep), _ptr(load),
+                                      _stream(stream)), "moe_schedule_batched")
+
+
+def moe_schedule_baseline_batched(pl: Placement, topk_ids, n_batches: int, T: int, k: int, policy: int, draws, rid, load,
+                                  stream=None) -> None:
+    _check(lib().moe_schedule_baseline_batched(pl.handle, _ptr(topk_ids), n_batches, T, k, policy, _ptr(draws), _ptr(rid),
+                                               _ptr(load), _stream(stream)), "moe_schedule_baseline_batched")
 
 
 def moe_permute(pl: Placement, g_self: int, rid, T: int, k: int, slot_count, slot_off, perm, pos, blocks,
@@ -343,8 +358,27 @@ def moe_grouped_ffn(X, W13, W2, T: int, k: int, C: int, d_h: int, d_e: int, dtyp
            "moe_grouped_ffn")
 
 
-def moe_read_probe(src, nbytes: int, sink, stream=None) -> None:
-    _check(lib().moe_read_probe(_ptr(src), nbytes, _ptr(sink), _stream(stream)), "moe_read_probe")
+_bench_lib: Optional[ctypes.CDLL] = None
+
+
+def bench_lib() -> ctypes.CDLL:
+    """libmoe_bench.so: the measurement helpers of bench.py (include/moe_bench.h)."""
+    global _bench_lib
+    if _bench_lib is None:
+        if not os.path.exists(BENCH_LIB_PATH):
+            raise MoeError(MOE_EINVAL, f"{BENCH_LIB_PATH} is missing: build it with `python -m paper_2512_13525_amd.build`")
+        L = ctypes.CDLL(BENCH_LIB_PATH)
+        L.moe_read_probe.restype = ctypes.c_int
+        L.moe_read_probe.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_int, ctypes.c_int,
+                                     ctypes.c_void_p]
+        _bench_lib = L
+    return _bench_lib
+
+
+def moe_read_probe(src, nbytes: int, sink, workgroups: int = 512, loads_in_flight: int = 8, stream=None) -> None:
+    rc = bench_lib().moe_read_probe(_ptr(src), nbytes, _ptr(sink), workgroups, loads_in_flight, _stream(stream))
+    if rc != 0:
+        raise MoeError(rc, f"moe_read_probe: {rc}")
 
 
 def moe_combine(Yp, pos, topk_w, T: int, k: int, d_h: int, dtype: int, Y, stream=None) -> None:
@@ -361,5 +395,6 @@ def moe_combine_shared(Yp, pos, topk_w, Ys, T: int, k: int, d_h: int, dtype: int
                                     _stream(stream)), "moe_combine_shared")
 
 
-def moe_ffn_set_wide_min_workgroups(n: int) -> None:
-    lib().moe_ffn_set_wide_min_workgroups(n)
+def moe_workspace_set_option(workspace, option: int, value: int, stream=None) -> None:
+    _check(lib().moe_workspace_set_option(_ptr(workspace), workspace.numel() * workspace.element_size(), option, value,
+                                          _stream(stream)), "moe_workspace_set_option")

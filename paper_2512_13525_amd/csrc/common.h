@@ -38,8 +38,13 @@ inline int check_launch(const char *where) {
     return MOE_OK;
 }
 
-// Control region at the start of the FFN workspace: error word + hand-off counters (ffn_stream.hip)
+// Control region at the start of the FFN workspace: a header of 256 ints, then the hand-off counters
+// of the blocks (ffn_stream.hip).  Header words: the status bits, and two per-workspace options
+// that moe_workspace_set_option writes and moe_workspace_init resets to 0 (= the default).
 constexpr size_t kFfnCtrlBytes = 4u << 20;
+constexpr int kCtrlStatus = 1;           // bit 0: a wait overran; bit 1: list cut for another block size
+constexpr int kCtrlSpinLimit = 2;        // polls a stage-2 workgroup spends on a block's flag before it gives up
+constexpr int kCtrlWideMin = 3;          // threshold of the tiled-GEMM launches (see kWideMinWorkgroups)
 
 // Blocks of the work list that get workgroups of their own in the streaming launch (longer lists wrap around)
 constexpr unsigned kFfnLaneBlocks = 128;
@@ -48,13 +53,11 @@ constexpr unsigned kFfnLaneBlocks = 128;
 // workgroups), larger ones blocks of 64 (hot slots then re-read their expert half as often).
 inline int ffn_block_rows(int T) { return T < 384 ? 32 : MOE_FFN_BLOCK_ROWS; }
 
-// Upper bound of the number of blocks over all slots: a slot receives at most one request per
-// token (a token's k experts are distinct).
+// Upper bound of the number of blocks over all slots, whatever the requests are (also when a
+// token names one expert several times): every slot has at most one partly filled block, and
+// the full ones hold T*k requests at most.
 inline long long ffn_max_blocks(int T, int k, int C) {
-    const int rows = ffn_block_rows(T);
-    const long long per_slot = (T + rows - 1) / rows;
-    const long long a = C * per_slot, b = C + static_cast<long long>(T) * k / rows;
-    return a < b ? a : b;
+    return C + static_cast<long long>(T) * k / ffn_block_rows(T);
 }
 
 // bf16 grouped FFN (ffn_stream.hip); shapes validated by the caller.  `ctrl` is the zero-initialised
@@ -77,7 +80,6 @@ inline bool ffn_has_wide(int T) { return T >= kWideMinTokens; }
 constexpr int kWideMinWorkgroups = 512;
 constexpr int kWideWaves = 4;            // wavefronts (= packed weight tiles) of a tiled-GEMM workgroup
 inline int ffn_wide_tiles1(int d_e) { return (d_e / 16 + kWideWaves - 1) / kWideWaves; }
-int ffn_wide_min_workgroups();           // kWideMinWorkgroups unless moe_ffn_set_wide_min_workgroups changed it
 __device__ __forceinline__ bool ffn_wide_on(int4 head, int wide_tiles1, int min_workgroups) {
     return head.y == 64 && head.z > 0 && head.z * wide_tiles1 >= min_workgroups;
 }
@@ -86,7 +88,7 @@ inline size_t ffn_stream_act_bytes(int T, int k, int C, int d_e) {
     return (b + 255) / 256 * 256;
 }
 int launch_ffn_wide(const void *X, const void *W13p, const void *W2p, int T, int k, int C, int d_h, int d_e,
-                    const int32_t *blocks, const int32_t *perm, uint16_t *act_rows,
+                    const int32_t *blocks, const int32_t *perm, const int *ctrl, uint16_t *act_rows,
                     float *Yp, hipStream_t st);
 
 inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }

@@ -292,7 +292,8 @@ __device__ __forceinline__ int load_id(const int32_t *p, bool coherent) {
 //                     step costs a few scalar instructions per host;
 //   Step 3 (rewrite)  every thread maps its share of requests through actRep held in LDS.
 // The layout tables are staged into LDS first.  ids_coherent: the ids were written by other
-// workgroups of the same launch.
+// workgroups of the same launch.  rid and act_rep may be null (the batched launch of the a_max
+// study only wants the loads): Step 3 and the actRep stores are then skipped.
 __device__ __forceinline__ void aebs_block(const SchedTables &tb, SchedShared &sh, int E, int n_inst, int C,
                                            int n_words, const int32_t *__restrict__ ids, int n_pairs, int vec_ok,
                                            bool ids_coherent, int32_t *__restrict__ rid,
@@ -359,11 +360,12 @@ __device__ __forceinline__ void aebs_block(const SchedTables &tb, SchedShared &s
                     else rep = sh.single_rid[e];
                 }
                 sh.rep[e] = rep;
-                act_rep[e] = rep;
+                if (act_rep) act_rep[e] = rep;
             }
         }
         if (lane < n_inst) load_out[lane] = load;
     }
+    if (!rid) return;                                    // uniform: no barrier is skipped by part of the workgroup
     __syncthreads();
 
     // ---- Step 3: rewrite every request

@@ -131,14 +131,20 @@ void down_f32_kernel(const float *__restrict__ act, const float *__restrict__ W2
 }  // namespace
 
 namespace {
-int g_wide_min_workgroups = moe::kWideMinWorkgroups;
-}
-namespace moe {
-int ffn_wide_min_workgroups() { return g_wide_min_workgroups; }
-}  // namespace moe
+__global__ void set_word_kernel(int *p, int v) { *p = v; }
+}  // namespace
 
-extern "C" void moe_ffn_set_wide_min_workgroups(int min_workgroups) {
-    g_wide_min_workgroups = min_workgroups > 0 ? min_workgroups : moe::kWideMinWorkgroups;
+extern "C" int moe_workspace_set_option(void *workspace_dev, size_t workspace_bytes, int option, int value, void *stream) {
+    if (!workspace_dev || !moe::aligned(workspace_dev, 256)) return MOE_EINVAL;
+    if (workspace_bytes < kCtrlBytes) return MOE_EWORKSPACE;
+    if (value < 0) return MOE_EINVAL;
+    int word;
+    if (option == MOE_WS_OPT_SPIN_LIMIT) word = moe::kCtrlSpinLimit;
+    else if (option == MOE_WS_OPT_WIDE_MIN_WORKGROUPS) word = moe::kCtrlWideMin;
+    else return MOE_EINVAL;
+    hipLaunchKernelGGL(set_word_kernel, dim3(1), dim3(1), 0, static_cast<hipStream_t>(stream),
+                       static_cast<int *>(workspace_dev) + word, value);
+    return moe::check_launch("moe_workspace_set_option");
 }
 
 extern "C" size_t moe_workspace_bytes(int T, int k, int C, int d_h, int d_e, int dtype) {
@@ -165,7 +171,7 @@ extern "C" int moe_workspace_status(const void *workspace_dev, int *status_host)
     int hdr[2] = {0, 0};
     hipError_t e = hipMemcpy(hdr, workspace_dev, sizeof(hdr), hipMemcpyDeviceToHost);
     if (e != hipSuccess) { moe::set_hip_error(e, "moe_workspace_status"); return MOE_EHIP; }
-    *status_host = hdr[1];
+    *status_host = hdr[moe::kCtrlStatus];
     return MOE_OK;
 }
 
@@ -211,7 +217,7 @@ extern "C" int moe_grouped_ffn(const void *X_dev, const void *W13_dev, const voi
         if (moe::ffn_has_wide(T)) {
             uint16_t *act_rows = reinterpret_cast<uint16_t *>(ws + kCtrlBytes + moe::ffn_stream_act_bytes(T, k, C, d_e));
             const int rcw = moe::launch_ffn_wide(X_dev, W13_dev, W2_dev, T, k, C, d_h, d_e, blocks_dev,
-                                                 perm_dev, act_rows, Yp_dev, st);
+                                                 perm_dev, reinterpret_cast<const int *>(ws), act_rows, Yp_dev, st);
             if (rcw != MOE_OK) return rcw;
         }
         const int rc = moe::launch_ffn_stream(X_dev, W13_dev, W2_dev, T, k, C, d_h, d_e, blocks_dev, perm_dev,

@@ -26,8 +26,8 @@
 // flight and then waits until the 16-channel tiles of its block of `act` rows are all written: a
 // counter per block in the workspace is bumped by each stage-1 workgroup once its stores are
 // acknowledged; the workgroup that completes the count raises the block's ready flags, which the
-// stage-2 workgroups poll (bounded; an overrun raises the workspace's error word and the
-// workgroup carries on, so every wave reaches the end of the kernel).  The 8 XCDs do not share an
+// stage-2 workgroups poll (bounded; on an overrun the workgroup raises the workspace's error word,
+// writes NaN rows instead of results and leaves, so every wave reaches the end of the kernel).  The 8 XCDs do not share an
 // L2: `act` is written with agent-scope (write-through) stores, every 128-byte line of it has one
 // writing workgroup, and no workgroup reads a line before its block is ready, so plain loads see
 // the data; counters and flags are agent-scope atomics.  The last stage-2 workgroup of a block to
@@ -53,18 +53,6 @@ constexpr int kCtrlLineInts = 32;
 constexpr int kCtrlCopies = 7;
 constexpr int kCtrlBlockInts = (1 + kCtrlCopies) * kCtrlLineInts;
 constexpr int kMaxItems = static_cast<int>(moe::kFfnCtrlBytes / 4) / kCtrlBlockInts - 1;
-
-#ifdef MOE_STREAM_TRACE
-// timeline of every workgroup (debug builds only): [linear id][start, stage, end, xcc/cu, first operands
-// staged, K loop done, stores acknowledged, 0]
-__device__ long long g_trace[1 << 15][8];
-__device__ __forceinline__ void trace_stamp(int i) {
-    if (threadIdx.x == 0 && blockIdx.x < (1u << 15)) g_trace[blockIdx.x][i] = wall_clock64();
-}
-#define MOE_TSTAMP(i) trace_stamp(i)
-#else
-#define MOE_TSTAMP(i) do { } while (0)
-#endif
 
 struct StageArgs {
     const uint16_t *B;                   // token operand: X (stage 1, rows through perm) or act (stage 2, blocks)
@@ -163,28 +151,45 @@ __device__ __forceinline__ void reduce_store(const StreamArgs &a, const StageArg
 // stage-1 workgroup that completes the count raises the block's ready flags.  Called by the whole
 // workgroup; thread 0 polls one copy of the flag.  The second counter of the block counts the
 // stage-2 workgroups that got through: the last one clears the block's control lines for the
-// next call.
-__device__ __forceinline__ void wait_block_ready(const StreamArgs &a, int item, int tile, int n_readers) {
+// next call.  Returns false when the bounded wait ran out: the status word gets bit 0, the
+// block's control lines are left as they are (a late stage-1 tile may still bump them, so the
+// region needs moe_workspace_init before the next call), and the caller must not read `act`.
+__device__ __forceinline__ bool wait_block_ready(const StreamArgs &a, int *s_ok, int item, int tile, int n_readers) {
     if (threadIdx.x == 0) {
         int *blk = a.ctrl + (item + 1) * kCtrlBlockInts;
         const int *flag = blk + (1 + tile % kCtrlCopies) * kCtrlLineInts;
-        int spins = 0;
+        // header word 2: a spin limit for this workspace (tests of the overrun path); 0 = the default
+        const int lim_ws = a.ctrl[moe::kCtrlSpinLimit];
+        const int limit = lim_ws > 0 ? lim_ws : a.spin_limit;
+        int spins = 0, ok = 1;
         while (__hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0) {
-            if (++spins > a.spin_limit) {
-                __hip_atomic_fetch_or(a.ctrl + 1, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (++spins > limit) {
+                __hip_atomic_fetch_or(a.ctrl + moe::kCtrlStatus, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                ok = 0;
                 break;
             }
             __builtin_amdgcn_s_sleep(8);
         }
-        if (__hip_atomic_fetch_add(blk + 1, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == n_readers - 1) {
+        if (ok && __hip_atomic_fetch_add(blk + 1, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == n_readers - 1) {
             __hip_atomic_store(blk, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             __hip_atomic_store(blk + 1, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 #pragma unroll
             for (int c = 1; c <= kCtrlCopies; ++c)
                 __hip_atomic_store(blk + c * kCtrlLineInts, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
+        *s_ok = ok;
     }
     lds_barrier();
+    return *s_ok != 0;
+}
+
+// The rows of a stage-2 item whose block never became ready: quiet NaNs, so that the combine
+// propagates them and nobody mistakes the rows for results.
+__device__ __forceinline__ void store_nan_rows(const StreamArgs &a, const StageArgs &g, int tile, int row0, int n_rows) {
+    const float qnan = __uint_as_float(0x7fc00000u);
+    const f32x4 v = {qnan, qnan, qnan, qnan};
+    for (int i = threadIdx.x; i < n_rows * 8; i += kThreads)
+        *reinterpret_cast<f32x4 *>(a.Yp + static_cast<size_t>(row0 + i / 8) * g.out_stride + tile * 32 + (i % 8) * 4) = v;
 }
 
 // One stage-1 item with an even number of K-steps.  A super-step is two K-steps = 64 columns = one
@@ -288,7 +293,6 @@ __device__ __forceinline__ void stream_item_lines(const StreamArgs &a, const Sta
             if (d < n) MOE_LOAD_A(d, d);
         }
         int i = 0;
-        MOE_TSTAMP(4);
         for (; i + 2 * D <= n; i += D) {
 #pragma unroll
             for (int d = 0; d < D; ++d) {
@@ -321,7 +325,6 @@ __device__ __forceinline__ void stream_item_lines(const StreamArgs &a, const Sta
 #undef MOE_LOAD_B
 #undef MOE_STAGE_B
 #undef MOE_MMA_STEP
-    MOE_TSTAMP(5);
     __syncthreads();                                             // the staging tiles are reused for the reduction
     reduce_store<true, NT, TT>(a, g, red, acc, item, 0, tile, row0, row_end, wave, lane);
 }
@@ -410,7 +413,7 @@ __device__ __forceinline__ void stream_item_steps(const StreamArgs &a, const Sta
 // the wavefronts, 4 / U or 3 of them in flight for both operands, the weights issued before the
 // wait for the block (they do not depend on stage 1).
 template <int NT, int TT, int U, bool STREAM>
-__device__ __forceinline__ void stream_item_down(const StreamArgs &a, const StageArgs &g, char *lds,
+__device__ __forceinline__ void stream_item_down(const StreamArgs &a, const StageArgs &g, char *lds, int *s_ok,
                                                  const char *w, int item, int tile, int row0, int row_end,
                                                  int wave, int lane) {
     constexpr int D = U == 2 ? 2 : NT > 2 ? 3 : 4;               // steps in flight that fit the registers
@@ -461,8 +464,11 @@ __device__ __forceinline__ void stream_item_down(const StreamArgs &a, const Stag
 #pragma unroll
     for (int d = 0; d < D; ++d)
         if (d < n) MOE_LOAD_W(d, d);
-    wait_block_ready(a, item, tile, g.tiles);
-    MOE_TSTAMP(4);
+    if (!wait_block_ready(a, s_ok, item, tile, g.tiles)) {
+        const int m_ = row_end - row0;
+        store_nan_rows(a, g, tile, row0, m_ < TT * 16 ? m_ : TT * 16);
+        return;
+    }
     if (n > 0) {
 #pragma unroll
         for (int d = 0; d < D; ++d)
@@ -490,13 +496,13 @@ __device__ __forceinline__ void stream_item_down(const StreamArgs &a, const Stag
 #undef MOE_LOAD_W
 #undef MOE_LOAD_T
 #undef MOE_MMA_STEP
-    MOE_TSTAMP(5);
     reduce_store<false, NT, TT>(a, g, red, acc, item, 0, tile, row0, row_end, wave, lane);
 }
 
 // LINES: this stage has an even number of K-steps
 template <bool STAGE1, bool LINES, int TT>
-__device__ __forceinline__ void run_item(const StreamArgs &a, const StageArgs &g, char *lds, unsigned id) {
+__device__ __forceinline__ void run_item(const StreamArgs &a, const StageArgs &g, char *lds, int *s_ok, int wide_min,
+                                         unsigned id) {
     const int tile = id % g.tiles_pad, item = id / g.tiles_pad;
     if (tile >= g.tiles) return;
     // work list entry: {slot, first row, end of the slot's rows, first of the slot's rows}; entry 0 holds the number of blocks
@@ -507,7 +513,7 @@ __device__ __forceinline__ void run_item(const StreamArgs &a, const StageArgs &g
     if (item >= n_blocks) return;                                // past the last block: nothing else is read
     // lists with blocks of 64 rows: slots with more than 64 requests belong to the tiled-GEMM launches
     // when those are on for this batch
-    if (TT == 4 && moe::ffn_wide_on(list[0], a.wide_tiles1, a.wide_min) && ent.z - ent.w > 64) return;
+    if (TT == 4 && moe::ffn_wide_on(list[0], a.wide_tiles1, wide_min) && ent.z - ent.w > 64) return;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / MOE_WAVE), lane = threadIdx.x % MOE_WAVE;
     const int slot = ent.x, row0 = ent.y, hi = ent.z;
     const char *w = g.Wp + (static_cast<size_t>(slot) * g.tiles + tile) * g.KS * 2048;
@@ -517,8 +523,8 @@ __device__ __forceinline__ void run_item(const StreamArgs &a, const StageArgs &g
         const int tiles16 = ((m < TT * 16 ? m : TT * 16) + 15) >> 4;     // 16-row token tiles that hold requests
 #define MOE_CASE(NT, U)                                                                              \
     case NT:                                                                                         \
-        if (single) stream_item_down<NT, TT, U, true>(a, g, lds, w, item, tile, row0, hi, wave, lane);  \
-        else stream_item_down<NT, TT, U, false>(a, g, lds, w, item, tile, row0, hi, wave, lane);        \
+        if (single) stream_item_down<NT, TT, U, true>(a, g, lds, s_ok, w, item, tile, row0, hi, wave, lane);  \
+        else stream_item_down<NT, TT, U, false>(a, g, lds, s_ok, w, item, tile, row0, hi, wave, lane);        \
         break;
         if constexpr (TT == 2) {
             switch (tiles16) { MOE_CASE(1, LINES ? 2 : 1) MOE_CASE(2, LINES ? 2 : 1) }
@@ -553,7 +559,6 @@ __device__ __forceinline__ void run_item(const StreamArgs &a, const StageArgs &g
         // one thread bumps the block's counter and, if it completes the count, raises the ready flags
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
-        MOE_TSTAMP(6);
         if (threadIdx.x == 0) {
             int *blk = a.ctrl + (item + 1) * kCtrlBlockInts;
             if (__hip_atomic_fetch_add(blk, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == g.tiles - 1) {
@@ -583,9 +588,7 @@ void ffn_stream_kernel(StreamArgs a) {
     __shared__ __attribute__((aligned(16))) char lds[kWaves * 2 * TT * MOE_WAVE * 16];
     static_assert(kWaves * TT * 2048 <= sizeof(lds), "staging tiles must fit in the reduction buffer");
     __shared__ unsigned long long s_visit;
-#ifdef MOE_STREAM_TRACE
-    const long long t_start = wall_clock64();
-#endif
+    __shared__ int s_ok;
     {
         // ids are decoded with the number of blocks the batch really has, so that the surplus of
         // the worst-case grid comes after all the work of both stages
@@ -593,8 +596,14 @@ void ffn_stream_kernel(StreamArgs a) {
         if (head.y != TT * 16) {
             // the list was cut for another block size (made for a different T): refuse, visibly
             if (threadIdx.x == 0 && blockIdx.x == 0)
-                __hip_atomic_fetch_or(a.ctrl + 1, 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_fetch_or(a.ctrl + moe::kCtrlStatus, 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             return;
+        }
+        // header word 3 of the workspace: the caller's threshold for the tiled-GEMM launches (0 = default)
+        int wide_min = a.wide_min;
+        if (TT == 4 && wide_min != 0x7fffffff) {
+            const int o = a.ctrl[moe::kCtrlWideMin];
+            wide_min = o > 0 ? o : wide_min;
         }
         // Up to kFfnLaneBlocks blocks have workgroups of their own; a longer list wraps around (the
         // workgroup of block b also takes blocks b + kFfnLaneBlocks, ..., at most 64 of them), which
@@ -604,8 +613,8 @@ void ffn_stream_kernel(StreamArgs a) {
         const unsigned lanes = n_blocks < moe::kFfnLaneBlocks ? n_blocks : moe::kFfnLaneBlocks;
         const unsigned n1 = lanes * a.s[0].tiles_pad, n2 = lanes * a.s[1].tiles_pad;
         if (n_blocks <= lanes) {
-            if (blockIdx.x < n1) run_item<true, LINES1, TT>(a, a.s[0], lds, blockIdx.x);
-            else if (blockIdx.x - n1 < n2) run_item<false, LINES2, TT>(a, a.s[1], lds, blockIdx.x - n1);
+            if (blockIdx.x < n1) run_item<true, LINES1, TT>(a, a.s[0], lds, &s_ok, wide_min, blockIdx.x);
+            else if (blockIdx.x - n1 < n2) run_item<false, LINES2, TT>(a, a.s[1], lds, &s_ok, wide_min, blockIdx.x - n1);
         } else if (blockIdx.x < n1 + n2) {
             // a long list: the first wavefront looks at all the blocks of this workgroup at once (lane l:
             // block + l*lanes) and the workgroup then visits only those that are its own to compute
@@ -618,7 +627,7 @@ void ffn_stream_kernel(StreamArgs a) {
                 bool mine = false;
                 if (b < n_blocks) {
                     const int4 e = reinterpret_cast<const int4 *>(a.blocks)[1 + b];
-                    mine = !(TT == 4 && moe::ffn_wide_on(head, a.wide_tiles1, a.wide_min) && e.z - e.w > 64);
+                    mine = !(TT == 4 && moe::ffn_wide_on(head, a.wide_tiles1, wide_min) && e.z - e.w > 64);
                 }
                 const unsigned long long m = __ballot(mine);
                 if (threadIdx.x == 0) s_visit = m;
@@ -631,20 +640,11 @@ void ffn_stream_kernel(StreamArgs a) {
                 visit &= visit - 1;
                 if (!first) __syncthreads();                         // the LDS buffer is reused
                 first = false;
-                if (s1) run_item<true, LINES1, TT>(a, a.s[0], lds, id0 + l * n1);
-                else run_item<false, LINES2, TT>(a, a.s[1], lds, id0 + l * n2);
+                if (s1) run_item<true, LINES1, TT>(a, a.s[0], lds, &s_ok, wide_min, id0 + l * n1);
+                else run_item<false, LINES2, TT>(a, a.s[1], lds, &s_ok, wide_min, id0 + l * n2);
             }
         }
     }
-#ifdef MOE_STREAM_TRACE
-    if (threadIdx.x == 0 && blockIdx.x < (1u << 15)) {
-        unsigned hwid, hw2;
-        asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(hwid));
-        asm volatile("s_getreg_b32 %0, hwreg(HW_REG_HW_ID)" : "=s"(hw2));
-        long long *tr = g_trace[blockIdx.x];
-        tr[0] = t_start; tr[1] = blockIdx.x < static_cast<unsigned>(reinterpret_cast<const int4 *>(a.blocks)[0].x) * a.s[0].tiles_pad; tr[2] = wall_clock64(); tr[3] = (static_cast<long long>(hwid) << 32) | hw2;
-    }
-#endif
 }
 
 template <bool L1, bool L2>
@@ -675,7 +675,7 @@ int launch_ffn_stream(const void *X, const void *W13p, const void *W2p, int T, i
     a.blocks = blocks; a.perm = perm; a.act = act; a.Yp = Yp; a.ctrl = ctrl; a.k = k; a.C = C;
     a.spin_limit = 1 << 20;
     a.wide_tiles1 = ffn_wide_tiles1(d_e);
-    a.wide_min = ffn_has_wide(T) ? ffn_wide_min_workgroups() : 0x7fffffff;
+    a.wide_min = ffn_has_wide(T) ? kWideMinWorkgroups : 0x7fffffff;
     a.s[0].B = static_cast<const uint16_t *>(X);
     a.s[0].Wp = static_cast<const char *>(W13p);
     a.s[0].tiles = d_e / 16; a.s[0].KS = d_h / 32; a.s[0].b_stride = d_h; a.s[0].out_stride = 0;
@@ -692,8 +692,3 @@ int launch_ffn_stream(const void *X, const void *W13p, const void *W2p, int T, i
 
 }  // namespace moe
 
-#ifdef MOE_STREAM_TRACE
-extern "C" int moe_debug_stream_trace(long long *host, size_t bytes) {
-    return hipMemcpyFromSymbol(host, HIP_SYMBOL(g_trace), bytes) == hipSuccess ? 0 : 1;
-}
-#endif

@@ -43,6 +43,7 @@ struct WideArgs {
     const char *B;                       // token operand: X (stage 1, rows through perm) or the intermediate (stage 2)
     const char *Wp;                      // packed weights: [C][ptiles][KS][2][64] fragments of 16 bytes
     const int32_t *blocks, *perm;
+    const int *ctrl;                     // control region of the workspace (header word kCtrlWideMin)
     uint16_t *act;                       // stage-1 output [request row][out_stride]
     float *Yp;                           // stage-2 output [request row][out_stride]
     int ptiles, tiles, tiles_pad, KS;    // tiles = workgroup tiles of 4 packed tiles
@@ -67,7 +68,9 @@ void ffn_wide_kernel(WideArgs a) {
     if (tile >= a.tiles) return;
     const int4 *list = reinterpret_cast<const int4 *>(a.blocks);
     const int4 head = list[0];
-    if (item >= head.x || !moe::ffn_wide_on(head, a.tiles1, a.wide_min)) return;
+    if (item >= head.x) return;
+    const int wm_ws = a.ctrl[moe::kCtrlWideMin];                     // the workspace's threshold, 0 = default
+    if (!moe::ffn_wide_on(head, a.tiles1, wm_ws > 0 ? wm_ws : a.wide_min)) return;
     const int4 ent = list[1 + item];
     const int slot = ent.x, row0 = ent.y, hi = ent.z;
     const int lo = ent.w;                                            // first of the slot's rows
@@ -250,15 +253,15 @@ namespace moe {
 // Both stages for every wide block of the list (two launches sized for the largest possible number
 // of blocks; workgroups that find no wide block leave after three scalar loads).
 int launch_ffn_wide(const void *X, const void *W13p, const void *W2p, int T, int k, int C, int d_h, int d_e,
-                    const int32_t *blocks, const int32_t *perm, uint16_t *act_rows,
+                    const int32_t *blocks, const int32_t *perm, const int *ctrl, uint16_t *act_rows,
                     float *Yp, hipStream_t st) {
     const long long items = ffn_max_blocks(T, k, C);
     WideArgs a;
-    a.blocks = blocks; a.perm = perm; a.act = act_rows; a.Yp = Yp; a.k = k;
+    a.blocks = blocks; a.perm = perm; a.ctrl = ctrl; a.act = act_rows; a.Yp = Yp; a.k = k;
     // stage 1
     a.B = static_cast<const char *>(X); a.Wp = static_cast<const char *>(W13p);
     a.ptiles = d_e / 16; a.KS = d_h / 32; a.b_row_bytes = static_cast<uint32_t>(d_h) * 2; a.out_stride = d_e;
-    a.tiles = (a.ptiles + kWaves - 1) / kWaves; a.tiles_pad = (a.tiles + 7) / 8 * 8; a.tiles1 = a.tiles; a.wide_min = ffn_wide_min_workgroups();
+    a.tiles = (a.ptiles + kWaves - 1) / kWaves; a.tiles_pad = (a.tiles + 7) / 8 * 8; a.tiles1 = a.tiles; a.wide_min = kWideMinWorkgroups;
     if (items * a.tiles_pad > 0x7fffffffLL) return MOE_ESHAPE;
     hipLaunchKernelGGL(ffn_wide_kernel<true>, dim3(static_cast<unsigned>(items * a.tiles_pad)), dim3(kThreads), 0, st, a);
     // stage 2

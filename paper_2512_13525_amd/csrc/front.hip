@@ -202,14 +202,6 @@ __device__ __forceinline__ TablePrefetch prefetch_tables(const FrontArgs &a) {
     return t;
 }
 
-#ifdef MOE_FRONT_TRACE
-// phase stamps of the last workgroup and arrival stamps of all (debug builds only)
-__device__ long long g_ftrace[64 + 2 * 4096];
-#define MOE_FSTAMP(i) do { if (threadIdx.x == 0) g_ftrace[i] = wall_clock64(); } while (0)
-#else
-#define MOE_FSTAMP(i) do { } while (0)
-#endif
-
 struct SmallShared {
     moe::SchedShared sched;
     moe::PermShared perm;
@@ -224,7 +216,6 @@ __device__ __forceinline__ void front_tail_small(const FrontArgs &a, SmallShared
     const int n_groups = (n_pairs + MOE_WAVE - 1) / MOE_WAVE;
     const int gpw = (n_groups + moe::kFrontWaves - 1) / moe::kFrontWaves;   // <= kGpwMax
 
-    MOE_FSTAMP(2);
     // ---- one round trip: request ids (written by other workgroups: agent-scope loads) and tables
     int id[kGpwMax];
 #pragma unroll
@@ -243,14 +234,12 @@ __device__ __forceinline__ void front_tail_small(const FrontArgs &a, SmallShared
     if (tid * 8 < E * n_inst) reinterpret_cast<uint4 *>(sh.slot_of)[tid] = tp.slot_of;
     for (int i = tid; i < moe::kFrontWaves * MOE_MAX_SLOTS; i += moe::kFrontThreads) (&sh.perm.cnt[0][0])[i] = 0;
     __syncthreads();
-    MOE_FSTAMP(3);
 
     // ---- Step 1
 #pragma unroll
     for (int g = 0; g < kGpwMax; ++g)
         if (id[g] >= 0) sh.sched.flag[id[g]] = 1u;
     __syncthreads();
-    MOE_FSTAMP(4);
 
     // ---- Step 2 (first wavefront), as in aebs_block but with slot_of in LDS
     if (tid < MOE_WAVE) {
@@ -295,7 +284,6 @@ __device__ __forceinline__ void front_tail_small(const FrontArgs &a, SmallShared
         if (lane < n_inst) a.load[lane] = load;
     }
     __syncthreads();
-    MOE_FSTAMP(5);
 
     // ---- Step 3 and pass A of the sort
     const int rid_lo = a.g_self * C;
@@ -323,12 +311,9 @@ __device__ __forceinline__ void front_tail_small(const FrontArgs &a, SmallShared
         a.slot_count[s] = run;
     }
     __syncthreads();
-    MOE_FSTAMP(6);
     if (wave == 0) moe::scan_slots(sh.perm, C, a.block_rows, a.slot_off, lane);
     __syncthreads();
-    MOE_FSTAMP(7);
     moe::list_blocks(sh.perm, C, a.block_rows, a.blocks);
-    MOE_FSTAMP(8);
 
     // ---- pass B
     if (C <= MOE_WAVE) {
@@ -358,7 +343,6 @@ __device__ __forceinline__ void front_tail_small(const FrontArgs &a, SmallShared
                 }
             }
         }
-        MOE_FSTAMP(9);
         return;
     }
     volatile int *base = &sh.perm.cnt[wave][0];
@@ -389,7 +373,6 @@ __device__ __forceinline__ void front_tail_small(const FrontArgs &a, SmallShared
             }
         }
     }
-    MOE_FSTAMP(9);
 }
 
 template <int VPL, bool GATE>
@@ -406,9 +389,6 @@ void front_kernel(FrontArgs a) {
     __shared__ Shared sh;
     __shared__ int s_last;
 
-#ifdef MOE_FRONT_TRACE
-    if (threadIdx.x == 0 && blockIdx.x < 4096) g_ftrace[64 + 2 * blockIdx.x] = wall_clock64();
-#endif
     const int wave = threadIdx.x / MOE_WAVE;
     const int lane = moe::lane_id();
     const int n_pairs = a.T * a.k;
@@ -463,13 +443,9 @@ void front_kernel(FrontArgs a) {
                                         a.ids + static_cast<size_t>(t) * a.k, a.w + static_cast<size_t>(t) * a.k);
         }
     }
-#ifdef MOE_FRONT_TRACE
-    if (threadIdx.x == 0 && blockIdx.x < 4096) g_ftrace[64 + 2 * blockIdx.x + 1] = wall_clock64();
-#endif
     // a workgroup barrier does not wait for global stores: the ticket must not overtake the ids
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
-    MOE_FSTAMP(0);
     if (threadIdx.x == 0) {
         const int old = __hip_atomic_fetch_add(a.ticket, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         s_last = old == expected - 1;
@@ -477,7 +453,6 @@ void front_kernel(FrontArgs a) {
     }
     __syncthreads();
     if (!s_last) return;
-    MOE_FSTAMP(1);
 
     if (small) {
         front_tail_small(a, sh.small, n_pairs, tp);
@@ -621,8 +596,3 @@ extern "C" int moe_gate_route_schedule_permute(const moe_placement_t *pl, int g_
     return launch_front_for<true>(a, "moe_gate_route_schedule_permute", static_cast<hipStream_t>(stream));
 }
 
-#ifdef MOE_FRONT_TRACE
-extern "C" int moe_debug_front_trace(long long *host, size_t bytes) {
-    return hipMemcpyFromSymbol(host, HIP_SYMBOL(g_ftrace), bytes) == hipSuccess ? 0 : 1;
-}
-#endif

@@ -12,8 +12,8 @@ from paper_2512_13525_amd import binding as B
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def declared_functions():
-    src = open(os.path.join(ROOT, "include", "moe_janus.h")).read()
+def declared_functions(header="moe_janus.h"):
+    src = open(os.path.join(ROOT, "include", header)).read()
     src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
     return sorted(set(re.findall(r"\b(moe_[a-z0-9_]+)\s*\(", src)))
 
@@ -25,6 +25,12 @@ def test_header_symbols_are_exported():
     for n in names:
         assert hasattr(L, n), n
     assert sorted(names) == sorted(B.EXPORTS)
+    # the measurement helpers of bench.py live in a library of their own
+    bench = declared_functions("moe_bench.h")
+    assert bench == sorted(B.BENCH_EXPORTS)
+    for n in bench:
+        assert hasattr(B.bench_lib(), n), n
+        assert not hasattr(L, n), n
 
 
 def test_strerror():
@@ -87,13 +93,14 @@ def test_argument_validation_without_launch():
     assert L.moe_combine(None, None, None, 4, 2, 128, B.MOE_DTYPE_F32, None, None) == B.MOE_EINVAL
     assert L.moe_pack_weights_bf16(None, None, 2, 100, 64, None, None, None) == B.MOE_ESHAPE
     assert L.moe_workspace_init(None, 0, None) == B.MOE_EINVAL
-    # a slot gets at most one request per token: min(C*ceil(T/R), C + T*k/R) blocks of R rows
+    # one partly filled block per slot plus the full ones: C + T*k/R blocks of R rows
     assert L.moe_block_rows(128) == 32 and L.moe_block_rows(512) == B.MOE_FFN_BLOCK_ROWS == 64
     assert L.moe_max_blocks(128, 6, 17) == 17 + 128 * 6 // 32
-    assert L.moe_max_blocks(16, 8, 36) == 36
+    assert L.moe_max_blocks(16, 8, 36) == 36 + 16 * 8 // 32
     assert L.moe_max_blocks(512, 8, 36) == 36 + 512 * 8 // 64
     assert L.moe_block_list_len(128, 6, 17) == 4 * (1 + 41)
     assert L.moe_workspace_status(None, None) == B.MOE_EINVAL
+    assert L.moe_workspace_set_option(None, 0, 0, 0, None) == B.MOE_EINVAL
     ws = L.moe_workspace_bytes(128, 6, 17, 2048, 1408, B.MOE_DTYPE_BF16)
     assert ws >= 128 * 6 * 1408 * 2 and ws % 256 == 0
     assert L.moe_workspace_bytes(64, 2, 5, 256, 512, B.MOE_DTYPE_F32) >= 64 * 2 * 512 * 4

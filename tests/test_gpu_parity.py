@@ -195,13 +195,16 @@ def test_schedule_empty_batch_and_layout_swap():
 FFN_CFGS = [W.tiny(), small(), small("multi_tile", T=300, k=4, E=8, n_inst=2, C=5, d_h=128, d_e=160, zipf_s=1.5),
             small("f32_ragged", dtype="f32", T=21, d_h=36, d_e=20),
             W.dsv2lite(), W.qwen3(32), W.qwen3(256), W.qwen3(1024), W.stress(64, 1.25, 0.8),
-            W.stress(2048, 1.25, 0.8), W.dsv3(512)]
+            W.stress(2048, 1.25, 0.8), W.dsv3(512),
+            # token-heavy points of the stress sweep: the tiled-GEMM launches (taken by the rule) next to the
+            # streaming launch on a list that wraps around
+            W.stress(4096, 1.25, 0.8), W.stress(8192, 1.25, 0.8)]
 
 
 @pytest.mark.parametrize("cfg", FFN_CFGS, ids=lambda c: f"{c.name}-T{c.T}")
 def test_layer_parity(cfg):
     """route -> schedule -> permute -> grouped FFN -> combine for the straggler instance."""
-    big = cfg.C * cfg.d_h * cfg.d_e > (1 << 28)
+    big = cfg.C * cfg.d_h * cfg.d_e > (1 << 26)
     orc = OracleRun(cfg, only_activated=big)      # big layers: unread slots hold NaN instead of weights
     print(f"  oracle ready: g_self={orc.g_self} n_local={len(orc.perm)} a_g={int((orc.slot_count > 0).sum())}", flush=True)
     step = LayerStep(cfg, orc.lay, orc.g_self)
@@ -336,12 +339,11 @@ def test_ffn_block_boundaries(d_h, d_e, T):
     for rep in range(3):
         # rep 1: the tiled-GEMM launches take the slots with more than 64 requests even though this
         # batch would not fill the chip with them (they exist for batches of at least 1024 tokens)
-        B.moe_ffn_set_wide_min_workgroups(1 if rep == 1 else 0)
+        B.moe_workspace_set_option(ws, B.MOE_WS_OPT_WIDE_MIN_WORKGROUPS, 1 if rep == 1 else 0)
         Yp.fill_(123.0)
         B.moe_grouped_ffn(to_device_bf16(X), W13p, W2p, T, k, C, d_h, d_e, B.MOE_DTYPE_BF16,
                           torch.from_numpy(slot_off).cuda(), torch.from_numpy(perm).cuda(), d_blk, Yp, ws)
         torch.cuda.synchronize()
-        B.moe_ffn_set_wide_min_workgroups(0)
         got = Yp.cpu().numpy()
         assert (got[n_local:] == 123.0).all()
         num = np.linalg.norm(got[:n_local] - Yp_ref, axis=1)
@@ -625,12 +627,10 @@ def test_layer_parity_with_tiled_gemm_forced_on(cfg):
     upload_weights(step, cfg, orc.W13, orc.W2)
     step.Yp.fill_(123.0)
     n_local = len(orc.perm)
-    try:
-        B.moe_ffn_set_wide_min_workgroups(1)
-        Y = step.step_fused(torch.from_numpy(orc.logits).cuda(), upload_x(cfg, orc.X))
-        torch.cuda.synchronize()
-    finally:
-        B.moe_ffn_set_wide_min_workgroups(0)
+    B.moe_workspace_set_option(step.workspace, B.MOE_WS_OPT_WIDE_MIN_WORKGROUPS, 1)
+    Y = step.step_fused(torch.from_numpy(orc.logits).cuda(), upload_x(cfg, orc.X))
+    torch.cuda.synchronize()
+    B.moe_workspace_set_option(step.workspace, B.MOE_WS_OPT_WIDE_MIN_WORKGROUPS, 0)
     Yp = step.Yp.cpu().numpy()
     assert (Yp[n_local:] == 123.0).all() and np.isfinite(Yp[:n_local]).all()
     num = np.linalg.norm(Yp[:n_local] - orc.Yp, axis=1)
@@ -757,3 +757,170 @@ def test_layer_parity_random_shapes(seed):
         else:
             assert not Y.float().cpu().numpy().any()
         assert B.moe_workspace_status(step.workspace) == 0
+
+
+@pytest.mark.parametrize("a", [1, 2, 17])
+def test_ffn_all_requests_on_a_slots(a):
+    """The shape of the activated-expert sweep (Sec. 2.2: a fixed batch of 64 tokens whose T*k requests
+    all land on exactly `a` experts of the instance, evenly): dispatch through moe_permute, rows
+    against the oracle's grouped FFN.  With a < k a token names one slot several times."""
+    cfg = W.dsv2lite(64)
+    T, k, C = cfg.T, cfg.k, cfg.C
+    lay = W.build_placement(cfg)
+    rid = (np.arange(T * k, dtype=np.int32) % a).reshape(T, k)
+    slot_count, slot_off, perm = dispatch.permute(rid, 0, C)
+    assert (slot_count > 0).sum() == a and slot_count.sum() == T * k
+    X = W.activations(cfg)
+    W13 = np.full((C, 2 * cfg.d_e, cfg.d_h), np.nan, dtype=np.float32)
+    W2 = np.full((C, cfg.d_h, cfg.d_e), np.nan, dtype=np.float32)
+    for s_ in range(a):
+        W13[s_], W2[s_] = W.expert_weights(cfg, int(lay[s_]))
+    Yp_ref = ffn.grouped_ffn(X, W13, W2, slot_off, perm, k)
+    st = LayerStep(cfg, lay, 0)
+    upload_weights(st, cfg, W13, W2)
+    st.rid.copy_(torch.from_numpy(rid))
+    st.Yp.fill_(123.0)
+    for rep in range(2):
+        st.permute()
+        st.ffn(upload_x(cfg, X))
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(st.slot_off.cpu().numpy(), slot_off)
+        np.testing.assert_array_equal(st.perm.cpu().numpy(), perm)
+        blk = st.blocks.cpu().numpy()
+        exp = expected_blocks(slot_off, B.moe_block_rows(T))
+        assert exp[0] <= B.moe_max_blocks(T, k, C)
+        np.testing.assert_array_equal(blk[:len(exp)], exp)
+        got = st.Yp.cpu().numpy()
+        num = np.linalg.norm(got - Yp_ref, axis=1)
+        den = np.linalg.norm(Yp_ref, axis=1)
+        assert (num <= 2.5 * TOL_BF16 * den + 1e-30).all()
+        assert rel_fro(got, Yp_ref) < TOL_BF16
+        assert B.moe_workspace_status(st.workspace) == 0
+
+
+def test_ffn_wait_overrun_is_loud():
+    """A second-stage workgroup whose block never becomes ready gives up after the workspace's spin
+    limit: status bit 0, NaN rows for that block and nothing else touched; every kernel exits
+    normally.  The condition is forced from the host: the block's first-stage counter is pre-loaded
+    so that no workgroup completes the count, and the spin limit is a few thousand polls.  After
+    moe_workspace_init the same call gives the bits of a clean run."""
+    cfg = small("overrun", T=90, E=12, k=4, n_inst=2, C=8, d_h=128, d_e=96, zipf_s=1.2)
+    orc = OracleRun(cfg)
+    st = LayerStep(cfg, orc.lay, orc.g_self)
+    upload_weights(st, cfg, orc.W13, orc.W2)
+    logits, X = torch.from_numpy(orc.logits).cuda(), upload_x(cfg, orc.X)
+    st.step_fused(logits, X)
+    torch.cuda.synchronize()
+    n_local = len(orc.perm)
+    clean_Yp, clean_Y = st.Yp[:n_local].clone(), st.Y.clone()
+    assert rel_fro(clean_Yp.cpu().numpy(), orc.Yp) < TOL_BF16 and B.moe_workspace_status(st.workspace) == 0
+    blk = st.blocks.cpu().numpy().reshape(-1, 4)
+    n_blocks, R = int(blk[0, 0]), int(blk[0, 1])
+    assert n_blocks >= 3
+    victim = 1                                               # second entry of the work list
+    _, r0, hi, _ = (int(v) for v in blk[1 + victim])
+    rows = np.arange(r0, min(hi, r0 + R))
+    ctrl = st.workspace.view(torch.int32)
+    ctrl[(victim + 1) * 256] = 1000                          # the block's first-stage counter: never completes
+    # long enough for the other blocks' first stage to finish (microseconds), short enough for a test:
+    # a few milliseconds of polling instead of the default's second
+    B.moe_workspace_set_option(st.workspace, B.MOE_WS_OPT_SPIN_LIMIT, 5000)
+    st.Yp.fill_(123.0)
+    st.ffn(X)
+    st.combine()
+    torch.cuda.synchronize()
+    assert B.moe_workspace_status(st.workspace) == 1
+    got = st.Yp[:n_local].cpu().numpy()
+    assert np.isnan(got[rows]).all()
+    others = np.setdiff1d(np.arange(n_local), rows)
+    np.testing.assert_array_equal(got[others], clean_Yp.cpu().numpy()[others])
+    assert (st.Yp[n_local:] == 123.0).all()
+    # tokens with a request in the block carry the NaN into Y; the others are unchanged
+    tok = np.unique(orc.perm[rows] // cfg.k)
+    Y = st.Y.float().cpu().numpy()
+    assert np.isnan(Y[tok]).all(axis=1).all()
+    rest = np.setdiff1d(np.arange(cfg.T), tok)
+    np.testing.assert_array_equal(Y[rest], clean_Y.float().cpu().numpy()[rest])
+    # recovery
+    B.moe_workspace_init(st.workspace)
+    assert B.moe_workspace_status(st.workspace) == 0
+    st.step_fused(logits, X)
+    torch.cuda.synchronize()
+    assert torch.equal(st.Yp[:n_local], clean_Yp) and torch.equal(st.Y, clean_Y)
+    assert B.moe_workspace_status(st.workspace) == 0
+    assert int(ctrl[2].item()) == 0                          # the option was reset with the region
+
+
+def test_permute_tolerates_repeated_slots_and_foreign_ids():
+    """rid is caller-supplied: every choice of every token on ONE slot (more than T requests on it),
+    the rest anywhere; the list stays within moe_max_blocks and the FFN computes every row."""
+    cfg = small("dups", T=50, E=6, k=5, n_inst=2, C=4, d_h=64, d_e=64)
+    T, k, C = cfg.T, cfg.k, cfg.C
+    lay = W.build_placement(cfg)
+    rid = np.full((T, k), C + 2, dtype=np.int32)            # instance 1, slot 2
+    rid[::7, 0] = 10 ** 6                                    # not a replica id of any instance
+    rid[::5, 1] = -3
+    slot_count, slot_off, perm = dispatch.permute(rid, 1, C)
+    assert slot_count.max() > T
+    st = LayerStep(cfg, lay, 1)
+    W13, W2 = W.instance_weights(cfg, lay, 1)
+    upload_weights(st, cfg, W13, W2)
+    st.rid.copy_(torch.from_numpy(rid))
+    st.blocks.fill_(-9)
+    st.permute()
+    X = W.activations(cfg)
+    st.ffn(upload_x(cfg, X))
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(st.slot_off.cpu().numpy(), slot_off)
+    np.testing.assert_array_equal(st.perm.cpu().numpy()[:len(perm)], perm)
+    exp = expected_blocks(slot_off, B.moe_block_rows(T))
+    assert exp[0] <= B.moe_max_blocks(T, k, C)
+    blk = st.blocks.cpu().numpy()
+    np.testing.assert_array_equal(blk[:len(exp)], exp)
+    assert (blk[len(exp):] == -9).all()
+    ref = ffn.grouped_ffn(X, W13, W2, slot_off, perm, k)
+    assert rel_fro(st.Yp.cpu().numpy()[:len(perm)], ref) < TOL_BF16
+    assert B.moe_workspace_status(st.workspace) == 0
+
+
+@pytest.mark.parametrize("cfg,N", [(W.stress(64, 1.25, 0.8), 40), (small("ragged", k=5, T=77), 9), (W.dsv2lite(128), 12),
+                                   (W.stress(1024, 1.125, 1.5), 5)], ids=lambda v: f"{v.name}-T{v.T}" if hasattr(v, "name") else f"N{v}")
+def test_schedule_batched_parity(cfg, N):
+    """moe_schedule_batched / moe_schedule_baseline_batched: N sampled batches in one launch, every
+    batch bit for bit what the oracle's Alg. 1 (and the two baseline policies) give for it, with and
+    without the optional outputs."""
+    lay = W.build_placement(cfg)
+    opl = scheduling.make_placement(lay, cfg.E, cfg.n_inst, cfg.C)
+    pl = B.Placement(lay, cfg.E, cfg.n_inst, cfg.C)
+    T, k = cfg.T, cfg.k
+    ids = np.stack([oracle_route(cfg, W.router_logits(cfg, sub=b))[0] for b in range(N)]).astype(np.int32)
+    U = np.random.default_rng(cfg.seed + 23).integers(0, 1 << 32, size=ids.shape, dtype=np.uint64)
+    want = [scheduling.aebs(ids[b], opl) for b in range(N)]
+    d_ids = dev_i32(ids)
+    d_rid = torch.full((N, T, k), -9, dtype=torch.int32, device="cuda")
+    d_rep = torch.full((N, cfg.E), -9, dtype=torch.int32, device="cuda")
+    d_load = torch.full((N, cfg.n_inst), -9, dtype=torch.int32, device="cuda")
+    B.moe_schedule_batched(pl, d_ids, N, T, k, d_rid, d_rep, d_load)
+    torch.cuda.synchronize()
+    for b in range(N):
+        O, act_rep, load = want[b]
+        np.testing.assert_array_equal(d_rid[b].cpu().numpy(), O)
+        np.testing.assert_array_equal(d_rep[b].cpu().numpy(), act_rep)
+        np.testing.assert_array_equal(d_load[b].cpu().numpy(), load)
+    # loads only
+    d_load2 = torch.full((N, cfg.n_inst), -9, dtype=torch.int32, device="cuda")
+    B.moe_schedule_batched(pl, d_ids, N, T, k, None, None, d_load2)
+    torch.cuda.synchronize()
+    assert torch.equal(d_load, d_load2)
+    # baselines
+    d_draws = torch.from_numpy(U.astype(np.uint32).view(np.int32)).cuda()
+    for policy in (B.MOE_POLICY_HOME, B.MOE_POLICY_RANDOM):
+        d_rid.fill_(-9); d_load.fill_(-9)
+        B.moe_schedule_baseline_batched(pl, d_ids, N, T, k, policy, d_draws if policy == B.MOE_POLICY_RANDOM else None,
+                                        d_rid, d_load)
+        torch.cuda.synchronize()
+        for b in range(N):
+            O = (scheduling.home_only(ids[b], opl) if policy == B.MOE_POLICY_HOME
+                 else scheduling.random_replica_from_draws(ids[b], opl, U[b]))
+            np.testing.assert_array_equal(d_rid[b].cpu().numpy(), O)
+            np.testing.assert_array_equal(d_load[b].cpu().numpy(), scheduling.loads_of(O, opl))
