@@ -352,6 +352,25 @@ int moe_grouped_ffn(const void *X_dev, const void *W13_dev, const void *W2_dev,
                     const int32_t *slot_off_dev, const int32_t *perm_dev, const int32_t *blocks_dev,
                     float *Yp_dev, void *workspace_dev, size_t workspace_bytes, void *stream);
 
+/* The same call for callers that cannot allocate device memory or hand over a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The
+ * workspace is a fixed array of MOE_FFN_STATIC_SCRATCH_BYTES inside the library's device image
+ * (one copy per GPU, held until the process ends); the call allocates nothing, on the host or
+ * on the device, and uses the copy of the device that is current when it is called.  Shapes
+ * whose moe_workspace_bytes() exceeds the array are refused with MOE_EWORKSPACE (the decode
+ * decode configurations of the workload list fit; batches of thousands of tokens do not).  Every call first clears the
+ * control lines it can use (one small extra launch), so no init call exists and per-workspace
+ * options are always at their defaults; a wait overrun still writes NaN rows but cannot be read
+ * back through moe_workspace_status.  All calls on one GPU share the array: calls that overlap
+ * in time on one GPU (different streams, or several host threads) race on it and must be
+ * ordered by the caller.  Results are bit for bit those of moe_grouped_ffn.
+ */
+#define MOE_FFN_STATIC_SCRATCH_BYTES (32u << 20)
+int moe_grouped_ffn_static(const void *X_dev, const void *W13_dev, const void *W2_dev,
+                           int T, int k, int C, int d_h, int d_e, int dtype,
+                           const int32_t *slot_off_dev, const int32_t *perm_dev, const int32_t *blocks_dev,
+                           float *Yp_dev, void *stream);
+
 /* Per-workspace options of the bf16 path: a word in the workspace's header, written by a one-thread
  * kernel on `stream` (so the call is ordered with the FFN calls on that stream and can be captured),
  * read by every later moe_grouped_ffn on this workspace, reset to the default by

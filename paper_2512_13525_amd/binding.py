@@ -30,8 +30,9 @@ EXPORTS = [
     "moe_coactivation_counts", "moe_replica_counts", "moe_place_replicas", "moe_scaling_solve",
     "moe_pack_weights_bf16",
     "moe_workspace_bytes", "moe_workspace_init", "moe_workspace_status", "moe_grouped_ffn", "moe_combine",
-    "moe_shared_dispatch", "moe_combine_shared", "moe_workspace_set_option",
+    "moe_shared_dispatch", "moe_combine_shared", "moe_workspace_set_option", "moe_grouped_ffn_static",
 ]
+MOE_FFN_STATIC_SCRATCH_BYTES = 32 << 20
 BENCH_EXPORTS = ["moe_read_probe"]
 MOE_WS_OPT_SPIN_LIMIT, MOE_WS_OPT_WIDE_MIN_WORKGROUPS = 0, 1
 
@@ -122,6 +123,8 @@ def lib() -> ctypes.CDLL:
     L.moe_workspace_status.argtypes = [vp, ctypes.POINTER(ci)]
     L.moe_grouped_ffn.restype = ci
     L.moe_grouped_ffn.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, ci, vp, vp, vp, vp, vp, cs, vp]
+    L.moe_grouped_ffn_static.restype = ci
+    L.moe_grouped_ffn_static.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, ci, vp, vp, vp, vp, vp]
     L.moe_combine.restype = ci
     L.moe_combine.argtypes = [vp, vp, vp, ci, ci, ci, ci, vp, vp]
     L.moe_workspace_set_option.restype = ci
@@ -379,6 +382,13 @@ def moe_read_probe(src, nbytes: int, sink, workgroups: int = 512, loads_in_fligh
     rc = bench_lib().moe_read_probe(_ptr(src), nbytes, _ptr(sink), workgroups, loads_in_flight, _stream(stream))
     if rc != 0:
         raise MoeError(rc, f"moe_read_probe: {rc}")
+
+
+def moe_grouped_ffn_static(X, W13, W2, T: int, k: int, C: int, d_h: int, d_e: int, dtype: int, slot_off, perm,
+                           blocks, Yp, stream=None) -> None:
+    _check(lib().moe_grouped_ffn_static(_ptr(X), _ptr(W13), _ptr(W2), T, k, C, d_h, d_e, dtype, _ptr(slot_off),
+                                        _ptr(perm), _ptr(blocks), _ptr(Yp), _stream(stream)),
+           "moe_grouped_ffn_static")
 
 
 def moe_combine(Yp, pos, topk_w, T: int, k: int, d_h: int, dtype: int, Y, stream=None) -> None:

@@ -15,6 +15,8 @@
 // fp32 path (correctness configuration): plain wave-per-output-row dot products, two kernels.
 #include <stdlib.h>
 
+#include <mutex>
+
 #include "common.h"
 
 namespace {
@@ -191,10 +193,12 @@ extern "C" int moe_pack_weights_bf16(const void *W13_dev, const void *W2_dev, in
     return moe::check_launch("moe_pack_weights_bf16");
 }
 
-extern "C" int moe_grouped_ffn(const void *X_dev, const void *W13_dev, const void *W2_dev,
-                               int T, int k, int C, int d_h, int d_e, int dtype,
-                               const int32_t *slot_off_dev, const int32_t *perm_dev, const int32_t *blocks_dev,
-                               float *Yp_dev, void *workspace_dev, size_t workspace_bytes, void *stream) {
+namespace {
+
+int grouped_ffn(const void *X_dev, const void *W13_dev, const void *W2_dev,
+                int T, int k, int C, int d_h, int d_e, int dtype,
+                const int32_t *slot_off_dev, const int32_t *perm_dev, const int32_t *blocks_dev,
+                float *Yp_dev, void *workspace_dev, size_t workspace_bytes, void *stream) {
     if (T < 0 || k < 1 || C < 1 || d_h < 1 || d_e < 1) return MOE_EINVAL;
     if (dtype != MOE_DTYPE_BF16 && dtype != MOE_DTYPE_F32) return MOE_EINVAL;
     if (C > MOE_MAX_SLOTS || k > MOE_MAX_TOPK) return MOE_ESHAPE;
@@ -236,4 +240,70 @@ extern "C" int moe_grouped_ffn(const void *X_dev, const void *W13_dev, const voi
                            act, static_cast<const float *>(W2_dev), slot_off_dev, Yp_dev, C, d_h, d_e);
     }
     return moe::check_launch("moe_grouped_ffn");
+}
+
+// Scratch of moe_grouped_ffn_static: one copy per GPU, held until the process ends.  In host code
+// this name is only a handle for hipGetSymbolAddress; the kernels get the address it returns.
+constexpr size_t kStaticScratchBytes = MOE_FFN_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices];        // device address of `scratch` on each GPU, looked up once per GPU
+
+// Address of this GPU's copy of the scratch array (the current device's), or null with the HIP error recorded.
+void *static_scratch() {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+        moe::set_hip_error(e != hipSuccess ? e : hipErrorInvalidDevice, "moe_grouped_ffn_static: hipGetDevice");
+        return nullptr;
+    }
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) {
+            moe::set_hip_error(e != hipSuccess ? e : hipErrorInvalidSymbol, "moe_grouped_ffn_static: hipGetSymbolAddress");
+            return nullptr;
+        }
+        g_scratch_ptr[dev] = p;
+    }
+    return g_scratch_ptr[dev];
+}
+
+}  // namespace
+
+extern "C" int moe_grouped_ffn(const void *X_dev, const void *W13_dev, const void *W2_dev,
+                               int T, int k, int C, int d_h, int d_e, int dtype,
+                               const int32_t *slot_off_dev, const int32_t *perm_dev, const int32_t *blocks_dev,
+                               float *Yp_dev, void *workspace_dev, size_t workspace_bytes, void *stream) {
+    return grouped_ffn(X_dev, W13_dev, W2_dev, T, k, C, d_h, d_e, dtype, slot_off_dev, perm_dev, blocks_dev, Yp_dev,
+                       workspace_dev, workspace_bytes, stream);
+}
+
+extern "C" int moe_grouped_ffn_static(const void *X_dev, const void *W13_dev, const void *W2_dev,
+                                      int T, int k, int C, int d_h, int d_e, int dtype,
+                                      const int32_t *slot_off_dev, const int32_t *perm_dev, const int32_t *blocks_dev,
+                                      float *Yp_dev, void *stream) {
+    if (T < 0 || k < 1 || C < 1 || d_h < 1 || d_e < 1) return MOE_EINVAL;
+    if (dtype != MOE_DTYPE_BF16 && dtype != MOE_DTYPE_F32) return MOE_EINVAL;
+    if (static_cast<long long>(T) * k > 0x7fffffffLL) return MOE_ESHAPE;
+    // the size the allocating entry point would ask its caller for must fit the fixed array
+    const size_t need = moe_workspace_bytes(T, k, C, d_h, d_e, dtype);
+    if (need == 0 || need > kStaticScratchBytes) return MOE_EWORKSPACE;
+    if (T == 0) return MOE_OK;
+    void *ws = static_scratch();
+    if (!ws) return MOE_EHIP;
+    // The array keeps what the last call on this GPU left: the header (status word, options) and the
+    // hand-off lines of every block this call can have must start at zero.  A fill kernel, not a
+    // memset node, so that the call can be captured into a graph.
+    if (dtype == MOE_DTYPE_BF16) {
+        const long long lines = 1 + moe::ffn_max_blocks(T, k, C);
+        if (lines * 1024 > static_cast<long long>(kCtrlBytes)) return MOE_ESHAPE;
+        hipLaunchKernelGGL(fill_zero_kernel, dim3(static_cast<unsigned>((lines + 3) / 4)), dim3(256), 0,
+                           static_cast<hipStream_t>(stream), static_cast<int *>(ws), static_cast<int>(lines * 256));
+    }
+    return grouped_ffn(X_dev, W13_dev, W2_dev, T, k, C, d_h, d_e, dtype, slot_off_dev, perm_dev, blocks_dev, Yp_dev,
+                       ws, kStaticScratchBytes, stream);
 }
