@@ -172,7 +172,7 @@ int moe_schedule_baseline_batched(const moe_placement_t *pl, const int32_t *topk
  *                  R = moe_block_rows(T) rows (32 for small batches, MOE_FFN_BLOCK_ROWS otherwise);
  *                  slots with more than 16 requests come first (their work takes longest),
  *                  ascending slot order otherwise.  Four int32 per entry: entry 0 = {number of
- *                  blocks B, R, number of 128-row blocks that the slots with more than 64 requests
+ *                  blocks B, R, number of 64-row blocks that the slots with more than 64 requests
  *                  make, 0}; entry 1+j = {slot, first row of the block, slot_off[slot+1], slot_off[slot]}.
  *                  Entries past B are left untouched.
  * n_local and B stay on the device; nothing is read back.  The grouped FFN cannot size its
@@ -324,7 +324,11 @@ int moe_pack_weights_bf16(const void *W13_dev, const void *W2_dev, int C, int d_
  *                    completion leaves it cleared for the next one.  Calls that share a
  *                    workspace must not overlap in time.
  * bf16 inputs are multiplied on the matrix cores with fp32 accumulation; `a` is rounded
- * to bf16 once.  The bf16 path is one launch in which the workgroups of the second stage
+ * to bf16 once.  A slot's rows are cut into blocks of R = moe_block_rows(T) rows, each a streaming
+ * item per channel tile (a slot with one block has its weights read from memory exactly once); in
+ * batches with many slots of more than 64 requests those slots are computed as tiled GEMMs over
+ * larger blocks by workgroups of the same launch (MOE_WS_OPT_WIDE_MIN_WORKGROUPS below).
+ * The bf16 path is one launch in which the workgroups of the second stage
  * wait for flags raised by the first.  The wait is bounded: a workgroup whose wait runs out
  * (which means the control region was not cleared, or the GPU was shared with work that starved
  * the kernel) sets bit 0 of the status word, writes quiet NaNs into its rows of Yp instead of
@@ -377,13 +381,14 @@ int moe_grouped_ffn_static(const void *X_dev, const void *W13_dev, const void *W
  * moe_workspace_init.  value 0 = default; value < 0 is MOE_EINVAL.
  *   MOE_WS_OPT_SPIN_LIMIT            polls a second-stage workgroup spends on its block's flag
  *                                    before it gives up (default 2^20).  For tests of the overrun path.
- *   MOE_WS_OPT_WIDE_MIN_WORKGROUPS   for batches of at least 1024 tokens, slots with more than 64
- *                                    requests are computed by two extra launches of a tiled GEMM
- *                                    (blocks of 128 rows) instead of the streaming launch, but only
- *                                    when the batch has enough such blocks to fill the chip: (number
- *                                    of 128-row blocks) x (d_e / 64 workgroups per block) >= this
- *                                    value, default 512.  Results do not depend on it beyond
- *                                    rounding order.
+ *   MOE_WS_OPT_WIDE_MIN_WORKGROUPS   slots with more than 64 requests are computed as tiled GEMMs
+ *                                    over blocks of 64 rows (128 for batches of at least 2048 tokens)
+ *                                    by workgroups of the same launch, but only when the batch has
+ *                                    enough such blocks to fill the chip: (number of 64-row blocks
+ *                                    of those slots) x (ceil(d_e / 64) workgroups per block) >= this
+ *                                    value, default 256; otherwise they are cut into streaming
+ *                                    items like every other slot.  Results do not depend on it
+ *                                    beyond rounding order.
  */
 #define MOE_WS_OPT_SPIN_LIMIT            0
 #define MOE_WS_OPT_WIDE_MIN_WORKGROUPS   1

@@ -39,12 +39,12 @@ inline int check_launch(const char *where) {
 }
 
 // Control region at the start of the FFN workspace: a header of 256 ints, then the hand-off counters
-// of the blocks (ffn_stream.hip).  Header words: the status bits, and two per-workspace options
+// of the blocks (ffn_stream.hip).  Header words: the status bits, and the per-workspace options
 // that moe_workspace_set_option writes and moe_workspace_init resets to 0 (= the default).
 constexpr size_t kFfnCtrlBytes = 4u << 20;
 constexpr int kCtrlStatus = 1;           // bit 0: a wait overran; bit 1: list cut for another block size
 constexpr int kCtrlSpinLimit = 2;        // polls a stage-2 workgroup spends on a block's flag before it gives up
-constexpr int kCtrlWideMin = 3;          // threshold of the tiled-GEMM launches (see kWideMinWorkgroups)
+constexpr int kCtrlWideMin = 3;          // workgroups of wide blocks a batch must have for them to be used (ffn_stream.hip)
 
 // Blocks of the work list that get workgroups of their own in the streaming launch (longer lists wrap around)
 constexpr unsigned kFfnLaneBlocks = 128;
@@ -60,36 +60,23 @@ inline long long ffn_max_blocks(int T, int k, int C) {
     return C + static_cast<long long>(T) * k / ffn_block_rows(T);
 }
 
+// Bytes of the intermediate `act` per entry of the work list: a block of rows x d_e rounded up to
+// whole 128-byte lines (64 channels).  A wide block (ffn_stream.hip) uses the regions of the entries
+// it spans.
+inline size_t ffn_act_block_bytes(int T, int d_e) {
+    return static_cast<size_t>(ffn_block_rows(T)) * ((d_e + 63) / 64 * 64) * 2;
+}
+inline size_t ffn_stream_act_bytes(int T, int k, int C, int d_e) {
+    const size_t b = static_cast<size_t>(ffn_max_blocks(T, k, C)) * ffn_act_block_bytes(T, d_e);
+    return (b + 255) / 256 * 256;
+}
+
 // bf16 grouped FFN (ffn_stream.hip); shapes validated by the caller.  `ctrl` is the zero-initialised
-// control region of the workspace, `act` holds ffn_max_blocks(T, k, C) blocks of ffn_block_rows(T) x d_e
-// bf16.  Returns MOE_OK or MOE_ESHAPE (too many blocks).
+// control region of the workspace, `act` holds ffn_stream_act_bytes(T, k, C, d_e) bytes.  Returns MOE_OK
+// or MOE_ESHAPE (too many blocks).
 int launch_ffn_stream(const void *X, const void *W13p, const void *W2p, int T, int k, int C, int d_h, int d_e,
                       const int32_t *blocks, const int32_t *perm, int *ctrl, uint16_t *act,
                       float *Yp, hipStream_t st);
-
-// Slots with more than 64 requests of batches of at least kWideMinTokens tokens: blocks of 128 rows
-// as tiled GEMMs (ffn_wide.hip); the streaming launch skips those slots.  Smaller batches never
-// have enough such blocks under top-k routing, and would pay two launches that find nothing.
-// `act_rows` holds T*k rows of d_e bf16.
-constexpr int kWideMinTokens = 1024;
-inline bool ffn_has_wide(int T) { return T >= kWideMinTokens; }
-// The tiled-GEMM launches pay off only when they can fill the chip (a workgroup runs the whole K
-// dimension of its tile): they take a batch's slots with more than 64 requests when the list counts
-// enough 128-row blocks for kWideMinWorkgroups stage-1 workgroups, otherwise the streaming launch
-// keeps them.  Every kernel takes the decision from the list's header in the same way.
-constexpr int kWideMinWorkgroups = 512;
-constexpr int kWideWaves = 4;            // wavefronts (= packed weight tiles) of a tiled-GEMM workgroup
-inline int ffn_wide_tiles1(int d_e) { return (d_e / 16 + kWideWaves - 1) / kWideWaves; }
-__device__ __forceinline__ bool ffn_wide_on(int4 head, int wide_tiles1, int min_workgroups) {
-    return head.y == 64 && head.z > 0 && head.z * wide_tiles1 >= min_workgroups;
-}
-inline size_t ffn_stream_act_bytes(int T, int k, int C, int d_e) {
-    const size_t b = static_cast<size_t>(ffn_max_blocks(T, k, C)) * ffn_block_rows(T) * d_e * 2;
-    return (b + 255) / 256 * 256;
-}
-int launch_ffn_wide(const void *X, const void *W13p, const void *W2p, int T, int k, int C, int d_h, int d_e,
-                    const int32_t *blocks, const int32_t *perm, const int *ctrl, uint16_t *act_rows,
-                    float *Yp, hipStream_t st);
 
 inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 

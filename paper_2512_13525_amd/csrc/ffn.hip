@@ -26,7 +26,7 @@ namespace {
 //                        int [1] = error word, then the per-block hand-off counters of the bf16
 //                        kernels (see ffn_stream.hip)
 //   [kCtrlBytes, ...)    act: SiLU(gate)*up of every local request row (fp32: [row][d_e];
-//                        bf16: per block of R = 32 or 64 rows, [d_e/16 tiles][R rows][16 channels])
+//                        bf16: one region per entry of the work list, see ffn_stream.hip)
 constexpr size_t kCtrlBytes = moe::kFfnCtrlBytes;
 
 // ------------------------------------------------------------------ packing
@@ -153,10 +153,9 @@ extern "C" size_t moe_workspace_bytes(int T, int k, int C, int d_h, int d_e, int
     (void)d_h;
     if (T < 0 || k < 1 || C < 1 || d_e < 1) return 0;
     // fp32: one row per request; bf16: whole blocks of rows (at most C partly filled ones)
-    // (+ one row per request for the slots that take the tiled-GEMM path)
     const size_t bytes = dtype == MOE_DTYPE_F32
         ? static_cast<size_t>(T) * k * d_e * 4
-        : moe::ffn_stream_act_bytes(T, k, C, d_e) + (moe::ffn_has_wide(T) ? static_cast<size_t>(T) * k * d_e * 2 : 0);
+        : moe::ffn_stream_act_bytes(T, k, C, d_e);
     return kCtrlBytes + (bytes + 255) / 256 * 256 + 256;
 }
 
@@ -218,12 +217,6 @@ int grouped_ffn(const void *X_dev, const void *W13_dev, const void *W2_dev,
     if (dtype == MOE_DTYPE_BF16) {
         // the kernels address token rows with 32-bit byte offsets
         if (static_cast<long long>(T) * d_h * 2 > 0xffffffffLL) return MOE_ESHAPE;
-        if (moe::ffn_has_wide(T)) {
-            uint16_t *act_rows = reinterpret_cast<uint16_t *>(ws + kCtrlBytes + moe::ffn_stream_act_bytes(T, k, C, d_e));
-            const int rcw = moe::launch_ffn_wide(X_dev, W13_dev, W2_dev, T, k, C, d_h, d_e, blocks_dev,
-                                                 perm_dev, reinterpret_cast<const int *>(ws), act_rows, Yp_dev, st);
-            if (rcw != MOE_OK) return rcw;
-        }
         const int rc = moe::launch_ffn_stream(X_dev, W13_dev, W2_dev, T, k, C, d_h, d_e, blocks_dev, perm_dev,
                                               reinterpret_cast<int *>(ws), reinterpret_cast<uint16_t *>(ws + kCtrlBytes),
                                               Yp_dev, st);

@@ -20,6 +20,11 @@
 // B-operand images, so stage 2 reads its token fragments like the weights, straight into
 // registers and as far ahead.
 //
+// A slot that received more requests than one block holds is not cut into streaming items (each
+// would stream the expert again): its rows are computed in blocks of twice that size as tiled
+// GEMMs by workgroups of the same launch (wide_item below), which read the weights once per block
+// and share the token rows of a block between four channel tiles through LDS.
+//
 // Both stages run in ONE launch: the stage-2 workgroups have the higher ids, so the hardware
 // starts them only after every stage-1 workgroup has been started, and they fill the compute
 // units that the tail of stage 1 leaves idle.  A stage-2 workgroup first puts its weight loads in
@@ -52,6 +57,7 @@ constexpr int kWaves = kThreads / MOE_WAVE;
 constexpr int kCtrlLineInts = 32;
 constexpr int kCtrlCopies = 7;
 constexpr int kCtrlBlockInts = (1 + kCtrlCopies) * kCtrlLineInts;
+constexpr int kWide128Tokens = 2048;    // batches from here on run their wide slots in blocks of 128 rows
 constexpr int kMaxItems = static_cast<int>(moe::kFfnCtrlBytes / 4) / kCtrlBlockInts - 1;
 
 struct StageArgs {
@@ -71,7 +77,7 @@ struct StreamArgs {
     int *ctrl;
     int k, C;
     int spin_limit;
-    int wide_tiles1, wide_min;           // stage-1 workgroup tiles of the tiled-GEMM launches and their on/off threshold
+    uint32_t act_block_bytes;            // bytes of `act` per entry of the work list: R rows x d_e rounded up to 64 channels
 };
 
 __device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
@@ -127,8 +133,8 @@ __device__ __forceinline__ void reduce_store(const StreamArgs &a, const StageArg
                 // tile is half a K-step, and every 128-byte line of the image has one writing workgroup
                 const int fl = (l & 15) + 16 * ((tile & 1) * 2 + (l >> 5));
                 uint64_t *dst = reinterpret_cast<uint64_t *>(
-                    reinterpret_cast<char *>(a.act) +
-                    ((static_cast<size_t>(item_id) * (g.tiles >> 1) + (tile >> 1)) * TT + (brow >> 4) + t) * 1024 +
+                    reinterpret_cast<char *>(a.act) + static_cast<size_t>(item_id) * a.act_block_bytes +
+                    (static_cast<size_t>(tile >> 1) * TT + (brow >> 4) + t) * 1024 +
                     fl * 16 + ((l >> 4) & 1) * 8);
                 __hip_atomic_store(dst, o, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
@@ -204,6 +210,7 @@ template <int NH, int TT, bool STREAM>
 __device__ __forceinline__ void stream_item_lines(const StreamArgs &a, const StageArgs &g, char *lds,
                                                   const char *w, int item, int tile, int row0, int row_end,
                                                   int wave, int lane) {
+    asm volatile("" : "+v"(lane));                             // see wide_item
     constexpr int NT = (NH + 1) / 2;
     constexpr int D = kDepthA;
     f32x4 (*red)[2][TT][MOE_WAVE] = reinterpret_cast<f32x4 (*)[2][TT][MOE_WAVE]>(lds);
@@ -336,6 +343,7 @@ template <int NT, int TT>
 __device__ __forceinline__ void stream_item_steps(const StreamArgs &a, const StageArgs &g, char *lds,
                                                   const char *w, int item, int brow, int tile, int row0, int row_end,
                                                   int wave, int lane) {
+    asm volatile("" : "+v"(lane));                             // see wide_item
     constexpr int D = 2 * kDepthA;
     f32x4 (*red)[2][TT][MOE_WAVE] = reinterpret_cast<f32x4 (*)[2][TT][MOE_WAVE]>(lds);
     const uint32_t aoff = lane * 16;
@@ -416,10 +424,11 @@ template <int NT, int TT, int U, bool STREAM>
 __device__ __forceinline__ void stream_item_down(const StreamArgs &a, const StageArgs &g, char *lds, int *s_ok,
                                                  const char *w, int item, int tile, int row0, int row_end,
                                                  int wave, int lane) {
+    asm volatile("" : "+v"(lane));                             // see wide_item
     constexpr int D = U == 2 ? 2 : NT > 2 ? 3 : 4;               // steps in flight that fit the registers
     f32x4 (*red)[2][TT][MOE_WAVE] = reinterpret_cast<f32x4 (*)[2][TT][MOE_WAVE]>(lds);
     const uint32_t aoff = lane * 16;
-    const char *bbase = reinterpret_cast<const char *>(g.B) + static_cast<size_t>(item) * g.KS * (TT * 1024) + aoff;
+    const char *bbase = reinterpret_cast<const char *>(g.B) + static_cast<size_t>(item) * a.act_block_bytes + aoff;
     const int n = (g.KS / U - wave + kWaves - 1) / kWaves;      // steps wave, wave+4, ... of this wavefront
     f32x4 acc[2][NT];
 #pragma unroll
@@ -499,9 +508,238 @@ __device__ __forceinline__ void stream_item_down(const StreamArgs &a, const Stag
     reduce_store<false, NT, TT>(a, g, red, acc, item, 0, tile, row0, row_end, wave, lane);
 }
 
+// ---------------------------------------------------------------------------------------------
+// Slots with more requests than one block holds ("wide" slots): blocks of up to RT*16 rows as tiled
+// GEMMs inside the same launch.  The streaming items above re-read a tile's weights for every block
+// of rows and every item gathers its token rows again; here a workgroup computes RT*16 rows x 4
+// packed weight tiles (64 channels of SiLU(gate)*up in stage 1, 128 output channels in stage 2),
+// so the weights are fetched once per RT*16 rows and the token rows once per 4 tiles.
+//
+// Each of the 4 wavefronts owns one packed tile (two MFMA A fragments per K-step, read straight from
+// global memory: the packed layout is the register image) and all rows: RT row tiles x 2
+// accumulators.  Gate and up of a channel live in the same lane, so stage 1 needs no exchange between
+// wavefronts, and a wavefront runs the whole K dimension (no split-K, no reduction).  The token rows
+// (the B operand, shared by the 4 wavefronts) go through LDS: per K-tile of 64 columns the workgroup
+// reads one 128-byte line of each row with whole-line loads (8 rows per instruction) into a
+// double-buffered, XOR-swizzled tile, from which every wavefront reads the MFMA layout.  One
+// barrier per K-tile; two K-tiles of both operands are in flight in registers.
+//
+// A wide block is led by the list entry whose first row is a multiple of RT*16 rows into the slot;
+// the block's workgroups are the first ceil(tiles/4) ids of that entry (the others, and all ids of
+// the slot's other entries, leave).  The intermediate of a wide block lives in the `act` region of
+// its leading entry as [K-tile of stage 2 = 64 channels][row][128 bytes]: every 128-byte line has one
+// writing workgroup, and stage 2 reads a K-tile of all rows as one contiguous run.  The hand-off is
+// the one of the streaming items: counter and flags of the leading entry.
+template <bool STAGE1, int RT>
+__device__ __forceinline__ void wide_item(const StreamArgs &a, const StageArgs &g, char *lds, int *s_ok,
+                                          int item, int group, int n_groups, int slot, int row0, int m) {
+    constexpr int kRing = 2;                                         // K-tiles of both operands in flight
+    constexpr bool STREAM = false;                                   // a wide slot has several blocks: they share the tiles through L2
+    constexpr int kPieces = RT * 16 * 8;                             // 16-byte pieces of one K-tile of the token tile
+    constexpr int kLoadsB = (kPieces + kThreads - 1) / kThreads;
+    constexpr int kBufBytes = RT * 16 * 128;
+    // an opaque copy of the thread id: nothing derived from it is shared with (and hoisted above) the
+    // other kinds of items, whose paths would then carry it in registers
+    int tid = threadIdx.x;
+    asm volatile("" : "+v"(tid));
+    const int wave = __builtin_amdgcn_readfirstlane(tid / MOE_WAVE), lane = tid % MOE_WAVE;
+    int pt = group * kWaves + wave;
+    const bool pt_ok = pt < g.tiles;
+    pt = pt_ok ? pt : g.tiles - 1;
+    const char *w = g.Wp + (static_cast<size_t>(slot) * g.tiles + pt) * g.KS * 2048 + lane * 16;
+    const int rows_pad = (m + 15) & ~15;
+    char *act_blk = reinterpret_cast<char *>(a.act) + static_cast<size_t>(item) * a.act_block_bytes;
+
+    if constexpr (!STAGE1) {
+        if (!wait_block_ready(a, s_ok, item, group, n_groups)) {
+            const float qnan = __uint_as_float(0x7fc00000u);
+            const f32x4 v = {qnan, qnan, qnan, qnan};
+            const int c0 = group * 128, nc = (g.tiles * 32 - c0 < 128 ? g.tiles * 32 - c0 : 128) / 4;
+            for (int i = tid; i < m * nc; i += kThreads)
+                *reinterpret_cast<f32x4 *>(a.Yp + static_cast<size_t>(row0 + i / nc) * g.out_stride + c0 + (i % nc) * 4) = v;
+            return;
+        }
+    }
+
+    // token rows this thread fetches: piece q*256 + tid = row (q*32 + tid/8), 16-byte chunk tid%8 of the line
+    const bool loader = kPieces >= kThreads || tid < kPieces;
+    const char *bp[kLoadsB];
+    const size_t kt_stride = STAGE1 ? 128 : static_cast<size_t>(rows_pad) * 128;   // bytes a K-tile advances a row
+#pragma unroll
+    for (int q = 0; q < kLoadsB; ++q) {
+        int r = q * (kThreads / 8) + (tid >> 3);
+        r = r < m ? r : m - 1;
+        if constexpr (STAGE1)
+            bp[q] = reinterpret_cast<const char *>(g.B) +
+                    static_cast<size_t>(a.perm[row0 + r] / a.k) * static_cast<uint32_t>(g.b_stride) * 2 + (tid & 7) * 16;
+        else
+            bp[q] = act_blk + static_cast<size_t>(r) * 128 + (tid & 7) * 16;
+    }
+    // LDS: row R at R*128, its 16-byte chunk c at ((c ^ ((R >> 1) & 7)) * 16): the 16 rows that one
+    // fragment read touches then fall into 16 different bank groups (rows R and R+8 share R & 7)
+    const uint32_t wr_lds = (tid >> 3) * 128 + (((tid & 7) ^ ((tid >> 4) & 7)) * 16);
+    const uint32_t rd_row = (lane & 15) * 128, rd_sw = (lane >> 1) & 7, rd_g = lane >> 4;
+
+    const int NKT = (g.KS + 1) >> 1;                                 // K-tiles of two K-steps (the last may hold one); >= 1
+    f32x4 acc[RT][2];
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) { acc[rt][0] = f32x4{0.f, 0.f, 0.f, 0.f}; acc[rt][1] = acc[rt][0]; }
+    // K-tile i uses register set i % kRing and LDS buffer i % 2; loads past the last K-tile fetch the
+    // last one again, so the steady-state loop has no branch around a load and the compiler counts
+    // outstanding loads exactly.
+    bf16x8 breg[kRing][kLoadsB];
+    bf16x8 areg[kRing][2][2];                                        // [set][K-step of the tile][fragment]
+    const int last = NKT - 1;
+
+    // K-tile j: columns 64*j .. 64*j+63.  With an odd number of K-steps the last tile has only its
+    // first half: its second K-step repeats the first (never multiplied) and chunks 4..7 of the
+    // line, which lie past the row (stage 1) or were never written (stage 2), repeat chunks 0..3.
+#define MOE_WIDE_LOAD_A(set, j)                                                                  \
+    do {                                                                                         \
+        const int j_ = (j) < last ? (j) : last;                                                  \
+        const int s0_ = 2 * j_, s1_ = 2 * j_ + 1 < g.KS ? 2 * j_ + 1 : 2 * j_;                   \
+        areg[set][0][0] = load_weights<STREAM>(w + static_cast<size_t>(s0_) * 2048);            \
+        areg[set][0][1] = load_weights<STREAM>(w + static_cast<size_t>(s0_) * 2048 + 1024);     \
+        areg[set][1][0] = load_weights<STREAM>(w + static_cast<size_t>(s1_) * 2048);            \
+        areg[set][1][1] = load_weights<STREAM>(w + static_cast<size_t>(s1_) * 2048 + 1024);     \
+        asm volatile("" ::: "memory");                                                           \
+    } while (0)
+#define MOE_WIDE_LOAD_B(set, j)                                                                  \
+    do {                                                                                         \
+        const int j_ = (j) < last ? (j) : last;                                                  \
+        const size_t off_ = static_cast<size_t>(j_) * kt_stride - ((2 * j_ + 1 >= g.KS && (tid & 7) >= 4) ? 64 : 0); \
+        if (loader) {                                                                            \
+            _Pragma("unroll") for (int q = 0; q < kLoadsB; ++q)                                  \
+                breg[set][q] = *reinterpret_cast<const bf16x8 *>(bp[q] + off_);                  \
+        }                                                                                        \
+        asm volatile("" ::: "memory");                                                           \
+    } while (0)
+#define MOE_WIDE_STAGE(set)                                                                      \
+    do {                                                                                         \
+        if (loader) {                                                                            \
+            _Pragma("unroll") for (int q = 0; q < kLoadsB; ++q)                                  \
+                *reinterpret_cast<bf16x8 *>(lds + ((set) & 1) * kBufBytes + q * (kThreads * 16) + wr_lds) = breg[set][q]; \
+        }                                                                                        \
+        asm volatile("" ::: "memory");                                                           \
+    } while (0)
+    // the multiply of one K-step: row tiles in groups of up to four (LDS reads of a group, then its MFMAs)
+#define MOE_WIDE_MMA_STEP(set, ss)                                                               \
+    do {                                                                                         \
+        _Pragma("unroll") for (int r0_ = 0; r0_ < RT; r0_ += 4) {                                \
+            bf16x8 b_[4];                                                                        \
+            _Pragma("unroll") for (int r4 = 0; r4 < 4; ++r4)                                     \
+                if (r0_ + r4 < RT)                                                               \
+                    b_[r4] = *reinterpret_cast<const bf16x8 *>(                                  \
+                        lds + ((set) & 1) * kBufBytes + (r0_ + r4) * 2048 + rd_row + (((4 * (ss) + rd_g) ^ rd_sw) * 16)); \
+            _Pragma("unroll") for (int r4 = 0; r4 < 4; ++r4)                                     \
+                if (r0_ + r4 < RT) {                                                             \
+                    acc[r0_ + r4][0] = mfma16(areg[set][ss][0], b_[r4], acc[r0_ + r4][0]);       \
+                    acc[r0_ + r4][1] = mfma16(areg[set][ss][1], b_[r4], acc[r0_ + r4][1]);       \
+                }                                                                                \
+        }                                                                                        \
+    } while (0)
+    // The LDS buffer written here was last read in the multiply of K-tile i-2, which every wavefront
+    // finished before the barrier of K-tile i-1.  full: both K-steps of the tile exist (a literal).
+#define MOE_WIDE_STEP(set, i, full)                                                              \
+    do {                                                                                         \
+        MOE_WIDE_STAGE(set);                                                                     \
+        MOE_WIDE_LOAD_B(set, (i) + kRing);                                                       \
+        lds_barrier();                                                                           \
+        MOE_WIDE_MMA_STEP(set, 0);                                                               \
+        if (full) MOE_WIDE_MMA_STEP(set, 1);                                                     \
+        asm volatile("" ::: "memory");                                                           \
+        MOE_WIDE_LOAD_A(set, (i) + kRing);                                                       \
+    } while (0)
+
+    const int n_full = g.KS >> 1;                                    // K-tiles with both K-steps
+    int i = 0;
+    MOE_WIDE_LOAD_A(0, 0); MOE_WIDE_LOAD_B(0, 0);
+    MOE_WIDE_LOAD_A(1, 1); MOE_WIDE_LOAD_B(1, 1);
+    for (; i + 2 <= n_full; i += 2) {
+        MOE_WIDE_STEP(0, i, true);
+        MOE_WIDE_STEP(1, i + 1, true);
+    }
+    const int rem = n_full - i;                                      // 0 .. 1
+    if (rem > 0) MOE_WIDE_STEP(0, i, true);
+    if (g.KS & 1) {
+        if (rem == 0) MOE_WIDE_STEP(0, n_full, false);
+        else MOE_WIDE_STEP(1, n_full, false);
+    }
+#undef MOE_WIDE_LOAD_A
+#undef MOE_WIDE_LOAD_B
+#undef MOE_WIDE_STAGE
+#undef MOE_WIDE_MMA_STEP
+#undef MOE_WIDE_STEP
+
+    // lane l holds, per row tile, 4 consecutive channels (l/16)*4.. of row (l%16) of the tile
+    if (pt_ok) {
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) {
+            const int r = rt * 16 + (lane & 15);
+            if (r >= m) continue;
+            if constexpr (STAGE1) {
+                const f32x4 gt = acc[rt][0], up = acc[rt][1];
+                const uint64_t o = static_cast<uint64_t>(moe::f32_to_bf16(silu_mul(gt[0], up[0]))) |
+                                   static_cast<uint64_t>(moe::f32_to_bf16(silu_mul(gt[1], up[1]))) << 16 |
+                                   static_cast<uint64_t>(moe::f32_to_bf16(silu_mul(gt[2], up[2]))) << 32 |
+                                   static_cast<uint64_t>(moe::f32_to_bf16(silu_mul(gt[3], up[3]))) << 48;
+                uint64_t *dst = reinterpret_cast<uint64_t *>(act_blk + (static_cast<size_t>(group) * rows_pad + r) * 128 +
+                                                             wave * 32 + (lane >> 4) * 8);
+                __hip_atomic_store(dst, o, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            } else {
+                float *dst = a.Yp + static_cast<size_t>(row0 + r) * g.out_stride + pt * 32 + (lane >> 4) * 4;
+                *reinterpret_cast<f32x4 *>(dst) = acc[rt][0];
+                *reinterpret_cast<f32x4 *>(dst + 16) = acc[rt][1];
+            }
+        }
+    }
+    if constexpr (STAGE1) {
+        // announce the tile group: stores acknowledged, then the counter of the leading entry
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        if (tid == 0) {
+            int *blk = a.ctrl + (item + 1) * kCtrlBlockInts;
+            if (__hip_atomic_fetch_add(blk, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == n_groups - 1) {
+#pragma unroll
+                for (int c = 1; c <= kCtrlCopies; ++c)
+                    __hip_atomic_store(blk + c * kCtrlLineInts, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+    }
+}
+
+// A slot with more than kWideMin requests is wide.  Its rows are cut into blocks of WR rows: 64 in the
+// launches for decode-size batches, 128 in the launch for batches of at least kWide128Tokens tokens,
+// which is compiled for two workgroups per CU (the 128-row block needs 64 accumulator registers more).
+constexpr int kWideMin = 64;
+// A wavefront of a wide workgroup runs its tile's whole K dimension, one round trip per K-tile, so wide
+// blocks only pay off when a batch has enough of them to fill the chip with such workgroups:
+// (64-row blocks of the wide slots, from the list's header) x (first-stage workgroups per block) must
+// reach kWideMinWorkgroups, otherwise the wide slots are cut into streaming items like the others.
+// Every workgroup takes the decision from the same two numbers.
+constexpr int kWideMinWorkgroups = 256;
+__device__ __forceinline__ bool wide_on(int4 head, int groups1, int override_min) {
+    return head.z * groups1 >= (override_min > 0 ? override_min : kWideMinWorkgroups);
+}
+// The leader of a wide block runs it, every other workgroup of a wide slot's entries leaves.
+template <bool STAGE1, int WR>
+__device__ __forceinline__ void run_wide(const StreamArgs &a, const StageArgs &g, char *lds, int *s_ok, int item,
+                                         int tile, int4 ent) {
+    const int slot = ent.x, row0 = ent.y, hi = ent.z, lo = ent.w;
+    if ((row0 - lo) % WR != 0) return;                               // not the leading entry of a wide block
+    const int groups = (g.tiles + kWaves - 1) / kWaves;              // workgroups of the block in this stage
+    if (tile >= groups) return;
+    const int m = hi - row0 < WR ? hi - row0 : WR;
+    const int rt = (m + 15) >> 4;
+    if (rt <= 1) wide_item<STAGE1, 1>(a, g, lds, s_ok, item, tile, groups, slot, row0, m);
+    else if (rt <= 2) wide_item<STAGE1, 2>(a, g, lds, s_ok, item, tile, groups, slot, row0, m);
+    else if (rt <= 4) wide_item<STAGE1, 4>(a, g, lds, s_ok, item, tile, groups, slot, row0, m);
+    else if constexpr (WR == 128) wide_item<STAGE1, 8>(a, g, lds, s_ok, item, tile, groups, slot, row0, m);
+}
+
 // LINES: this stage has an even number of K-steps
-template <bool STAGE1, bool LINES, int TT>
-__device__ __forceinline__ void run_item(const StreamArgs &a, const StageArgs &g, char *lds, int *s_ok, int wide_min,
+template <bool STAGE1, bool LINES, int TT, int WR>
+__device__ __forceinline__ void run_item(const StreamArgs &a, const StageArgs &g, char *lds, int *s_ok, bool wide,
                                          unsigned id) {
     const int tile = id % g.tiles_pad, item = id / g.tiles_pad;
     if (tile >= g.tiles) return;
@@ -511,9 +749,11 @@ __device__ __forceinline__ void run_item(const StreamArgs &a, const StageArgs &g
     const int n_blocks = list[0].x;
     const int4 ent = list[1 + item];
     if (item >= n_blocks) return;                                // past the last block: nothing else is read
-    // lists with blocks of 64 rows: slots with more than 64 requests belong to the tiled-GEMM launches
-    // when those are on for this batch
-    if (TT == 4 && moe::ffn_wide_on(list[0], a.wide_tiles1, wide_min) && ent.z - ent.w > 64) return;
+    // a slot with more than kWideRows requests is computed as tiled GEMMs over blocks of kWideRows rows
+    if (wide && ent.z - ent.w > kWideMin) {
+        run_wide<STAGE1, WR>(a, g, lds, s_ok, item, tile, ent);
+        return;
+    }
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / MOE_WAVE), lane = threadIdx.x % MOE_WAVE;
     const int slot = ent.x, row0 = ent.y, hi = ent.z;
     const char *w = g.Wp + (static_cast<size_t>(slot) * g.tiles + tile) * g.KS * 2048;
@@ -580,13 +820,14 @@ __device__ __forceinline__ void run_item(const StreamArgs &a, const StageArgs &g
 // L2.  LINES1 / LINES2 select the whole-line token path of a stage (even number of K-steps).
 // TT = token tiles per block (2: blocks of 32 rows, 4 workgroups per CU; 4: blocks of 64 rows, whose
 // larger register set allows 3 per CU).
-template <bool LINES1, bool LINES2, int TT>
-__global__ __launch_bounds__(kThreads, TT == 2 ? 4 : 3)
+template <bool LINES1, bool LINES2, int TT, int WR>
+__global__ __launch_bounds__(kThreads, WR == 128 ? 2 : TT == 2 ? 4 : 3)
 void ffn_stream_kernel(StreamArgs a) {
     // split-K reduction buffer [4 waves][2][TT][64] x 16 B, which the whole-line path also uses as
     // its per-wavefront staging tiles during the K loop
     __shared__ __attribute__((aligned(16))) char lds[kWaves * 2 * TT * MOE_WAVE * 16];
     static_assert(kWaves * TT * 2048 <= sizeof(lds), "staging tiles must fit in the reduction buffer");
+    static_assert(2 * WR * 128 <= sizeof(lds), "the two token tiles of a wide block must fit");
     __shared__ unsigned long long s_visit;
     __shared__ int s_ok;
     {
@@ -599,22 +840,19 @@ void ffn_stream_kernel(StreamArgs a) {
                 __hip_atomic_fetch_or(a.ctrl + moe::kCtrlStatus, 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             return;
         }
-        // header word 3 of the workspace: the caller's threshold for the tiled-GEMM launches (0 = default)
-        int wide_min = a.wide_min;
-        if (TT == 4 && wide_min != 0x7fffffff) {
-            const int o = a.ctrl[moe::kCtrlWideMin];
-            wide_min = o > 0 ? o : wide_min;
-        }
+
         // Up to kFfnLaneBlocks blocks have workgroups of their own; a longer list wraps around (the
         // workgroup of block b also takes blocks b + kFfnLaneBlocks, ..., at most 64 of them), which
         // keeps the worst-case grid of large batches small.  A stage-1 workgroup never waits, and all of them are started
         // before any stage-2 workgroup, so every flag a stage-2 workgroup waits for is raised.
+        // header word 3 of the workspace: the caller's threshold for wide blocks (0 = default)
+        const bool wide = wide_on(head, (a.s[0].tiles + kWaves - 1) / kWaves, a.ctrl[moe::kCtrlWideMin]);
         const unsigned n_blocks = static_cast<unsigned>(head.x);
         const unsigned lanes = n_blocks < moe::kFfnLaneBlocks ? n_blocks : moe::kFfnLaneBlocks;
         const unsigned n1 = lanes * a.s[0].tiles_pad, n2 = lanes * a.s[1].tiles_pad;
         if (n_blocks <= lanes) {
-            if (blockIdx.x < n1) run_item<true, LINES1, TT>(a, a.s[0], lds, &s_ok, wide_min, blockIdx.x);
-            else if (blockIdx.x - n1 < n2) run_item<false, LINES2, TT>(a, a.s[1], lds, &s_ok, wide_min, blockIdx.x - n1);
+            if (blockIdx.x < n1) run_item<true, LINES1, TT, WR>(a, a.s[0], lds, &s_ok, wide, blockIdx.x);
+            else if (blockIdx.x - n1 < n2) run_item<false, LINES2, TT, WR>(a, a.s[1], lds, &s_ok, wide, blockIdx.x - n1);
         } else if (blockIdx.x < n1 + n2) {
             // a long list: the first wavefront looks at all the blocks of this workgroup at once (lane l:
             // block + l*lanes) and the workgroup then visits only those that are its own to compute
@@ -624,10 +862,11 @@ void ffn_stream_kernel(StreamArgs a) {
             if (id0 % tp >= static_cast<unsigned>(s1 ? a.s[0].tiles : a.s[1].tiles)) return;
             if (threadIdx.x < MOE_WAVE) {
                 const unsigned b = id0 / tp + threadIdx.x * lanes;
+                // entries of wide slots that lead no block are not visited
                 bool mine = false;
                 if (b < n_blocks) {
                     const int4 e = reinterpret_cast<const int4 *>(a.blocks)[1 + b];
-                    mine = !(TT == 4 && moe::ffn_wide_on(head, a.wide_tiles1, wide_min) && e.z - e.w > 64);
+                    mine = !wide || e.z - e.w <= kWideMin || (e.y - e.w) % WR == 0;
                 }
                 const unsigned long long m = __ballot(mine);
                 if (threadIdx.x == 0) s_visit = m;
@@ -640,25 +879,26 @@ void ffn_stream_kernel(StreamArgs a) {
                 visit &= visit - 1;
                 if (!first) __syncthreads();                         // the LDS buffer is reused
                 first = false;
-                if (s1) run_item<true, LINES1, TT>(a, a.s[0], lds, &s_ok, wide_min, id0 + l * n1);
-                else run_item<false, LINES2, TT>(a, a.s[1], lds, &s_ok, wide_min, id0 + l * n2);
+                if (s1) run_item<true, LINES1, TT, WR>(a, a.s[0], lds, &s_ok, wide, id0 + l * n1);
+                else run_item<false, LINES2, TT, WR>(a, a.s[1], lds, &s_ok, wide, id0 + l * n2);
             }
         }
     }
 }
 
 template <bool L1, bool L2>
-void launch(const StreamArgs &a, int block_rows, unsigned blocks, hipStream_t st) {
-    if (block_rows == 32) hipLaunchKernelGGL((ffn_stream_kernel<L1, L2, 2>), dim3(blocks), dim3(kThreads), 0, st, a);
-    else hipLaunchKernelGGL((ffn_stream_kernel<L1, L2, 4>), dim3(blocks), dim3(kThreads), 0, st, a);
+void launch(const StreamArgs &a, int block_rows, bool wide128, unsigned blocks, hipStream_t st) {
+    if (block_rows == 32) hipLaunchKernelGGL((ffn_stream_kernel<L1, L2, 2, 64>), dim3(blocks), dim3(kThreads), 0, st, a);
+    else if (!wide128) hipLaunchKernelGGL((ffn_stream_kernel<L1, L2, 4, 64>), dim3(blocks), dim3(kThreads), 0, st, a);
+    else hipLaunchKernelGGL((ffn_stream_kernel<L1, L2, 4, 128>), dim3(blocks), dim3(kThreads), 0, st, a);
 }
 
-void launch_lines(const StreamArgs &a, int block_rows, unsigned blocks, hipStream_t st) {
+void launch_lines(const StreamArgs &a, int block_rows, bool wide128, unsigned blocks, hipStream_t st) {
     const bool l1 = a.s[0].KS % 2 == 0, l2 = a.s[1].KS % 2 == 0;
-    if (l1 && l2) launch<true, true>(a, block_rows, blocks, st);
-    else if (l1) launch<true, false>(a, block_rows, blocks, st);
-    else if (l2) launch<false, true>(a, block_rows, blocks, st);
-    else launch<false, false>(a, block_rows, blocks, st);
+    if (l1 && l2) launch<true, true>(a, block_rows, wide128, blocks, st);
+    else if (l1) launch<true, false>(a, block_rows, wide128, blocks, st);
+    else if (l2) launch<false, true>(a, block_rows, wide128, blocks, st);
+    else launch<false, false>(a, block_rows, wide128, blocks, st);
 }
 
 }  // namespace
@@ -674,8 +914,7 @@ int launch_ffn_stream(const void *X, const void *W13p, const void *W2p, int T, i
     StreamArgs a;
     a.blocks = blocks; a.perm = perm; a.act = act; a.Yp = Yp; a.ctrl = ctrl; a.k = k; a.C = C;
     a.spin_limit = 1 << 20;
-    a.wide_tiles1 = ffn_wide_tiles1(d_e);
-    a.wide_min = ffn_has_wide(T) ? kWideMinWorkgroups : 0x7fffffff;
+    a.act_block_bytes = static_cast<uint32_t>(ffn_act_block_bytes(T, d_e));
     a.s[0].B = static_cast<const uint16_t *>(X);
     a.s[0].Wp = static_cast<const char *>(W13p);
     a.s[0].tiles = d_e / 16; a.s[0].KS = d_h / 32; a.s[0].b_stride = d_h; a.s[0].out_stride = 0;
@@ -686,7 +925,7 @@ int launch_ffn_stream(const void *X, const void *W13p, const void *W2p, int T, i
     const long long lanes = items < kFfnLaneBlocks ? items : kFfnLaneBlocks;
     const long long n1 = lanes * a.s[0].tiles_pad, n2 = lanes * a.s[1].tiles_pad;
     if (n1 + n2 > 0x7fffffffLL) return MOE_ESHAPE;
-    launch_lines(a, block_rows, static_cast<unsigned>(n1 + n2), st);
+    launch_lines(a, block_rows, T >= kWide128Tokens, static_cast<unsigned>(n1 + n2), st);
     return MOE_OK;
 }
 

@@ -60,7 +60,7 @@ def expected_blocks(slot_off, block_rows, heavy_rows=16):
     """The FFN work list that follows from slot_off: every slot's rows cut into blocks of at
     most `block_rows` rows; slots with more than `heavy_rows` requests first, ascending slot
     order within each class; [n_blocks, block_rows, n_wide, 0] then [slot, first row, slot end, slot start] per
-    block (flattened int32); n_wide = number of 128-row blocks of the slots with more than 64 requests."""
+    block (flattened int32); n_wide = number of 64-row blocks of the slots with more than 64 requests."""
     out = []
     for heavy in (True, False):
         for s in range(len(slot_off) - 1):
@@ -70,5 +70,5 @@ def expected_blocks(slot_off, block_rows, heavy_rows=16):
             for r in range(lo, hi, block_rows):
                 out.append([s, r, hi, lo])
     rows = np.diff(np.asarray(slot_off, dtype=np.int64))
-    n_wide = int(sum((int(v) + 127) // 128 for v in rows if v > 64))
+    n_wide = int(sum((int(v) + 63) // 64 for v in rows if v > 64))
     return np.array([[len(out), block_rows, n_wide, 0]] + out, dtype=np.int32).reshape(-1)

@@ -302,7 +302,7 @@ def test_unactivated_slots_are_not_read_bf16():
     assert np.isfinite(Y).all() and rel_fro(Y, orc.Y) < TOL_BF16
 
 
-@pytest.mark.parametrize("T", [70, 400, 1030], ids=["blocks32", "blocks64", "blocks64+gemm"])
+@pytest.mark.parametrize("T", [70, 400], ids=["blocks32", "blocks64"])
 @pytest.mark.parametrize("d_h,d_e", [(256, 192), (160, 96), (192, 160)], ids=["even-even", "odd-odd", "even-odd"])
 def test_ffn_block_boundaries(d_h, d_e, T):
     """The grouped FFN alone on a hand-made dispatch whose slots hold 0, 1, 8, 9, 16, 17, 24, 25,
@@ -310,12 +310,13 @@ def test_ffn_block_boundaries(d_h, d_e, T):
     32 and of 64 rows), for even and odd numbers of K-steps in either stage, against the oracle's
     grouped FFN.  A list cut for another block size is refused."""
     counts = [8, 9, 0, 16, 17, 24, 1, 25, 32, 33, 0, 65, 40, 41, 48, 49, 56, 57, 64]
+    # slots with more than 64 requests can be computed as tiled GEMMs over blocks of 64 rows: one full
+    # + 2 or 6 rows, exactly two, two + 1 row, several + a rest
     if T >= 400:
-        # slots with more than 64 requests: several blocks of 64 rows in the streaming launch; in
-        # batches of at least 1024 tokens the tiled-GEMM launches can take them in blocks of 128
-        # rows (one partly filled, exactly one, one + 1 row, two full + 44)
         counts += [66, 128, 129, 300]
-    C, k = len(counts), 10
+    else:
+        counts += [70, 130]
+    C, k = len(counts), 12
     assert B.moe_block_rows(T) == (32 if T == 70 else 64)
     cfg = W.MoEConfig("blocks", E=C, k=k, d_h=d_h, d_e=d_e, T=T, n_inst=1, C=C, zipf_s=0.0, seed=11)
     rng = np.random.default_rng(3)
@@ -337,8 +338,8 @@ def test_ffn_block_boundaries(d_h, d_e, T):
     B.moe_workspace_init(ws)
     Yp = torch.full((T * k, d_h), 123.0, dtype=torch.float32, device="cuda")
     for rep in range(3):
-        # rep 1: the tiled-GEMM launches take the slots with more than 64 requests even though this
-        # batch would not fill the chip with them (they exist for batches of at least 1024 tokens)
+        # rep 1: the slots with more than 64 requests are computed as tiled-GEMM blocks even though this
+        # batch has too few of them to fill the chip (the rule's threshold set to one workgroup)
         B.moe_workspace_set_option(ws, B.MOE_WS_OPT_WIDE_MIN_WORKGROUPS, 1 if rep == 1 else 0)
         Yp.fill_(123.0)
         B.moe_grouped_ffn(to_device_bf16(X), W13p, W2p, T, k, C, d_h, d_e, B.MOE_DTYPE_BF16,
@@ -617,10 +618,11 @@ def test_steps_replayed_from_a_hip_graph_match_eager():
         assert B.moe_workspace_status(s.workspace) == 0
 
 
-@pytest.mark.parametrize("cfg", [W.qwen3(1024), W.stress(2048, 1.25, 0.8)], ids=lambda c: f"{c.name}-T{c.T}")
-def test_layer_parity_with_tiled_gemm_forced_on(cfg):
-    """The full-size layers whose hottest slots hold more than 64 requests, with those slots taken
-    by the tiled-GEMM launches (forced on: these batches have too few such blocks for the rule)."""
+@pytest.mark.parametrize("cfg", [W.qwen3(1024), W.stress(2048, 1.25, 0.8), W.dsv3(512)], ids=lambda c: f"{c.name}-T{c.T}")
+def test_layer_parity_with_wide_blocks_forced_on(cfg):
+    """Full-size layers whose hottest slots hold more than 64 requests, with those slots computed as
+    tiled-GEMM blocks (forced on: these batches have too few such blocks for the rule; blocks of 64
+    rows, and of 128 rows in the launch for batches of at least 2048 tokens)."""
     orc = OracleRun(cfg, only_activated=True)
     assert (orc.slot_count > 64).any()
     step = LayerStep(cfg, orc.lay, orc.g_self)
@@ -628,35 +630,31 @@ def test_layer_parity_with_tiled_gemm_forced_on(cfg):
     step.Yp.fill_(123.0)
     n_local = len(orc.perm)
     B.moe_workspace_set_option(step.workspace, B.MOE_WS_OPT_WIDE_MIN_WORKGROUPS, 1)
-    Y = step.step_fused(torch.from_numpy(orc.logits).cuda(), upload_x(cfg, orc.X))
-    torch.cuda.synchronize()
+    for rep in range(2):
+        Y = step.step_fused(torch.from_numpy(orc.logits).cuda(), upload_x(cfg, orc.X))
+        torch.cuda.synchronize()
+        Yp = step.Yp.cpu().numpy()
+        assert (Yp[n_local:] == 123.0).all() and np.isfinite(Yp[:n_local]).all()
+        num = np.linalg.norm(Yp[:n_local] - orc.Yp, axis=1)
+        den = np.linalg.norm(orc.Yp, axis=1)
+        assert (num <= 2.5 * TOL_BF16 * den + 1e-30).all()
+        assert rel_fro(Yp[:n_local], orc.Yp) < TOL_BF16
+        assert rel_fro(Y.float().cpu().numpy(), orc.Y) < TOL_BF16
+        assert B.moe_workspace_status(step.workspace) == 0
     B.moe_workspace_set_option(step.workspace, B.MOE_WS_OPT_WIDE_MIN_WORKGROUPS, 0)
-    Yp = step.Yp.cpu().numpy()
-    assert (Yp[n_local:] == 123.0).all() and np.isfinite(Yp[:n_local]).all()
-    num = np.linalg.norm(Yp[:n_local] - orc.Yp, axis=1)
-    den = np.linalg.norm(orc.Yp, axis=1)
-    assert (num <= 2.5 * TOL_BF16 * den + 1e-30).all()
-    assert rel_fro(Yp[:n_local], orc.Yp) < TOL_BF16
-    assert rel_fro(Y.float().cpu().numpy(), orc.Y) < TOL_BF16
-    assert B.moe_workspace_status(step.workspace) == 0
-    # and the streaming launch alone gives the same rows within the same bar
-    Y2 = step.step_fused(torch.from_numpy(orc.logits).cuda(), upload_x(cfg, orc.X))
-    torch.cuda.synchronize()
-    assert rel_fro(step.Yp.cpu().numpy()[:n_local], orc.Yp) < TOL_BF16
-    assert rel_fro(Y2.float().cpu().numpy(), orc.Y) < TOL_BF16
 
 
-def test_tiled_gemm_taken_by_the_rule_on_a_token_heavy_batch():
-    """Every slot of the instance holds 361 or 362 requests (config 2's shape, T = 1024): 51 blocks of
-    128 rows x 22 workgroups reach the threshold, so the default rule hands all slots to the
-    tiled-GEMM launches.  Dispatch through moe_permute, rows against the oracle's grouped FFN."""
+def test_token_heavy_batch_all_slots_wide():
+    """Every slot of the instance holds 361 or 362 requests (config 2's shape, T = 1024): all slots are
+    computed as tiled GEMMs over blocks of 64 rows (five full blocks and a partly filled one each).
+    Dispatch through moe_permute, rows against the oracle's grouped FFN."""
     cfg = W.dsv2lite(1024)
     T, k, C = cfg.T, cfg.k, cfg.C
     lay = W.build_placement(cfg)
     g_self = 1
     rid = (g_self * C + np.arange(T * k, dtype=np.int32) % C).reshape(T, k)
     slot_count, slot_off, perm = dispatch.permute(rid, g_self, C)
-    assert slot_count.min() > 64 and int(sum((c + 127) // 128 for c in slot_count)) * (cfg.d_e // 64) >= 512
+    assert slot_count.min() > 64
     X = W.activations(cfg)
     W13, W2 = W.instance_weights(cfg, lay, g_self)
     Yp_ref = ffn.grouped_ffn(X, W13, W2, slot_off, perm, k)
@@ -707,7 +705,9 @@ def test_ffn_long_block_list_wraps_around():
     ws = torch.empty((B.moe_workspace_bytes(T, k, C, d_h, d_e, B.MOE_DTYPE_BF16),), dtype=torch.uint8, device="cuda")
     B.moe_workspace_init(ws)
     Yp = torch.full((T * k, d_h), 123.0, dtype=torch.float32, device="cuda")
-    for rep in range(2):
+    for rep in range(4):
+        # reps 2 and 3: the slots with more than 64 requests as tiled-GEMM blocks
+        B.moe_workspace_set_option(ws, B.MOE_WS_OPT_WIDE_MIN_WORKGROUPS, 1 if rep >= 2 else 100000)
         Yp.fill_(123.0)
         B.moe_grouped_ffn(to_device_bf16(X), W13p, W2p, T, k, C, d_h, d_e, B.MOE_DTYPE_BF16,
                           torch.from_numpy(slot_off).cuda(), torch.from_numpy(perm).cuda(), d_blk, Yp, ws)
@@ -781,6 +781,8 @@ def test_ffn_all_requests_on_a_slots(a):
     st.rid.copy_(torch.from_numpy(rid))
     st.Yp.fill_(123.0)
     for rep in range(2):
+        # second round: the slots with more than 64 requests as tiled-GEMM blocks
+        B.moe_workspace_set_option(st.workspace, B.MOE_WS_OPT_WIDE_MIN_WORKGROUPS, rep)
         st.permute()
         st.ffn(upload_x(cfg, X))
         torch.cuda.synchronize()
@@ -817,8 +819,11 @@ def test_ffn_wait_overrun_is_loud():
     blk = st.blocks.cpu().numpy().reshape(-1, 4)
     n_blocks, R = int(blk[0, 0]), int(blk[0, 1])
     assert n_blocks >= 3
-    victim = 1                                               # second entry of the work list
-    _, r0, hi, _ = (int(v) for v in blk[1 + victim])
+    # the victim: the second entry of the list.  This batch has too few slots with more than 64 requests
+    # for tiled-GEMM blocks, so every entry is a streaming block of its own
+    assert int(blk[0, 2]) * -(-cfg.d_e // 64) < 256
+    victim = 1
+    _, r0, hi, lo = (int(v) for v in blk[1 + victim])
     rows = np.arange(r0, min(hi, r0 + R))
     ctrl = st.workspace.view(torch.int32)
     ctrl[(victim + 1) * 256] = 1000                          # the block's first-stage counter: never completes
