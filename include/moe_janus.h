@@ -195,9 +195,15 @@ size_t moe_block_list_len(int T, int k, int C);
  * Same results, bit for bit, as moe_route + moe_schedule + moe_permute called one after the
  * other with the same arguments (E is the placement's).  At decode sizes each of those steps is a
  * few microseconds of work behind a launch of similar cost; this entry point pays one launch.
- * sync_dev: one int32 of device memory, zero before the first call; every call leaves it zero.
- * Calls that share sync_dev must not overlap in time.
+ * sync_dev: moe_front_sync_len() int32 of device memory, zero before the first call; every call
+ * leaves its first 33 words zero (the rest is scratch).  Calls that share sync_dev must not overlap
+ * in time.  Up to 8192 requests (T*k) the call is one launch and sync_dev is one word; larger
+ * batches take three launches: the routing workgroups collect the activated experts in a bitset
+ * (Alg. 1, Step 1, token-parallel), the last of them runs Step 2, and Step 3 and the sort run
+ * over chunks of 2048 requests, one workgroup each (per-chunk counts, then the scatter; no
+ * ordering comes from atomics).
  */
+size_t moe_front_sync_len(const moe_placement_t *pl, int T, int k);
 int moe_route_schedule_permute(const moe_placement_t *pl, int g_self, const float *logits_dev, int T, int k,
                                const moe_route_cfg *cfg, int32_t *topk_ids_dev, float *topk_w_dev,
                                int32_t *rid_dev, int32_t *act_rep_dev, int32_t *load_dev,

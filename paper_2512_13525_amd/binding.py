@@ -26,7 +26,7 @@ EXPORTS = [
     "moe_strerror", "moe_last_error",
     "moe_placement_create", "moe_placement_destroy", "moe_placement_replicas", "moe_placement_dims",
     "moe_route", "moe_schedule", "moe_schedule_baseline", "moe_schedule_batched", "moe_schedule_baseline_batched", "moe_permute", "moe_block_rows", "moe_max_blocks", "moe_block_list_len",
-    "moe_route_schedule_permute", "moe_gate_sync_len", "moe_gate_route", "moe_gate_route_schedule_permute",
+    "moe_route_schedule_permute", "moe_front_sync_len", "moe_gate_sync_len", "moe_gate_route", "moe_gate_route_schedule_permute",
     "moe_coactivation_counts", "moe_replica_counts", "moe_place_replicas", "moe_scaling_solve",
     "moe_pack_weights_bf16",
     "moe_workspace_bytes", "moe_workspace_init", "moe_workspace_status", "moe_grouped_ffn", "moe_combine",
@@ -107,6 +107,8 @@ def lib() -> ctypes.CDLL:
     cd = ctypes.c_double
     L.moe_scaling_solve.restype = ci
     L.moe_scaling_solve.argtypes = [vp, vp, vp, ci, vp, ci, cd, cd, ci, ci, cd, vp, vp, vp, vp]
+    L.moe_front_sync_len.restype = cs
+    L.moe_front_sync_len.argtypes = [vp, ci, ci]
     L.moe_gate_sync_len.restype = cs
     L.moe_gate_sync_len.argtypes = [ci]
     L.moe_gate_route.restype = ci
@@ -304,6 +306,10 @@ def moe_scaling_solve(model, table, ne_values, B_values, lam: float, slo: float,
     if n_a.value == 0:
         return None
     return n_a.value, n_e.value, b_star.value, t.value
+
+
+def moe_front_sync_len(pl: Placement, T: int, k: int) -> int:
+    return int(lib().moe_front_sync_len(pl.handle, T, k))
 
 
 def moe_gate_sync_len(T: int) -> int:

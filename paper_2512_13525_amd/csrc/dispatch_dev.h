@@ -101,9 +101,11 @@ __device__ __forceinline__ float sigmoid_f32(float x) { return 1.0f / (1.0f + ex
 // row_lds: VPL*64 floats private to this wavefront.  ROW_IN_LDS: `row` already is that LDS copy (the
 // caller passes the same address twice and has ordered its writes).  COHERENT: results are written with agent-scope
 // stores (read by another workgroup of the same launch).
+// mark_lds (optional): a bitset in LDS in which the selected experts are raised.
 template <int VPL, bool COHERENT, bool ROW_IN_LDS = false>
 __device__ __forceinline__ void route_token(const float *row, int E, int k, const moe_route_cfg &cfg,
-                                            float *row_lds, int lane, int32_t *ids_out, float *w_out) {
+                                            float *row_lds, int lane, int32_t *ids_out, float *w_out,
+                                            uint32_t *mark_lds = nullptr) {
     float v[VPL];
     uint64_t key[VPL];
 #pragma unroll
@@ -205,6 +207,7 @@ __device__ __forceinline__ void route_token(const float *row, int E, int k, cons
                 } else {
                     ids_out[rank[i]] = e;
                 }
+                if (mark_lds) atomicOr(mark_lds + (e >> 5), 1u << (e & 31));
                 w_out[rank[i]] = w;
             }
         }
@@ -243,6 +246,7 @@ __device__ __forceinline__ void route_token(const float *row, int E, int k, cons
             } else {
                 ids_out[lane] = sel_id;
             }
+            if (mark_lds) atomicOr(mark_lds + (sel_id >> 5), 1u << (sel_id & 31));
             w_out[lane] = w;
         }
     }
@@ -294,10 +298,8 @@ __device__ __forceinline__ int load_id(const int32_t *p, bool coherent) {
 // The layout tables are staged into LDS first.  ids_coherent: the ids were written by other
 // workgroups of the same launch.  rid and act_rep may be null (the batched launch of the a_max
 // study only wants the loads): Step 3 and the actRep stores are then skipped.
-__device__ __forceinline__ void aebs_block(const SchedTables &tb, SchedShared &sh, int E, int n_inst, int C,
-                                           int n_words, const int32_t *__restrict__ ids, int n_pairs, int vec_ok,
-                                           bool ids_coherent, int32_t *__restrict__ rid,
-                                           int32_t *__restrict__ act_rep, int32_t *__restrict__ load_out) {
+// The layout tables into LDS, expert flags cleared (all threads; ends with a barrier).
+__device__ __forceinline__ void aebs_stage_tables(const SchedTables &tb, SchedShared &sh, int E, int n_inst, int n_words) {
     const int tid = threadIdx.x;
     for (int e = tid; e < E; e += kFrontThreads) {
         sh.flag[e] = 0u;
@@ -307,22 +309,13 @@ __device__ __forceinline__ void aebs_block(const SchedTables &tb, SchedShared &s
     for (int i = tid; i < n_words; i += kFrontThreads) sh.multi_mask[i] = tb.multi_mask[i];
     for (int i = tid; i < n_inst * n_words; i += kFrontThreads) sh.single_mask[i] = tb.single_mask[i];
     __syncthreads();
+}
 
-    // ---- Step 1: collect the activated experts
-    if (vec_ok) {
-        const int n4 = n_pairs >> 2;
-        const int4 *ids4 = reinterpret_cast<const int4 *>(ids);
-        for (int i = tid; i < n4; i += kFrontThreads) {
-            const int4 v = load_ids4(ids4 + i, ids_coherent);
-            sh.flag[v.x] = 1u; sh.flag[v.y] = 1u; sh.flag[v.z] = 1u; sh.flag[v.w] = 1u;
-        }
-        for (int i = (n4 << 2) + tid; i < n_pairs; i += kFrontThreads) sh.flag[load_id(ids + i, ids_coherent)] = 1u;
-    } else {
-        for (int i = tid; i < n_pairs; i += kFrontThreads) sh.flag[load_id(ids + i, ids_coherent)] = 1u;
-    }
-    __syncthreads();
-
-    // ---- Step 2: select one replica per activated expert (first wavefront)
+// Step 2 of Alg. 1 from the expert flags in LDS (first wavefront; the caller orders the flags before
+// and sh.rep after with barriers): actRep into sh.rep and act_rep (if not null), loads into load_out.
+__device__ __forceinline__ void aebs_select(const SchedTables &tb, SchedShared &sh, int E, int n_inst, int C, int n_words,
+                                            int32_t *__restrict__ act_rep, int32_t *__restrict__ load_out) {
+    const int tid = threadIdx.x;
     if (tid < MOE_WAVE) {
         const int lane = tid;
         int load = 0;                                   // lane g: load[g]
@@ -365,6 +358,31 @@ __device__ __forceinline__ void aebs_block(const SchedTables &tb, SchedShared &s
         }
         if (lane < n_inst) load_out[lane] = load;
     }
+}
+
+__device__ __forceinline__ void aebs_block(const SchedTables &tb, SchedShared &sh, int E, int n_inst, int C,
+                                           int n_words, const int32_t *__restrict__ ids, int n_pairs, int vec_ok,
+                                           bool ids_coherent, int32_t *__restrict__ rid,
+                                           int32_t *__restrict__ act_rep, int32_t *__restrict__ load_out) {
+    const int tid = threadIdx.x;
+    aebs_stage_tables(tb, sh, E, n_inst, n_words);
+
+    // ---- Step 1: collect the activated experts
+    if (vec_ok) {
+        const int n4 = n_pairs >> 2;
+        const int4 *ids4 = reinterpret_cast<const int4 *>(ids);
+        for (int i = tid; i < n4; i += kFrontThreads) {
+            const int4 v = load_ids4(ids4 + i, ids_coherent);
+            sh.flag[v.x] = 1u; sh.flag[v.y] = 1u; sh.flag[v.z] = 1u; sh.flag[v.w] = 1u;
+        }
+        for (int i = (n4 << 2) + tid; i < n_pairs; i += kFrontThreads) sh.flag[load_id(ids + i, ids_coherent)] = 1u;
+    } else {
+        for (int i = tid; i < n_pairs; i += kFrontThreads) sh.flag[load_id(ids + i, ids_coherent)] = 1u;
+    }
+    __syncthreads();
+
+    // ---- Step 2: select one replica per activated expert (first wavefront)
+    aebs_select(tb, sh, E, n_inst, C, n_words, act_rep, load_out);
     if (!rid) return;                                    // uniform: no barrier is skipped by part of the workgroup
     __syncthreads();
 
@@ -519,6 +537,112 @@ __device__ __forceinline__ void permute_block(PermShared &sh, const int32_t *__r
             todo &= ~same;
         }
         if (p < n_pairs) {
+            pos[p] = row;
+            if (local) perm[row] = p;
+        }
+    }
+}
+
+// The same sort cut into chunks of requests, one workgroup per chunk, for batches too large for one
+// workgroup (two launches: the grid is the only synchronisation).  hist [n_chunks][C]: requests of
+// every chunk per slot.
+//   count_chunk    Step 3 of Alg. 1 for the chunk's requests (rid = actRep[id], act_rep staged in
+//                  LDS by the caller) and the chunk's row of hist;
+//   scatter_chunk  every workgroup rebuilds the slot totals and its own base per slot from hist
+//                  (the chunks before it come first inside a slot), then sorts its chunk exactly
+//                  like permute_block; the first workgroup also writes the counts, the offsets and
+//                  the FFN's work list.
+__device__ __forceinline__ void count_chunk(PermShared &sh, const int32_t *__restrict__ rep_lds,
+                                            const int32_t *__restrict__ ids, int32_t *__restrict__ rid, int p0, int p1,
+                                            int g_self, int C, int32_t *__restrict__ hist_row) {
+    const int tid = threadIdx.x;
+    for (int s = tid; s < C; s += kFrontThreads) sh.total[s] = 0;
+    __syncthreads();
+    const int rid_lo = g_self * C;
+    for (int p = p0 + tid; p < p1; p += kFrontThreads) {
+        const int r = rep_lds[ids[p]];
+        rid[p] = r;
+        const int s = r - rid_lo;
+        if (s >= 0 && s < C) atomicAdd(&sh.total[s], 1);
+    }
+    __syncthreads();
+    for (int s = tid; s < C; s += kFrontThreads) hist_row[s] = sh.total[s];
+}
+
+__device__ __forceinline__ void scatter_chunk(PermShared &sh, int *__restrict__ lower, const int32_t *__restrict__ rid,
+                                              int p0, int p1, int chunk, int n_chunks, const int32_t *__restrict__ hist,
+                                              int g_self, int C, int32_t *__restrict__ slot_count,
+                                              int32_t *__restrict__ slot_off, int32_t *__restrict__ perm,
+                                              int32_t *__restrict__ pos, int32_t *__restrict__ blocks, int block_rows) {
+    const int tid = threadIdx.x;
+    const int wave = tid / MOE_WAVE;
+    const int lane = tid % MOE_WAVE;
+    for (int i = tid; i < kFrontWaves * MOE_MAX_SLOTS; i += kFrontThreads) (&sh.cnt[0][0])[i] = 0;
+    // slot totals over all chunks, and the requests of the chunks before this one
+    for (int s = tid; s < C; s += kFrontThreads) {
+        int tot = 0, low = 0;
+        for (int c = 0; c < n_chunks; ++c) {
+            const int v = hist[c * C + s];
+            tot += v;
+            low += c < chunk ? v : 0;
+        }
+        sh.total[s] = tot;
+        lower[s] = low;
+        if (chunk == 0) slot_count[s] = tot;
+    }
+    __syncthreads();
+
+    const int n = p1 - p0;
+    const int n_groups = (n + MOE_WAVE - 1) / MOE_WAVE;
+    const int gpw = (n_groups + kFrontWaves - 1) / kFrontWaves;
+    const int g_begin = wave * gpw;
+    const int g_end = min(n_groups, g_begin + gpw);
+    const int rid_lo = g_self * C;
+    // pass A of the chunk
+    for (int grp = g_begin; grp < g_end; ++grp) {
+        const int p = p0 + grp * MOE_WAVE + lane;
+        const int s = (p < p1 ? rid[p] : -1) - rid_lo;
+        if (p < p1 && s >= 0 && s < C) atomicAdd(&sh.cnt[wave][s], 1);
+    }
+    __syncthreads();
+    for (int s = tid; s < C; s += kFrontThreads) {
+        int run = 0;
+#pragma unroll
+        for (int w = 0; w < kFrontWaves; ++w) {
+            const int c = sh.cnt[w][s];
+            sh.cnt[w][s] = run;
+            run += c;
+        }
+    }
+    __syncthreads();
+    // offsets of the slots (every workgroup computes them; they are identical) and, once, the work list
+    __shared__ int32_t off_sink[MOE_MAX_SLOTS + 1];
+    if (wave == 0) scan_slots(sh, C, block_rows, chunk == 0 ? slot_off : off_sink, lane);
+    __syncthreads();
+    if (chunk == 0) list_blocks(sh, C, block_rows, blocks);
+
+    // pass B of the chunk
+    volatile int *base = &sh.cnt[wave][0];
+    for (int grp = g_begin; grp < g_end; ++grp) {
+        const int p = p0 + grp * MOE_WAVE + lane;
+        const int s = (p < p1 ? rid[p] : -1) - rid_lo;
+        const bool local = p < p1 && s >= 0 && s < C;
+        int row = -1;
+        uint64_t todo = __ballot(local);
+        while (todo) {
+            const int lead = __builtin_ctzll(todo);
+            const int s0 = __builtin_amdgcn_readlane(s, lead);
+            const uint64_t same = __ballot(local && s == s0);
+            const int b = base[s0] + sh.off[s0] + lower[s0];
+            if (local && s == s0) row = b + __popcll(same & lanemask_lt());
+            __builtin_amdgcn_wave_barrier();
+            if (lane == lead) base[s0] += __popcll(same);
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            todo &= ~same;
+        }
+        if (p < p1) {
             pos[p] = row;
             if (local) perm[row] = p;
         }

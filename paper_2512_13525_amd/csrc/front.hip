@@ -34,7 +34,15 @@ struct FrontArgs {
     float *logits_out;                   // [T,E]
     int d_h, n_tiles;                    // n_tiles = ceil(E/16) expert tiles
     int tail;                            // 0: stop after the gating selection
+    // batches too large for the one-workgroup tail (launch from logits only): the routing workgroups
+    // raise the activated experts in act_bits, the last one runs Step 2 of Alg. 1 from them, and two
+    // further launches (front_count_kernel, front_scatter_kernel) rewrite and sort the requests in chunks
+    uint32_t *act_bits;                  // [kBitWords], zero between calls; null = one-workgroup tail
+    int32_t *hist;                       // [n_chunks][C]
+    int chunk_pairs, n_chunks;
 };
+constexpr int kBitWords = MOE_MAX_EXPERTS / 32;
+constexpr int kChunkPairs = 2048;
 
 constexpr int kGateUnroll = 4;
 constexpr int kGateDepth = 4;
@@ -388,6 +396,7 @@ void front_kernel(FrontArgs a) {
     };
     __shared__ Shared sh;
     __shared__ int s_last;
+    __shared__ uint32_t s_bits[kBitWords];                            // experts this workgroup's tokens selected
 
     const int wave = threadIdx.x / MOE_WAVE;
     const int lane = moe::lane_id();
@@ -437,10 +446,21 @@ void front_kernel(FrontArgs a) {
         if (!a.tail) return;
     } else {
         if (small) tp = prefetch_tables(a);
+        if (a.act_bits) {
+            if (threadIdx.x < kBitWords) s_bits[threadIdx.x] = 0u;
+            __syncthreads();
+        }
         const int t = blockIdx.x * moe::kFrontWaves + wave;
         if (t < a.T) {
             moe::route_token<VPL, true>(a.logits + static_cast<size_t>(t) * a.E, a.E, a.k, a.cfg, sh.row[wave], lane,
-                                        a.ids + static_cast<size_t>(t) * a.k, a.w + static_cast<size_t>(t) * a.k);
+                                        a.ids + static_cast<size_t>(t) * a.k, a.w + static_cast<size_t>(t) * a.k,
+                                        a.act_bits ? s_bits : nullptr);
+        }
+        if (a.act_bits) {
+            // Step 1 of Alg. 1, spread over the routing workgroups: one atomic per non-empty word
+            __syncthreads();
+            if (threadIdx.x < kBitWords && s_bits[threadIdx.x])
+                __hip_atomic_fetch_or(a.act_bits + threadIdx.x, s_bits[threadIdx.x], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     }
     // a workgroup barrier does not wait for global stores: the ticket must not overtake the ids
@@ -458,6 +478,19 @@ void front_kernel(FrontArgs a) {
         front_tail_small(a, sh.small, n_pairs, tp);
         return;
     }
+    if (a.act_bits) {
+        // Step 2 from the bitset the routing workgroups left; Step 3 and the sort follow in two launches
+        moe::aebs_stage_tables(a.tb, sh.sched, a.E, a.n_inst, a.n_words);
+        for (int e = threadIdx.x; e < a.E; e += moe::kFrontThreads) {
+            const uint32_t word = __hip_atomic_load(a.act_bits + (e >> 5), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            sh.sched.flag[e] = (word >> (e & 31)) & 1u;
+        }
+        __syncthreads();
+        if (threadIdx.x < kBitWords)                                  // ready for the next call
+            __hip_atomic_store(a.act_bits + threadIdx.x, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        moe::aebs_select(a.tb, sh.sched, a.E, a.n_inst, a.C, a.n_words, a.act_rep, a.load);
+        return;
+    }
     const int vec_ok = ((reinterpret_cast<uintptr_t>(a.ids) | reinterpret_cast<uintptr_t>(a.rid)) & 15) == 0;
     moe::aebs_block(a.tb, sh.sched, a.E, a.n_inst, a.C, a.n_words, a.ids, n_pairs, vec_ok, true,
                     a.rid, a.act_rep, a.load);
@@ -467,12 +500,45 @@ void front_kernel(FrontArgs a) {
     moe::permute_block(sh.perm, a.rid, n_pairs, a.g_self, a.C, a.slot_count, a.slot_off, a.perm, a.pos, a.blocks, a.block_rows);
 }
 
+// Step 3 of Alg. 1 for one chunk of requests and the chunk's per-slot counts.
+__global__ __launch_bounds__(moe::kFrontThreads)
+void front_count_kernel(FrontArgs a) {
+    __shared__ moe::PermShared sh;
+    __shared__ int32_t rep[MOE_MAX_EXPERTS];
+    for (int e = threadIdx.x; e < a.E; e += moe::kFrontThreads) rep[e] = a.act_rep[e];
+    __syncthreads();
+    const int n_pairs = a.T * a.k;
+    const int p0 = blockIdx.x * a.chunk_pairs, p1 = min(n_pairs, p0 + a.chunk_pairs);
+    moe::count_chunk(sh, rep, a.ids, a.rid, p0, p1, a.g_self, a.C, a.hist + blockIdx.x * a.C);
+}
+
+// The stable sort of one chunk into its places, from the counts of all chunks.
+__global__ __launch_bounds__(moe::kFrontThreads)
+void front_scatter_kernel(FrontArgs a) {
+    __shared__ moe::PermShared sh;
+    __shared__ int lower[MOE_MAX_SLOTS];
+    const int n_pairs = a.T * a.k;
+    const int p0 = blockIdx.x * a.chunk_pairs, p1 = min(n_pairs, p0 + a.chunk_pairs);
+    moe::scatter_chunk(sh, lower, a.rid, p0, p1, blockIdx.x, a.n_chunks, a.hist, a.g_self, a.C, a.slot_count, a.slot_off,
+                       a.perm, a.pos, a.blocks, a.block_rows);
+}
+
 template <int VPL, bool GATE>
 int launch_front(const FrontArgs &a, const char *what, hipStream_t st) {
     int blocks = 1;
     if (a.T > 0) blocks = GATE ? (a.T + 127) / 128 * 8 * a.n_tiles : (a.T + moe::kFrontWaves - 1) / moe::kFrontWaves;
     hipLaunchKernelGGL((front_kernel<VPL, GATE>), dim3(blocks), dim3(moe::kFrontThreads), 0, st, a);
+    if (!GATE && a.act_bits) {
+        hipLaunchKernelGGL(front_count_kernel, dim3(a.n_chunks), dim3(moe::kFrontThreads), 0, st, a);
+        hipLaunchKernelGGL(front_scatter_kernel, dim3(a.n_chunks), dim3(moe::kFrontThreads), 0, st, a);
+    }
     return moe::check_launch(what);
+}
+
+// Batches whose requests do not fit the registers of one workgroup (or whose layout table does not
+// fit its LDS) take the chunked tail.
+bool front_is_large(const moe_placement_t *pl, int T, int k) {
+    return static_cast<long long>(T) * k > kRegPairs || pl->E * pl->n_inst > kSlotOfLds;
 }
 
 template <bool GATE>
@@ -546,7 +612,20 @@ extern "C" int moe_route_schedule_permute(const moe_placement_t *pl, int g_self,
     a.logits = logits_dev; a.T = T; a.E = E; a.k = k; a.cfg = *cfg;
     a.ids = topk_ids_dev; a.w = topk_w_dev;
     a.ticket = sync_dev;
+    if (T > 0 && front_is_large(pl, T, k)) {
+        a.act_bits = reinterpret_cast<uint32_t *>(sync_dev + 1);
+        a.hist = sync_dev + 1 + kBitWords;
+        a.chunk_pairs = kChunkPairs;
+        a.n_chunks = static_cast<int>((static_cast<long long>(T) * k + kChunkPairs - 1) / kChunkPairs);
+    }
     return launch_front_for<false>(a, "moe_route_schedule_permute", static_cast<hipStream_t>(stream));
+}
+
+extern "C" size_t moe_front_sync_len(const moe_placement_t *pl, int T, int k) {
+    if (!pl || T < 0 || k < 1) return 0;
+    if (T == 0 || !front_is_large(pl, T, k)) return 1;
+    const size_t n_chunks = (static_cast<size_t>(T) * k + kChunkPairs - 1) / kChunkPairs;
+    return 1 + kBitWords + n_chunks * pl->C;
 }
 
 extern "C" size_t moe_gate_sync_len(int T) { return T > 0 ? 1 + (static_cast<size_t>(T) + 15) / 16 : 1; }

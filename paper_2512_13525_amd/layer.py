@@ -43,7 +43,7 @@ class LayerStep:
         ws = B.moe_workspace_bytes(T, k, C, cfg.d_h, cfg.d_e, self.dtype)
         self.workspace = torch.empty((ws,), dtype=torch.uint8, device=device)
         B.moe_workspace_init(self.workspace)
-        self.sync = torch.zeros((64,), **i32)
+        self.sync = torch.zeros((B.moe_front_sync_len(self.pl, T, k),), **i32)
         self.gate_sync = torch.zeros((B.moe_gate_sync_len(T),), **i32)
         self.gate_logits = torch.empty((T, cfg.E), dtype=torch.float32, device=device)
         self.W13 = None

@@ -73,6 +73,7 @@ def test_argument_validation_without_launch():
     assert L.moe_schedule(None, None, 4, 2, None, None, None, None) == B.MOE_EINVAL
     assert L.moe_schedule_baseline(None, None, 4, 2, 0, None, None, None, None) == B.MOE_EINVAL
     # gate: selection arguments, then the hidden size, then pointers; T == 0 launches nothing
+    assert L.moe_front_sync_len(None, 4, 2) == 0
     assert L.moe_gate_sync_len(0) == 1 and L.moe_gate_sync_len(16) == 2 and L.moe_gate_sync_len(17) == 3
     gate = lambda T, E, d_h, k: L.moe_gate_route(None, None, None, T, E, d_h, k, ctypes.byref(cfg), None, None, None,
                                                  None, None)
