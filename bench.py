@@ -443,6 +443,24 @@ def _time_us(fn, reps):
     return a.elapsed_time(b) * 1e3 / reps
 
 
+def _time_us_each(fn, reps):
+    """Median microseconds of ONE call of fn, every call between an event pair of its own (queued back
+    to back): consecutive launches cannot hide each other's start and end, which a pair around the
+    whole run allows."""
+    import torch
+    for _ in range(5):
+        fn()
+    te = TimingEvents()
+    ev = [(te.new(), te.new()) for _ in range(reps)]
+    torch.cuda.synchronize()
+    for a, b in ev:
+        te.record(a); fn(); te.record(b)
+    torch.cuda.synchronize()
+    us = statistics.median(te.us(a, b) for a, b in ev)
+    te.close()
+    return us
+
+
 def _time_us_graph(fn, per_graph=50, reps=8):
     """Mean microseconds per call of fn on the GPU's own timeline: per_graph back-to-back calls are
     captured in a HIP graph and the graph is replayed, so that the Python and launch-call overhead
@@ -701,7 +719,7 @@ def act_sweep(args) -> None:
             step.ffn(X, W13=W13s[j], W2=W2s[j])
 
         us = _time_us(layer, 100)
-        ffn_us = _time_us(ffn_only, 100)
+        ffn_us = _time_us_each(ffn_only, 100)
         gbps = a * 3 * d_h * d_e * 2 / (ffn_us * 1e-6) / 1e9
         pts.append((a, us))
         print(json.dumps({"mode": "act_sweep", "workload": cfg.name, "T": T, "activated": a,
@@ -873,7 +891,7 @@ def amax_study(args) -> None:
 def all_configs(args) -> None:
     """One line per configuration and token count of the workload list: the step (front + FFN +
     combine, queued back to back over a ring of batches and weight copies) on the instance with the
-    largest load of batch 0, the FFN launch alone, the activated experts and requests of that
+    largest load of batch 0, the FFN launch alone (every launch between an event pair of its own), the activated experts and requests of that
     instance, and the FFN's algorithmic GB/s and fraction of the 8 TB/s peak."""
     import numpy as np
     import torch
@@ -924,7 +942,7 @@ def all_configs(args) -> None:
 
         reps = 200 if T <= 1024 else 50
         step_us, front_us = _time_us(step, reps), _time_us_graph(front, 20, 4)
-        ffn_us = _time_us(ffn, reps)          # the dispatch of the last step stays in place: the batch of copy j
+        ffn_us = _time_us_each(ffn, reps)     # the dispatch of the last step stays in place: the batch of copy j
         bytes_ffn = float(np.mean([a * 3 * d_h * d_e * esz + min(T, n) * d_h * esz + n * d_h * 4 for a, n in zip(a_g, n_local)]))
         gbps = bytes_ffn / (ffn_us * 1e-6) / 1e9
         print(json.dumps({"mode": "configs", "workload": cfg.name, "T": T, "dtype": cfg.dtype, "E": cfg.E, "k": k,

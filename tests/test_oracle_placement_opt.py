@@ -156,6 +156,72 @@ def test_alg3_invariants_and_step_replay():
     assert swaps > 0                      # the swap branch was exercised by the random instances
 
 
+def total_load_from_scratch(P, a):
+    """Sum over instances of Eq. 6, each I(g) evaluated as half the sum of the sub-matrix of a over the
+    instance's experts (a is symmetric with a zero diagonal): no incremental bookkeeping."""
+    tot = 0.0
+    for members in P:
+        idx = np.asarray(members, dtype=np.int64)
+        if len(idx) > 1:
+            tot += float(a[np.ix_(idx, idx)].sum()) / 2.0
+    return tot
+
+
+def test_alg3_full_replay_with_the_objective_recomputed_from_scratch():
+    """A pin of different structure than the implementation: every step of Alg. 3, swaps included, is
+    replayed by trying each candidate move on a copy of the layout and evaluating the summed
+    co-activation load of the whole candidate layout from the definition (Eq. 6); the move with the
+    smallest increase wins (ties: lowest instance; lowest (g, position, h) for swaps).  Entries of a
+    are multiples of 1/4, so every sum is exact and the order of additions cannot move a tie."""
+    rng = np.random.default_rng(16)
+    swaps = 0
+    for _ in range(150):
+        n = int(rng.integers(2, 5))
+        E = int(rng.integers(n, 9))
+        c = rng.integers(1, 40, size=E).astype(np.float64) / 4.0
+        R = rng.integers(1, n + 1, size=E)
+        while R.sum() % n:
+            R[int(rng.integers(E))] = 1 + (R[int(rng.integers(E))] % n)
+        C = int(R.sum() // n)
+        a = rng.integers(0, 21, size=(E, E)).astype(np.float64) / 4.0
+        a = np.triu(a, 1); a = a + a.T
+        try:
+            want = PO.place_replicas(n, C, R, c, a)
+        except ValueError:
+            continue
+        order = sorted([(e, r) for e in range(E) for r in range(int(R[e]))], key=lambda t: (-(c[t[0]] / R[t[0]]), t[0], t[1]))
+        P = [[] for _ in range(n)]
+        for e, _ in order:
+            base = total_load_from_scratch(P, a)
+            cands = []
+            for g in range(n):
+                if len(P[g]) < C and e not in P[g]:
+                    Q = [list(m) for m in P]
+                    Q[g].append(e)
+                    cands.append((total_load_from_scratch(Q, a) - base, g, Q))
+            if cands:
+                P = min(cands, key=lambda t: (t[0], t[1]))[2]
+                continue
+            swaps += 1
+            for g in range(n):
+                if e in P[g]:
+                    continue
+                for pos, ej in enumerate(P[g]):
+                    for h in range(n):
+                        if h == g or len(P[h]) >= C or ej in P[h]:
+                            continue
+                        Q = [list(m) for m in P]
+                        Q[g][pos] = e
+                        Q[h].append(ej)
+                        cands.append((total_load_from_scratch(Q, a) - base, (g, pos, h), Q))
+            assert cands
+            P = min(cands, key=lambda t: (t[0], t[1]))[2]
+        got = [x for q in range(n) for x in P[q] + [-1] * (C - len(P[q]))]
+        assert got == want.tolist()
+        np.testing.assert_array_equal(both_places(n, C, R, c, a), want)
+    assert swaps >= 10
+
+
 def test_alg3_against_the_exact_min_max_on_tiny_instances():
     """Alg. 3 is a heuristic for the min-max problem of Appendix B: on instances small enough to
     enumerate, its objective is never below the optimum and stays within a factor of it."""
