@@ -172,8 +172,8 @@ int moe_schedule_baseline_batched(const moe_placement_t *pl, const int32_t *topk
  *                  R = moe_block_rows(T) rows (32 for small batches, MOE_FFN_BLOCK_ROWS otherwise);
  *                  slots with more than 16 requests come first (their work takes longest),
  *                  ascending slot order otherwise.  Four int32 per entry: entry 0 = {number of
- *                  blocks B, R, number of 64-row blocks that the slots with more than 64 requests
- *                  make, 0}; entry 1+j = {slot, first row of the block, slot_off[slot+1], slot_off[slot]}.
+ *                  blocks B, R, number of 64-row blocks and number of 128-row blocks that the slots
+ *                  with more than 64 requests make}; entry 1+j = {slot, first row of the block, slot_off[slot+1], slot_off[slot]}.
  *                  Entries past B are left untouched.
  * n_local and B stay on the device; nothing is read back.  The grouped FFN cannot size its
  * launch by them, so it sizes it for moe_max_blocks() and lets the surplus leave at once.
@@ -387,14 +387,16 @@ int moe_grouped_ffn_static(const void *X_dev, const void *W13_dev, const void *W
  * moe_workspace_init.  value 0 = default; value < 0 is MOE_EINVAL.
  *   MOE_WS_OPT_SPIN_LIMIT            polls a second-stage workgroup spends on its block's flag
  *                                    before it gives up (default 2^20).  For tests of the overrun path.
- *   MOE_WS_OPT_WIDE_MIN_WORKGROUPS   slots with more than 64 requests are computed as tiled GEMMs
- *                                    over blocks of 64 rows (128 for batches of at least 2048 tokens)
- *                                    by workgroups of the same launch, but only when the batch has
- *                                    enough such blocks to fill the chip: (number of 64-row blocks
- *                                    of those slots) x (ceil(d_e / 64) workgroups per block) >= this
- *                                    value, default 256; otherwise they are cut into streaming
- *                                    items like every other slot.  Results do not depend on it
- *                                    beyond rounding order.
+ *   MOE_WS_OPT_WIDE_MIN_WORKGROUPS   slots with more than 64 requests are computed as tiled GEMMs,
+ *                                    but only when the batch has enough blocks of them to fill the
+ *                                    chip: over blocks of 64 rows by workgroups of the same launch
+ *                                    when (number of 64-row blocks of those slots) x (ceil(d_e / 64)
+ *                                    workgroups per block) >= this value (default 256); in batches
+ *                                    of at least 2048 tokens over blocks of 128 rows by two launches
+ *                                    of their own when (number of 128-row blocks) x (workgroups per
+ *                                    block) >= this value (default 512), which takes precedence.
+ *                                    Otherwise they are cut into streaming items like every other
+ *                                    slot.  Results do not depend on it beyond rounding order.
  */
 #define MOE_WS_OPT_SPIN_LIMIT            0
 #define MOE_WS_OPT_WIDE_MIN_WORKGROUPS   1

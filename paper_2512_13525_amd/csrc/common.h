@@ -78,6 +78,24 @@ int launch_ffn_stream(const void *X, const void *W13p, const void *W2p, int T, i
                       const int32_t *blocks, const int32_t *perm, int *ctrl, uint16_t *act,
                       float *Yp, hipStream_t st);
 
+// Batches of at least kGemmMinTokens tokens: slots with more than 64 requests as blocks of 128 rows in
+// two tiled-GEMM launches of their own (ffn_wide.hip, three workgroups of 168 registers per CU),
+// when the list counts enough 128-row blocks (header word 3) for kGemmMinWorkgroups first-stage
+// workgroups; the streaming launch then skips those slots.  Every kernel takes the decision from
+// the list's header in the same way.  `act_rows` holds T*k rows of d_e bf16 behind the streaming
+// launch's intermediate.
+constexpr int kGemmMinTokens = 2048;
+inline bool ffn_has_gemm(int T) { return T >= kGemmMinTokens; }
+constexpr int kGemmMinWorkgroups = 512;
+constexpr int kWideWaves = 4;            // wavefronts (= packed weight tiles) of a tiled-GEMM workgroup
+inline int ffn_gemm_tiles1(int d_e) { return (d_e / 16 + kWideWaves - 1) / kWideWaves; }
+__device__ __forceinline__ bool ffn_gemm_on(int4 head, int tiles1, int override_min) {
+    return head.y == 64 && head.w > 0 && head.w * tiles1 >= (override_min > 0 ? override_min : kGemmMinWorkgroups);
+}
+int launch_ffn_wide(const void *X, const void *W13p, const void *W2p, int T, int k, int C, int d_h, int d_e,
+                    const int32_t *blocks, const int32_t *perm, const int *ctrl, uint16_t *act_rows,
+                    float *Yp, hipStream_t st);
+
 inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 
 __device__ __forceinline__ int lane_id() { return threadIdx.x & (MOE_WAVE - 1); }

@@ -410,6 +410,7 @@ struct PermShared {
     int off[MOE_MAX_SLOTS + 1];
     int blk_base[MOE_MAX_SLOTS + 1];         // exclusive scan of the slots' block counts
     int n_wide;                              // 64-row blocks of the slots with more than 64 requests
+    int n_wide128;                           // 128-row blocks of the same slots
 };
 
 // Exclusive scan over slots of the request totals (sh.total -> sh.off, slot_off), and the place of
@@ -419,12 +420,13 @@ struct PermShared {
 constexpr int kHeavyRows = 16;
 __device__ __forceinline__ void scan_slots(PermShared &sh, int C, int block_rows, int32_t *__restrict__ slot_off,
                                            int lane) {
-    int carry = 0, hcarry = 0, lcarry = 0, wide = 0;
+    int carry = 0, hcarry = 0, lcarry = 0, wide = 0, wide128 = 0;
     for (int s0 = 0; s0 < C; s0 += MOE_WAVE) {
         const int s = s0 + lane;
         const int v = s < C ? sh.total[s] : 0;
         const int nb = (v + block_rows - 1) / block_rows;
         wide += v > 64 ? (v + 63) / 64 : 0;
+        wide128 += v > 64 ? (v + 127) / 128 : 0;
         const int hb = v > kHeavyRows ? nb : 0, lb = nb - hb;
         const int incl = wave_incl_scan_i32(v), hincl = wave_incl_scan_i32(hb), lincl = wave_incl_scan_i32(lb);
         if (s < C) {
@@ -440,8 +442,10 @@ __device__ __forceinline__ void scan_slots(PermShared &sh, int C, int block_rows
     for (int s = lane; s < C; s += MOE_WAVE)
         if (sh.blk_base[s] < 0) sh.blk_base[s] = hcarry + (-sh.blk_base[s] - 1);
     wide = __builtin_amdgcn_readlane(wave_incl_scan_i32(wide), MOE_WAVE - 1);
+    wide128 = __builtin_amdgcn_readlane(wave_incl_scan_i32(wide128), MOE_WAVE - 1);
     if (lane == 0) {
         sh.n_wide = wide;
+        sh.n_wide128 = wide128;
         sh.off[C] = carry;
         slot_off[C] = carry;
         sh.blk_base[C] = hcarry + lcarry;
@@ -450,12 +454,13 @@ __device__ __forceinline__ void scan_slots(PermShared &sh, int C, int block_rows
 
 // Work list of the grouped FFN (a5): the local request rows cut into blocks of at most
 // block_rows rows of one slot, in the order scan_slots fixed.  Entry 0 = {number of blocks,
-// block_rows, number of 64-row blocks of the slots with more than 64 requests, 0}; entry 1+j = {slot, first row, end of the slot's rows, first of the slot's rows}.  All threads, after
+// block_rows, number of 64-row blocks of the slots with more than 64 requests, number of 128-row blocks
+// of the same slots}; entry 1+j = {slot, first row, end of the slot's rows, first of the slot's rows}.  All threads, after
 // scan_slots and a barrier; one thread per slot writes that slot's entries.
 __device__ __forceinline__ void list_blocks(const PermShared &sh, int C, int block_rows,
                                             int32_t *__restrict__ blocks) {
     int4 *out = reinterpret_cast<int4 *>(blocks);
-    if (threadIdx.x == 0) out[0] = make_int4(sh.blk_base[C], block_rows, sh.n_wide, 0);
+    if (threadIdx.x == 0) out[0] = make_int4(sh.blk_base[C], block_rows, sh.n_wide, sh.n_wide128);
     for (int s = threadIdx.x; s < C; s += blockDim.x) {
         const int lo = sh.off[s], hi = sh.off[s + 1];
         int j = sh.blk_base[s];

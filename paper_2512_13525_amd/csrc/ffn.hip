@@ -155,7 +155,7 @@ extern "C" size_t moe_workspace_bytes(int T, int k, int C, int d_h, int d_e, int
     // fp32: one row per request; bf16: whole blocks of rows (at most C partly filled ones)
     const size_t bytes = dtype == MOE_DTYPE_F32
         ? static_cast<size_t>(T) * k * d_e * 4
-        : moe::ffn_stream_act_bytes(T, k, C, d_e);
+        : moe::ffn_stream_act_bytes(T, k, C, d_e) + (moe::ffn_has_gemm(T) ? static_cast<size_t>(T) * k * d_e * 2 : 0);
     return kCtrlBytes + (bytes + 255) / 256 * 256 + 256;
 }
 
@@ -217,6 +217,12 @@ int grouped_ffn(const void *X_dev, const void *W13_dev, const void *W2_dev,
     if (dtype == MOE_DTYPE_BF16) {
         // the kernels address token rows with 32-bit byte offsets
         if (static_cast<long long>(T) * d_h * 2 > 0xffffffffLL) return MOE_ESHAPE;
+        if (moe::ffn_has_gemm(T)) {
+            uint16_t *act_rows = reinterpret_cast<uint16_t *>(ws + kCtrlBytes + moe::ffn_stream_act_bytes(T, k, C, d_e));
+            const int rcw = moe::launch_ffn_wide(X_dev, W13_dev, W2_dev, T, k, C, d_h, d_e, blocks_dev,
+                                                 perm_dev, reinterpret_cast<const int *>(ws), act_rows, Yp_dev, st);
+            if (rcw != MOE_OK) return rcw;
+        }
         const int rc = moe::launch_ffn_stream(X_dev, W13_dev, W2_dev, T, k, C, d_h, d_e, blocks_dev, perm_dev,
                                               reinterpret_cast<int *>(ws), reinterpret_cast<uint16_t *>(ws + kCtrlBytes),
                                               Yp_dev, st);

@@ -57,7 +57,6 @@ constexpr int kWaves = kThreads / MOE_WAVE;
 constexpr int kCtrlLineInts = 32;
 constexpr int kCtrlCopies = 7;
 constexpr int kCtrlBlockInts = (1 + kCtrlCopies) * kCtrlLineInts;
-constexpr int kWide128Tokens = 2048;    // batches from here on run their wide slots in blocks of 128 rows
 constexpr int kMaxItems = static_cast<int>(moe::kFfnCtrlBytes / 4) / kCtrlBlockInts - 1;
 
 struct StageArgs {
@@ -78,6 +77,7 @@ struct StreamArgs {
     int k, C;
     int spin_limit;
     uint32_t act_block_bytes;            // bytes of `act` per entry of the work list: R rows x d_e rounded up to 64 channels
+    int has_gemm;                        // the batch is large enough for the separate tiled-GEMM launches (common.h)
 };
 
 __device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
@@ -708,9 +708,9 @@ __device__ __forceinline__ void wide_item(const StreamArgs &a, const StageArgs &
     }
 }
 
-// A slot with more than kWideMin requests is wide.  Its rows are cut into blocks of WR rows: 64 in the
-// launches for decode-size batches, 128 in the launch for batches of at least kWide128Tokens tokens,
-// which is compiled for two workgroups per CU (the 128-row block needs 64 accumulator registers more).
+// A slot with more than kWideMin requests is wide.  Its rows are cut into blocks of WR = 64 rows (a block
+// of 128 rows needs 64 accumulator registers more than the streaming items leave at three workgroups
+// per CU; batches of thousands of tokens take the tiled-GEMM launches of ffn_wide.hip instead).
 constexpr int kWideMin = 64;
 // A wavefront of a wide workgroup runs its tile's whole K dimension, one round trip per K-tile, so wide
 // blocks only pay off when a batch has enough of them to fill the chip with such workgroups:
@@ -733,13 +733,14 @@ __device__ __forceinline__ void run_wide(const StreamArgs &a, const StageArgs &g
     const int rt = (m + 15) >> 4;
     if (rt <= 1) wide_item<STAGE1, 1>(a, g, lds, s_ok, item, tile, groups, slot, row0, m);
     else if (rt <= 2) wide_item<STAGE1, 2>(a, g, lds, s_ok, item, tile, groups, slot, row0, m);
-    else if (rt <= 4) wide_item<STAGE1, 4>(a, g, lds, s_ok, item, tile, groups, slot, row0, m);
-    else if constexpr (WR == 128) wide_item<STAGE1, 8>(a, g, lds, s_ok, item, tile, groups, slot, row0, m);
+    else wide_item<STAGE1, 4>(a, g, lds, s_ok, item, tile, groups, slot, row0, m);
 }
 
 // LINES: this stage has an even number of K-steps
+// wide: 0 = every slot is cut into streaming items; 1 = slots with more than kWideMin requests are wide
+// blocks of this launch; 2 = those slots belong to the tiled-GEMM launches and are skipped here
 template <bool STAGE1, bool LINES, int TT, int WR>
-__device__ __forceinline__ void run_item(const StreamArgs &a, const StageArgs &g, char *lds, int *s_ok, bool wide,
+__device__ __forceinline__ void run_item(const StreamArgs &a, const StageArgs &g, char *lds, int *s_ok, int wide,
                                          unsigned id) {
     const int tile = id % g.tiles_pad, item = id / g.tiles_pad;
     if (tile >= g.tiles) return;
@@ -751,7 +752,7 @@ __device__ __forceinline__ void run_item(const StreamArgs &a, const StageArgs &g
     if (item >= n_blocks) return;                                // past the last block: nothing else is read
     // a slot with more than kWideRows requests is computed as tiled GEMMs over blocks of kWideRows rows
     if (wide && ent.z - ent.w > kWideMin) {
-        run_wide<STAGE1, WR>(a, g, lds, s_ok, item, tile, ent);
+        if (wide == 1) run_wide<STAGE1, WR>(a, g, lds, s_ok, item, tile, ent);
         return;
     }
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / MOE_WAVE), lane = threadIdx.x % MOE_WAVE;
@@ -821,7 +822,7 @@ __device__ __forceinline__ void run_item(const StreamArgs &a, const StageArgs &g
 // TT = token tiles per block (2: blocks of 32 rows, 4 workgroups per CU; 4: blocks of 64 rows, whose
 // larger register set allows 3 per CU).
 template <bool LINES1, bool LINES2, int TT, int WR>
-__global__ __launch_bounds__(kThreads, WR == 128 ? 2 : TT == 2 ? 4 : 3)
+__global__ __launch_bounds__(kThreads, TT == 2 ? 4 : 3)
 void ffn_stream_kernel(StreamArgs a) {
     // split-K reduction buffer [4 waves][2][TT][64] x 16 B, which the whole-line path also uses as
     // its per-wavefront staging tiles during the K loop
@@ -846,7 +847,9 @@ void ffn_stream_kernel(StreamArgs a) {
         // keeps the worst-case grid of large batches small.  A stage-1 workgroup never waits, and all of them are started
         // before any stage-2 workgroup, so every flag a stage-2 workgroup waits for is raised.
         // header word 3 of the workspace: the caller's threshold for wide blocks (0 = default)
-        const bool wide = wide_on(head, (a.s[0].tiles + kWaves - 1) / kWaves, a.ctrl[moe::kCtrlWideMin]);
+        const int wide_min = a.ctrl[moe::kCtrlWideMin];
+        const int wide = a.has_gemm && moe::ffn_gemm_on(head, (a.s[0].tiles + kWaves - 1) / kWaves, wide_min) ? 2
+                         : wide_on(head, (a.s[0].tiles + kWaves - 1) / kWaves, wide_min) ? 1 : 0;
         const unsigned n_blocks = static_cast<unsigned>(head.x);
         const unsigned lanes = n_blocks < moe::kFfnLaneBlocks ? n_blocks : moe::kFfnLaneBlocks;
         const unsigned n1 = lanes * a.s[0].tiles_pad, n2 = lanes * a.s[1].tiles_pad;
@@ -866,7 +869,7 @@ void ffn_stream_kernel(StreamArgs a) {
                 bool mine = false;
                 if (b < n_blocks) {
                     const int4 e = reinterpret_cast<const int4 *>(a.blocks)[1 + b];
-                    mine = !wide || e.z - e.w <= kWideMin || (e.y - e.w) % WR == 0;
+                    mine = !wide || e.z - e.w <= kWideMin || (wide == 1 && (e.y - e.w) % WR == 0);
                 }
                 const unsigned long long m = __ballot(mine);
                 if (threadIdx.x == 0) s_visit = m;
@@ -887,18 +890,17 @@ void ffn_stream_kernel(StreamArgs a) {
 }
 
 template <bool L1, bool L2>
-void launch(const StreamArgs &a, int block_rows, bool wide128, unsigned blocks, hipStream_t st) {
+void launch(const StreamArgs &a, int block_rows, unsigned blocks, hipStream_t st) {
     if (block_rows == 32) hipLaunchKernelGGL((ffn_stream_kernel<L1, L2, 2, 64>), dim3(blocks), dim3(kThreads), 0, st, a);
-    else if (!wide128) hipLaunchKernelGGL((ffn_stream_kernel<L1, L2, 4, 64>), dim3(blocks), dim3(kThreads), 0, st, a);
-    else hipLaunchKernelGGL((ffn_stream_kernel<L1, L2, 4, 128>), dim3(blocks), dim3(kThreads), 0, st, a);
+    else hipLaunchKernelGGL((ffn_stream_kernel<L1, L2, 4, 64>), dim3(blocks), dim3(kThreads), 0, st, a);
 }
 
-void launch_lines(const StreamArgs &a, int block_rows, bool wide128, unsigned blocks, hipStream_t st) {
+void launch_lines(const StreamArgs &a, int block_rows, unsigned blocks, hipStream_t st) {
     const bool l1 = a.s[0].KS % 2 == 0, l2 = a.s[1].KS % 2 == 0;
-    if (l1 && l2) launch<true, true>(a, block_rows, wide128, blocks, st);
-    else if (l1) launch<true, false>(a, block_rows, wide128, blocks, st);
-    else if (l2) launch<false, true>(a, block_rows, wide128, blocks, st);
-    else launch<false, false>(a, block_rows, wide128, blocks, st);
+    if (l1 && l2) launch<true, true>(a, block_rows, blocks, st);
+    else if (l1) launch<true, false>(a, block_rows, blocks, st);
+    else if (l2) launch<false, true>(a, block_rows, blocks, st);
+    else launch<false, false>(a, block_rows, blocks, st);
 }
 
 }  // namespace
@@ -915,6 +917,7 @@ int launch_ffn_stream(const void *X, const void *W13p, const void *W2p, int T, i
     a.blocks = blocks; a.perm = perm; a.act = act; a.Yp = Yp; a.ctrl = ctrl; a.k = k; a.C = C;
     a.spin_limit = 1 << 20;
     a.act_block_bytes = static_cast<uint32_t>(ffn_act_block_bytes(T, d_e));
+    a.has_gemm = ffn_has_gemm(T) ? 1 : 0;
     a.s[0].B = static_cast<const uint16_t *>(X);
     a.s[0].Wp = static_cast<const char *>(W13p);
     a.s[0].tiles = d_e / 16; a.s[0].KS = d_h / 32; a.s[0].b_stride = d_h; a.s[0].out_stride = 0;
@@ -925,7 +928,7 @@ int launch_ffn_stream(const void *X, const void *W13p, const void *W2p, int T, i
     const long long lanes = items < kFfnLaneBlocks ? items : kFfnLaneBlocks;
     const long long n1 = lanes * a.s[0].tiles_pad, n2 = lanes * a.s[1].tiles_pad;
     if (n1 + n2 > 0x7fffffffLL) return MOE_ESHAPE;
-    launch_lines(a, block_rows, T >= kWide128Tokens, static_cast<unsigned>(n1 + n2), st);
+    launch_lines(a, block_rows, static_cast<unsigned>(n1 + n2), st);
     return MOE_OK;
 }
 

@@ -26,7 +26,7 @@ void shared_dispatch_kernel(int T, int block_rows, int32_t *__restrict__ slot_of
     if (tid == 0) {
         slot_off[0] = 0;
         slot_off[1] = T;
-        reinterpret_cast<int4 *>(blocks)[0] = make_int4(n_blocks, block_rows, T > 64 ? (T + 63) / 64 : 0, 0);
+        reinterpret_cast<int4 *>(blocks)[0] = make_int4(n_blocks, block_rows, T > 64 ? (T + 63) / 64 : 0, T > 64 ? (T + 127) / 128 : 0);
     }
     for (int i = tid; i < T; i += n) perm[i] = i;
     for (int b = tid; b < n_blocks; b += n) reinterpret_cast<int4 *>(blocks)[1 + b] = make_int4(0, b * block_rows, T, 0);

@@ -59,8 +59,9 @@ def rel_fro(a, b):
 def expected_blocks(slot_off, block_rows, heavy_rows=16):
     """The FFN work list that follows from slot_off: every slot's rows cut into blocks of at
     most `block_rows` rows; slots with more than `heavy_rows` requests first, ascending slot
-    order within each class; [n_blocks, block_rows, n_wide, 0] then [slot, first row, slot end, slot start] per
-    block (flattened int32); n_wide = number of 64-row blocks of the slots with more than 64 requests."""
+    order within each class; [n_blocks, block_rows, n_wide, n_wide128] then [slot, first row, slot end, slot
+    start] per block (flattened int32); n_wide / n_wide128 = number of 64-row / 128-row blocks of the slots
+    with more than 64 requests."""
     out = []
     for heavy in (True, False):
         for s in range(len(slot_off) - 1):
@@ -71,4 +72,5 @@ def expected_blocks(slot_off, block_rows, heavy_rows=16):
                 out.append([s, r, hi, lo])
     rows = np.diff(np.asarray(slot_off, dtype=np.int64))
     n_wide = int(sum((int(v) + 63) // 64 for v in rows if v > 64))
-    return np.array([[len(out), block_rows, n_wide, 0]] + out, dtype=np.int32).reshape(-1)
+    n_wide128 = int(sum((int(v) + 127) // 128 for v in rows if v > 64))
+    return np.array([[len(out), block_rows, n_wide, n_wide128]] + out, dtype=np.int32).reshape(-1)
