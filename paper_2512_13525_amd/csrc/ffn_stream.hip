@@ -62,7 +62,7 @@ constexpr int kMaxItems = static_cast<int>(moe::kFfnCtrlBytes / 4) / kCtrlBlockI
 struct StageArgs {
     const uint16_t *B;                   // token operand: X (stage 1, rows through perm) or act (stage 2, blocks)
     const char *Wp;                      // packed weights: [C][tiles][KS][2][64] fragments of 16 bytes
-    int tiles, tiles_pad, KS;            // tiles_pad = tiles rounded up to a multiple of 8
+    int tiles, items, tiles_pad, KS;     // items = workgroups per block (stage 2: one per pair of tiles); tiles_pad = items rounded up to a multiple of 8
     int b_stride;                        // elements between rows of X (stage 1)
     int out_stride;                      // elements between rows of Yp (stage 2)
 };
@@ -420,22 +420,28 @@ __device__ __forceinline__ void stream_item_steps(const StreamArgs &a, const Sta
 // K-steps is even and the token tiles leave room in the registers); the steps go round-robin over
 // the wavefronts, 4 / U or 3 of them in flight for both operands, the weights issued before the
 // wait for the block (they do not depend on stage 1).
-template <int NT, int TT, int U, bool STREAM>
+// NW = 2: the item is a pair of adjacent tiles (64 output channels; their weights follow each other in
+// the packed layout) multiplied with the same token fragments: half as many items and `act`
+// loads per block, twice the weight bytes in flight per workgroup.  Blocks of up to 16 rows (32
+// in the 64-row launch) have the registers for it.  n_readers: calls of this function per block.
+template <int NT, int TT, int U, bool STREAM, int NW>
 __device__ __forceinline__ void stream_item_down(const StreamArgs &a, const StageArgs &g, char *lds, int *s_ok,
-                                                 const char *w, int item, int tile, int row0, int row_end,
+                                                 const char *w, int item, int tile, int n_readers, int row0, int row_end,
                                                  int wave, int lane) {
     asm volatile("" : "+v"(lane));                             // see wide_item
     constexpr int D = U == 2 ? 2 : NT > 2 ? 3 : 4;               // steps in flight that fit the registers
+    constexpr int F = 2 * NW;                                    // weight fragments per K-step
+    const size_t w_tile = static_cast<size_t>(g.KS) * 2048;     // bytes between the tiles of the pair
     f32x4 (*red)[2][TT][MOE_WAVE] = reinterpret_cast<f32x4 (*)[2][TT][MOE_WAVE]>(lds);
     const uint32_t aoff = lane * 16;
     const char *bbase = reinterpret_cast<const char *>(g.B) + static_cast<size_t>(item) * a.act_block_bytes + aoff;
     const int n = (g.KS / U - wave + kWaves - 1) / kWaves;      // steps wave, wave+4, ... of this wavefront
-    f32x4 acc[2][NT];
+    f32x4 acc[F][NT];
 #pragma unroll
-    for (int h = 0; h < 2; ++h)
+    for (int h = 0; h < F; ++h)
 #pragma unroll
         for (int t = 0; t < NT; ++t) acc[h][t] = f32x4{0.f, 0.f, 0.f, 0.f};
-    bf16x8 wr[D][U][2], br[D][U][NT];
+    bf16x8 wr[D][U][F], br[D][U][NT];
     const int last = n > 0 ? n - 1 : 0;
     const int rot = n > 0 ? static_cast<int>(static_cast<unsigned>(tile) % static_cast<unsigned>(n)) : 0;
 #define MOE_STEP_INDEX(step)                                                                     \
@@ -447,10 +453,11 @@ __device__ __forceinline__ void stream_item_down(const StreamArgs &a, const Stag
     do {                                                                                         \
         MOE_STEP_INDEX(step)                                                                     \
         const char *ws_ = w + static_cast<size_t>(s_) * (U * 2048) + aoff;                       \
-        _Pragma("unroll") for (int u = 0; u < U; ++u) {                                          \
-            wr[d][u][0] = load_weights<STREAM>(ws_ + u * 2048);                                 \
-            wr[d][u][1] = load_weights<STREAM>(ws_ + u * 2048 + 1024);                          \
-        }                                                                                        \
+        _Pragma("unroll") for (int nw = 0; nw < NW; ++nw)                                        \
+            _Pragma("unroll") for (int u = 0; u < U; ++u) {                                      \
+                wr[d][u][2 * nw] = load_weights<STREAM>(ws_ + nw * w_tile + u * 2048);          \
+                wr[d][u][2 * nw + 1] = load_weights<STREAM>(ws_ + nw * w_tile + u * 2048 + 1024); \
+            }                                                                                    \
         asm volatile("" ::: "memory");                                                           \
     } while (0)
 #define MOE_LOAD_T(d, step)                                                                      \
@@ -465,17 +472,17 @@ __device__ __forceinline__ void stream_item_down(const StreamArgs &a, const Stag
 #define MOE_MMA_STEP(d)                                                                          \
     do {                                                                                         \
         _Pragma("unroll") for (int u = 0; u < U; ++u)                                            \
-            _Pragma("unroll") for (int t = 0; t < NT; ++t) {                                     \
-                acc[0][t] = mfma16(wr[d][u][0], br[d][u][t], acc[0][t]);                         \
-                acc[1][t] = mfma16(wr[d][u][1], br[d][u][t], acc[1][t]);                         \
-            }                                                                                    \
+            _Pragma("unroll") for (int t = 0; t < NT; ++t)                                       \
+                _Pragma("unroll") for (int f = 0; f < F; ++f)                                    \
+                    acc[f][t] = mfma16(wr[d][u][f], br[d][u][t], acc[f][t]);                     \
     } while (0)
 #pragma unroll
     for (int d = 0; d < D; ++d)
         if (d < n) MOE_LOAD_W(d, d);
-    if (!wait_block_ready(a, s_ok, item, tile, g.tiles)) {
+    if (!wait_block_ready(a, s_ok, item, tile, n_readers)) {
         const int m_ = row_end - row0;
-        store_nan_rows(a, g, tile, row0, m_ < TT * 16 ? m_ : TT * 16);
+#pragma unroll
+        for (int nw = 0; nw < NW; ++nw) store_nan_rows(a, g, tile + nw, row0, m_ < TT * 16 ? m_ : TT * 16);
         return;
     }
     if (n > 0) {
@@ -505,7 +512,14 @@ __device__ __forceinline__ void stream_item_down(const StreamArgs &a, const Stag
 #undef MOE_LOAD_W
 #undef MOE_LOAD_T
 #undef MOE_MMA_STEP
-    reduce_store<false, NT, TT>(a, g, red, acc, item, 0, tile, row0, row_end, wave, lane);
+#pragma unroll
+    for (int nw = 0; nw < NW; ++nw) {
+        if (nw) __syncthreads();                                 // the reduction buffer is reused
+        f32x4 part[2][NT];
+#pragma unroll
+        for (int t = 0; t < NT; ++t) { part[0][t] = acc[2 * nw][t]; part[1][t] = acc[2 * nw + 1][t]; }
+        reduce_store<false, NT, TT>(a, g, red, part, item, 0, tile + nw, row0, row_end, wave, lane);
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -742,8 +756,9 @@ __device__ __forceinline__ void run_wide(const StreamArgs &a, const StageArgs &g
 template <bool STAGE1, bool LINES, int TT, int WR>
 __device__ __forceinline__ void run_item(const StreamArgs &a, const StageArgs &g, char *lds, int *s_ok, int wide,
                                          unsigned id) {
-    const int tile = id % g.tiles_pad, item = id / g.tiles_pad;
-    if (tile >= g.tiles) return;
+    int tile = id % g.tiles_pad;
+    const int item = id / g.tiles_pad;
+    if (tile >= g.items) return;
     // work list entry: {slot, first row, end of the slot's rows, first of the slot's rows}; entry 0 holds the number of blocks
     // (both are wave-uniform scalar loads issued together; an entry past the end is never used)
     const int4 *list = reinterpret_cast<const int4 *>(a.blocks);
@@ -757,22 +772,48 @@ __device__ __forceinline__ void run_item(const StreamArgs &a, const StageArgs &g
     }
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / MOE_WAVE), lane = threadIdx.x % MOE_WAVE;
     const int slot = ent.x, row0 = ent.y, hi = ent.z;
+    // in the 64-row launch a stage-2 workgroup owns a pair of tiles (larger batches: the pairs halve
+    // the workgroup turnover of the second stage; small batches want every tile on a workgroup of its own)
+    constexpr bool kPairs = !STAGE1 && TT == 4;
+    if constexpr (kPairs) tile *= 2;
     const char *w = g.Wp + (static_cast<size_t>(slot) * g.tiles + tile) * g.KS * 2048;
     const int m = hi - row0;
     const bool single = m <= TT * 16 && row0 == ent.w;                  // the slot's only block
     if constexpr (!STAGE1) {
         const int tiles16 = ((m < TT * 16 ? m : TT * 16) + 15) >> 4;     // 16-row token tiles that hold requests
-#define MOE_CASE(NT, U)                                                                              \
+        const bool two = kPairs && tile + 1 < g.tiles;                   // an odd number of tiles leaves the last one alone
+        // blocks with few rows multiply both tiles at once (every workgroup of a block takes the same
+        // branch, so the block's readers are counted the same way by all)
+        const bool paired = kPairs && tiles16 <= 2;
+#define MOE_DOWN(NT, U, NW, t_, n_readers_)                                                          \
+        do {                                                                                         \
+            const char *w_ = w + static_cast<size_t>((t_) - tile) * g.KS * 2048;                     \
+            if (single) stream_item_down<NT, TT, U, true, NW>(a, g, lds, s_ok, w_, item, t_, n_readers_, row0, hi, wave, lane);  \
+            else stream_item_down<NT, TT, U, false, NW>(a, g, lds, s_ok, w_, item, t_, n_readers_, row0, hi, wave, lane);        \
+        } while (0)
+#define MOE_CASE_PAIR(NT, U)                                                                         \
     case NT:                                                                                         \
-        if (single) stream_item_down<NT, TT, U, true>(a, g, lds, s_ok, w, item, tile, row0, hi, wave, lane);  \
-        else stream_item_down<NT, TT, U, false>(a, g, lds, s_ok, w, item, tile, row0, hi, wave, lane);        \
+        if (two) MOE_DOWN(NT, U, 2, tile, g.items);                                                  \
+        else MOE_DOWN(NT, U, 1, tile, g.items);                                                      \
+        break;
+#define MOE_CASE_SEQ(NT, U)                                                                          \
+    case NT:                                                                                         \
+        MOE_DOWN(NT, U, 1, tile, g.tiles);                                                           \
+        if (two) {                                                                                   \
+            __syncthreads();                                             /* the LDS buffer is reused */ \
+            MOE_DOWN(NT, U, 1, tile + 1, g.tiles);                                                   \
+        }                                                                                            \
         break;
         if constexpr (TT == 2) {
-            switch (tiles16) { MOE_CASE(1, LINES ? 2 : 1) MOE_CASE(2, LINES ? 2 : 1) }
+            switch (tiles16) { MOE_CASE_SEQ(1, LINES ? 2 : 1) MOE_CASE_SEQ(2, LINES ? 2 : 1) }
+        } else if (paired) {
+            switch (tiles16) { MOE_CASE_PAIR(1, LINES ? 2 : 1) MOE_CASE_PAIR(2, LINES ? 2 : 1) }
         } else {
-            switch (tiles16) { MOE_CASE(1, LINES ? 2 : 1) MOE_CASE(2, LINES ? 2 : 1) MOE_CASE(3, 1) MOE_CASE(4, 1) }
+            switch (tiles16) { MOE_CASE_SEQ(3, 1) MOE_CASE_SEQ(4, 1) }
         }
-#undef MOE_CASE
+#undef MOE_DOWN
+#undef MOE_CASE_PAIR
+#undef MOE_CASE_SEQ
     } else if (LINES) {
         const int halves = ((m < TT * 16 ? m : TT * 16) + 7) >> 3;     // 8-row halves that hold requests
 #define MOE_CASE(NH)                                                                                 \
@@ -862,7 +903,7 @@ void ffn_stream_kernel(StreamArgs a) {
             const bool s1 = blockIdx.x < n1;
             const unsigned id0 = s1 ? blockIdx.x : blockIdx.x - n1;
             const unsigned tp = s1 ? a.s[0].tiles_pad : a.s[1].tiles_pad;
-            if (id0 % tp >= static_cast<unsigned>(s1 ? a.s[0].tiles : a.s[1].tiles)) return;
+            if (id0 % tp >= static_cast<unsigned>(s1 ? a.s[0].items : a.s[1].items)) return;
             if (threadIdx.x < MOE_WAVE) {
                 const unsigned b = id0 / tp + threadIdx.x * lanes;
                 // entries of wide slots that lead no block are not visited
@@ -924,7 +965,9 @@ int launch_ffn_stream(const void *X, const void *W13p, const void *W2p, int T, i
     a.s[1].B = act;
     a.s[1].Wp = static_cast<const char *>(W2p);
     a.s[1].tiles = d_h / 32; a.s[1].KS = d_e / 32; a.s[1].b_stride = 0; a.s[1].out_stride = d_h;
-    for (int i = 0; i < 2; ++i) a.s[i].tiles_pad = (a.s[i].tiles + 7) / 8 * 8;
+    a.s[0].items = a.s[0].tiles;
+    a.s[1].items = block_rows == 32 ? a.s[1].tiles : (a.s[1].tiles + 1) / 2;   // 64-row launch: a stage-2 workgroup owns a pair of tiles
+    for (int i = 0; i < 2; ++i) a.s[i].tiles_pad = (a.s[i].items + 7) / 8 * 8;
     const long long lanes = items < kFfnLaneBlocks ? items : kFfnLaneBlocks;
     const long long n1 = lanes * a.s[0].tiles_pad, n2 = lanes * a.s[1].tiles_pad;
     if (n1 + n2 > 0x7fffffffLL) return MOE_ESHAPE;
