@@ -86,8 +86,9 @@ int  moe_placement_replicas(const moe_placement_t *pl, int e);
 int  moe_placement_dims(const moe_placement_t *pl, int *E, int *n_inst, int *C);
 
 /* ------------------------------------------------------------------ a0: gating selection
- * Sec. 3.4 workflow: "gating first produces the top-k logical expert ids".  The score
- * function is a property of the model, not of the paper:
+ * Sec. 3.4, first step of the scheduling workflow: the gate yields, per token, the k logical
+ * expert ids that the scheduler then maps to replicas.  The score function is a property of
+ * the model, not of the paper:
  *   MOE_ROUTE_SOFTMAX        ids = the k largest logits (largest first; equal logits:
  *                            lower id first); w = softmax over all E logits gathered at
  *                            ids, rescaled to sum to 1 when renormalize != 0.

@@ -38,6 +38,9 @@ constexpr int kLoadsB = 128 * 8 / kThreads;     // 16-byte pieces of the 128 x 1
 constexpr int kRows = 128;               // request rows of a wide block
 constexpr int kRowTiles = kRows / 16;
 constexpr int kRing = 2;                 // K-tiles of both operands in flight (register sets)
+constexpr unsigned kPanelItems = 24;     // list entries (of 64 rows: 12 blocks of 128 rows) of a panel of workgroups
+constexpr unsigned kPanelTiles = 8;      // workgroup tiles of a panel
+constexpr unsigned kPanelSize = kPanelItems * kPanelTiles;
 
 struct WideArgs {
     const char *B;                       // token operand: X (stage 1, rows through perm) or the intermediate (stage 2)
@@ -64,11 +67,21 @@ template <bool STAGE1>
 __global__ __launch_bounds__(kThreads, kRing == 2 ? 3 : 2)
 void ffn_wide_kernel(WideArgs a) {
     __shared__ __attribute__((aligned(16))) char lds[2][kRows * 128];
-    const int tile = blockIdx.x % a.tiles_pad, item = blockIdx.x / a.tiles_pad;
+    // Workgroup ids go round-robin over the eight XCDs, each with an L2 of its own.  The (list entry, tile)
+    // grid is cut into panels of kPanelItems entries x kPanelTiles tiles; a panel is a run of consecutive
+    // workgroups of ONE XCD (about as many as the XCD holds at a time), so the tiles of a block share its
+    // token rows and the sibling blocks of a slot share the expert's tiles in that L2 while they walk K
+    // side by side.  Panels go to the XCDs in turn, the tile panels of the same entries first.
+    const unsigned xcd = blockIdx.x & 7u, q = blockIdx.x >> 3;
+    const unsigned panel = (q / kPanelSize) * 8u + xcd, r = q % kPanelSize;
+    const unsigned tile_panels = static_cast<unsigned>(a.tiles + kPanelTiles - 1) / kPanelTiles;
+    const int tile = static_cast<int>((panel % tile_panels) * kPanelTiles + r % kPanelTiles);
+    const long long item_ll = static_cast<long long>(panel / tile_panels) * kPanelItems + r / kPanelTiles;
     if (tile >= a.tiles) return;
     const int4 *list = reinterpret_cast<const int4 *>(a.blocks);
     const int4 head = list[0];
-    if (item >= head.x) return;
+    if (item_ll >= head.x) return;
+    const int item = static_cast<int>(item_ll);
     const int wm_ws = a.ctrl[moe::kCtrlWideMin];                     // the workspace's threshold, 0 = default
     if (!moe::ffn_gemm_on(head, a.tiles1, wm_ws)) return;
     const int4 ent = list[1 + item];
@@ -246,6 +259,12 @@ __device__ __forceinline__ void wide_block(const WideArgs &a, char (*lds)[kRows 
     }
 }
 
+// Workgroups of a launch over `items` list entries and `tiles` workgroup tiles: whole panels, eight at a time.
+long long wide_grid(long long items, int tiles) {
+    const long long panels = ((items + kPanelItems - 1) / kPanelItems) * ((tiles + kPanelTiles - 1) / kPanelTiles);
+    return (panels + 7) / 8 * 8 * kPanelSize;
+}
+
 }  // namespace
 
 namespace moe {
@@ -262,14 +281,16 @@ int launch_ffn_wide(const void *X, const void *W13p, const void *W2p, int T, int
     a.B = static_cast<const char *>(X); a.Wp = static_cast<const char *>(W13p);
     a.ptiles = d_e / 16; a.KS = d_h / 32; a.b_row_bytes = static_cast<uint32_t>(d_h) * 2; a.out_stride = d_e;
     a.tiles = (a.ptiles + kWaves - 1) / kWaves; a.tiles_pad = (a.tiles + 7) / 8 * 8; a.tiles1 = a.tiles; a.wide_min = 0;
-    if (items * a.tiles_pad > 0x7fffffffLL) return MOE_ESHAPE;
-    hipLaunchKernelGGL(ffn_wide_kernel<true>, dim3(static_cast<unsigned>(items * a.tiles_pad)), dim3(kThreads), 0, st, a);
+    long long grid = wide_grid(items, a.tiles);
+    if (grid > 0x7fffffffLL) return MOE_ESHAPE;
+    hipLaunchKernelGGL(ffn_wide_kernel<true>, dim3(static_cast<unsigned>(grid)), dim3(kThreads), 0, st, a);
     // stage 2
     a.B = reinterpret_cast<const char *>(act_rows); a.Wp = static_cast<const char *>(W2p);
     a.ptiles = d_h / 32; a.KS = d_e / 32; a.b_row_bytes = static_cast<uint32_t>(d_e) * 2; a.out_stride = d_h;
     a.tiles = (a.ptiles + kWaves - 1) / kWaves; a.tiles_pad = (a.tiles + 7) / 8 * 8;
-    if (items * a.tiles_pad > 0x7fffffffLL) return MOE_ESHAPE;
-    hipLaunchKernelGGL(ffn_wide_kernel<false>, dim3(static_cast<unsigned>(items * a.tiles_pad)), dim3(kThreads), 0, st, a);
+    grid = wide_grid(items, a.tiles);
+    if (grid > 0x7fffffffLL) return MOE_ESHAPE;
+    hipLaunchKernelGGL(ffn_wide_kernel<false>, dim3(static_cast<unsigned>(grid)), dim3(kThreads), 0, st, a);
     return MOE_OK;
 }
 
