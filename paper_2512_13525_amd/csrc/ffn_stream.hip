@@ -735,19 +735,33 @@ constexpr int kWideMinWorkgroups = 256;
 __device__ __forceinline__ bool wide_on(int4 head, int groups1, int override_min) {
     return head.z * groups1 >= (override_min > 0 ? override_min : kWideMinWorkgroups);
 }
-// The leader of a wide block runs it, every other workgroup of a wide slot's entries leaves.
-template <bool STAGE1, int WR>
+// The workgroups of a wide slot's leading entries (one entry per block of WR rows; ids tile = 0 .. tiles_pad-1
+// each) run the slot's blocks x groups of 4 tiles; all other workgroups of the slot's entries leave.
+// Workgroup ids go round-robin over the eight XCDs, so tile % 8 is the XCD and (leader index, tile / 8)
+// the place in that XCD's start order.  That order is walked block-fastest: the blocks of one group of
+// tiles start next to each other on one XCD, walk the expert's tiles side by side, and all but the first
+// find them in that L2.  (Group-fastest, the natural order of the ids, put the sibling blocks tiles_pad / 8
+// starts apart: on a busy chip that is longer than a line survives in a streaming L2, and every block of a
+// slot fetched the expert from memory again.)  BR = rows per list entry.
+template <bool STAGE1, int WR, int BR>
 __device__ __forceinline__ void run_wide(const StreamArgs &a, const StageArgs &g, char *lds, int *s_ok, int item,
                                          int tile, int4 ent) {
-    const int slot = ent.x, row0 = ent.y, hi = ent.z, lo = ent.w;
-    if ((row0 - lo) % WR != 0) return;                               // not the leading entry of a wide block
-    const int groups = (g.tiles + kWaves - 1) / kWaves;              // workgroups of the block in this stage
-    if (tile >= groups) return;
+    const int slot = ent.x, hi = ent.z, lo = ent.w;
+    if ((ent.y - lo) % WR != 0) return;                              // not the leading entry of a wide block
+    const int groups = (g.tiles + kWaves - 1) / kWaves;              // workgroups of a block in this stage
+    const int nb = (hi - lo + WR - 1) / WR;                          // blocks of the slot
+    const int leader = (ent.y - lo) / WR;                            // which of them this entry leads
+    const int xcd = tile & 7;
+    const int place = leader * (g.tiles_pad >> 3) + (tile >> 3);     // in the XCD's start order, within the slot
+    const int group = xcd + 8 * (place / nb), b = place % nb;
+    if (group >= groups) return;
+    item += (b - leader) * (WR / BR);                                // the block's leading entry: its control lines and `act`
+    const int row0 = lo + b * WR;
     const int m = hi - row0 < WR ? hi - row0 : WR;
     const int rt = (m + 15) >> 4;
-    if (rt <= 1) wide_item<STAGE1, 1>(a, g, lds, s_ok, item, tile, groups, slot, row0, m);
-    else if (rt <= 2) wide_item<STAGE1, 2>(a, g, lds, s_ok, item, tile, groups, slot, row0, m);
-    else wide_item<STAGE1, 4>(a, g, lds, s_ok, item, tile, groups, slot, row0, m);
+    if (rt <= 1) wide_item<STAGE1, 1>(a, g, lds, s_ok, item, group, groups, slot, row0, m);
+    else if (rt <= 2) wide_item<STAGE1, 2>(a, g, lds, s_ok, item, group, groups, slot, row0, m);
+    else wide_item<STAGE1, 4>(a, g, lds, s_ok, item, group, groups, slot, row0, m);
 }
 
 // LINES: this stage has an even number of K-steps
@@ -758,7 +772,6 @@ __device__ __forceinline__ void run_item(const StreamArgs &a, const StageArgs &g
                                          unsigned id) {
     int tile = id % g.tiles_pad;
     const int item = id / g.tiles_pad;
-    if (tile >= g.items) return;
     // work list entry: {slot, first row, end of the slot's rows, first of the slot's rows}; entry 0 holds the number of blocks
     // (both are wave-uniform scalar loads issued together; an entry past the end is never used)
     const int4 *list = reinterpret_cast<const int4 *>(a.blocks);
@@ -767,9 +780,10 @@ __device__ __forceinline__ void run_item(const StreamArgs &a, const StageArgs &g
     if (item >= n_blocks) return;                                // past the last block: nothing else is read
     // a slot with more than kWideRows requests is computed as tiled GEMMs over blocks of kWideRows rows
     if (wide && ent.z - ent.w > kWideMin) {
-        if (wide == 1) run_wide<STAGE1, WR>(a, g, lds, s_ok, item, tile, ent);
+        if (wide == 1) run_wide<STAGE1, WR, TT * 16>(a, g, lds, s_ok, item, tile, ent);
         return;
     }
+    if (tile >= g.items) return;                                 // ids that pad the tiles to a multiple of 8
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / MOE_WAVE), lane = threadIdx.x % MOE_WAVE;
     const int slot = ent.x, row0 = ent.y, hi = ent.z;
     // in the 64-row launch a stage-2 workgroup owns a pair of tiles (larger batches: the pairs halve
@@ -903,7 +917,7 @@ void ffn_stream_kernel(StreamArgs a) {
             const bool s1 = blockIdx.x < n1;
             const unsigned id0 = s1 ? blockIdx.x : blockIdx.x - n1;
             const unsigned tp = s1 ? a.s[0].tiles_pad : a.s[1].tiles_pad;
-            if (id0 % tp >= static_cast<unsigned>(s1 ? a.s[0].items : a.s[1].items)) return;
+            // (ids that pad the tiles to a multiple of 8 stay: the wide slots use them)
             if (threadIdx.x < MOE_WAVE) {
                 const unsigned b = id0 / tp + threadIdx.x * lanes;
                 // entries of wide slots that lead no block are not visited
