@@ -392,7 +392,9 @@ int moe_grouped_ffn_static(const void *X_dev, const void *W13_dev, const void *W
  *                                    but only when the batch has enough blocks of them to fill the
  *                                    chip: over blocks of 64 rows by workgroups of the same launch
  *                                    when (number of 64-row blocks of those slots) x (ceil(d_e / 64)
- *                                    workgroups per block) >= this value (default 256); in batches
+ *                                    workgroups per block) >= this value (default 256; by default
+ *                                    also from 64 such workgroups on when the launch has enough
+ *                                    other experts to stream to hide them); in batches
  *                                    of at least 2048 tokens over blocks of 128 rows by two launches
  *                                    of their own when (number of 128-row blocks) x (workgroups per
  *                                    block) >= this value (default 512), which takes precedence.

@@ -726,14 +726,28 @@ __device__ __forceinline__ void wide_item(const StreamArgs &a, const StageArgs &
 // of 128 rows needs 64 accumulator registers more than the streaming items leave at three workgroups
 // per CU; batches of thousands of tokens take the tiled-GEMM launches of ffn_wide.hip instead).
 constexpr int kWideMin = 64;
-// A wavefront of a wide workgroup runs its tile's whole K dimension, one round trip per K-tile, so wide
-// blocks only pay off when a batch has enough of them to fill the chip with such workgroups:
-// (64-row blocks of the wide slots, from the list's header) x (first-stage workgroups per block) must
-// reach kWideMinWorkgroups, otherwise the wide slots are cut into streaming items like the others.
-// Every workgroup takes the decision from the same two numbers.
+// A wavefront of a wide workgroup runs its tile's whole K dimension, one round trip per K-tile (about
+// kWideTileNs each), so a wide workgroup lasts much longer than a streaming item.  Wide blocks pay off
+//  - when a batch has enough of them to fill the chip with such workgroups: (64-row blocks of the wide
+//    slots, from the list's header) x (first-stage workgroups per block) >= kWideMinWorkgroups; or
+//  - from kWideMinHidden workgroups on, when the rest of the launch lasts long enough to hide them (they
+//    come first in the list and start with the launch): the time the launch needs to stream one expert
+//    per list entry at kStreamBytesPerNs must exceed 5/4 of the K-tiles of both stages x kWideTileNs.
+// Otherwise the wide slots are cut into streaming items like the others.  Every workgroup takes the
+// decision from the same numbers.  A caller's threshold replaces the first rule and switches the
+// second off.
 constexpr int kWideMinWorkgroups = 256;
-__device__ __forceinline__ bool wide_on(int4 head, int groups1, int override_min) {
-    return head.z * groups1 >= (override_min > 0 ? override_min : kWideMinWorkgroups);
+constexpr int kWideMinHidden = 64;
+constexpr long long kWideTileNs = 900, kStreamBytesPerNs = 7000;
+__device__ __forceinline__ bool wide_on(int4 head, int groups1, int override_min, int ks1, int ks2) {
+    const int wgs = head.z * groups1;
+    if (override_min > 0) return wgs >= override_min;
+    if (wgs >= kWideMinWorkgroups) return true;
+    if (wgs < kWideMinHidden) return false;
+    // an expert's three matrices: 3 * d_h * d_e bf16 = ks1 * ks2 * 32 * 32 * 6 bytes
+    const long long stream_ns = static_cast<long long>(head.x) * ks1 * ks2 * (32 * 32 * 6) / kStreamBytesPerNs;
+    const long long chain_ns = static_cast<long long>((ks1 + 1) / 2 + (ks2 + 1) / 2) * kWideTileNs;
+    return 4 * stream_ns >= 5 * chain_ns;
 }
 // The workgroups of a wide slot's leading entries (one entry per block of WR rows; ids tile = 0 .. tiles_pad-1
 // each) run the slot's blocks x groups of 4 tiles; all other workgroups of the slot's entries leave.
@@ -904,7 +918,7 @@ void ffn_stream_kernel(StreamArgs a) {
         // header word 3 of the workspace: the caller's threshold for wide blocks (0 = default)
         const int wide_min = a.ctrl[moe::kCtrlWideMin];
         const int wide = a.has_gemm && moe::ffn_gemm_on(head, (a.s[0].tiles + kWaves - 1) / kWaves, wide_min) ? 2
-                         : wide_on(head, (a.s[0].tiles + kWaves - 1) / kWaves, wide_min) ? 1 : 0;
+                         : wide_on(head, (a.s[0].tiles + kWaves - 1) / kWaves, wide_min, a.s[0].KS, a.s[1].KS) ? 1 : 0;
         const unsigned n_blocks = static_cast<unsigned>(head.x);
         const unsigned lanes = n_blocks < moe::kFfnLaneBlocks ? n_blocks : moe::kFfnLaneBlocks;
         const unsigned n1 = lanes * a.s[0].tiles_pad, n2 = lanes * a.s[1].tiles_pad;

@@ -826,7 +826,7 @@ def test_ffn_wait_overrun_is_loud():
     assert n_blocks >= 3
     # the victim: the second entry of the list.  This batch has too few slots with more than 64 requests
     # for tiled-GEMM blocks, so every entry is a streaming block of its own
-    assert int(blk[0, 2]) * -(-cfg.d_e // 64) < 256
+    assert int(blk[0, 2]) * -(-cfg.d_e // 64) < 64
     victim = 1
     _, r0, hi, lo = (int(v) for v in blk[1 + victim])
     rows = np.arange(r0, min(hi, r0 + R))
