@@ -128,7 +128,38 @@ __device__ __forceinline__ void route_token(const float *row, int E, int k, cons
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
         uint64_t gkey = 0ull;
-        if (lane < cfg.n_group) {
+        int owner_shift = 0;                             // group g's key sits in lane g << owner_shift
+        if (cfg.n_group <= MOE_WAVE / 8) {
+            // eight lanes per group: each scans an eighth of the group, then three exchanges inside the
+            // eight lanes merge the (largest, second largest) pairs; the two largest values of a group do
+            // not depend on the order in which they are found
+            owner_shift = 3;
+            const int g = lane >> 3, sub = lane & 7;
+            float a = -INFINITY, b = -INFINITY;
+            if (g < cfg.n_group) {
+                for (int j = sub; j < per; j += 8) {
+                    const float x = row_lds[g * per + j];
+                    if (x > a) { b = a; a = x; }
+                    else if (x > b) { b = x; }
+                }
+            }
+#define MOE_TOP2_MERGE(ctrl)                                                                      \
+            do {                                                                                  \
+                const float a2 = __uint_as_float(static_cast<uint32_t>(__builtin_amdgcn_update_dpp(  \
+                    0, static_cast<int>(__float_as_uint(a)), ctrl, 0xf, 0xf, false)));            \
+                const float b2 = __uint_as_float(static_cast<uint32_t>(__builtin_amdgcn_update_dpp(  \
+                    0, static_cast<int>(__float_as_uint(b)), ctrl, 0xf, 0xf, false)));            \
+                const float hi = a2 > a ? a2 : a, lo = a2 > a ? a : a2;                           \
+                const float bb = b2 > b ? b2 : b;                                                 \
+                a = hi;                                                                           \
+                b = bb > lo ? bb : lo;                                                            \
+            } while (0)
+            MOE_TOP2_MERGE(0xB1);                        // quad_perm [1,0,3,2]
+            MOE_TOP2_MERGE(0x4E);                        // quad_perm [2,3,0,1]
+            MOE_TOP2_MERGE(0x141);                       // row_half_mirror: the other quad of the eight
+#undef MOE_TOP2_MERGE
+            if (sub == 0 && g < cfg.n_group) gkey = make_key(sigmoid_f32(a) + sigmoid_f32(b), g);
+        } else if (lane < cfg.n_group) {
             float a = -INFINITY, b = -INFINITY;          // a >= b: two largest logits of the group
             for (int j = 0; j < per; ++j) {
                 const float x = row_lds[lane * per + j];
@@ -143,7 +174,7 @@ __device__ __forceinline__ void route_token(const float *row, int E, int k, cons
             const uint64_t best = wave_max_u64(gkey);
             const int g = 0x7fffffff - static_cast<int>(best & 0xffffffffu);
             keep |= 1ull << g;
-            if (lane == g) gkey = 0ull;
+            if (lane == (g << owner_shift)) gkey = 0ull;
         }
 #pragma unroll
         for (int i = 0; i < VPL; ++i) {
