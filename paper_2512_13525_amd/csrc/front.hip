@@ -40,6 +40,7 @@ struct FrontArgs {
     uint32_t *act_bits;                  // [kBitWords], zero between calls; null = one-workgroup tail
     int32_t *hist;                       // [n_chunks][C]
     int chunk_pairs, n_chunks;
+    int tok_per_wg;                      // launch from logits: wavefronts of a workgroup that route a token (4, 8 or 16)
 };
 constexpr int kBitWords = MOE_MAX_EXPERTS / 32;
 constexpr int kChunkPairs = 2048;
@@ -450,8 +451,11 @@ void front_kernel(FrontArgs a) {
             if (threadIdx.x < kBitWords) s_bits[threadIdx.x] = 0u;
             __syncthreads();
         }
-        const int t = blockIdx.x * moe::kFrontWaves + wave;
-        if (t < a.T) {
+        // small batches route on a few wavefronts per workgroup (one or two per SIMD instead of four),
+        // spread over more CUs: the selection is a long chain of cross-lane steps that four wavefronts
+        // of one SIMD would take turns at
+        const int t = blockIdx.x * a.tok_per_wg + wave;
+        if (wave < a.tok_per_wg && t < a.T) {
             moe::route_token<VPL, true>(a.logits + static_cast<size_t>(t) * a.E, a.E, a.k, a.cfg, sh.row[wave], lane,
                                         a.ids + static_cast<size_t>(t) * a.k, a.w + static_cast<size_t>(t) * a.k,
                                         a.act_bits ? s_bits : nullptr);
@@ -523,10 +527,16 @@ void front_scatter_kernel(FrontArgs a) {
                        a.perm, a.pos, a.blocks, a.block_rows);
 }
 
+#ifndef MOE_TPW
+#define MOE_TPW 0
+#endif
 template <int VPL, bool GATE>
-int launch_front(const FrontArgs &a, const char *what, hipStream_t st) {
+int launch_front(const FrontArgs &a_in, const char *what, hipStream_t st) {
+    FrontArgs a = a_in;
+    // every routing workgroup takes a ticket from one counter: keep them to about a hundred
+    a.tok_per_wg = MOE_TPW ? MOE_TPW : a.T <= 512 ? 4 : a.T <= 1024 ? 8 : moe::kFrontWaves;
     int blocks = 1;
-    if (a.T > 0) blocks = GATE ? (a.T + 127) / 128 * 8 * a.n_tiles : (a.T + moe::kFrontWaves - 1) / moe::kFrontWaves;
+    if (a.T > 0) blocks = GATE ? (a.T + 127) / 128 * 8 * a.n_tiles : (a.T + a.tok_per_wg - 1) / a.tok_per_wg;
     hipLaunchKernelGGL((front_kernel<VPL, GATE>), dim3(blocks), dim3(moe::kFrontThreads), 0, st, a);
     if (!GATE && a.act_bits) {
         hipLaunchKernelGGL(front_count_kernel, dim3(a.n_chunks), dim3(moe::kFrontThreads), 0, st, a);
