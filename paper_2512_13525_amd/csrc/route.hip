@@ -1,5 +1,5 @@
-// a0: gating selection (Janus Sec. 3.4 workflow: "gating first produces the top-k logical
-// expert ids"; Sec. 3.3: gating runs on the MoE side over the complete activations).
+// a0: gating selection (Janus Sec. 3.4, first step of the scheduling workflow: the gate yields the k
+// logical expert ids per token; Sec. 3.3: gating runs on the MoE side over the complete activations).
 // One wavefront per token; the selection itself lives in dispatch_dev.h (route_token).
 #include "dispatch_dev.h"
 
