@@ -368,6 +368,55 @@ def test_ffn_block_boundaries(d_h, d_e, T):
     assert B.moe_workspace_status(ws) == 0
 
 
+@pytest.mark.parametrize("seed", range(6))
+def test_ffn_random_dispatches_with_and_without_wide_blocks(seed):
+    """The grouped FFN alone on randomly drawn hand-made dispatches (empty, light, 33-64-row and
+    100-300-row slots mixed; channel counts that give more than eight groups of tiles per block and
+    tile counts that are no multiple of eight; both block sizes), with the tiled-GEMM blocks taken by
+    the default rule and forced on, against the oracle's grouped FFN."""
+    rng = np.random.default_rng([77, seed])
+    T = int(rng.choice([70, 200, 400, 600]))
+    d_h = int(rng.choice([128, 320]))
+    d_e = int(rng.choice([96, 608, 1088]))
+    C, k = int(rng.integers(5, 12)), 8
+    kinds = rng.integers(0, 5, size=C)
+    counts = [int({0: 0, 1: rng.integers(1, 17), 2: rng.integers(17, 33), 3: rng.integers(33, 65),
+                   4: rng.integers(65, 301)}[int(c)]) for c in kinds]
+    counts[int(rng.integers(0, C))] = int(rng.integers(65, 301))        # at least one slot with several blocks
+    while sum(counts) > T * k:
+        counts[int(np.argmax(counts))] //= 2
+    cfg = W.MoEConfig("random_blocks", E=C, k=k, d_h=d_h, d_e=d_e, T=T, n_inst=1, C=C, zipf_s=0.0, seed=100 + seed)
+    slot_off = np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
+    n_local = int(slot_off[-1])
+    perm = rng.permutation(T * k)[:n_local].astype(np.int32)
+    X = W.activations(cfg)
+    W13 = np.stack([W.expert_weights(cfg, e)[0] for e in range(C)])
+    W2 = np.stack([W.expert_weights(cfg, e)[1] for e in range(C)])
+    Yp_ref = ffn.grouped_ffn(X, W13, W2, slot_off, perm, k)
+    blk = expected_blocks(slot_off, B.moe_block_rows(T))
+    assert blk[0] <= B.moe_max_blocks(T, k, C)
+    d_blk = torch.zeros((B.moe_block_list_len(T, k, C),), dtype=torch.int32)
+    d_blk[:len(blk)] = torch.from_numpy(blk)
+    d_blk = d_blk.cuda()
+    W13p, W2p = torch.empty_like(to_device_bf16(W13)), torch.empty_like(to_device_bf16(W2))
+    B.moe_pack_weights_bf16(to_device_bf16(W13), to_device_bf16(W2), C, d_h, d_e, W13p, W2p)
+    ws = torch.empty((B.moe_workspace_bytes(T, k, C, d_h, d_e, B.MOE_DTYPE_BF16),), dtype=torch.uint8, device="cuda")
+    B.moe_workspace_init(ws)
+    Yp = torch.full((T * k, d_h), 123.0, dtype=torch.float32, device="cuda")
+    for forced in (0, 1, 0):
+        B.moe_workspace_set_option(ws, B.MOE_WS_OPT_WIDE_MIN_WORKGROUPS, forced)
+        Yp.fill_(123.0)
+        B.moe_grouped_ffn(to_device_bf16(X), W13p, W2p, T, k, C, d_h, d_e, B.MOE_DTYPE_BF16,
+                          torch.from_numpy(slot_off).cuda(), torch.from_numpy(perm).cuda(), d_blk, Yp, ws)
+        torch.cuda.synchronize()
+        got = Yp.cpu().numpy()
+        assert (got[n_local:] == 123.0).all(), (counts, forced)
+        num = np.linalg.norm(got[:n_local] - Yp_ref, axis=1)
+        den = np.linalg.norm(Yp_ref, axis=1)
+        assert (num <= 2.5 * TOL_BF16 * den + 1e-30).all(), (counts, forced, int(np.argmax(num / den)))
+        assert B.moe_workspace_status(ws) == 0
+
+
 def test_ffn_rejects_small_workspace():
     cfg = small()
     step = LayerStep(cfg, W.build_placement(cfg), 0)
