@@ -200,6 +200,12 @@ def step_bench(args, name: str, T: int, steps: int, warmup: int, full: bool) -> 
         # + combine (read Yp, write Y) + routing/schedule index traffic
         return (bytes_ffn(j) + n_local[j] * d_h * 4 + T * d_h * 2 + T * cfg.E * 4 + 6 * T * k * 4)
 
+    # the plain read of the same number of bytes (mean over the ring), measured before the timed region:
+    # a reference point for the FFN launch, and the GPU has reached its streaming clocks when the
+    # warm-up steps begin (a run of 20 steps after 5 warm-up steps alone read 2-3 % slow)
+    mean_b = statistics.mean(bytes_ffn(j) for j in range(n_ring))
+    probe = read_probe_best(W13s, int(mean_b)) if (full and not args.no_events) else None
+
     for i in range(warmup):
         run_step(i)
     torch.cuda.synchronize()
@@ -209,7 +215,6 @@ def step_bench(args, name: str, T: int, steps: int, warmup: int, full: bool) -> 
     # (more than 0.5 GB per launch) or the run is short (<= 50 steps), every 4th step otherwise.  The
     # events are created without the system-scope fence of default events (a cache write-back between
     # the kernels they separate).
-    mean_b = statistics.mean(bytes_ffn(j) for j in range(n_ring))
     every = 1 if (steps <= 50 or mean_b > 5e8) else 4
     timed = [] if args.no_events else [i for i in range(steps) if i % every == 0]
     te = TimingEvents()
@@ -257,9 +262,8 @@ def step_bench(args, name: str, T: int, steps: int, warmup: int, full: bool) -> 
                     "p50_us": round(ffn_p50_us, 2),
                     "p90_us": round(float(np.percentile(ffn_us, 90)), 2),
                     "algorithmic_bytes": int(mean_bytes_ffn)}
-        if full:
-            best = read_probe_best(W13s, int(mean_bytes_ffn))
-            roofline["read_probe_same_bytes"] = best
+        if probe is not None:
+            roofline["read_probe_same_bytes"] = probe
     te.close()
 
     out = {
