@@ -20,10 +20,12 @@
 // B-operand images, so stage 2 reads its token fragments like the weights, straight into
 // registers and as far ahead.
 //
-// A slot that received more requests than one block holds is not cut into streaming items (each
-// would stream the expert again): its rows are computed in blocks of twice that size as tiled
-// GEMMs by workgroups of the same launch (wide_item below), which read the weights once per block
-// and share the token rows of a block between four channel tiles through LDS.
+// Every further streaming block of a slot streams the expert's tiles again.  When a batch has enough
+// slots with more than 64 requests (wide_on below), those slots are computed as tiled GEMMs over
+// blocks of 64 rows by workgroups of the same launch instead (wide_item): a workgroup takes four
+// channel tiles through the whole K dimension, shares the token rows of the block between them
+// through LDS, and the blocks of a slot are dealt to the workgroups so that they find the
+// expert's tiles in their XCD's L2 (run_wide).
 //
 // Both stages run in ONE launch: the stage-2 workgroups have the higher ids, so the hardware
 // starts them only after every stage-1 workgroup has been started, and they fill the compute
