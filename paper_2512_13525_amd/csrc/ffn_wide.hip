@@ -2,9 +2,9 @@
 //
 // Janus Sec. 2.2: an expert's two GEMMs are memory-bound while few tokens visit it and turn
 // compute-bound as the batch grows.  The streaming kernel (ffn_stream.hip) is built for the first
-// regime: a slot with several blocks of rows streams its expert once per block.  A slot that
-// received more than 64 requests is therefore taken out of the streaming launch and handled here:
-// its rows are cut into blocks of 128, and a workgroup computes 128 rows x 4 packed weight tiles
+// regime: a slot with several blocks of rows streams its expert once per block.  In batches of
+// thousands of tokens a slot that received more than 64 requests is therefore taken out of the
+// streaming launch and handled here: its rows are cut into blocks of 128, and a workgroup computes 128 rows x 4 packed weight tiles
 // (64 channels of SiLU(gate)*up in stage 1, 128 output channels in stage 2), so that the weights
 // are fetched once per 128 rows and the token rows once per 4 tiles.
 //
@@ -19,7 +19,7 @@
 //
 // A workgroup runs the whole K dimension of its tile, so these launches pay off only when a
 // batch has enough wide blocks to fill the chip; the list header counts them and this kernel and
-// the streaming kernel take the same decision from it (moe::ffn_wide_on).
+// the streaming kernel take the same decision from it (moe::ffn_gemm_on).
 //
 // Work comes from the same block list as the streaming launch (blocks of 64 rows): the entry
 // whose first row is a multiple of 128 rows into a slot with more than 64 requests leads a wide

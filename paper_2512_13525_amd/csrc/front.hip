@@ -2,8 +2,8 @@
 // dispatch (Janus Sec. 3.4, workflow Steps 0-4).  At decode sizes each of these steps is a few
 // microseconds of work behind a launch of about the same cost, so three launches become one.
 //
-// Every workgroup routes 16 tokens (one per wavefront) and publishes their expert ids with
-// agent-scope stores; the workgroup that finishes last (an atomic ticket, nobody waits) then
+// Every workgroup routes 4, 8 or 16 tokens (one per wavefront; the fewer, the smaller the batch:
+// launch_front) and publishes their expert ids with agent-scope stores; the workgroup that finishes last (an atomic ticket, nobody waits) then
 // runs Alg. 1 and the counting sort on its own, reading the ids with agent-scope loads because
 // they were written on other XCDs.
 //
